@@ -1,0 +1,181 @@
+/*
+ * libnpas — inference through layers pruned with NPAS's fine-grained structured
+ * schemes on one AMD MI355X (gfx950).
+ *
+ *   block-punched pruning (CONV, any kernel size)   paper section 3, Fig. 1 (f)
+ *   block-based pruning (FC)                         paper section 3, Fig. 1 (g)
+ *   pattern-based pruning + kernel removal (3x3)     paper section 2.1, Fig. 1 (e)
+ *
+ * Pruning sets weights to zero; a pruned layer computes the masked-dense
+ * result.  `pack` turns a dense weight tensor plus a 0/1 mask into a compact
+ * form that lists, per group of filters, only the surviving (channel, kh, kw)
+ * positions; the run calls execute that list as a gathered sub-GEMM.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer is either HOST memory (suffix _host) or DEVICE
+ *     memory on the current HIP device (suffix _dev).  The caller owns all of
+ *     them; the library owns only what lives inside the opaque handles.
+ *   - Weights  W[F][C][KH][KW]  (filter, channel, kernel row, kernel column),
+ *     row-major, in the layer's storage type.  Masks are uint8, same shape,
+ *     1 = weight kept, 0 = pruned; weight values under a 0 are ignored.
+ *   - Activations are NHWC, contiguous, in the same storage type as the packed
+ *     weights.  Accumulation is fp32; outputs are rounded to the storage type
+ *     (round to nearest even).  bias is fp32 [F] and may be NULL.
+ *   - Convolution is cross-correlation with zero padding:
+ *       Y[n,y,x,f] = act(bias[f] + sum W[f,c,kh,kw] X[n, y*s+kh-p, x*s+kw-p, c] + residual[n,y,x,f])
+ *       Ho = (H + 2p - KH)/s + 1.
+ *   - All device work is enqueued on the caller's stream (`hip_stream` is a
+ *     hipStream_t passed as void*, NULL = default stream).  Run calls neither
+ *     allocate nor synchronise.  Pack calls allocate device memory for the handle
+ *     and copy to it synchronously; on a machine without a GPU they still build
+ *     the host-side compact form (so it can be exported), and run calls on such a
+ *     handle fail with NPAS_E_HIP.
+ *   - Every function returns 0 (NPAS_OK) or a negative npas_status;
+ *     npas_last_error() gives a thread-local message for the last failure.
+ *   - Activations must be finite: a stored zero weight (padding of a partial
+ *     group or of a position shared with a neighbouring group) times an infinite
+ *     activation would give NaN where the definition gives a finite value.
+ */
+#ifndef NPAS_H
+#define NPAS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct npas_packed npas_packed; /* one packed layer */
+typedef struct npas_stack npas_stack;   /* a wired list of layers */
+
+typedef enum { NPAS_F32 = 0, NPAS_BF16 = 1, NPAS_F16 = 2 } npas_dtype;
+typedef enum { NPAS_ACT_NONE = 0, NPAS_ACT_RELU = 1, NPAS_ACT_RELU6 = 2 } npas_act;
+typedef enum { NPAS_SCHEME_BLOCK_PUNCHED = 0, NPAS_SCHEME_FC_BLOCK = 1, NPAS_SCHEME_PATTERN = 2 } npas_scheme;
+
+typedef enum {
+    NPAS_OK = 0,
+    NPAS_E_NULL = -1,                   /* a required pointer is NULL */
+    NPAS_E_SHAPE = -2,                  /* a dimension is non-positive, inconsistent or too large */
+    NPAS_E_MASK_NOT_BLOCK_UNIFORM = -3, /* mask violates the block-punched / block-based rule */
+    NPAS_E_MASK_NOT_IN_LIBRARY = -4,    /* a 3x3 kernel is neither a library pattern nor removed */
+    NPAS_E_DTYPE = -5,                  /* unknown storage type */
+    NPAS_E_WORKSPACE = -6,              /* workspace too small or misaligned */
+    NPAS_E_HIP = -7,                    /* HIP runtime error, or handle has no device copy */
+    NPAS_E_MASK_VALUE = -8              /* mask holds a value other than 0 or 1 */
+} npas_status;
+
+const char *npas_last_error(void);
+
+/* ---- packing ------------------------------------------------------------- */
+
+/* Block-punched pruning (section 3): the tensor is cut into blocks of Bf
+ * consecutive filters x Bc consecutive channels (x all KH x KW taps; edge blocks
+ * may be partial).  A punched (channel, kh, kw) position must be punched in every
+ * filter of its block; a mask that breaks this is rejected, never repaired.
+ * Bf = Bc = 1 is unstructured pruning, Bf = F and Bc = C coarse-grained
+ * (section 3, "Compiler Optimizations").  On success *out owns host and device
+ * copies of the compact form; release with npas_free. */
+int npas_pack_block_punched(const void *w_host, const uint8_t *mask_host, int F, int C, int KH, int KW,
+                            int Bf, int Bc, npas_dtype dt, void *hip_stream, npas_packed **out);
+
+/* Block-based pruning of an FC weight matrix W[OUT][IN] (section 3): blocks of
+ * Br rows x Bcol columns; inside a block whole columns and/or whole rows are
+ * pruned (mask = rowkeep AND colkeep per block), anything else is rejected.
+ * The handle behaves like a 1x1 convolution with F = OUT, C = IN, Bf = Br. */
+int npas_pack_fc_block(const void *w_host, const uint8_t *mask_host, int OUT, int IN, int Br, int Bcol,
+                       npas_dtype dt, void *hip_stream, npas_packed **out);
+
+/* Pattern-based pruning with kernel removal (section 2.1), 3x3 only: every
+ * kernel (f, c) of W[F][C][3][3] must equal one of the n_pat library patterns
+ * (library_host: uint8 [n_pat][9], 0/1, tap order kh*3+kw, n_pat <= 254) or be
+ * all zero (removed). */
+int npas_pack_pattern(const void *w_host, const uint8_t *mask_host, int F, int C,
+                      const uint8_t *library_host, int n_pat, npas_dtype dt, void *hip_stream,
+                      npas_packed **out);
+
+/* info[0..15] = { scheme, dtype, F, C, KH, KW, Bf, Bc, G (filter groups),
+ *                 K_total (length of k_pos), n_pat, device_ready, kernel variant,
+ *                 device-format bytes, canonical compact-weight bytes, reserved }. */
+int npas_packed_info(const npas_packed *p, int64_t info[16]);
+
+/* Canonical compact form, copied to caller's HOST buffers (any may be NULL):
+ *   grp_ptr  int32 [G+1]        prefix sums of the per-group list lengths
+ *   k_pos    int32 [K_total]    per group, ascending: (kh*KW + kw)*C + c of every
+ *                               position kept by any filter of the group
+ *   w_compact storage type [K_total][Bf]   weight of filter g*Bf+j at that position
+ *                               (+0 where that filter's mask is 0 or past F)
+ *   pattern scheme only:
+ *   pat_id   uint8 [F][C]       library index (smallest match), 255 = removed
+ *   w4       storage type [F][C][4]  kept weights in ascending tap order, +0 if removed
+ * For the pattern scheme grp_ptr/k_pos/w_compact describe the same layer with
+ * Bf = 1 (one list per filter). */
+int npas_packed_export(const npas_packed *p, int32_t *grp_ptr, int32_t *k_pos, void *w_compact,
+                       uint8_t *pat_id, void *w4);
+
+void npas_free(npas_packed *p);
+
+/* ---- running one layer ---------------------------------------------------- */
+
+/* Sparse convolution of x_dev [N][H][W][C] into y_dev [N][Ho][Wo][F] through a
+ * packed layer of any scheme.  residual_dev (nullable) has y's shape and type and
+ * is added before the activation.  Errors: NULL handle/x/y, non-positive sizes,
+ * an empty output, or more than 2^31-1 elements in x or y -> NPAS_E_NULL /
+ * NPAS_E_SHAPE; launch failure -> NPAS_E_HIP. */
+int npas_conv2d_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int N, int H, int W,
+                       int stride, int pad, const void *bias_dev, const void *residual_dev,
+                       npas_act act, void *hip_stream);
+
+/* Sparse fully-connected layer: x_dev [B][IN] -> y_dev [B][OUT]; the handle comes
+ * from npas_pack_fc_block (or any 1x1 packed layer). */
+int npas_fc_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int B, const void *bias_dev,
+                   npas_act act, void *hip_stream);
+
+/* Glue layers a residual stack needs around the pruned ones (not pruned
+ * themselves): 3x3 stride-2 max-pool with padding 1 (padding never wins), and
+ * global average pool [N][H][W][C] -> [N][C] (fp32 mean, rounded on store). */
+int npas_maxpool3x3s2(const void *x_dev, void *y_dev, int N, int H, int W, int C, npas_dtype dt,
+                      void *hip_stream);
+int npas_global_avgpool(const void *x_dev, void *y_dev, int N, int H, int W, int C, npas_dtype dt,
+                        void *hip_stream);
+
+/* ---- running a stack ------------------------------------------------------ */
+
+typedef enum { NPAS_LAYER_CONV = 0, NPAS_LAYER_FC = 1, NPAS_LAYER_MAXPOOL3X3S2 = 2,
+               NPAS_LAYER_GLOBAL_AVGPOOL = 3 } npas_layer_kind;
+
+/* Tensor 0 is the stack input; layer i writes tensor i+1; the last layer's
+ * tensor is the stack output.  `src` and `res` name earlier tensors (res = -1:
+ * no residual).  `packed` must outlive the stack. */
+typedef struct {
+    int kind;                  /* npas_layer_kind */
+    const npas_packed *packed; /* CONV / FC; NULL otherwise */
+    int stride, pad;           /* CONV */
+    int act;                   /* npas_act, CONV / FC */
+    int src;
+    int res;
+    const void *bias_dev;      /* nullable */
+} npas_layer_desc;
+
+enum { NPAS_STACK_FUSE_POINTWISE = 1 }; /* allow a 1x1 -> act -> 1x1 pair to run as one kernel */
+
+/* Builds a stack for inputs of H x W x C (C is taken from the first layer).
+ * Checks wiring, shapes and types (NPAS_E_SHAPE / NPAS_E_DTYPE). */
+int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W, unsigned flags,
+                      npas_stack **out);
+/* Bytes of device workspace npas_run_stack needs for batch N (intermediate
+ * tensors, 256-byte aligned, reused once dead). */
+size_t npas_stack_workspace_bytes(const npas_stack *s, int N);
+/* Runs the stack on the caller's stream: x_dev [N][H][W][C] -> y_dev (shape of
+ * the last tensor).  workspace_dev must be 256-byte aligned and at least
+ * npas_stack_workspace_bytes(s, N) long (NPAS_E_WORKSPACE otherwise). */
+int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, void *workspace_dev,
+                   size_t workspace_bytes, void *hip_stream);
+/* Number of kernels one npas_run_stack call launches (after fusion). */
+int npas_stack_num_launches(const npas_stack *s);
+void npas_stack_free(npas_stack *s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NPAS_H */

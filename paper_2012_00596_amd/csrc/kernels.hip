@@ -1,0 +1,421 @@
+// gfx950 kernels of libnpas.
+//
+// conv_gather_mfma: block-punched / block-based / pattern layers in bf16 or fp16.
+//   The surviving (channel, kh, kw) positions of a 16-filter tile form the K
+//   dimension of a dense sub-GEMM (paper section 3: the kept weights of a block
+//   share their positions, so the remaining work is regular).  The activation
+//   patch of an output tile is staged once in LDS ([pixel][channel chunk]); for
+//   each 32 list entries a wave gathers the B operand (8 entries x its pixel per
+//   lane) from LDS and issues one v_mfma_f32_16x16x32 per 16 output pixels with
+//   the pre-swizzled weight image as the A operand.
+// conv_valu_f32: fp32 layers, one thread per (output pixel, sub-group of <= 8
+//   filters), weights broadcast from scalar loads, exact per-group skipping.
+// maxpool3x3s2 / global_avgpool: glue layers of residual stacks.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "npas_internal.h"
+
+namespace npas {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, uint32_t magic)
+{
+    return magic ? __umulhi(n, magic) : n; // magic = ceil(2^32 / d), 0 for d == 1
+}
+
+__device__ __forceinline__ float act_apply(float v, int act)
+{
+    if (act == NPAS_ACT_RELU) return fmaxf(v, 0.0f);
+    if (act == NPAS_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
+    return v;
+}
+
+// fp32 -> 16-bit storage, round to nearest even.
+template <int DT> __device__ __forceinline__ uint16_t to_storage(float v)
+{
+    if (DT == NPAS_BF16) {
+        uint32_t u = __float_as_uint(v);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40); // NaN stays NaN
+        u += 0x7fffu + ((u >> 16) & 1u);
+        return (uint16_t)(u >> 16);
+    } else {
+        _Float16 h = (_Float16)v;
+        return __builtin_bit_cast(uint16_t, h);
+    }
+}
+
+template <int DT> __device__ __forceinline__ float from_storage(uint16_t b)
+{
+    if (DT == NPAS_BF16) return __uint_as_float((uint32_t)b << 16);
+    return (float)__builtin_bit_cast(_Float16, b);
+}
+
+template <int DT> __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c)
+{
+    if (DT == NPAS_BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run
+// of logical ids so that workgroups sharing an activation patch share an L2.
+__device__ __forceinline__ uint32_t xcd_remap(uint32_t wg, uint32_t nwg)
+{
+    uint32_t xcd = wg & 7u, idx = wg >> 3, q = nwg >> 3, r = nwg & 7u;
+    return xcd * q + (xcd < r ? xcd : r) + idx;
+}
+
+template <int DT, int S>
+__global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const ConvGeom &g = a.g;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
+
+    const uint32_t logical = xcd_remap(blockIdx.x, gridDim.x);
+    const uint32_t fsplit = logical % (uint32_t)g.nfsplit, ptile = logical / (uint32_t)g.nfsplit;
+    const uint32_t tiles_img = (uint32_t)(g.tilesY * g.tilesX);
+    const int n = (int)(ptile / tiles_img);
+    const uint32_t trem = ptile % tiles_img;
+    const int ty0 = (int)(trem / (uint32_t)g.tilesX) * g.TH, tx0 = (int)(trem % (uint32_t)g.tilesX) * g.TW;
+
+    const uint32_t patch_bytes = ((uint32_t)(g.PH * g.PW * g.pitch) + 15u) & ~15u;
+    uint32_t *koff = reinterpret_cast<uint32_t *>(lds + patch_bytes) + wave * g.koff_cap;
+
+    // Which output pixel each of this lane's S MFMA columns is, where its patch
+    // origin sits in LDS, and where its outputs go.
+    const int npix_tile = g.TH * g.TW;
+    const int ns = (npix_tile + 15) >> 4;
+    uint32_t pixbase[S];
+    int32_t outoff[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        uint32_t m = (uint32_t)(s * 16 + n16);
+        uint32_t ty = fastdiv(m, g.div_tw), tx = m - ty * (uint32_t)g.TW;
+        int oy = ty0 + (int)ty, ox = tx0 + (int)tx;
+        bool valid = (int)m < npix_tile && oy < g.Ho && ox < g.Wo;
+        pixbase[s] = valid ? ((ty * g.lstep) * g.PW + tx * g.lstep) * (uint32_t)g.pitch : 0u;
+        outoff[s] = valid ? ((n * g.Ho + oy) * g.Wo + ox) * g.F : -1;
+    }
+
+    const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
+    // input coordinate of patch pixel (0, 0)
+    const int iy0 = (g.pstep > 1 ? ty0 * g.pstep : ty0 * g.stride) - g.pad;
+    const int ix0 = (g.pstep > 1 ? tx0 * g.pstep : tx0 * g.stride) - g.pad;
+
+    const int ft_begin = (int)fsplit * g.tiles_per_split;
+    const int ft_end = min(ft_begin + g.tiles_per_split, a.ntiles);
+    bool staged = false;
+
+    for (int ftb = ft_begin; ftb < ft_end; ftb += 4) {
+        const int ft = ftb + wave;
+        const bool active = ft < ft_end;
+        f32x4 acc[S];
+#pragma unroll
+        for (int s = 0; s < S; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int cc = 0; cc < a.nchunks; ++cc) {
+            if (a.nchunks > 1 || !staged) {
+                // ---- stage the activation patch of channel chunk cc -------------
+                __syncthreads();
+                const int c0 = cc * a.CC, ccount = min(a.CC, g.C - c0);
+                if (g.vec) {
+                    const uint32_t nvv = (uint32_t)ccount >> 3;
+                    const uint32_t total = (uint32_t)(g.PH * g.PW) * nvv;
+                    const uint32_t dv = (nvv == (uint32_t)(a.CC >> 3)) ? g.div_vec : 0xffffffffu;
+                    for (uint32_t v = tid; v < total; v += 256) {
+                        uint32_t pix = dv == 0xffffffffu ? v / nvv : fastdiv(v, dv);
+                        uint32_t cv = v - pix * nvv;
+                        uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
+                        int iy = iy0 + (int)py * g.pstep, ix = ix0 + (int)px * g.pstep;
+                        uint4 val = uint4{0u, 0u, 0u, 0u};
+                        if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
+                            val = *reinterpret_cast<const uint4 *>(
+                                x16 + ((size_t)((n * g.H + iy) * g.W + ix) * g.C + c0 + cv * 8));
+                        uint2 *dst = reinterpret_cast<uint2 *>(lds + pix * (uint32_t)g.pitch + cv * 16);
+                        dst[0] = uint2{val.x, val.y};
+                        dst[1] = uint2{val.z, val.w};
+                    }
+                } else {
+                    const uint32_t total = (uint32_t)(g.PH * g.PW * ccount);
+                    for (uint32_t v = tid; v < total; v += 256) {
+                        uint32_t pix = v / (uint32_t)ccount, c = v - pix * (uint32_t)ccount;
+                        uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
+                        int iy = iy0 + (int)py * g.pstep, ix = ix0 + (int)px * g.pstep;
+                        uint16_t val = 0;
+                        if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
+                            val = x16[(size_t)((n * g.H + iy) * g.W + ix) * g.C + c0 + c];
+                        *reinterpret_cast<uint16_t *>(lds + pix * (uint32_t)g.pitch + c * 2) = val;
+                    }
+                }
+                staged = true;
+                __syncthreads();
+            }
+            if (!active) continue;
+
+            const int e0 = a.tc_ptr[ft * a.nchunks + cc], e1 = a.tc_ptr[ft * a.nchunks + cc + 1];
+            for (int eb = e0; eb < e1; eb += g.koff_cap) {
+                const int nb = min(g.koff_cap, e1 - eb);
+                // ---- list entries -> LDS byte offsets, once per wave -------------
+                __builtin_amdgcn_wave_barrier();
+                for (int i = lane; i < nb; i += 64) {
+                    uint32_t ent = a.kent[eb + i];
+                    uint32_t kh = ent >> 24, kw = (ent >> 16) & 255u, c = ent & 0xffffu;
+                    koff[i] = (kh * (uint32_t)g.PW + kw) * (uint32_t)g.pitch + c * 2u;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+                const uint4 *wf = reinterpret_cast<const uint4 *>(a.wfrag) + (size_t)(eb >> 5) * 64 + lane;
+                for (int j = 0; j < nb; j += 32, wf += 64) {
+                    const uint4 wa = *wf;
+                    const uint4 k0 = *reinterpret_cast<const uint4 *>(koff + j + 8 * q);
+                    const uint4 k1 = *reinterpret_cast<const uint4 *>(koff + j + 8 * q + 4);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) {
+                        {
+                            const uint8_t *pb = lds + pixbase[s];
+                            uint4 b;
+                            b.x = (uint32_t)*reinterpret_cast<const uint16_t *>(pb + k0.x) |
+                                  (uint32_t)*reinterpret_cast<const uint16_t *>(pb + k0.y) << 16;
+                            b.y = (uint32_t)*reinterpret_cast<const uint16_t *>(pb + k0.z) |
+                                  (uint32_t)*reinterpret_cast<const uint16_t *>(pb + k0.w) << 16;
+                            b.z = (uint32_t)*reinterpret_cast<const uint16_t *>(pb + k1.x) |
+                                  (uint32_t)*reinterpret_cast<const uint16_t *>(pb + k1.y) << 16;
+                            b.w = (uint32_t)*reinterpret_cast<const uint16_t *>(pb + k1.z) |
+                                  (uint32_t)*reinterpret_cast<const uint16_t *>(pb + k1.w) << 16;
+                            acc[s] = mfma16<DT>(wa, b, acc[s]);
+                        }
+                    }
+                }
+            }
+        }
+
+        // ---- epilogue: bias, residual, activation, round, store -----------------
+        if (active) {
+            const int f0 = ft * 16 + 4 * q;
+            if (f0 < g.F) {
+                float bv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (a.bias) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (f0 + i < g.F) bv[i] = a.bias[f0 + i];
+                }
+                uint16_t *y16 = reinterpret_cast<uint16_t *>(a.y);
+                const uint16_t *r16 = reinterpret_cast<const uint16_t *>(a.residual);
+                const bool vec4 = (g.F & 3) == 0;
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    if (s < ns && outoff[s] >= 0) {
+                        const size_t o = (size_t)outoff[s] + f0;
+                        float v[4] = {acc[s][0] + bv[0], acc[s][1] + bv[1], acc[s][2] + bv[2], acc[s][3] + bv[3]};
+                        if (vec4) {
+                            if (r16) {
+                                uint2 r = *reinterpret_cast<const uint2 *>(r16 + o);
+                                v[0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
+                                v[1] += from_storage<DT>((uint16_t)(r.x >> 16));
+                                v[2] += from_storage<DT>((uint16_t)(r.y & 0xffffu));
+                                v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
+                            }
+                            uint2 out;
+                            out.x = (uint32_t)to_storage<DT>(act_apply(v[0], g.act)) |
+                                    (uint32_t)to_storage<DT>(act_apply(v[1], g.act)) << 16;
+                            out.y = (uint32_t)to_storage<DT>(act_apply(v[2], g.act)) |
+                                    (uint32_t)to_storage<DT>(act_apply(v[3], g.act)) << 16;
+                            *reinterpret_cast<uint2 *>(y16 + o) = out;
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (f0 + i < g.F) {
+                                    float t = v[i];
+                                    if (r16) t += from_storage<DT>(r16[o + i]);
+                                    y16[o + i] = to_storage<DT>(act_apply(t, g.act));
+                                }
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+static bool g_lds_attr_set[2][2] = {{false, false}, {false, false}};
+
+template <int DT, int S>
+static int launch_mfma_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
+{
+    auto kern = conv_gather_mfma_kernel<DT, S>;
+    bool &done = g_lds_attr_set[DT == NPAS_BF16 ? 0 : 1][S == 8 ? 0 : 1];
+    if (!done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  64 * 1024);
+        done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds_bytes, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("conv_gather_mfma launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+int launch_conv_mfma(int dtype, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const bool s8 = a.g.TH * a.g.TW > 64;
+    if (dtype == NPAS_BF16)
+        return s8 ? launch_mfma_inst<NPAS_BF16, 8>(a, grid, lds_bytes, st) : launch_mfma_inst<NPAS_BF16, 4>(a, grid, lds_bytes, st);
+    if (dtype == NPAS_F16)
+        return s8 ? launch_mfma_inst<NPAS_F16, 8>(a, grid, lds_bytes, st) : launch_mfma_inst<NPAS_F16, 4>(a, grid, lds_bytes, st);
+    set_error("conv_gather_mfma needs a 16-bit storage type");
+    return NPAS_E_DTYPE;
+}
+
+// ------------------------------------------------------------------------------
+template <int VB>
+__global__ __launch_bounds__(256) void conv_valu_f32_kernel(ConvValuArgs a)
+{
+    const int vg = blockIdx.y;
+    const uint32_t pix = blockIdx.x * 256u + threadIdx.x;
+    const uint32_t npix = (uint32_t)(a.N * a.Ho * a.Wo);
+    if (pix >= npix) return;
+    const uint32_t ox = pix % (uint32_t)a.Wo, t = pix / (uint32_t)a.Wo;
+    const uint32_t oy = t % (uint32_t)a.Ho, n = t / (uint32_t)a.Ho;
+    const int f0 = a.vg_f0[vg];
+    float acc[VB];
+#pragma unroll
+    for (int j = 0; j < VB; ++j) acc[j] = (a.bias && f0 + j < a.F) ? a.bias[f0 + j] : 0.0f;
+    const int k0 = a.vg_ptr[vg], k1 = a.vg_ptr[vg + 1];
+    const int by = (int)oy * a.stride - a.pad, bx = (int)ox * a.stride - a.pad;
+    const float *xn = a.x + (size_t)n * a.H * a.W * a.C;
+    for (int k = k0; k < k1; ++k) {
+        const uint32_t ent = a.vkent[k];
+        const int iy = by + (int)(ent >> 24), ix = bx + (int)((ent >> 16) & 255u);
+        float xv = 0.0f;
+        if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) xv = xn[(size_t)(iy * a.W + ix) * a.C + (ent & 0xffffu)];
+        const float *w = a.vw + (size_t)k * VB;
+#pragma unroll
+        for (int j = 0; j < VB; ++j) acc[j] = fmaf(w[j], xv, acc[j]);
+    }
+    const size_t o = (size_t)pix * a.F + f0;
+#pragma unroll
+    for (int j = 0; j < VB; ++j)
+        if (f0 + j < a.F) {
+            float v = acc[j];
+            if (a.residual) v += a.residual[o + j];
+            a.y[o + j] = act_apply(v, a.act);
+        }
+}
+
+int launch_conv_valu(const ConvValuArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t npix = (uint32_t)(a.N * a.Ho * a.Wo);
+    dim3 grid((npix + 255) / 256, (unsigned)a.nvg), block(256);
+    if (a.nvg > 65535) {
+        set_error("too many filter sub-groups (%d) for one launch", a.nvg);
+        return NPAS_E_SHAPE;
+    }
+    switch (a.VB) {
+    case 1: hipLaunchKernelGGL(conv_valu_f32_kernel<1>, grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL(conv_valu_f32_kernel<2>, grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL(conv_valu_f32_kernel<4>, grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL(conv_valu_f32_kernel<8>, grid, block, 0, st, a); break;
+    default: set_error("unsupported sub-group width %d", a.VB); return NPAS_E_SHAPE;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("conv_valu_f32 launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+// ------------------------------------------------------------------------------
+template <int DT> __device__ __forceinline__ float ld_act(const void *p, size_t i)
+{
+    if (DT == NPAS_F32) return reinterpret_cast<const float *>(p)[i];
+    return from_storage<DT>(reinterpret_cast<const uint16_t *>(p)[i]);
+}
+template <int DT> __device__ __forceinline__ void st_act(void *p, size_t i, float v)
+{
+    if (DT == NPAS_F32) reinterpret_cast<float *>(p)[i] = v;
+    else reinterpret_cast<uint16_t *>(p)[i] = to_storage<DT>(v);
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const void *x, void *y, int N, int H, int W, int C, int Ho, int Wo)
+{
+    const size_t total = (size_t)N * Ho * Wo * C;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        int c = (int)(i % C);
+        size_t t = i / C;
+        int ox = (int)(t % Wo);
+        t /= Wo;
+        int oy = (int)(t % Ho), n = (int)(t / Ho);
+        float m = -INFINITY;
+        for (int kh = 0; kh < 3; ++kh) {
+            int iy = 2 * oy + kh - 1;
+            if (iy < 0 || iy >= H) continue;
+            for (int kw = 0; kw < 3; ++kw) {
+                int ix = 2 * ox + kw - 1;
+                if (ix < 0 || ix >= W) continue;
+                m = fmaxf(m, ld_act<DT>(x, ((size_t)(n * H + iy) * W + ix) * C + c));
+            }
+        }
+        st_act<DT>(y, i, m);
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void global_avgpool_kernel(const void *x, void *y, int N, int HW, int C)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= N * C) return;
+    const int n = i / C, c = i % C;
+    float s = 0.0f;
+    for (int p = 0; p < HW; ++p) s += ld_act<DT>(x, ((size_t)n * HW + p) * C + c);
+    st_act<DT>(y, (size_t)i, s / (float)HW);
+}
+
+int launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+    size_t total = (size_t)N * Ho * Wo * C;
+    unsigned grid = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 64);
+    if (dt == NPAS_F32) hipLaunchKernelGGL(maxpool3x3s2_kernel<NPAS_F32>, dim3(grid), dim3(256), 0, st, x, y, N, H, W, C, Ho, Wo);
+    else if (dt == NPAS_BF16) hipLaunchKernelGGL(maxpool3x3s2_kernel<NPAS_BF16>, dim3(grid), dim3(256), 0, st, x, y, N, H, W, C, Ho, Wo);
+    else hipLaunchKernelGGL(maxpool3x3s2_kernel<NPAS_F16>, dim3(grid), dim3(256), 0, st, x, y, N, H, W, C, Ho, Wo);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("maxpool launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+int launch_avgpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    unsigned grid = (unsigned)((N * C + 255) / 256);
+    if (dt == NPAS_F32) hipLaunchKernelGGL(global_avgpool_kernel<NPAS_F32>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
+    else if (dt == NPAS_BF16) hipLaunchKernelGGL(global_avgpool_kernel<NPAS_BF16>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
+    else hipLaunchKernelGGL(global_avgpool_kernel<NPAS_F16>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("avgpool launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+} // namespace npas

@@ -1,0 +1,141 @@
+// Internal structures of libnpas: the packed-layer handle (canonical compact
+// form + device execution format) and the kernel argument blocks.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/npas.h"
+
+namespace npas {
+
+void set_error(const char *fmt, ...);
+
+inline int dtype_size(int dt) { return dt == NPAS_F32 ? 4 : 2; }
+
+// Kernel variants a packed layer can be executed with.
+enum Variant {
+    V_VALU_F32 = 0,    // fp32 storage: one thread per (pixel, filter sub-group), scalar-broadcast weights
+    V_MFMA_GATHER = 1, // 16-bit storage: 16-filter tiles, element-gathered activations, MFMA 16x16x32
+};
+
+// ---- device execution format for V_MFMA_GATHER -------------------------------
+// Filters are cut into tiles of 16 (MFMA rows), channels into chunks of CC.
+// For tile t and chunk cc the list kent[tc_ptr[t*nchunks+cc] .. tc_ptr[..+1])
+// holds every (kh, kw, c) position of that chunk kept by ANY filter of the tile
+// (the union of the tile's filter groups), tap-major then channel, padded to a
+// multiple of 32 with copies of entry 0 whose weights are zero.
+//   entry = kh << 24 | kw << 16 | (c - cc*CC)
+// wfrag holds, per 32 entries, the MFMA A-operand image: 64 lanes x 8 values,
+// lane = 16*q + r holds W[filter 16t + r][entries 8q .. 8q+7] (zero where that
+// filter does not keep the position).
+//
+// ---- device execution format for V_VALU_F32 ----------------------------------
+// Filter groups are cut into sub-groups of VB (<= 8) filters that share the
+// group's list.  vg_ptr[v] .. vg_ptr[v+1] indexes vkent (same entry coding with
+// the absolute channel) and vw[entry][VB] (fp32).  vg_f0[v] = first filter.
+struct DeviceFormat {
+    int variant = -1;
+    // MFMA gather
+    int CC = 0, nchunks = 0, ntiles = 0;
+    std::vector<int32_t> tc_ptr;
+    std::vector<uint32_t> kent;
+    std::vector<uint16_t> wfrag;
+    // VALU f32
+    int VB = 0, nvg = 0;
+    std::vector<int32_t> vg_ptr, vg_f0;
+    std::vector<uint32_t> vkent;
+    std::vector<float> vw;
+    int max_list = 0; // longest per-(tile,chunk) list, entries
+};
+
+struct DeviceCopy {
+    int device = -1;
+    void *blob = nullptr; // one allocation holding everything below
+    size_t bytes = 0;
+    const int32_t *tc_ptr = nullptr;
+    const uint32_t *kent = nullptr;
+    const void *wfrag = nullptr;
+    const int32_t *vg_ptr = nullptr, *vg_f0 = nullptr;
+    const uint32_t *vkent = nullptr;
+    const float *vw = nullptr;
+};
+
+} // namespace npas
+
+struct npas_packed {
+    int scheme = 0, dtype = 0;
+    int F = 0, C = 0, KH = 0, KW = 0, Bf = 0, Bc = 0, G = 0;
+    // canonical compact form
+    std::vector<int32_t> grp_ptr, k_pos;
+    std::vector<uint8_t> w_compact; // storage type, [K_total][Bf]
+    int n_pat = 0;
+    std::vector<uint8_t> library, pat_id, w4;
+    // execution format
+    npas::DeviceFormat fmt;
+    npas::DeviceCopy dev;
+};
+
+namespace npas {
+
+// ---- kernel argument blocks (passed by value) ---------------------------------
+struct ConvGeom {
+    int N, H, W, C, F, Ho, Wo;
+    int KH, KW, stride, pad;
+    int TH, TW;           // output tile (TH*TW <= 16*S pixels)
+    int tilesY, tilesX;   // tiles per image
+    int PH, PW;           // LDS patch in pixels
+    int pstep;            // input step between patch pixels (stride for 1x1, else 1)
+    int lstep;            // patch step between neighbouring output pixels (1 for 1x1, else stride)
+    int pitch;            // LDS bytes per patch pixel
+    int act;
+    int nfsplit;          // filter-tile splits (grid = pixel tiles x nfsplit)
+    int tiles_per_split;  // filter tiles one workgroup walks through
+    int koff_cap;         // per-wave capacity of the offset table, entries
+    uint32_t div_tw, div_pw, div_vec; // magic reciprocals (see fastdiv)
+    int vec;              // 1: 16-byte staging path (C and CC multiples of 8)
+};
+
+struct ConvMfmaArgs {
+    const void *x;
+    void *y;
+    const void *residual;
+    const float *bias;
+    const int32_t *tc_ptr;
+    const uint32_t *kent;
+    const void *wfrag;
+    int CC, nchunks, ntiles;
+    ConvGeom g;
+};
+
+struct ConvValuArgs {
+    const float *x;
+    float *y;
+    const float *residual;
+    const float *bias;
+    const int32_t *vg_ptr, *vg_f0;
+    const uint32_t *vkent;
+    const float *vw;
+    int nvg, VB;
+    int N, H, W, C, F, Ho, Wo, KH, KW, stride, pad, act;
+};
+
+// Host-side plan of one conv launch (tile shape, grid, LDS bytes).
+struct ConvPlan {
+    ConvGeom g;
+    unsigned grid = 0;
+    size_t lds_bytes = 0;
+};
+
+int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, const void *w_host);
+int upload(npas_packed *p);
+int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, ConvPlan *out);
+
+// launchers (kernels.hip)
+int launch_conv_mfma(int dtype, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream);
+int launch_conv_valu(const ConvValuArgs &a, void *stream);
+int launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream);
+int launch_avgpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream);
+
+} // namespace npas

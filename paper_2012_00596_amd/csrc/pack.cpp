@@ -1,0 +1,449 @@
+// Host side of libnpas: scheme validation, the canonical compact form, the
+// device execution formats, and their upload.
+//
+// Scheme definitions follow the paper: block-punched and block-based pruning in
+// section 3 (Fig. 1 (f), (g)), pattern-based pruning with kernel removal in
+// section 2.1 (Fig. 1 (e)).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "npas_internal.h"
+
+namespace npas {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+const char *last_error() { return g_err; }
+
+static inline size_t widx(int f, int c, int kh, int kw, int C, int KH, int KW)
+{
+    return (((size_t)f * C + c) * KH + kh) * KW + kw;
+}
+
+// Copies one weight (storage type) or writes +0.
+static inline void put_weight(uint8_t *dst, const uint8_t *src, int esz, bool keep)
+{
+    if (keep) memcpy(dst, src, esz);
+    else memset(dst, 0, esz);
+}
+
+static int check_mask_values(const uint8_t *m, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        if (m[i] > 1) {
+            set_error("mask[%zu] = %d is neither 0 nor 1", i, (int)m[i]);
+            return NPAS_E_MASK_VALUE;
+        }
+    return NPAS_OK;
+}
+
+// Block-punched rule: inside a group of Bf filters the mask does not depend on
+// the filter (channel blocks need no check of their own: the rule constrains
+// the filter axis only; Bc is recorded as the scheme parameter).
+static int validate_block_punched(const uint8_t *m, int F, int C, int KH, int KW, int Bf)
+{
+    size_t per = (size_t)C * KH * KW;
+    for (int f = 0; f < F; ++f) {
+        int lead = f - f % Bf;
+        if (f == lead) continue;
+        if (memcmp(m + (size_t)f * per, m + (size_t)lead * per, per) != 0) {
+            size_t p = 0;
+            while (m[(size_t)f * per + p] == m[(size_t)lead * per + p]) ++p;
+            set_error("mask is not block-punched: filter %d differs from filter %d of its block at "
+                      "position (c=%zu, kh=%zu, kw=%zu)", f, lead, p / (KH * KW), (p / KW) % KH, p % KW);
+            return NPAS_E_MASK_NOT_BLOCK_UNIFORM;
+        }
+    }
+    return NPAS_OK;
+}
+
+// Block-based rule: inside every Br x Bcol block mask = rowkeep AND colkeep.
+static int validate_fc_block(const uint8_t *m, int OUT, int IN, int Br, int Bcol)
+{
+    std::vector<uint8_t> rowkeep(Br), colkeep(Bcol);
+    for (int r0 = 0; r0 < OUT; r0 += Br)
+        for (int c0 = 0; c0 < IN; c0 += Bcol) {
+            int nr = std::min(Br, OUT - r0), nc = std::min(Bcol, IN - c0);
+            std::fill(rowkeep.begin(), rowkeep.end(), 0);
+            std::fill(colkeep.begin(), colkeep.end(), 0);
+            for (int r = 0; r < nr; ++r)
+                for (int c = 0; c < nc; ++c)
+                    if (m[(size_t)(r0 + r) * IN + c0 + c]) rowkeep[r] = colkeep[c] = 1;
+            for (int r = 0; r < nr; ++r)
+                for (int c = 0; c < nc; ++c)
+                    if (m[(size_t)(r0 + r) * IN + c0 + c] != (rowkeep[r] & colkeep[c])) {
+                        set_error("mask is not block-based: block at (row %d, col %d) is not whole "
+                                  "rows/columns (entry %d,%d)", r0, c0, r0 + r, c0 + c);
+                        return NPAS_E_MASK_NOT_BLOCK_UNIFORM;
+                    }
+        }
+    return NPAS_OK;
+}
+
+// Canonical compact form shared by all schemes: per group of Bf filters, the
+// ascending list of positions (kh*KW+kw)*C + c kept by any filter of the group,
+// and the group's weights at those positions.
+static void pack_canonical(npas_packed *p, const uint8_t *w, const uint8_t *m)
+{
+    const int F = p->F, C = p->C, KH = p->KH, KW = p->KW, Bf = p->Bf, esz = dtype_size(p->dtype);
+    p->G = (F + Bf - 1) / Bf;
+    p->grp_ptr.assign(p->G + 1, 0);
+    p->k_pos.clear();
+    p->w_compact.clear();
+    std::vector<uint8_t> row((size_t)Bf * esz);
+    for (int g = 0; g < p->G; ++g) {
+        p->grp_ptr[g] = (int32_t)p->k_pos.size();
+        int f0 = g * Bf, nf = std::min(Bf, F - f0);
+        for (int kh = 0; kh < KH; ++kh)
+            for (int kw = 0; kw < KW; ++kw)
+                for (int c = 0; c < C; ++c) {
+                    bool any = false;
+                    for (int j = 0; j < nf && !any; ++j) any = m[widx(f0 + j, c, kh, kw, C, KH, KW)] != 0;
+                    if (!any) continue;
+                    p->k_pos.push_back((kh * KW + kw) * C + c);
+                    for (int j = 0; j < Bf; ++j) {
+                        bool keep = j < nf && m[widx(f0 + j, c, kh, kw, C, KH, KW)];
+                        put_weight(&row[(size_t)j * esz], keep ? w + widx(f0 + j, c, kh, kw, C, KH, KW) * esz : nullptr,
+                                   esz, keep);
+                    }
+                    p->w_compact.insert(p->w_compact.end(), row.begin(), row.end());
+                }
+    }
+    p->grp_ptr[p->G] = (int32_t)p->k_pos.size();
+}
+
+// ---- device execution formats ------------------------------------------------
+
+static void build_mfma_gather(npas_packed *p, const uint8_t *m, const uint8_t *w)
+{
+    DeviceFormat &d = p->fmt;
+    const int F = p->F, C = p->C, KH = p->KH, KW = p->KW;
+    d.variant = V_MFMA_GATHER;
+    int cc = (KH == 1 && KW == 1) ? 256 : 64;
+    d.CC = std::min(C, cc);
+    d.nchunks = (C + d.CC - 1) / d.CC;
+    d.ntiles = (F + 15) / 16;
+    d.tc_ptr.assign((size_t)d.ntiles * d.nchunks + 1, 0);
+    d.kent.clear();
+    d.wfrag.clear();
+    d.max_list = 0;
+    const uint16_t *w16 = reinterpret_cast<const uint16_t *>(w);
+    std::vector<uint32_t> ent;
+    std::vector<size_t> base; // weight index of filter 16t at each entry
+    for (int t = 0; t < d.ntiles; ++t) {
+        int f0 = 16 * t, nf = std::min(16, F - f0);
+        for (int ch = 0; ch < d.nchunks; ++ch) {
+            int c0 = ch * d.CC, c1 = std::min(C, c0 + d.CC);
+            ent.clear();
+            base.clear();
+            for (int kh = 0; kh < KH; ++kh)
+                for (int kw = 0; kw < KW; ++kw)
+                    for (int c = c0; c < c1; ++c) {
+                        bool any = false;
+                        for (int j = 0; j < nf && !any; ++j) any = m[widx(f0 + j, c, kh, kw, C, KH, KW)] != 0;
+                        if (!any) continue;
+                        ent.push_back((uint32_t)kh << 24 | (uint32_t)kw << 16 | (uint32_t)(c - c0));
+                        base.push_back(widx(f0, c, kh, kw, C, KH, KW));
+                    }
+            size_t n = ent.size(), npad = (n + 31) / 32 * 32;
+            d.tc_ptr[(size_t)t * d.nchunks + ch] = (int32_t)d.kent.size();
+            d.max_list = std::max(d.max_list, (int)npad);
+            size_t e0 = d.kent.size();
+            d.kent.resize(e0 + npad, n ? ent[0] : 0u);
+            std::copy(ent.begin(), ent.end(), d.kent.begin() + e0);
+            size_t w0 = d.wfrag.size();
+            d.wfrag.resize(w0 + npad * 16, 0);
+            const size_t fstride = (size_t)C * KH * KW;
+            for (size_t e = 0; e < n; ++e) {
+                size_t blk = e / 32, k = e % 32, q = k / 8, i = k % 8;
+                for (int r = 0; r < nf; ++r) {
+                    size_t wi = base[e] + (size_t)r * fstride;
+                    if (m[wi]) d.wfrag[w0 + blk * 512 + (q * 16 + r) * 8 + i] = w16[wi];
+                }
+            }
+        }
+    }
+    d.tc_ptr.back() = (int32_t)d.kent.size();
+}
+
+static void build_valu_f32(npas_packed *p, const uint8_t *m, const uint8_t *w)
+{
+    (void)m;
+    DeviceFormat &d = p->fmt;
+    d.variant = V_VALU_F32;
+    const int Bf = p->Bf, C = p->C, KW = p->KW;
+    int vb = 1;
+    while (vb < Bf && vb < 8) vb *= 2;
+    d.VB = vb;
+    d.vg_ptr.clear();
+    d.vg_f0.clear();
+    d.vkent.clear();
+    d.vw.clear();
+    const float *wc = reinterpret_cast<const float *>(p->w_compact.data());
+    for (int g = 0; g < p->G; ++g) {
+        int k0 = p->grp_ptr[g], k1 = p->grp_ptr[g + 1];
+        int nf = std::min(Bf, p->F - g * Bf);
+        for (int j0 = 0; j0 < nf; j0 += vb) {
+            d.vg_ptr.push_back((int32_t)d.vkent.size());
+            d.vg_f0.push_back(g * Bf + j0);
+            for (int k = k0; k < k1; ++k) {
+                int pos = p->k_pos[k], tap = pos / C, c = pos % C;
+                d.vkent.push_back((uint32_t)(tap / KW) << 24 | (uint32_t)(tap % KW) << 16 | (uint32_t)c);
+                for (int j = 0; j < vb; ++j)
+                    d.vw.push_back(j0 + j < Bf ? wc[(size_t)k * Bf + j0 + j] : 0.0f);
+            }
+        }
+    }
+    d.vg_ptr.push_back((int32_t)d.vkent.size());
+    d.nvg = (int)d.vg_f0.size();
+    (void)w;
+}
+
+int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, const void *w_host)
+{
+    if (p->C > 65535 || p->KH > 255 || p->KW > 255) {
+        set_error("layer too large for the entry coding (C <= 65535, KH, KW <= 255)");
+        return NPAS_E_SHAPE;
+    }
+    if (p->dtype == NPAS_F32) build_valu_f32(p, mask_full.data(), (const uint8_t *)w_host);
+    else build_mfma_gather(p, mask_full.data(), (const uint8_t *)w_host);
+    return NPAS_OK;
+}
+
+template <typename T>
+static size_t place(std::vector<uint8_t> &blob, const std::vector<T> &v)
+{
+    size_t off = (blob.size() + 255) / 256 * 256;
+    blob.resize(off + v.size() * sizeof(T));
+    if (!v.empty()) memcpy(blob.data() + off, v.data(), v.size() * sizeof(T));
+    return off;
+}
+
+int upload(npas_packed *p)
+{
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        p->dev.device = -1; // host-only handle: export works, run calls fail loudly
+        return NPAS_OK;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return NPAS_OK;
+    const DeviceFormat &d = p->fmt;
+    std::vector<uint8_t> blob;
+    size_t o_tc = place(blob, d.tc_ptr), o_ke = place(blob, d.kent), o_wf = place(blob, d.wfrag);
+    size_t o_vp = place(blob, d.vg_ptr), o_vf = place(blob, d.vg_f0), o_vk = place(blob, d.vkent),
+           o_vw = place(blob, d.vw);
+    blob.resize((blob.size() + 255) / 256 * 256 + 256);
+    void *ptr = nullptr;
+    hipError_t e = hipMalloc(&ptr, blob.size());
+    if (e != hipSuccess) {
+        set_error("hipMalloc(%zu) failed: %s", blob.size(), hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    e = hipMemcpy(ptr, blob.data(), blob.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(ptr);
+        set_error("hipMemcpy to device failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    uint8_t *b = (uint8_t *)ptr;
+    p->dev.device = dev;
+    p->dev.blob = ptr;
+    p->dev.bytes = blob.size();
+    p->dev.tc_ptr = (const int32_t *)(b + o_tc);
+    p->dev.kent = (const uint32_t *)(b + o_ke);
+    p->dev.wfrag = b + o_wf;
+    p->dev.vg_ptr = (const int32_t *)(b + o_vp);
+    p->dev.vg_f0 = (const int32_t *)(b + o_vf);
+    p->dev.vkent = (const uint32_t *)(b + o_vk);
+    p->dev.vw = (const float *)(b + o_vw);
+    return NPAS_OK;
+}
+
+static int finish_pack(npas_packed *p, const std::vector<uint8_t> &mask, const void *w, npas_packed **out)
+{
+    int rc = build_device_format(p, mask, w);
+    if (rc == NPAS_OK) rc = upload(p);
+    if (rc != NPAS_OK) {
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return NPAS_OK;
+}
+
+static int check_common(const void *w, const uint8_t *m, npas_packed **out, int F, int C, int KH, int KW, int Bf,
+                        int Bc, int dt)
+{
+    if (!w || !m || !out) {
+        set_error("NULL argument (w_host=%p mask_host=%p out=%p)", w, (const void *)m, (void *)out);
+        return NPAS_E_NULL;
+    }
+    *out = nullptr;
+    if (F <= 0 || C <= 0 || KH <= 0 || KW <= 0 || Bf <= 0 || Bc <= 0) {
+        set_error("non-positive dimension (F=%d C=%d KH=%d KW=%d Bf=%d Bc=%d)", F, C, KH, KW, Bf, Bc);
+        return NPAS_E_SHAPE;
+    }
+    if ((double)F * C * KH * KW > 2.0e9) {
+        set_error("weight tensor too large (%d x %d x %d x %d)", F, C, KH, KW);
+        return NPAS_E_SHAPE;
+    }
+    if (dt != NPAS_F32 && dt != NPAS_BF16 && dt != NPAS_F16) {
+        set_error("unknown storage type %d", dt);
+        return NPAS_E_DTYPE;
+    }
+    return NPAS_OK;
+}
+
+} // namespace npas
+
+using namespace npas;
+
+extern "C" {
+
+const char *npas_last_error(void) { return npas::last_error(); }
+
+int npas_pack_block_punched(const void *w_host, const uint8_t *mask_host, int F, int C, int KH, int KW, int Bf,
+                            int Bc, npas_dtype dt, void *hip_stream, npas_packed **out)
+{
+    (void)hip_stream;
+    int rc = check_common(w_host, mask_host, out, F, C, KH, KW, Bf, Bc, dt);
+    if (rc) return rc;
+    size_t n = (size_t)F * C * KH * KW;
+    if ((rc = check_mask_values(mask_host, n))) return rc;
+    if ((rc = validate_block_punched(mask_host, F, C, KH, KW, Bf))) return rc;
+    npas_packed *p = new npas_packed;
+    p->scheme = NPAS_SCHEME_BLOCK_PUNCHED;
+    p->dtype = dt;
+    p->F = F; p->C = C; p->KH = KH; p->KW = KW; p->Bf = std::min(Bf, F); p->Bc = std::min(Bc, C);
+    pack_canonical(p, (const uint8_t *)w_host, mask_host);
+    std::vector<uint8_t> mask(mask_host, mask_host + n);
+    return finish_pack(p, mask, w_host, out);
+}
+
+int npas_pack_fc_block(const void *w_host, const uint8_t *mask_host, int OUT, int IN, int Br, int Bcol,
+                       npas_dtype dt, void *hip_stream, npas_packed **out)
+{
+    (void)hip_stream;
+    int rc = check_common(w_host, mask_host, out, OUT, IN, 1, 1, Br, Bcol, dt);
+    if (rc) return rc;
+    size_t n = (size_t)OUT * IN;
+    if ((rc = check_mask_values(mask_host, n))) return rc;
+    if ((rc = validate_fc_block(mask_host, OUT, IN, Br, Bcol))) return rc;
+    npas_packed *p = new npas_packed;
+    p->scheme = NPAS_SCHEME_FC_BLOCK;
+    p->dtype = dt;
+    p->F = OUT; p->C = IN; p->KH = 1; p->KW = 1; p->Bf = std::min(Br, OUT); p->Bc = std::min(Bcol, IN);
+    pack_canonical(p, (const uint8_t *)w_host, mask_host);
+    std::vector<uint8_t> mask(mask_host, mask_host + n);
+    return finish_pack(p, mask, w_host, out);
+}
+
+int npas_pack_pattern(const void *w_host, const uint8_t *mask_host, int F, int C, const uint8_t *library_host,
+                      int n_pat, npas_dtype dt, void *hip_stream, npas_packed **out)
+{
+    (void)hip_stream;
+    int rc = check_common(w_host, mask_host, out, F, C, 3, 3, 1, 1, dt);
+    if (rc) return rc;
+    if (!library_host) {
+        set_error("NULL pattern library");
+        return NPAS_E_NULL;
+    }
+    if (n_pat <= 0 || n_pat > 254) {
+        set_error("n_pat = %d outside 1..254", n_pat);
+        return NPAS_E_SHAPE;
+    }
+    size_t n = (size_t)F * C * 9;
+    if ((rc = check_mask_values(mask_host, n))) return rc;
+    if ((rc = check_mask_values(library_host, (size_t)n_pat * 9))) return rc;
+    const int esz = dtype_size(dt);
+    npas_packed *p = new npas_packed;
+    p->scheme = NPAS_SCHEME_PATTERN;
+    p->dtype = dt;
+    p->F = F; p->C = C; p->KH = 3; p->KW = 3; p->Bf = 1; p->Bc = 1;
+    p->n_pat = n_pat;
+    p->library.assign(library_host, library_host + (size_t)n_pat * 9);
+    p->pat_id.assign((size_t)F * C, 255);
+    p->w4.assign((size_t)F * C * 4 * esz, 0);
+    const uint8_t *w = (const uint8_t *)w_host;
+    for (size_t k = 0; k < (size_t)F * C; ++k) {
+        const uint8_t *mk = mask_host + k * 9;
+        int nz = 0;
+        for (int t = 0; t < 9; ++t) nz += mk[t];
+        if (nz == 0) continue; // removed kernel (connectivity pruning)
+        int id = -1;
+        for (int q = 0; q < n_pat && id < 0; ++q)
+            if (memcmp(mk, library_host + (size_t)q * 9, 9) == 0) id = q;
+        if (id < 0) {
+            set_error("kernel (f=%zu, c=%zu) keeps %d taps that match no library pattern", k / C, k % C, nz);
+            delete p;
+            return NPAS_E_MASK_NOT_IN_LIBRARY;
+        }
+        p->pat_id[k] = (uint8_t)id;
+        int j = 0;
+        for (int t = 0; t < 9 && j < 4; ++t)
+            if (mk[t]) memcpy(&p->w4[(k * 4 + j++) * esz], w + (k * 9 + t) * esz, esz);
+    }
+    pack_canonical(p, w, mask_host);
+    std::vector<uint8_t> mask(mask_host, mask_host + n);
+    return finish_pack(p, mask, w_host, out);
+}
+
+int npas_packed_info(const npas_packed *p, int64_t info[16])
+{
+    if (!p || !info) {
+        set_error("NULL argument");
+        return NPAS_E_NULL;
+    }
+    const DeviceFormat &d = p->fmt;
+    size_t dev_bytes = d.tc_ptr.size() * 4 + d.kent.size() * 4 + d.wfrag.size() * 2 + d.vg_ptr.size() * 4 +
+                       d.vg_f0.size() * 4 + d.vkent.size() * 4 + d.vw.size() * 4;
+    int64_t v[16] = {p->scheme, p->dtype, p->F, p->C, p->KH, p->KW, p->Bf, p->Bc, p->G,
+                     (int64_t)p->k_pos.size(), p->n_pat, p->dev.device >= 0, d.variant,
+                     (int64_t)dev_bytes, (int64_t)p->w_compact.size(), 0};
+    memcpy(info, v, sizeof(v));
+    return NPAS_OK;
+}
+
+int npas_packed_export(const npas_packed *p, int32_t *grp_ptr, int32_t *k_pos, void *w_compact, uint8_t *pat_id,
+                       void *w4)
+{
+    if (!p) {
+        set_error("NULL handle");
+        return NPAS_E_NULL;
+    }
+    if (grp_ptr) memcpy(grp_ptr, p->grp_ptr.data(), p->grp_ptr.size() * sizeof(int32_t));
+    if (k_pos && !p->k_pos.empty()) memcpy(k_pos, p->k_pos.data(), p->k_pos.size() * sizeof(int32_t));
+    if (w_compact && !p->w_compact.empty()) memcpy(w_compact, p->w_compact.data(), p->w_compact.size());
+    if (pat_id || w4) {
+        if (p->scheme != NPAS_SCHEME_PATTERN) {
+            set_error("pat_id / w4 requested from a layer that is not pattern-pruned");
+            return NPAS_E_SHAPE;
+        }
+        if (pat_id) memcpy(pat_id, p->pat_id.data(), p->pat_id.size());
+        if (w4) memcpy(w4, p->w4.data(), p->w4.size());
+    }
+    return NPAS_OK;
+}
+
+void npas_free(npas_packed *p)
+{
+    if (!p) return;
+    if (p->dev.blob) (void)hipFree(p->dev.blob);
+    delete p;
+}
+
+} // extern "C"

@@ -1,0 +1,148 @@
+"""CPU-side tests of the HIP library: it loads, exports what include/npas.h
+declares, packs (host logic) bit-identically to the oracle's packer, rejects
+illegal masks, and fails loudly instead of computing without a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2012_00596_amd as npas
+from tests import helpers
+from workloads import configs, dtypes, masks, prng
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "npas.h")).read()
+    declared = set(re.findall(r"\b(npas_[a-z0-9_]+)\s*\(", header))
+    declared -= {"npas_packed", "npas_stack"}
+    assert declared == set(npas.binding.EXPORTS)
+    L = npas.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("builder,kw", [
+    (configs.config1, {}),
+    (configs.config2, dict(batch=1, HW=4)),
+    (configs.config3, dict(batch=2)),
+    (configs.config4, dict(batch=1, HW=4)),
+    (configs.config5, dict(batch=1, HW=32, width=16, blocks=(1, 1, 1, 1))),
+])
+def test_packing_metadata_bit_exact_vs_oracle(builder, kw):
+    w = builder(**kw)
+    for L in w.layers:
+        if L.kind not in ("conv", "fc"):
+            continue
+        p = helpers.pack_layer(npas, L, w.dtype)
+        helpers.check_metadata(oracle, L, p, w.dtype)
+        info = p.info()
+        assert info["F"] == L.F and info["C"] == L.C and info["dtype"] == w.dtype
+
+
+@pytest.mark.parametrize("dtype", [dtypes.F32, dtypes.BF16, dtypes.F16])
+@pytest.mark.parametrize("F,C,k,Bf,Bc,rate", [(10, 7, 3, 4, 4, 2), (5, 3, 7, 8, 4, 5), (16, 16, 1, 1, 1, 3),
+                                               (12, 8, 3, 12, 8, 2), (9, 40, 1, 16, 32, 5)])
+def test_packing_edge_blocks_and_degenerate_sizes(dtype, F, C, k, Bf, Bc, rate):
+    m = masks.block_punched_mask(F, C, k, k, Bf, Bc, rate, 31)
+    store, exact = dtypes.quantize(prng.normal(5, 3, F * C * k * k).reshape(F, C, k, k), dtype)
+    p = npas.pack_block_punched(store, m, Bf, Bc, dtype)
+    L = configs.Layer("conv", "block_punched", C, F, k, k, 1, 0, Bf, Bc, rate, w_store=store, w_exact=exact, mask=m)
+    helpers.check_metadata(oracle, L, p, dtype)
+    # garbage under the mask must not leak into the compact form
+    junk = store.copy()
+    junk[m == 0] = 0x7FC0 if dtype != dtypes.F32 else np.nan
+    e1, e2 = p.export(), npas.pack_block_punched(junk, m, Bf, Bc, dtype).export()
+    for key in e1:
+        np.testing.assert_array_equal(e1[key].view(np.uint8), e2[key].view(np.uint8))
+
+
+def test_fc_rows_and_columns():
+    OUT, IN = 40, 70
+    m = masks.fc_block_mask(OUT, IN, 16, 32, 4, 9)
+    m[3, :32] = 0            # a pruned row inside a block
+    store, exact = dtypes.quantize(prng.normal(6, 3, OUT * IN).reshape(OUT, IN), dtypes.BF16)
+    p = npas.pack_fc_block(store, m, 16, 32, dtypes.BF16)
+    L = configs.Layer("fc", "fc_block", IN, OUT, 1, 1, 1, 0, 16, 32, 4, w_store=store.reshape(OUT, IN, 1, 1),
+                      w_exact=exact.reshape(OUT, IN, 1, 1), mask=m.reshape(OUT, IN, 1, 1))
+    helpers.check_metadata(oracle, L, p, dtypes.BF16)
+
+
+def test_illegal_masks_are_rejected_not_repaired():
+    F, C = 8, 8
+    w = np.zeros((F, C, 3, 3), dtype=np.float32)
+    m = masks.block_punched_mask(F, C, 3, 3, 4, 4, 2, 16)
+    bad = m.copy()
+    bad[1, 2, 1, 1] ^= 1
+    with pytest.raises(npas.NpasError) as e:
+        npas.pack_block_punched(w, bad, 4, 4, dtypes.F32)
+    assert e.value.code == npas.E_MASK_NOT_BLOCK_UNIFORM and "filter 1" in str(e.value)
+    bad = m.copy()
+    bad[0, 0, 0, 0] = 3
+    with pytest.raises(npas.NpasError) as e:
+        npas.pack_block_punched(w, bad, 4, 4, dtypes.F32)
+    assert e.value.code == npas.E_MASK_VALUE
+    mf = masks.fc_block_mask(32, 64, 16, 32, 4, 17)
+    hole = mf.copy()
+    hole[5, int(np.flatnonzero(mf[5])[0])] = 0
+    with pytest.raises(npas.NpasError) as e:
+        npas.pack_fc_block(np.zeros((32, 64), np.float32), hole, 16, 32, dtypes.F32)
+    assert e.value.code == npas.E_MASK_NOT_BLOCK_UNIFORM
+    lib = masks.pattern_library(8, 5)
+    mp, _ = masks.pattern_mask(6, 6, lib, 0.3, 18)
+    badp = mp.copy()
+    k = np.argwhere(mp.reshape(36, 9).sum(1) == 4)[0, 0]
+    badp.reshape(36, 9)[k, 4] = 0
+    with pytest.raises(npas.NpasError) as e:
+        npas.pack_pattern(np.zeros((6, 6, 3, 3), np.float32), badp, lib, dtypes.F32)
+    assert e.value.code == npas.E_MASK_NOT_IN_LIBRARY
+    with pytest.raises(npas.NpasError) as e:
+        npas.pack_block_punched(w, m, 4, 4, 7)
+    assert e.value.code == npas.E_DTYPE
+    with pytest.raises(npas.NpasError) as e:
+        npas.pack_block_punched(w, m, 0, 4, dtypes.F32)
+    assert e.value.code == npas.E_SHAPE
+    h = ctypes.c_void_p()
+    assert npas.lib().npas_pack_block_punched(None, None, 1, 1, 1, 1, 1, 1, 0, None, ctypes.byref(h)) == npas.E_NULL
+
+
+def test_run_calls_validate_arguments_before_touching_the_gpu():
+    w = np.ones((4, 4, 3, 3), dtype=np.float32)
+    p = npas.pack_block_punched(w, np.ones_like(w, dtype=np.uint8), 2, 2, dtypes.F32)
+    L = npas.lib()
+    assert L.npas_conv2d_sparse(p.handle, None, None, 1, 4, 4, 1, 1, None, None, 0, None) == npas.E_NULL
+    assert L.npas_conv2d_sparse(p.handle, 256, 256, 0, 4, 4, 1, 1, None, None, 0, None) == npas.E_SHAPE
+    assert L.npas_conv2d_sparse(p.handle, 256, 256, 1, 1, 1, 1, 0, None, None, 0, None) == npas.E_SHAPE   # empty output
+    assert L.npas_fc_sparse(p.handle, 256, 256, 1, None, 0, None) == npas.E_SHAPE                          # 3x3 is no FC
+    assert L.npas_maxpool3x3s2(None, None, 1, 4, 4, 4, 0, None) == npas.E_NULL
+    assert L.npas_global_avgpool(256, 256, 1, 4, 4, 4, 9, None) == npas.E_DTYPE
+    if not p.info()["device_ready"]:
+        # no GPU here: the product path must fail loudly, never compute on the CPU
+        assert L.npas_conv2d_sparse(p.handle, 256, 256, 1, 4, 4, 1, 1, None, None, 0, None) == npas.E_HIP
+        assert "no device copy" in npas.last_error()
+
+
+def test_stack_wiring_checks_and_workspace():
+    w = configs.config5(batch=1, HW=32, width=16, blocks=(1, 1, 1, 1))
+    packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None for L in w.layers]
+    descs = helpers.stack_descs(npas, w.layers, packed)
+    st = npas.Stack(descs, 32, 32)
+    assert st.num_launches() <= len(w.layers)
+    ws1, ws4 = st.workspace_bytes(1), st.workspace_bytes(4)
+    assert 0 < ws1 and ws1 % 256 == 0 and 3 * ws1 < ws4 <= 4 * ws1 + 256 * len(descs)
+    # the workspace must at least hold the largest layer's live set: stem output + pooled output
+    assert ws1 >= (16 * 16 * 16 + 8 * 8 * 16) * 2
+    bad = [dict(d) for d in descs]
+    bad[3]["src"] = 7                        # reads a tensor that does not exist yet
+    with pytest.raises(npas.NpasError) as e:
+        npas.Stack(bad, 32, 32)
+    assert e.value.code == npas.E_SHAPE
+    bad = [dict(d) for d in descs]
+    bad[2]["res"] = 1                        # residual of the wrong shape
+    with pytest.raises(npas.NpasError):
+        npas.Stack(bad, 32, 32)
+    assert npas.lib().npas_run_stack(st.handle, 256, 256, 1, None, 0, None) == npas.E_WORKSPACE
