@@ -1,0 +1,146 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-inference hot path on one MI355X.
+
+One step = one pass of the block-punched 1x1 stack 24 -> 144 -> 24 (ReLU6 between,
+8x8 blocks, 4x pruning, batch 64, 56x56, bf16) through npas_run_stack, inputs
+already resident in HBM.  Prints one JSON line: dense-equivalent TFLOP/s, the
+HBM roofline of the dominant kernel (timed with events on the launch stream) and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--no-fuse", action="store_true", help="run the two layers as two kernels")
+    ap.add_argument("--no-rotate", action="store_true", help="reuse one buffer set (stays in the 256 MB Infinity Cache)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2012_00596_amd as npas
+    from tests import helpers
+    from workloads import configs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = configs.config2(batch=args.batch)
+    N, H, W, C = w.x_shape
+    npx = N * H * W
+    packed = [helpers.pack_layer(npas, L, w.dtype) for L in w.layers]
+    flags = 0 if args.no_fuse else npas.STACK_FUSE_POINTWISE
+    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W, flags)
+    wsb = st.workspace_bytes(N)
+    launches = st.num_launches()
+
+    F1, F2 = w.layers[0].F, w.layers[1].F
+    x_bytes, mid_bytes, y_bytes = npx * C * 2, npx * F1 * 2, npx * F2 * 2
+    meta_bytes = sum(p.info()["device_bytes"] for p in packed)
+    set_bytes = x_bytes + y_bytes + wsb
+    nsets = 1 if args.no_rotate else max(2, -(-640 * 2**20 // set_bytes))
+    xs = [helpers.to_dev(w.x_store, torch) for _ in range(nsets)]
+    ys = [helpers.new_dev((N, H, W, F2), w.dtype, torch, fill=0) for _ in range(nsets)]
+    wss = [torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(i):
+        k = i % nsets
+        st.run(xs[k], ys[k], N, wss[k], wsb, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+
+    # per-step device time with events on the launch stream (excludes host launch gaps only if the
+    # queue stays full; reported next to the wall-clock figure)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(args.steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    dev_ms = e0.elapsed_time(e1) / args.steps
+
+    dense_flop = 2.0 * w.dense_macs()
+    # dominant kernel: fused -> the only kernel (reads x, writes y); per-layer -> either layer moves
+    # x/mid (read) + mid/y (write) = 67.4 MB, the slower one is timed
+    if launches == 1:
+        alg_bytes = x_bytes + y_bytes + meta_bytes
+        kern_ms = dev_ms
+        kname = "pointwise_pair_fused"
+    else:
+        alg_bytes = x_bytes + mid_bytes + packed[0].info()["device_bytes"]
+        mids = [helpers.new_dev((N, H, W, F1), w.dtype, torch, fill=0) for _ in range(nsets)]
+        per = []
+        for li, L in enumerate(w.layers):
+            e0.record()
+            for i in range(args.steps):
+                k = i % nsets
+                if li == 0:
+                    npas.conv2d_sparse(packed[0], xs[k], mids[k], N, H, W, 1, 0, None, None, L.act, stream)
+                else:
+                    npas.conv2d_sparse(packed[1], mids[k], ys[k], N, H, W, 1, 0, None, None, L.act, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            per.append(e0.elapsed_time(e1) / args.steps)
+        kern_ms = max(per)
+        kname = "conv_gather_mfma(layer %d of 2)" % (per.index(kern_ms) + 1)
+    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "dense-equivalent TFLOP/s and per-layer us for block-punched sparse conv at 1 GPU",
+        "value": dense_flop / dt / 1e12,
+        "unit": "TFLOP/s (dense-equivalent)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3,
+        "device_ms_per_step": dev_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: 1x1 stack 24->144->24, batch %d, 56x56, bf16 NHWC, 8x8 blocks, 4x pruning, ReLU6"
+                               % N, "launches_per_step": launches, "buffer_sets": nsets,
+                   "dense_equiv_gflop_per_step": dense_flop / 1e9},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kname,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_ms},
+    }
+
+    if not args.no_cpu:
+        import oracle
+        sample_px = 2 * H * W                      # two images' worth of pixels
+        xsub = w.x_exact.reshape(npx, C)[:sample_px].reshape(1, 1, sample_px, C)
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            oracle.run_stack(xsub, w.layers, w.dtype)
+            reps += 1
+        cdt = (time.perf_counter() - t0) / reps
+        out["cpu_baseline"] = {"value": dense_flop * (sample_px / npx) / cdt / 1e12,
+                               "unit": "TFLOP/s (dense-equivalent)", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "%d of %d pixels of the same stack, %d repetitions" % (sample_px, npx, reps)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -40,7 +40,8 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
     g.koff_cap = std::min(512, std::max(32, d.max_list));
     const size_t koff_bytes = (size_t)4 * g.koff_cap * 4;
 
-    double best = -1.0;
+    double best = -1e30;
+    bool found = false;
     for (int TW = 1; TW <= std::min(g.Wo, 128); ++TW)
         for (int TH = 1; TH <= std::min(g.Ho, 128 / TW); ++TH) {
             int PH = pointwise ? TH : (TH - 1) * stride + p->KH;
@@ -54,10 +55,11 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
             double score = cover - 0.05 * halo + 0.1 * (used_cols / 128.0);
             if (score > best) {
                 best = score;
+                found = true;
                 g.TH = TH; g.TW = TW; g.PH = PH; g.PW = PW;
             }
         }
-    if (best < 0) {
+    if (!found) {
         set_error("no output tile fits in LDS (kernel %dx%d stride %d)", p->KH, p->KW, stride);
         return NPAS_E_SHAPE;
     }

@@ -290,9 +290,12 @@ __global__ __launch_bounds__(256) void conv_valu_f32_kernel(ConvValuArgs a)
     const uint32_t ox = pix % (uint32_t)a.Wo, t = pix / (uint32_t)a.Wo;
     const uint32_t oy = t % (uint32_t)a.Ho, n = t / (uint32_t)a.Ho;
     const int f0 = a.vg_f0[vg];
-    float acc[VB];
+    // fp32 storage, fp64 accumulation: products of two fp32 values are exact in fp64,
+    // so the only rounding of note is the final one to fp32 (keeps small outputs of
+    // cancelling sums within 1e-5 of the exact result).
+    double acc[VB];
 #pragma unroll
-    for (int j = 0; j < VB; ++j) acc[j] = (a.bias && f0 + j < a.F) ? a.bias[f0 + j] : 0.0f;
+    for (int j = 0; j < VB; ++j) acc[j] = (a.bias && f0 + j < a.F) ? (double)a.bias[f0 + j] : 0.0;
     const int k0 = a.vg_ptr[vg], k1 = a.vg_ptr[vg + 1];
     const int by = (int)oy * a.stride - a.pad, bx = (int)ox * a.stride - a.pad;
     const float *xn = a.x + (size_t)n * a.H * a.W * a.C;
@@ -303,15 +306,15 @@ __global__ __launch_bounds__(256) void conv_valu_f32_kernel(ConvValuArgs a)
         if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) xv = xn[(size_t)(iy * a.W + ix) * a.C + (ent & 0xffffu)];
         const float *w = a.vw + (size_t)k * VB;
 #pragma unroll
-        for (int j = 0; j < VB; ++j) acc[j] = fmaf(w[j], xv, acc[j]);
+        for (int j = 0; j < VB; ++j) acc[j] = fma((double)w[j], (double)xv, acc[j]);
     }
     const size_t o = (size_t)pix * a.F + f0;
 #pragma unroll
     for (int j = 0; j < VB; ++j)
         if (f0 + j < a.F) {
-            float v = acc[j];
-            if (a.residual) v += a.residual[o + j];
-            a.y[o + j] = act_apply(v, a.act);
+            double v = acc[j];
+            if (a.residual) v += (double)a.residual[o + j];
+            a.y[o + j] = act_apply((float)v, a.act);
         }
 }
 
@@ -381,9 +384,9 @@ __global__ __launch_bounds__(256) void global_avgpool_kernel(const void *x, void
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= N * C) return;
     const int n = i / C, c = i % C;
-    float s = 0.0f;
-    for (int p = 0; p < HW; ++p) s += ld_act<DT>(x, ((size_t)n * HW + p) * C + c);
-    st_act<DT>(y, (size_t)i, s / (float)HW);
+    double s = 0.0; // fp64 sum: the mean of an fp32 map stays within 1e-5 of the exact one
+    for (int p = 0; p < HW; ++p) s += (double)ld_act<DT>(x, ((size_t)n * HW + p) * C + c);
+    st_act<DT>(y, (size_t)i, (float)(s / (double)HW));
 }
 
 int launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream)

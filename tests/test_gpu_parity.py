@@ -1,0 +1,236 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Packing metadata must be bit-exact; outputs
+within max relative error 1e-2 (bf16) / 1e-5 (fp32), each layer fed the oracle's
+rounded input (teacher forcing), stacks additionally end to end."""
+import numpy as np
+import pytest
+
+import oracle
+from tests import helpers
+from tests.helpers import TOL, from_dev, new_dev, pack_layer, rel_err, run_layer_gpu, to_dev
+from workloads import configs, dtypes, masks, prng
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "GPU tests need a GPU"
+    return t
+
+
+def layerwise(npas, torch, w, check_meta=True):
+    """Teacher-forced layer-by-layer comparison of a workload; returns worst error."""
+    rounded, raw = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+    shapes = {0: w.x_shape}
+    worst = 0.0
+    for i, L in enumerate(w.layers):
+        in_shape = shapes[L.src]
+        shapes[i + 1] = helpers.out_shape(L, in_shape)
+        packed = pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None
+        if packed is not None and check_meta:
+            helpers.check_metadata(oracle, L, packed, w.dtype)
+            assert packed.info()["device_ready"] == 1
+        xs, _ = dtypes.quantize(rounded[L.src], w.dtype)
+        x_dev = to_dev(xs, torch)
+        res_dev = None
+        if L.res >= 0:
+            rs, _ = dtypes.quantize(rounded[L.res], w.dtype)
+            res_dev = to_dev(rs, torch)
+        y = run_layer_gpu(npas, torch, L, packed, x_dev, in_shape, w.dtype, res_dev)
+        got = from_dev(y, w.dtype).reshape(shapes[i + 1])
+        err = rel_err(got, rounded[i + 1].reshape(shapes[i + 1]))
+        print(f"  layer {i:2d} {L.name or L.kind:12s} in={in_shape} out={shapes[i + 1]} err={err:.3e}", flush=True)
+        assert err <= TOL[w.dtype], (i, L.name, err)
+        worst = max(worst, err)
+    return worst
+
+
+def test_config1_conv3x3_fp32(npas, torch):
+    print("config1 fp32 3x3", flush=True)
+    layerwise(npas, torch, configs.config1())
+
+
+def test_config2_pointwise_stack_small(npas, torch):
+    print("config2 small batch", flush=True)
+    layerwise(npas, torch, configs.config2(batch=2, HW=23))        # 1058 pixels: several tiles + ragged tail
+
+
+def test_config3_fc_block_full(npas, torch):
+    print("config3 full", flush=True)
+    layerwise(npas, torch, configs.config3())
+
+
+def test_config4_pattern_small(npas, torch):
+    print("config4 small", flush=True)
+    layerwise(npas, torch, configs.config4(batch=2, HW=28))
+
+
+def test_config5_residual_stack_reduced(npas, torch):
+    print("config5 reduced (64x64 input, width 16)", flush=True)
+    layerwise(npas, torch, configs.config5(batch=2, HW=64, width=16))
+
+
+def test_config5_full_size_batch1_layerwise(npas, torch):
+    print("config5 full size, batch 1", flush=True)
+    layerwise(npas, torch, configs.config5(batch=1), check_meta=False)
+
+
+EDGE = [
+    # name, N, H, W, C, F, KH, KW, stride, pad, Bf, Bc, rate, dtype, act, use_res, use_bias
+    ("ragged_F_and_tail", 3, 9, 11, 16, 40, 3, 3, 1, 1, 8, 4, 3, dtypes.BF16, 1, True, True),
+    ("stem_like_C3_7x7s2", 2, 29, 31, 3, 24, 7, 7, 2, 3, 8, 4, 2, dtypes.BF16, 1, False, True),
+    ("stride2_3x3_two_chunks", 2, 15, 14, 128, 72, 3, 3, 2, 1, 8, 4, 3, dtypes.BF16, 0, False, False),
+    ("pointwise_stride2", 2, 15, 14, 320, 72, 1, 1, 2, 0, 8, 4, 5, dtypes.BF16, 2, False, False),
+    ("unstructured_1x1_blocks", 1, 8, 8, 16, 16, 3, 3, 1, 1, 1, 1, 3, dtypes.BF16, 0, False, False),
+    ("coarse_whole_tensor_block", 1, 8, 8, 16, 32, 3, 3, 1, 1, 32, 16, 2, dtypes.BF16, 0, False, False),
+    ("rate1_dense", 1, 6, 7, 8, 16, 3, 3, 1, 1, 8, 4, 1, dtypes.BF16, 0, False, False),
+    ("one_pixel_input", 1, 1, 1, 64, 48, 1, 1, 1, 0, 8, 4, 2, dtypes.BF16, 0, False, False),
+    ("fp16_storage", 2, 10, 10, 32, 32, 3, 3, 1, 1, 8, 4, 2, dtypes.F16, 1, True, False),
+    ("fp32_stride2_res_bias", 2, 9, 9, 8, 12, 3, 3, 2, 1, 4, 4, 2, dtypes.F32, 2, True, True),
+    ("fp32_wide_group", 1, 5, 5, 8, 24, 1, 1, 1, 0, 24, 8, 2, dtypes.F32, 0, False, False),
+    ("large_C_many_chunks", 1, 7, 7, 600, 130, 1, 1, 1, 0, 8, 4, 2, dtypes.BF16, 1, True, False),
+    ("kernel_5x3", 1, 30, 30, 8, 16, 5, 3, 1, 2, 4, 4, 2, dtypes.BF16, 0, False, False),
+]
+
+
+@pytest.mark.parametrize("case", EDGE, ids=[c[0] for c in EDGE])
+def test_edge_cases(npas, torch, case):
+    name, N, H, W, C, F, KH, KW, stride, pad, Bf, Bc, rate, dtype, act, use_res, use_bias = case
+    print(f"edge {name}", flush=True)
+    xs, xe = dtypes.quantize(prng.normal(7, 1, N * H * W * C).reshape(N, H, W, C), dtype)
+    ws, we = dtypes.quantize(prng.normal(7, 2, F * C * KH * KW, 0.2).reshape(F, C, KH, KW), dtype)
+    m = masks.block_punched_mask(F, C, KH, KW, Bf, Bc, rate, 99)
+    L = configs.Layer("conv", "block_punched", C, F, KH, KW, stride, pad, Bf, Bc, rate, act, w_store=ws, w_exact=we, mask=m)
+    oshape = helpers.out_shape(L, (N, H, W, C))
+    bias = prng.normal(7, 3, F).astype(np.float32) if use_bias else None
+    rs = re = None
+    if use_res:
+        rs, re = dtypes.quantize(prng.normal(7, 4, int(np.prod(oshape))).reshape(oshape), dtype)
+    ref = oracle.round_to(oracle.conv2d_masked(xe, we, m, stride, pad, None if bias is None else bias.astype(np.float64),
+                                               re, act), dtype)
+    p = pack_layer(npas, L, dtype)
+    helpers.check_metadata(oracle, L, p, dtype)
+    y = run_layer_gpu(npas, torch, L, p, to_dev(xs, torch), (N, H, W, C), dtype,
+                      None if rs is None else to_dev(rs, torch), None if bias is None else to_dev(bias, torch))
+    got = from_dev(y, dtype).reshape(oshape)
+    err = rel_err(got, ref)
+    print(f"  err={err:.3e}", flush=True)
+    assert err <= TOL[dtype]
+    # run-to-run determinism: no atomics, one writer per element
+    y2 = run_layer_gpu(npas, torch, L, p, to_dev(xs, torch), (N, H, W, C), dtype,
+                       None if rs is None else to_dev(rs, torch), None if bias is None else to_dev(bias, torch))
+    assert torch.equal(y, y2)
+
+
+def test_group_with_everything_pruned_gives_bias_only(npas, torch):
+    F, C = 32, 16
+    m = masks.block_punched_mask(F, C, 3, 3, 8, 4, 2, 5)
+    m[8:16] = 0                                  # filter group 1 keeps nothing
+    ws, we = dtypes.quantize(prng.normal(8, 2, F * C * 9, 0.2).reshape(F, C, 3, 3), dtypes.BF16)
+    xs, xe = dtypes.quantize(prng.normal(8, 1, 6 * 6 * C).reshape(1, 6, 6, C), dtypes.BF16)
+    bias = prng.normal(8, 3, F).astype(np.float32)
+    L = configs.Layer("conv", "block_punched", C, F, 3, 3, 1, 1, 8, 4, 2, 0, w_store=ws, w_exact=we, mask=m)
+    p = pack_layer(npas, L, dtypes.BF16)
+    y = from_dev(run_layer_gpu(npas, torch, L, p, to_dev(xs, torch), (1, 6, 6, C), dtypes.BF16, None, to_dev(bias, torch)),
+                 dtypes.BF16).reshape(1, 6, 6, F)
+    ref = oracle.round_to(oracle.conv2d_masked(xe, we, m, 1, 1, bias.astype(np.float64)), dtypes.BF16)
+    np.testing.assert_array_equal(y[..., 8:16], ref[..., 8:16])
+    assert rel_err(y, ref) <= 1e-2
+
+
+def test_garbage_under_the_mask_changes_nothing(npas, torch):
+    w = configs.config2(batch=1, HW=9)
+    L = w.layers[0]
+    junk = L.w_store.copy()
+    junk[L.mask == 0] = 0x7F80                    # +inf bit pattern where pruned
+    p1 = npas.pack_block_punched(L.w_store, L.mask, L.Bf, L.Bc, w.dtype)
+    p2 = npas.pack_block_punched(junk, L.mask, L.Bf, L.Bc, w.dtype)
+    x = to_dev(w.x_store, torch)
+    y1 = run_layer_gpu(npas, torch, L, p1, x, w.x_shape, w.dtype)
+    y2 = run_layer_gpu(npas, torch, L, p2, x, w.x_shape, w.dtype)
+    assert torch.equal(y1, y2)
+
+
+def _run_stack_gpu(npas, torch, w, flags=0):
+    packed = [pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None for L in w.layers]
+    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), w.x_shape[1], w.x_shape[2], flags)
+    N = w.x_shape[0]
+    shape = w.x_shape
+    shapes = {0: shape}
+    for i, L in enumerate(w.layers):
+        shapes[i + 1] = helpers.out_shape(L, shapes[L.src])
+    wsb = st.workspace_bytes(N)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    y = new_dev(shapes[len(w.layers)], w.dtype, torch, fill=(float("nan") if w.dtype == dtypes.F32 else 0x7FC1))
+    st.run(to_dev(w.x_store, torch), y, N, ws, wsb)
+    torch.cuda.synchronize()
+    return from_dev(y, w.dtype).reshape(shapes[len(w.layers)]), st
+
+
+@pytest.mark.parametrize("flags", [0, 1], ids=["per_layer", "fused_pointwise"])
+def test_config2_run_stack_end_to_end(npas, torch, flags):
+    print(f"config2 run_stack flags={flags}", flush=True)
+    w = configs.config2(batch=2, HW=23)
+    got, st = _run_stack_gpu(npas, torch, w, flags)
+    rounded, _ = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+    err = rel_err(got, rounded[-1])
+    print(f"  launches={st.num_launches()} err={err:.3e}", flush=True)
+    assert err <= 1e-2
+
+
+def test_config5_run_stack_end_to_end(npas, torch):
+    print("config5 reduced run_stack", flush=True)
+    w = configs.config5(batch=2, HW=64, width=16)
+    got, st = _run_stack_gpu(npas, torch, w)
+    rounded, _ = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+    ref = rounded[-1]
+    norm_err = np.abs(got - ref).max() / np.abs(ref).max()
+    print(f"  launches={st.num_launches()} norm-wise err={norm_err:.3e} elementwise={rel_err(got, ref):.3e}", flush=True)
+    # 50+ bf16 layers: element-wise 1e-2 cannot hold end to end (roundings compound), the norm-wise bound must
+    assert norm_err <= 1e-2 * np.sqrt(len(w.layers))
+    assert (got.argmax(1) == ref.argmax(1)).all()
+
+
+def test_full_size_config2_sampled(npas, torch):
+    """Bench configuration (batch 64, 56x56): sampled pixels against the oracle."""
+    print("config2 full size, sampled", flush=True)
+    w = configs.config2()
+    got, _ = _run_stack_gpu(npas, torch, w)
+    N, H, W, C = w.x_shape
+    npx = N * H * W
+    idx = (prng.u64(3, 3, 4096) % np.uint64(npx)).astype(np.int64)
+    idx[:8] = [0, 1, npx - 1, npx - 2, 127, 128, 129, npx // 2]
+    xsub = w.x_exact.reshape(npx, C)[idx].reshape(1, 1, -1, C)
+    rounded, _ = oracle.run_stack(xsub, w.layers, w.dtype)
+    err = rel_err(got.reshape(npx, -1)[idx], rounded[-1].reshape(len(idx), -1))
+    print(f"  err={err:.3e}", flush=True)
+    assert err <= 1e-2
+
+
+def test_full_size_config4_sampled_images(npas, torch):
+    print("config4 full size, images 0/17/31", flush=True)
+    w = configs.config4()
+    L = w.layers[0]
+    p = pack_layer(npas, L, w.dtype)
+    helpers.check_metadata(oracle, L, p, w.dtype)
+    y = from_dev(run_layer_gpu(npas, torch, L, p, to_dev(w.x_store, torch), w.x_shape, w.dtype), w.dtype)
+    y = y.reshape(helpers.out_shape(L, w.x_shape))
+    for n in (0, 17, 31):
+        ref = oracle.round_to(oracle.conv2d_masked(w.x_exact[n:n + 1], L.w_exact, L.mask, 1, 1), w.dtype)
+        err = rel_err(y[n:n + 1], ref)
+        print(f"  image {n} err={err:.3e}", flush=True)
+        assert err <= 1e-2
+
+
+def test_pools(npas, torch):
+    for dtype in (dtypes.BF16, dtypes.F32):
+        xs, xe = dtypes.quantize(prng.normal(9, 1, 2 * 9 * 11 * 24).reshape(2, 9, 11, 24), dtype)
+        x = to_dev(xs, torch)
+        y = new_dev((2, 5, 6, 24), dtype, torch)
+        npas.maxpool3x3s2(x, y, 2, 9, 11, 24, dtype)
+        np.testing.assert_array_equal(from_dev(y, dtype).reshape(2, 5, 6, 24), oracle.maxpool3x3s2(xe))
+        z = new_dev((2, 24), dtype, torch)
+        npas.global_avgpool(x, z, 2, 9, 11, 24, dtype)
+        assert rel_err(from_dev(z, dtype).reshape(2, 24), oracle.round_to(oracle.global_avgpool(xe), dtype)) <= TOL[dtype]
