@@ -155,8 +155,13 @@ struct npas_stack {
         int H, W, C;    // input dims
         int Ho, Wo, F;  // output dims (FC / avgpool: Ho = Wo = 1)
         int dtype;
+        const void *fused_blob = nullptr; // set on the first layer of a fused 1x1 pair
+        int fpp_nt1 = 0;                  // live intermediate tiles of that pair
+        uint32_t fpp_use[2] = {0, 0};     // chunk masks of that pair
+        bool fused_away = false;          // second layer of a fused pair: runs inside the first
     };
     std::vector<Node> nodes;
+    std::vector<void *> blobs; // device allocations owned by the stack (fused-pair weight images)
     int H = 0, W = 0, C = 0, dtype = 0;
     unsigned flags = 0;
     // per-tensor placement for a given N is computed on the fly (sizes scale with N)
@@ -184,6 +189,7 @@ static size_t place_tensors(const npas_stack *s, int N, std::vector<size_t> *off
     size_t total = 0;
     const int esz = dtype_size(s->dtype);
     for (int t = 1; t < nt - 1; ++t) { // tensor t is written by layer t-1
+        if (s->nodes[t - 1].fused_blob) continue; // intermediate of a fused pair never reaches memory
         sz[t] = (tensor_elems_per_image(s, t) * N * esz + 255) / 256 * 256;
         // drop tensors whose last reader ran before layer t-1
         live.erase(std::remove_if(live.begin(), live.end(), [&](const Live &l) { return l.until < t - 1; }),
@@ -200,6 +206,96 @@ static size_t place_tensors(const npas_stack *s, int N, std::vector<size_t> *off
     }
     if (offsets) *offsets = off;
     return total;
+}
+
+} // namespace npas
+
+namespace npas {
+
+// Dense [F][C] weights (storage bits, zero where pruned) of a packed 1x1 layer.
+static std::vector<uint16_t> dense_pointwise(const npas_packed *p)
+{
+    std::vector<uint16_t> d((size_t)p->F * p->C, 0);
+    const uint16_t *wc = reinterpret_cast<const uint16_t *>(p->w_compact.data());
+    for (int g = 0; g < p->G; ++g)
+        for (int k = p->grp_ptr[g]; k < p->grp_ptr[g + 1]; ++k)
+            for (int j = 0; j < p->Bf && g * p->Bf + j < p->F; ++j)
+                d[(size_t)(g * p->Bf + j) * p->C + p->k_pos[k]] = wc[(size_t)k * p->Bf + j];
+    return d;
+}
+
+// Plan and weight images of a fused pointwise pair (layouts: see fused_pointwise_pair_kernel).
+struct FppPlan {
+    int nt1 = 0;               // live intermediate tiles, rounded up to even
+    uint32_t use[2] = {0, 0};  // chunks each layer-2 tile needs
+    std::vector<uint16_t> blob;
+};
+
+static FppPlan build_fpp(const npas_packed *p1, const npas_packed *p2)
+{
+    FppPlan plan;
+    const int F1 = p1->F, nt2 = (p2->F + 15) / 16;
+    // intermediate channels each 16-filter tile of layer 2 keeps (union of its filter groups' lists)
+    std::vector<uint8_t> need[2] = {std::vector<uint8_t>(F1, 0), std::vector<uint8_t>(F1, 0)};
+    for (int g = 0; g < p2->G; ++g)
+        for (int u = 0; u < nt2; ++u) {
+            int f_lo = std::max(g * p2->Bf, 16 * u), f_hi = std::min({(g + 1) * p2->Bf, 16 * u + 16, p2->F});
+            if (f_lo >= f_hi) continue;
+            for (int k = p2->grp_ptr[g]; k < p2->grp_ptr[g + 1]; ++k) need[u][p2->k_pos[k]] = 1;
+        }
+    // slot order: channels only tile 0 needs, then shared ones, then those only tile 1 needs;
+    // dead channels get no slot.  Optionally pad so that tile 1's range starts on a chunk.
+    std::vector<int> only0, both, only1;
+    for (int c = 0; c < F1; ++c) {
+        if (need[0][c] && need[1][c]) both.push_back(c);
+        else if (need[0][c]) only0.push_back(c);
+        else if (need[1][c]) only1.push_back(c);
+    }
+    auto cost = [&](int pad, std::vector<int> *perm_out, uint32_t use_out[2]) {
+        std::vector<int> perm(only0);
+        perm.insert(perm.end(), pad, -1);
+        perm.insert(perm.end(), both.begin(), both.end());
+        perm.insert(perm.end(), only1.begin(), only1.end());
+        int tiles = std::max(2, ((int)perm.size() + 31) / 32 * 2);
+        perm.resize((size_t)tiles * 16, -1);
+        uint32_t use[2] = {0, 0};
+        for (size_t s = 0; s < perm.size(); ++s)
+            for (int u = 0; u < nt2; ++u)
+                if (perm[s] >= 0 && need[u][perm[s]]) use[u] |= 1u << (s / 32);
+        if (perm_out) *perm_out = perm;
+        if (use_out) { use_out[0] = use[0]; use_out[1] = use[1]; }
+        return tiles + __builtin_popcount(use[0]) + __builtin_popcount(use[1]);
+    };
+    int pad = (int)((32 - only0.size() % 32) % 32);
+    if (only1.empty() || cost(pad, nullptr, nullptr) >= cost(0, nullptr, nullptr)) pad = 0;
+    std::vector<int> perm;
+    cost(pad, &perm, plan.use);
+    plan.nt1 = (int)perm.size() / 16;
+    const int nt1 = plan.nt1, nch = nt1 / 2;
+    std::vector<uint16_t> d1 = dense_pointwise(p1), d2 = dense_pointwise(p2);
+    plan.blob.assign((size_t)(nt1 + nt2 * nch) * 512, 0);
+    for (int t = 0; t < nt1; ++t)
+        for (int lane = 0; lane < 64; ++lane)
+            for (int i = 0; i < 8; ++i) {
+                int r = lane & 15, q = lane >> 4, f = perm[16 * t + r], c = 8 * q + i;
+                if (f >= 0 && c < p1->C) plan.blob[((size_t)t * 64 + lane) * 8 + i] = d1[(size_t)f * p1->C + c];
+            }
+    for (int u = 0; u < nt2; ++u)
+        for (int j = 0; j < nch; ++j)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int i = 0; i < 8; ++i) {
+                    int r = lane & 15, q = lane >> 4, f = 16 * u + r;
+                    int c = perm[16 * (2 * j + (i >> 2)) + 4 * q + (i & 3)];
+                    if (f < p2->F && c >= 0)
+                        plan.blob[((size_t)(nt1 + u * nch + j) * 64 + lane) * 8 + i] = d2[(size_t)f * p2->C + c];
+                }
+    return plan;
+}
+
+static bool is_plain_pointwise(const npas_layer_desc &d)
+{
+    return d.kind == NPAS_LAYER_CONV && d.packed && d.packed->KH == 1 && d.packed->KW == 1 && d.stride == 1 &&
+           d.pad == 0 && d.packed->dtype != NPAS_F32 && !d.bias_dev;
 }
 
 } // namespace npas
@@ -350,6 +446,40 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
         dims[i + 1] = {nd.Ho, nd.Wo, nd.F};
         s->nodes.push_back(nd);
     }
+    if (flags & NPAS_STACK_FUSE_POINTWISE) {
+        int ndev = 0;
+        bool have_dev = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
+        if (!have_dev) (void)hipGetLastError();
+        for (int i = 0; i + 1 < n_layers && have_dev; ++i) {
+            npas_stack::Node &a = s->nodes[i], &b = s->nodes[i + 1];
+            if (a.fused_away || !is_plain_pointwise(a.d) || !is_plain_pointwise(b.d)) continue;
+            // the intermediate (tensor i+1) must feed layer i+1 only, and neither layer adds a residual
+            if (b.d.src != i + 1 || a.d.res >= 0 || b.d.res >= 0) continue;
+            bool other_reader = false;
+            for (int j = i + 1; j < n_layers; ++j)
+                if ((j != i + 1 && s->nodes[j].d.src == i + 1) || s->nodes[j].d.res == i + 1) other_reader = true;
+            if (other_reader || i + 1 == n_layers) continue;
+            const npas_packed *p1 = a.d.packed, *p2 = b.d.packed;
+            if (p1->C > 32 || p1->C % 8 || p2->F % 4 || p2->F > 32) continue;
+            FppPlan fp = build_fpp(p1, p2);
+            if (!fpp_supported(fp.nt1, (p2->F + 15) / 16)) continue;
+            std::vector<uint16_t> &blob = fp.blob;
+            void *dptr = nullptr;
+            if (hipMalloc(&dptr, blob.size() * 2) != hipSuccess ||
+                hipMemcpy(dptr, blob.data(), blob.size() * 2, hipMemcpyHostToDevice) != hipSuccess) {
+                if (dptr) (void)hipFree(dptr);
+                set_error("could not upload the fused-pair weight image");
+                for (void *q : s->blobs) (void)hipFree(q);
+                return NPAS_E_HIP;
+            }
+            s->blobs.push_back(dptr);
+            a.fused_blob = dptr;
+            a.fpp_nt1 = fp.nt1;
+            a.fpp_use[0] = fp.use[0];
+            a.fpp_use[1] = fp.use[1];
+            b.fused_away = true;
+        }
+    }
     *out = s.release();
     return NPAS_OK;
 }
@@ -360,7 +490,13 @@ size_t npas_stack_workspace_bytes(const npas_stack *s, int N)
     return place_tensors(s, N, nullptr);
 }
 
-int npas_stack_num_launches(const npas_stack *s) { return s ? (int)s->nodes.size() : 0; }
+int npas_stack_num_launches(const npas_stack *s)
+{
+    if (!s) return 0;
+    int n = 0;
+    for (const npas_stack::Node &nd : s->nodes) n += nd.fused_away ? 0 : 1;
+    return n;
+}
 
 int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, void *workspace_dev,
                    size_t workspace_bytes, void *hip_stream)
@@ -387,9 +523,20 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
     };
     for (int i = 0; i < nl; ++i) {
         const npas_stack::Node &n = s->nodes[i];
+        if (n.fused_away) continue;
         const void *x = tensor(n.d.src);
         void *y = tensor(i + 1);
         int rc = NPAS_OK;
+        if (n.fused_blob) { // this layer and the next as one kernel; the tensor between them is never stored
+            const npas_packed *p1 = n.d.packed, *p2 = s->nodes[i + 1].d.packed;
+            rc = check_run(p1, x, tensor(i + 2), N, n.H, n.W, 1, 0);
+            if (!rc)
+                rc = launch_fused_pointwise_pair(p1->dtype, x, tensor(i + 2), n.fused_blob, N * n.H * n.W, p1->C,
+                                                 n.fpp_nt1, p2->F, n.d.act, s->nodes[i + 1].d.act, n.fpp_use[0],
+                                                 n.fpp_use[1], hip_stream);
+            if (rc) return rc;
+            continue;
+        }
         switch (n.d.kind) {
         case NPAS_LAYER_CONV:
             rc = check_run(n.d.packed, x, y, N, n.H, n.W, n.d.stride, n.d.pad);
@@ -413,6 +560,11 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
     return NPAS_OK;
 }
 
-void npas_stack_free(npas_stack *s) { delete s; }
+void npas_stack_free(npas_stack *s)
+{
+    if (!s) return;
+    for (void *q : s->blobs) (void)hipFree(q);
+    delete s;
+}
 
 } // extern "C"

@@ -13,6 +13,7 @@
 // maxpool3x3s2 / global_avgpool: glue layers of residual stacks.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 
 #include "npas_internal.h"
@@ -35,6 +36,16 @@ __device__ __forceinline__ float act_apply(float v, int act)
     return v;
 }
 
+// The three activations as one clamp to [lo, hi] (none: +-inf, ReLU: [0, inf), ReLU6: [0, 6]).
+struct Clamp {
+    float lo, hi;
+};
+__device__ __forceinline__ Clamp clamp_of(int act)
+{
+    return Clamp{act == NPAS_ACT_NONE ? -INFINITY : 0.0f, act == NPAS_ACT_RELU6 ? 6.0f : INFINITY};
+}
+__device__ __forceinline__ float clampf(float v, Clamp c) { return __builtin_amdgcn_fmed3f(v, c.lo, c.hi); }
+
 // fp32 -> 16-bit storage, round to nearest even.
 template <int DT> __device__ __forceinline__ uint16_t to_storage(float v)
 {
@@ -46,6 +57,19 @@ template <int DT> __device__ __forceinline__ uint16_t to_storage(float v)
     } else {
         _Float16 h = (_Float16)v;
         return __builtin_bit_cast(uint16_t, h);
+    }
+}
+
+// two fp32 -> one dword of two 16-bit storage values (lo, hi), round to nearest even
+template <int DT> __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    if (DT == NPAS_BF16) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+    } else {
+        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, f16x2));
     }
 }
 
@@ -211,6 +235,7 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
                 uint16_t *y16 = reinterpret_cast<uint16_t *>(a.y);
                 const uint16_t *r16 = reinterpret_cast<const uint16_t *>(a.residual);
                 const bool vec4 = (g.F & 3) == 0;
+                const Clamp cl = clamp_of(g.act);
 #pragma unroll
                 for (int s = 0; s < S; ++s) {
                     if (s < ns && outoff[s] >= 0) {
@@ -225,10 +250,8 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
                                 v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
                             }
                             uint2 out;
-                            out.x = (uint32_t)to_storage<DT>(act_apply(v[0], g.act)) |
-                                    (uint32_t)to_storage<DT>(act_apply(v[1], g.act)) << 16;
-                            out.y = (uint32_t)to_storage<DT>(act_apply(v[2], g.act)) |
-                                    (uint32_t)to_storage<DT>(act_apply(v[3], g.act)) << 16;
+                            out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
+                            out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
                             *reinterpret_cast<uint2 *>(y16 + o) = out;
                         } else {
 #pragma unroll
@@ -236,7 +259,7 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
                                 if (f0 + i < g.F) {
                                     float t = v[i];
                                     if (r16) t += from_storage<DT>(r16[o + i]);
-                                    y16[o + i] = to_storage<DT>(act_apply(t, g.act));
+                                    y16[o + i] = (uint16_t)(pack2<DT>(clampf(t, cl), 0.f) & 0xffffu);
                                 }
                         }
                     }
@@ -277,6 +300,159 @@ int launch_conv_mfma(int dtype, const ConvMfmaArgs &a, unsigned grid, size_t lds
         return s8 ? launch_mfma_inst<NPAS_F16, 8>(a, grid, lds_bytes, st) : launch_mfma_inst<NPAS_F16, 4>(a, grid, lds_bytes, st);
     set_error("conv_gather_mfma needs a 16-bit storage type");
     return NPAS_E_DTYPE;
+}
+
+// ------------------------------------------------------------------------------
+// Fused pointwise pair: y = act2(W2 * act1(W1 * x + b1) + b2) for two 1x1 layers
+// whose intermediate tensor has no other reader (the expand -> project pair of an
+// inverted-residual bottleneck).  HBM-bound: x is read once and y written once,
+// the F1-channel intermediate never leaves registers.
+//
+// One wave owns 16 pixels at a time.  Layer 1: the B operand is the pixel's C1
+// (<= 32) channels straight from global memory, one MFMA per 16 intermediate
+// channels.  The 16x16 result tile of MFMA t holds, in lane (pixel n, quarter q),
+// channels 16t + 4q .. 4q+3 of that pixel; two such tiles, activated and rounded
+// to the storage type, are exactly the B operand of a 32-deep MFMA of layer 2
+// whose K slots are ordered  slot 8q+i <-> channel 16(2j) + 4q + i      (i < 4)
+//                            slot 8q+4+i <-> channel 16(2j+1) + 4q + i
+// and layer 2's weights are stored pre-permuted to that order.  All weights live
+// in registers for the life of the wave.
+//
+// Pruning shows up twice.  An intermediate channel that no filter of layer 2 keeps
+// is dead and layer 1 never computes it; the live channels are renumbered ("slots")
+// so that the ones each 16-filter tile of layer 2 needs are contiguous, and a tile
+// skips the 32-slot chunks it keeps nothing in (bit j of use[u] = tile u needs chunk j).
+struct FppArgs {
+    const void *x;
+    void *y;
+    const void *wblob;   // [NT1 + NT2*NCH][64 lanes][8] 16-bit weight images
+    int M, C1, F2;       // pixels, input channels, output channels
+    int act1, act2;
+    uint32_t use[2];     // per layer-2 tile: which 32-slot chunks it needs
+};
+
+constexpr int kFppBlocksPerWave = 8; // 16-pixel blocks a wave owns; all their loads are issued up front
+
+template <int DT, int NT1, int NT2>
+__global__ __launch_bounds__(256, 2) void fused_pointwise_pair_kernel(FppArgs a)
+{
+    constexpr int NCH = (NT1 + 1) / 2;
+    constexpr int PER = kFppBlocksPerWave;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n16 = lane & 15, q = lane >> 4;
+    const int nblk = (a.M + 15) >> 4;
+    const int nw = gridDim.x * 4, gw = blockIdx.x * 4 + wave;
+    // contiguous run of blocks per wave, remainder spread over the first waves
+    const int base = nblk / nw, extra = nblk % nw;
+    const int b0 = gw * base + min(gw, extra), cnt = base + (gw < extra ? 1 : 0);
+    if (cnt <= 0) return;
+
+    const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
+    uint16_t *y16 = reinterpret_cast<uint16_t *>(a.y);
+    const bool ld_on = 8 * q < a.C1;
+    const Clamp c1 = clamp_of(a.act1), c2 = clamp_of(a.act2);
+
+    // activations of all the wave's blocks: in flight together, nothing to wait for later
+    // Weights first, then the activations of all the wave's blocks, every load issued
+    // before the first use: block k is computed as soon as its own load has landed while
+    // the later ones are still in flight.  Loads are unconditional (addresses clamped into
+    // the tensor); lanes past C1 are zeroed by a select, columns past M are never stored.
+    const uint4 *wb = reinterpret_cast<const uint4 *>(a.wblob) + lane;
+    uint4 A1[NT1], A2[NT2][NCH];
+#pragma unroll
+    for (int t = 0; t < NT1; ++t) A1[t] = wb[t * 64];
+#pragma unroll
+    for (int u = 0; u < NT2; ++u)
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) A2[u][j] = wb[(NT1 + u * NCH + j) * 64];
+    uint4 xin[PER];
+    const int cq = ld_on ? 8 * q : 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int pix = min((b0 + min(k, cnt - 1)) * 16 + n16, a.M - 1);
+        xin[k] = *reinterpret_cast<const uint4 *>(x16 + (size_t)pix * a.C1 + cq);
+    }
+
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        if (k < cnt) { // wave-uniform
+            f32x4 d1[NT1];
+            uint4 xb = xin[k];
+            if (!ld_on) xb = uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int t = 0; t < NT1; ++t) d1[t] = mfma16<DT>(A1[t], xb, f32x4{0.f, 0.f, 0.f, 0.f});
+            f32x4 d2[NT2];
+#pragma unroll
+            for (int u = 0; u < NT2; ++u) d2[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < NCH; ++j) {
+                uint4 b;
+                b.x = pack2<DT>(clampf(d1[2 * j][0], c1), clampf(d1[2 * j][1], c1));
+                b.y = pack2<DT>(clampf(d1[2 * j][2], c1), clampf(d1[2 * j][3], c1));
+                if (2 * j + 1 < NT1) {
+                    b.z = pack2<DT>(clampf(d1[2 * j + 1][0], c1), clampf(d1[2 * j + 1][1], c1));
+                    b.w = pack2<DT>(clampf(d1[2 * j + 1][2], c1), clampf(d1[2 * j + 1][3], c1));
+                } else {
+                    b.z = b.w = 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < NT2; ++u)
+                    if ((a.use[u] >> j) & 1u) d2[u] = mfma16<DT>(A2[u][j], b, d2[u]);
+            }
+            const int pix = (b0 + k) * 16 + n16;
+            if (pix < a.M) {
+#pragma unroll
+                for (int u = 0; u < NT2; ++u) {
+                    const int f0 = 16 * u + 4 * q;
+                    if (f0 < a.F2) {
+                        uint2 o;
+                        o.x = pack2<DT>(clampf(d2[u][0], c2), clampf(d2[u][1], c2));
+                        o.y = pack2<DT>(clampf(d2[u][2], c2), clampf(d2[u][3], c2));
+                        *reinterpret_cast<uint2 *>(y16 + (size_t)pix * a.F2 + f0) = o;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int DT, int NT1, int NT2> static void fpp_launch(const FppArgs &a, unsigned grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((fused_pointwise_pair_kernel<DT, NT1, NT2>), dim3(grid), dim3(256), 0, st, a);
+}
+
+// nt1 = live intermediate tiles rounded up to an even count, nt2 = output tiles
+bool fpp_supported(int nt1, int nt2) { return nt1 >= 2 && nt1 <= 12 && nt1 % 2 == 0 && (nt2 == 1 || nt2 == 2); }
+
+int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
+                                int act1, int act2, uint32_t use0, uint32_t use1, void *stream)
+{
+    FppArgs a{x, y, wblob, M, C1, F2, act1, act2, {use0, use1}};
+    hipStream_t st = (hipStream_t)stream;
+    const int nt2 = (F2 + 15) / 16;
+    const int nblk = (M + 15) / 16;
+    // two workgroups per CU when the batch allows it, more when a wave would otherwise own
+    // more than kFppBlocksPerWave blocks
+    const int min_grid = (nblk + 4 * kFppBlocksPerWave - 1) / (4 * kFppBlocksPerWave);
+    unsigned grid = (unsigned)std::max(min_grid, std::min((nblk + 3) / 4, 512));
+#define NPAS_FPP_CASE(N1, N2)                                                              \
+    if (nt1 == N1 && nt2 == N2) {                                                          \
+        if (dtype == NPAS_BF16) fpp_launch<NPAS_BF16, N1, N2>(a, grid, st);                \
+        else fpp_launch<NPAS_F16, N1, N2>(a, grid, st);                                    \
+    } else
+    NPAS_FPP_CASE(2, 1) NPAS_FPP_CASE(2, 2) NPAS_FPP_CASE(4, 1) NPAS_FPP_CASE(4, 2) NPAS_FPP_CASE(6, 1)
+    NPAS_FPP_CASE(6, 2) NPAS_FPP_CASE(8, 1) NPAS_FPP_CASE(8, 2) NPAS_FPP_CASE(10, 1) NPAS_FPP_CASE(10, 2)
+    NPAS_FPP_CASE(12, 1) NPAS_FPP_CASE(12, 2)
+    {
+        set_error("fused pointwise pair: unsupported tile counts %d, %d", nt1, nt2);
+        return NPAS_E_SHAPE;
+    }
+#undef NPAS_FPP_CASE
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("fused_pointwise_pair launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
 }
 
 // ------------------------------------------------------------------------------

@@ -135,6 +135,9 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
 // launchers (kernels.hip)
 int launch_conv_mfma(int dtype, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream);
 int launch_conv_valu(const ConvValuArgs &a, void *stream);
+bool fpp_supported(int nt1, int nt2);
+int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
+                                int act1, int act2, uint32_t use0, uint32_t use1, void *stream);
 int launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream);
 int launch_avgpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream);
 
