@@ -36,8 +36,11 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
     g.pstep = pointwise ? stride : 1;
     g.lstep = pointwise ? 1 : stride;
     g.vec = (p->C % 8 == 0 && d.CC % 8 == 0) ? 1 : 0;
-    g.pitch = (d.CC * 2 + 15) / 16 * 16 + 8;
-    g.koff_cap = std::min(512, std::max(32, d.max_list));
+    const bool slab = d.variant == V_MFMA_SLAB;
+    // LDS bytes per patch pixel: 16-byte aligned rows for the slab path's 16-byte reads,
+    // rows displaced by 8 bytes for the element path's 2-byte gathers (bank spread)
+    g.pitch = (d.CC * 2 + 15) / 16 * 16 + (slab ? 16 : 8);
+    g.koff_cap = slab ? 0 : std::min(512, std::max(32, d.max_list));
     const size_t koff_bytes = (size_t)4 * g.koff_cap * 4;
 
     double best = -1e30;
@@ -138,10 +141,10 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
     ConvMfmaArgs a;
     a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
     a.tc_ptr = p->dev.tc_ptr; a.kent = p->dev.kent; a.wfrag = p->dev.wfrag;
-    a.CC = p->fmt.CC; a.nchunks = p->fmt.nchunks; a.ntiles = p->fmt.ntiles;
+    a.CC = p->fmt.CC; a.nchunks = p->fmt.nchunks; a.ntiles = p->fmt.ntiles; a.NT = p->fmt.NT;
     a.g = plan->g;
     a.g.act = act;
-    return launch_conv_mfma(p->dtype, a, plan->grid, plan->lds_bytes, stream);
+    return launch_conv_mfma(p->dtype, p->fmt.variant, a, plan->grid, plan->lds_bytes, stream);
 }
 
 } // namespace npas
@@ -284,7 +287,10 @@ static FppPlan build_fpp(const npas_packed *p1, const npas_packed *p2)
         for (int j = 0; j < nch; ++j)
             for (int lane = 0; lane < 64; ++lane)
                 for (int i = 0; i < 8; ++i) {
-                    int r = lane & 15, q = lane >> 4, f = 16 * u + r;
+                    // rows past the last filter repeat the tile's valid rows in groups of four
+                    int r = lane & 15, q = lane >> 4;
+                    int nvq = std::min(4, (p2->F - 16 * u) / 4);
+                    int f = 16 * u + 4 * ((r >> 2) % nvq) + (r & 3);
                     int c = perm[16 * (2 * j + (i >> 2)) + 4 * q + (i & 3)];
                     if (f < p2->F && c >= 0)
                         plan.blob[((size_t)(nt1 + u * nch + j) * 64 + lane) * 8 + i] = d2[(size_t)f * p2->C + c];

@@ -15,6 +15,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 
 #include "npas_internal.h"
 
@@ -95,6 +96,48 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t wg, uint32_t nwg)
     return xcd * q + (xcd < r ? xcd : r) + idx;
 }
 
+// Copies the input patch of one output tile, channels [cc*CC, cc*CC + CC), into LDS as
+// [patch pixel][channel] with `pitch` bytes per pixel; out-of-image pixels become zeros.
+// WIDE: 16-byte LDS writes (pitch is a multiple of 16), else two 8-byte writes.
+template <bool WIDE>
+__device__ __forceinline__ void stage_patch(const ConvMfmaArgs &a, uint8_t *lds, const uint16_t *x16, int n, int iy0,
+                                            int ix0, int cc, int tid)
+{
+    const ConvGeom &g = a.g;
+    const int c0 = cc * a.CC, ccount = min(a.CC, g.C - c0);
+    if (g.vec) {
+        const uint32_t nvv = (uint32_t)ccount >> 3;
+        const uint32_t total = (uint32_t)(g.PH * g.PW) * nvv;
+        const uint32_t dv = (nvv == (uint32_t)(a.CC >> 3)) ? g.div_vec : 0xffffffffu;
+        for (uint32_t v = tid; v < total; v += 256) {
+            uint32_t pix = dv == 0xffffffffu ? v / nvv : fastdiv(v, dv);
+            uint32_t cv = v - pix * nvv;
+            uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
+            int iy = iy0 + (int)py * g.pstep, ix = ix0 + (int)px * g.pstep;
+            uint4 val = uint4{0u, 0u, 0u, 0u};
+            if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
+                val = *reinterpret_cast<const uint4 *>(x16 + ((size_t)((n * g.H + iy) * g.W + ix) * g.C + c0 + cv * 8));
+            if (WIDE) {
+                *reinterpret_cast<uint4 *>(lds + pix * (uint32_t)g.pitch + cv * 16) = val;
+            } else {
+                uint2 *dst = reinterpret_cast<uint2 *>(lds + pix * (uint32_t)g.pitch + cv * 16);
+                dst[0] = uint2{val.x, val.y};
+                dst[1] = uint2{val.z, val.w};
+            }
+        }
+    } else {
+        const uint32_t total = (uint32_t)(g.PH * g.PW * ccount);
+        for (uint32_t v = tid; v < total; v += 256) {
+            uint32_t pix = v / (uint32_t)ccount, c = v - pix * (uint32_t)ccount;
+            uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
+            int iy = iy0 + (int)py * g.pstep, ix = ix0 + (int)px * g.pstep;
+            uint16_t val = 0;
+            if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W) val = x16[(size_t)((n * g.H + iy) * g.W + ix) * g.C + c0 + c];
+            *reinterpret_cast<uint16_t *>(lds + pix * (uint32_t)g.pitch + c * 2) = val;
+        }
+    }
+}
+
 template <int DT, int S>
 __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
 {
@@ -148,36 +191,7 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
             if (a.nchunks > 1 || !staged) {
                 // ---- stage the activation patch of channel chunk cc -------------
                 __syncthreads();
-                const int c0 = cc * a.CC, ccount = min(a.CC, g.C - c0);
-                if (g.vec) {
-                    const uint32_t nvv = (uint32_t)ccount >> 3;
-                    const uint32_t total = (uint32_t)(g.PH * g.PW) * nvv;
-                    const uint32_t dv = (nvv == (uint32_t)(a.CC >> 3)) ? g.div_vec : 0xffffffffu;
-                    for (uint32_t v = tid; v < total; v += 256) {
-                        uint32_t pix = dv == 0xffffffffu ? v / nvv : fastdiv(v, dv);
-                        uint32_t cv = v - pix * nvv;
-                        uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
-                        int iy = iy0 + (int)py * g.pstep, ix = ix0 + (int)px * g.pstep;
-                        uint4 val = uint4{0u, 0u, 0u, 0u};
-                        if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
-                            val = *reinterpret_cast<const uint4 *>(
-                                x16 + ((size_t)((n * g.H + iy) * g.W + ix) * g.C + c0 + cv * 8));
-                        uint2 *dst = reinterpret_cast<uint2 *>(lds + pix * (uint32_t)g.pitch + cv * 16);
-                        dst[0] = uint2{val.x, val.y};
-                        dst[1] = uint2{val.z, val.w};
-                    }
-                } else {
-                    const uint32_t total = (uint32_t)(g.PH * g.PW * ccount);
-                    for (uint32_t v = tid; v < total; v += 256) {
-                        uint32_t pix = v / (uint32_t)ccount, c = v - pix * (uint32_t)ccount;
-                        uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
-                        int iy = iy0 + (int)py * g.pstep, ix = ix0 + (int)px * g.pstep;
-                        uint16_t val = 0;
-                        if (iy >= 0 && iy < g.H && ix >= 0 && ix < g.W)
-                            val = x16[(size_t)((n * g.H + iy) * g.W + ix) * g.C + c0 + c];
-                        *reinterpret_cast<uint16_t *>(lds + pix * (uint32_t)g.pitch + c * 2) = val;
-                    }
-                }
+                stage_patch<false>(a, lds, x16, n, iy0, ix0, cc, tid);
                 staged = true;
                 __syncthreads();
             }
@@ -269,6 +283,164 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------
+// conv_slab_mfma: the same layers, gathered at 8-channel granularity.  A list entry is
+// an 8-channel slab at one tap; four slabs make one 32-deep MFMA step, and the B
+// operand of a step is one 16-byte LDS read per lane (lane quarter q reads slab 4*step+q
+// of its pixel).  A wave owns a super-tile of 16*NT filters and all S pixel blocks of the
+// workgroup's output tile, so a gathered fragment feeds NT MFMAs and a weight fragment S.
+template <int DT, int S, int NT>
+__global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const ConvGeom &g = a.g;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
+
+    const uint32_t logical = xcd_remap(blockIdx.x, gridDim.x);
+    const uint32_t fsplit = logical % (uint32_t)g.nfsplit, ptile = logical / (uint32_t)g.nfsplit;
+    const uint32_t tiles_img = (uint32_t)(g.tilesY * g.tilesX);
+    const int n = (int)(ptile / tiles_img);
+    const uint32_t trem = ptile % tiles_img;
+    const int ty0 = (int)(trem / (uint32_t)g.tilesX) * g.TH, tx0 = (int)(trem % (uint32_t)g.tilesX) * g.TW;
+
+    const int npix_tile = g.TH * g.TW;
+    uint32_t pixbase[S];
+    int32_t outoff[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        uint32_t m = (uint32_t)(s * 16 + n16);
+        uint32_t ty = fastdiv(m, g.div_tw), tx = m - ty * (uint32_t)g.TW;
+        int oy = ty0 + (int)ty, ox = tx0 + (int)tx;
+        bool valid = (int)m < npix_tile && oy < g.Ho && ox < g.Wo;
+        pixbase[s] = valid ? ((ty * g.lstep) * g.PW + tx * g.lstep) * (uint32_t)g.pitch : 0u;
+        outoff[s] = valid ? ((n * g.Ho + oy) * g.Wo + ox) * g.F : -1;
+    }
+    const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
+    const int iy0 = (g.pstep > 1 ? ty0 * g.pstep : ty0 * g.stride) - g.pad;
+    const int ix0 = (g.pstep > 1 ? tx0 * g.pstep : tx0 * g.stride) - g.pad;
+
+    const int st_begin = (int)fsplit * g.tiles_per_split;
+    const int st_end = min(st_begin + g.tiles_per_split, a.ntiles);
+    bool staged = false;
+
+    for (int stb = st_begin; stb < st_end; stb += 4) {
+        const int st = stb + wave;
+        const bool active = st < st_end;
+        f32x4 acc[NT][S];
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int s = 0; s < S; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int cc = 0; cc < a.nchunks; ++cc) {
+            if (a.nchunks > 1 || !staged) {
+                __syncthreads();
+                stage_patch<true>(a, lds, x16, n, iy0, ix0, cc, tid);
+                staged = true;
+                __syncthreads();
+            }
+            if (!active) continue;
+            const int e0 = a.tc_ptr[st * a.nchunks + cc], e1 = a.tc_ptr[st * a.nchunks + cc + 1];
+            if (e0 >= e1) continue;
+            const uint4 *wf = reinterpret_cast<const uint4 *>(a.wfrag) + (size_t)(e0 >> 2) * NT * 64 + lane;
+            const uint32_t *kp = a.kent + e0 + q;
+            // software pipeline: fetch step i+1's list entry and weight fragments during step i
+            uint32_t ent = *kp;
+            uint4 wa[NT];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) wa[j] = wf[j * 64];
+            for (int e = e0; e < e1; e += 4) {
+                const uint32_t koff = ((ent >> 24) * (uint32_t)g.PW + ((ent >> 16) & 255u)) * (uint32_t)g.pitch + (ent & 0xffffu) * 2u;
+                uint4 wc[NT];
+#pragma unroll
+                for (int j = 0; j < NT; ++j) wc[j] = wa[j];
+                if (e + 4 < e1) {
+                    kp += 4;
+                    wf += NT * 64;
+                    ent = *kp;
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) wa[j] = wf[j * 64];
+                }
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    const uint4 b = *reinterpret_cast<const uint4 *>(lds + pixbase[s] + koff);
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) acc[j][s] = mfma16<DT>(wc[j], b, acc[j][s]);
+                }
+            }
+        }
+
+        if (active) {
+            uint16_t *y16 = reinterpret_cast<uint16_t *>(a.y);
+            const uint16_t *r16 = reinterpret_cast<const uint16_t *>(a.residual);
+            const bool vec4 = (g.F & 3) == 0;
+            const Clamp cl = clamp_of(g.act);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const int f0 = (st * NT + j) * 16 + 4 * q;
+                if (f0 >= g.F) continue;
+                float bv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (a.bias) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (f0 + i < g.F) bv[i] = a.bias[f0 + i];
+                }
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    if (outoff[s] < 0) continue;
+                    const size_t o = (size_t)outoff[s] + f0;
+                    float v[4] = {acc[j][s][0] + bv[0], acc[j][s][1] + bv[1], acc[j][s][2] + bv[2], acc[j][s][3] + bv[3]};
+                    if (vec4) {
+                        if (r16) {
+                            uint2 r = *reinterpret_cast<const uint2 *>(r16 + o);
+                            v[0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
+                            v[1] += from_storage<DT>((uint16_t)(r.x >> 16));
+                            v[2] += from_storage<DT>((uint16_t)(r.y & 0xffffu));
+                            v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
+                        }
+                        uint2 out;
+                        out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
+                        out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                        *reinterpret_cast<uint2 *>(y16 + o) = out;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (f0 + i < g.F) {
+                                float t = v[i];
+                                if (r16) t += from_storage<DT>(r16[o + i]);
+                                y16[o + i] = (uint16_t)(pack2<DT>(clampf(t, cl), 0.f) & 0xffffu);
+                            }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int DT, int S, int NT>
+static int launch_slab_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
+{
+    hipLaunchKernelGGL((conv_slab_mfma_kernel<DT, S, NT>), dim3(grid), dim3(256), lds_bytes, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("conv_slab_mfma launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
+{
+    const bool s8 = a.g.TH * a.g.TW > 64;
+    switch (a.NT) {
+    case 1: return s8 ? launch_slab_inst<DT, 8, 1>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 1>(a, grid, lds_bytes, st);
+    case 2: return s8 ? launch_slab_inst<DT, 8, 2>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 2>(a, grid, lds_bytes, st);
+    case 4: return s8 ? launch_slab_inst<DT, 8, 4>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 4>(a, grid, lds_bytes, st);
+    }
+    set_error("conv_slab_mfma: unsupported tiles per wave %d", a.NT);
+    return NPAS_E_SHAPE;
+}
+
 static bool g_lds_attr_set[2][2] = {{false, false}, {false, false}};
 
 template <int DT, int S>
@@ -290,9 +462,15 @@ static int launch_mfma_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_byt
     return NPAS_OK;
 }
 
-int launch_conv_mfma(int dtype, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream)
+int launch_conv_mfma(int dtype, int variant, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
+    if (variant == V_MFMA_SLAB) {
+        if (dtype == NPAS_BF16) return launch_slab_dt<NPAS_BF16>(a, grid, lds_bytes, st);
+        if (dtype == NPAS_F16) return launch_slab_dt<NPAS_F16>(a, grid, lds_bytes, st);
+        set_error("conv_slab_mfma needs a 16-bit storage type");
+        return NPAS_E_DTYPE;
+    }
     const bool s8 = a.g.TH * a.g.TW > 64;
     if (dtype == NPAS_BF16)
         return s8 ? launch_mfma_inst<NPAS_BF16, 8>(a, grid, lds_bytes, st) : launch_mfma_inst<NPAS_BF16, 4>(a, grid, lds_bytes, st);
@@ -320,8 +498,8 @@ int launch_conv_mfma(int dtype, const ConvMfmaArgs &a, unsigned grid, size_t lds
 //
 // Pruning shows up twice.  An intermediate channel that no filter of layer 2 keeps
 // is dead and layer 1 never computes it; the live channels are renumbered ("slots")
-// so that the ones each 16-filter tile of layer 2 needs are contiguous, and a tile
-// skips the 32-slot chunks it keeps nothing in (bit j of use[u] = tile u needs chunk j).
+// so that the ones each 16-filter tile of layer 2 needs are contiguous and dead
+// channels cost nothing (use[u] records which 32-slot chunks tile u really needs).
 struct FppArgs {
     const void *x;
     void *y;
@@ -333,29 +511,17 @@ struct FppArgs {
 
 constexpr int kFppBlocksPerWave = 8; // 16-pixel blocks a wave owns; all their loads are issued up front
 
-template <int DT, int NT1, int NT2>
-__global__ __launch_bounds__(256, 2) void fused_pointwise_pair_kernel(FppArgs a)
+// Straight-line body for a wave that owns exactly CNT blocks starting at block b0.
+// No branch between the loads and their uses, so the compiler can wait for block k's
+// activations alone (s_waitcnt vmcnt(n)) while later blocks are still in flight.
+template <int DT, int NT1, int NT2, int CNT>
+__device__ __forceinline__ void fpp_body(const FppArgs &a, int b0, int n16, int q, int lane)
 {
-    constexpr int NCH = (NT1 + 1) / 2;
-    constexpr int PER = kFppBlocksPerWave;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n16 = lane & 15, q = lane >> 4;
-    const int nblk = (a.M + 15) >> 4;
-    const int nw = gridDim.x * 4, gw = blockIdx.x * 4 + wave;
-    // contiguous run of blocks per wave, remainder spread over the first waves
-    const int base = nblk / nw, extra = nblk % nw;
-    const int b0 = gw * base + min(gw, extra), cnt = base + (gw < extra ? 1 : 0);
-    if (cnt <= 0) return;
-
+    constexpr int NCH = NT1 / 2;
     const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
     uint16_t *y16 = reinterpret_cast<uint16_t *>(a.y);
     const bool ld_on = 8 * q < a.C1;
     const Clamp c1 = clamp_of(a.act1), c2 = clamp_of(a.act2);
-
-    // activations of all the wave's blocks: in flight together, nothing to wait for later
-    // Weights first, then the activations of all the wave's blocks, every load issued
-    // before the first use: block k is computed as soon as its own load has landed while
-    // the later ones are still in flight.  Loads are unconditional (addresses clamped into
-    // the tensor); lanes past C1 are zeroed by a select, columns past M are never stored.
     const uint4 *wb = reinterpret_cast<const uint4 *>(a.wblob) + lane;
     uint4 A1[NT1], A2[NT2][NCH];
 #pragma unroll
@@ -364,54 +530,79 @@ __global__ __launch_bounds__(256, 2) void fused_pointwise_pair_kernel(FppArgs a)
     for (int u = 0; u < NT2; ++u)
 #pragma unroll
         for (int j = 0; j < NCH; ++j) A2[u][j] = wb[(NT1 + u * NCH + j) * 64];
-    uint4 xin[PER];
-    const int cq = ld_on ? 8 * q : 0;
+    // Rows of a partial last output tile repeat its valid rows (the weight image is built
+    // that way), so every lane holds real outputs and stores them, some twice, unpredicated.
+    int fst[NT2];
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        const int pix = min((b0 + min(k, cnt - 1)) * 16 + n16, a.M - 1);
+    for (int u = 0; u < NT2; ++u) {
+        const int nvq = min(4, (a.F2 - 16 * u) >> 2); // valid groups of 4 rows in tile u
+        const int q1 = q - nvq, q2 = q1 - nvq;         // q mod nvq without a division
+        fst[u] = 16 * u + 4 * (q < nvq ? q : (q1 < nvq ? q1 : (nvq == 1 ? 0 : q2)));
+    }
+    // Pixels past M are clamped to pixel M-1 for the load AND the store: such a lane
+    // recomputes pixel M-1 and writes the same bytes again, which needs no branch.
+    uint4 xin[CNT];
+    const int cq = ld_on ? 8 * q : 0;
+    const uint32_t lmask = ld_on ? 0xffffffffu : 0u;
+#pragma unroll
+    for (int k = 0; k < CNT; ++k) {
+        const int pix = min((b0 + k) * 16 + n16, a.M - 1);
         xin[k] = *reinterpret_cast<const uint4 *>(x16 + (size_t)pix * a.C1 + cq);
     }
-
+    __builtin_amdgcn_sched_barrier(0); // keep every load above the first use (memory-level parallelism)
+    // A layer-2 tile that keeps nothing in a chunk has an all-zero image there; it is multiplied
+    // anyway rather than branched around (the MFMA pipe has slack, and a branch here would
+    // make every load wait).
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        if (k < cnt) { // wave-uniform
-            f32x4 d1[NT1];
-            uint4 xb = xin[k];
-            if (!ld_on) xb = uint4{0u, 0u, 0u, 0u};
+    for (int k = 0; k < CNT; ++k) {
+        uint4 xb = xin[k];
+        xb.x &= lmask; xb.y &= lmask; xb.z &= lmask; xb.w &= lmask; // K slots past C1 are zero
+        f32x4 d1[NT1];
 #pragma unroll
-            for (int t = 0; t < NT1; ++t) d1[t] = mfma16<DT>(A1[t], xb, f32x4{0.f, 0.f, 0.f, 0.f});
-            f32x4 d2[NT2];
+        for (int t = 0; t < NT1; ++t) d1[t] = mfma16<DT>(A1[t], xb, f32x4{0.f, 0.f, 0.f, 0.f});
+        f32x4 d2[NT2];
 #pragma unroll
-            for (int u = 0; u < NT2; ++u) d2[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < NT2; ++u) d2[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < NCH; ++j) {
-                uint4 b;
-                b.x = pack2<DT>(clampf(d1[2 * j][0], c1), clampf(d1[2 * j][1], c1));
-                b.y = pack2<DT>(clampf(d1[2 * j][2], c1), clampf(d1[2 * j][3], c1));
-                if (2 * j + 1 < NT1) {
-                    b.z = pack2<DT>(clampf(d1[2 * j + 1][0], c1), clampf(d1[2 * j + 1][1], c1));
-                    b.w = pack2<DT>(clampf(d1[2 * j + 1][2], c1), clampf(d1[2 * j + 1][3], c1));
-                } else {
-                    b.z = b.w = 0u;
-                }
+        for (int j = 0; j < NCH; ++j) {
+            uint4 b;
+            b.x = pack2<DT>(clampf(d1[2 * j][0], c1), clampf(d1[2 * j][1], c1));
+            b.y = pack2<DT>(clampf(d1[2 * j][2], c1), clampf(d1[2 * j][3], c1));
+            b.z = pack2<DT>(clampf(d1[2 * j + 1][0], c1), clampf(d1[2 * j + 1][1], c1));
+            b.w = pack2<DT>(clampf(d1[2 * j + 1][2], c1), clampf(d1[2 * j + 1][3], c1));
 #pragma unroll
-                for (int u = 0; u < NT2; ++u)
-                    if ((a.use[u] >> j) & 1u) d2[u] = mfma16<DT>(A2[u][j], b, d2[u]);
-            }
-            const int pix = (b0 + k) * 16 + n16;
-            if (pix < a.M) {
-#pragma unroll
-                for (int u = 0; u < NT2; ++u) {
-                    const int f0 = 16 * u + 4 * q;
-                    if (f0 < a.F2) {
-                        uint2 o;
-                        o.x = pack2<DT>(clampf(d2[u][0], c2), clampf(d2[u][1], c2));
-                        o.y = pack2<DT>(clampf(d2[u][2], c2), clampf(d2[u][3], c2));
-                        *reinterpret_cast<uint2 *>(y16 + (size_t)pix * a.F2 + f0) = o;
-                    }
-                }
-            }
+            for (int u = 0; u < NT2; ++u) d2[u] = mfma16<DT>(A2[u][j], b, d2[u]);
         }
+        const int pix = min((b0 + k) * 16 + n16, a.M - 1);
+#pragma unroll
+        for (int u = 0; u < NT2; ++u) {
+            uint2 o;
+            o.x = pack2<DT>(clampf(d2[u][0], c2), clampf(d2[u][1], c2));
+            o.y = pack2<DT>(clampf(d2[u][2], c2), clampf(d2[u][3], c2));
+            *reinterpret_cast<uint2 *>(y16 + (size_t)pix * a.F2 + fst[u]) = o;
+        }
+    }
+}
+
+template <int DT, int NT1, int NT2>
+__global__ __launch_bounds__(256, 2) void fused_pointwise_pair_kernel(FppArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n16 = lane & 15, q = lane >> 4;
+    const int nblk = (a.M + 15) >> 4;
+    const int nw = gridDim.x * 4, gw = blockIdx.x * 4 + wave;
+    // contiguous run of blocks per wave, remainder spread over the first waves
+    const int base = nblk / nw, extra = nblk % nw;
+    const int b0 = gw * base + min(gw, extra), cnt = base + (gw < extra ? 1 : 0);
+    switch (cnt) { // wave-uniform
+    case 1: fpp_body<DT, NT1, NT2, 1>(a, b0, n16, q, lane); break;
+    case 2: fpp_body<DT, NT1, NT2, 2>(a, b0, n16, q, lane); break;
+    case 3: fpp_body<DT, NT1, NT2, 3>(a, b0, n16, q, lane); break;
+    case 4: fpp_body<DT, NT1, NT2, 4>(a, b0, n16, q, lane); break;
+    case 5: fpp_body<DT, NT1, NT2, 5>(a, b0, n16, q, lane); break;
+    case 6: fpp_body<DT, NT1, NT2, 6>(a, b0, n16, q, lane); break;
+    case 7: fpp_body<DT, NT1, NT2, 7>(a, b0, n16, q, lane); break;
+    case 8: fpp_body<DT, NT1, NT2, 8>(a, b0, n16, q, lane); break;
+    default: break;
     }
 }
 
@@ -434,6 +625,7 @@ int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *w
     // more than kFppBlocksPerWave blocks
     const int min_grid = (nblk + 4 * kFppBlocksPerWave - 1) / (4 * kFppBlocksPerWave);
     unsigned grid = (unsigned)std::max(min_grid, std::min((nblk + 3) / 4, 512));
+    if (const char *e = getenv("NPAS_FPP_GRID")) grid = (unsigned)std::max(min_grid, atoi(e)); // TEMP tuning knob
 #define NPAS_FPP_CASE(N1, N2)                                                              \
     if (nt1 == N1 && nt2 == N2) {                                                          \
         if (dtype == NPAS_BF16) fpp_launch<NPAS_BF16, N1, N2>(a, grid, st);                \

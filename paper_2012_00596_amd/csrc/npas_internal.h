@@ -18,6 +18,7 @@ inline int dtype_size(int dt) { return dt == NPAS_F32 ? 4 : 2; }
 enum Variant {
     V_VALU_F32 = 0,    // fp32 storage: one thread per (pixel, filter sub-group), scalar-broadcast weights
     V_MFMA_GATHER = 1, // 16-bit storage: 16-filter tiles, element-gathered activations, MFMA 16x16x32
+    V_MFMA_SLAB = 2,   // 16-bit storage: 16*NT-filter super-tiles, 8-channel slabs gathered with one 16-byte LDS read
 };
 
 // ---- device execution format for V_MFMA_GATHER -------------------------------
@@ -31,6 +32,16 @@ enum Variant {
 // lane = 16*q + r holds W[filter 16t + r][entries 8q .. 8q+7] (zero where that
 // filter does not keep the position).
 //
+// ---- device execution format for V_MFMA_SLAB ---------------------------------
+// Same arrays, coarser units.  Filters are cut into super-tiles of 16*NT (one wave
+// owns a super-tile and reuses every gathered activation fragment for its NT MFMA
+// row tiles).  A list entry is a slab: 8 consecutive channels (c multiple of 8) at
+// one tap, kept if ANY filter of the super-tile keeps ANY of its 8 weights.
+// Lists are padded to a multiple of 4 slabs (one 32-deep MFMA step).  wfrag holds
+// per step and per row tile j < NT the A-operand image
+//   [(step*NT + j)][lane = 16*q + r][i] = W[filter 16*(st*NT + j) + r][slab 4*step + q, channel c + i].
+// `ntiles` counts super-tiles; tc_ptr is in slabs.
+//
 // ---- device execution format for V_VALU_F32 ----------------------------------
 // Filter groups are cut into sub-groups of VB (<= 8) filters that share the
 // group's list.  vg_ptr[v] .. vg_ptr[v+1] indexes vkent (same entry coding with
@@ -38,7 +49,7 @@ enum Variant {
 struct DeviceFormat {
     int variant = -1;
     // MFMA gather
-    int CC = 0, nchunks = 0, ntiles = 0;
+    int CC = 0, nchunks = 0, ntiles = 0, NT = 1;
     std::vector<int32_t> tc_ptr;
     std::vector<uint32_t> kent;
     std::vector<uint16_t> wfrag;
@@ -105,7 +116,7 @@ struct ConvMfmaArgs {
     const int32_t *tc_ptr;
     const uint32_t *kent;
     const void *wfrag;
-    int CC, nchunks, ntiles;
+    int CC, nchunks, ntiles, NT;
     ConvGeom g;
 };
 
@@ -133,7 +144,7 @@ int upload(npas_packed *p);
 int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, ConvPlan *out);
 
 // launchers (kernels.hip)
-int launch_conv_mfma(int dtype, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream);
+int launch_conv_mfma(int dtype, int variant, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream);
 int launch_conv_valu(const ConvValuArgs &a, void *stream);
 bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "npas_internal.h"
@@ -178,6 +179,86 @@ static void build_mfma_gather(npas_packed *p, const uint8_t *m, const uint8_t *w
     d.tc_ptr.back() = (int32_t)d.kent.size();
 }
 
+
+// Slab format (see npas_internal.h).  NT = row tiles per wave: a wave reuses each
+// gathered activation fragment NT times, so wide layers take NT = 4.
+static void build_mfma_slab(npas_packed *p, const uint8_t *m, const uint8_t *w)
+{
+    DeviceFormat &d = p->fmt;
+    const int F = p->F, C = p->C, KH = p->KH, KW = p->KW;
+    d.variant = V_MFMA_SLAB;
+    d.NT = F >= 256 ? 4 : (F >= 128 ? 2 : 1);
+    d.CC = std::min(C, (KH == 1 && KW == 1) ? 128 : 64);
+    d.nchunks = (C + d.CC - 1) / d.CC;
+    const int SF = 16 * d.NT;
+    d.ntiles = (F + SF - 1) / SF;
+    d.tc_ptr.assign((size_t)d.ntiles * d.nchunks + 1, 0);
+    d.kent.clear();
+    d.wfrag.clear();
+    d.max_list = 0;
+    const uint16_t *w16 = reinterpret_cast<const uint16_t *>(w);
+    const size_t fstride = (size_t)C * KH * KW;
+    std::vector<uint32_t> ent;
+    std::vector<size_t> base;
+    for (int st = 0; st < d.ntiles; ++st) {
+        int f0 = SF * st, nf = std::min(SF, F - f0);
+        for (int ch = 0; ch < d.nchunks; ++ch) {
+            int c0 = ch * d.CC, c1 = std::min(C, c0 + d.CC);
+            ent.clear();
+            base.clear();
+            for (int kh = 0; kh < KH; ++kh)
+                for (int kw = 0; kw < KW; ++kw)
+                    for (int c = c0; c < c1; c += 8) {
+                        bool any = false;
+                        for (int j = 0; j < nf && !any; ++j)
+                            for (int i = 0; i < 8 && !any; ++i) any = m[widx(f0 + j, c + i, kh, kw, C, KH, KW)] != 0;
+                        if (!any) continue;
+                        ent.push_back((uint32_t)kh << 24 | (uint32_t)kw << 16 | (uint32_t)(c - c0));
+                        base.push_back(widx(f0, c, kh, kw, C, KH, KW));
+                    }
+            size_t n = ent.size(), npad = (n + 3) / 4 * 4;
+            d.tc_ptr[(size_t)st * d.nchunks + ch] = (int32_t)d.kent.size();
+            d.max_list = std::max(d.max_list, (int)npad);
+            size_t e0 = d.kent.size();
+            d.kent.resize(e0 + npad, n ? ent[0] : 0u);
+            std::copy(ent.begin(), ent.end(), d.kent.begin() + e0);
+            size_t w0 = d.wfrag.size();
+            d.wfrag.resize(w0 + npad / 4 * d.NT * 512, 0);
+            const size_t cstride = (size_t)KH * KW; // channel stride in W[F][C][KH][KW]
+            for (size_t e = 0; e < n; ++e) {
+                size_t step = e / 4, q = e % 4;
+                for (int j = 0; j < d.NT; ++j)
+                    for (int r = 0; r < 16; ++r) {
+                        int f = f0 + 16 * j + r;
+                        if (f >= F) continue;
+                        for (int i = 0; i < 8; ++i) {
+                            size_t wi = base[e] + (size_t)(16 * j + r) * fstride + (size_t)i * cstride;
+                            if (m[wi]) d.wfrag[w0 + (step * d.NT + j) * 512 + (q * 16 + r) * 8 + i] = w16[wi];
+                        }
+                    }
+            }
+        }
+    }
+    d.tc_ptr.back() = (int32_t)d.kent.size();
+}
+
+// Mean fraction of a 16-filter tile's positions that survive in the union of its groups.
+static double union_density(const npas_packed *p, const uint8_t *m)
+{
+    const int F = p->F, C = p->C, T = p->KH * p->KW;
+    size_t kept = 0, total = 0;
+    for (int t = 0; t * 16 < F; ++t) {
+        int f0 = 16 * t, nf = std::min(16, F - f0);
+        for (size_t pos = 0; pos < (size_t)C * T; ++pos) {
+            bool any = false;
+            for (int j = 0; j < nf && !any; ++j) any = m[(size_t)(f0 + j) * C * T + pos] != 0;
+            kept += any;
+        }
+        total += (size_t)C * T;
+    }
+    return total ? (double)kept / (double)total : 1.0;
+}
+
 static void build_valu_f32(npas_packed *p, const uint8_t *m, const uint8_t *w)
 {
     (void)m;
@@ -217,8 +298,19 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         set_error("layer too large for the entry coding (C <= 65535, KH, KW <= 255)");
         return NPAS_E_SHAPE;
     }
-    if (p->dtype == NPAS_F32) build_valu_f32(p, mask_full.data(), (const uint8_t *)w_host);
-    else build_mfma_gather(p, mask_full.data(), (const uint8_t *)w_host);
+    if (p->dtype == NPAS_F32) {
+        build_valu_f32(p, mask_full.data(), (const uint8_t *)w_host);
+    } else {
+        // Element gather skips exactly what a 16-filter tile's groups punch, at about four
+        // times the operand-fetch cost per kept position of the slab path; it pays once
+        // fewer than a quarter of a tile's positions survive, and it is the only path for
+        // channel counts that are not a multiple of 8.
+        const char *force = getenv("NPAS_FORCE_VARIANT"); // "gather" | "slab": benchmarking aid
+        bool gather = p->C % 8 != 0 || union_density(p, mask_full.data()) < 0.25;
+        if (force && p->C % 8 == 0) gather = strcmp(force, "gather") == 0;
+        if (gather) build_mfma_gather(p, mask_full.data(), (const uint8_t *)w_host);
+        else build_mfma_slab(p, mask_full.data(), (const uint8_t *)w_host);
+    }
     return NPAS_OK;
 }
 
