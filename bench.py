@@ -13,6 +13,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
@@ -28,6 +30,11 @@ def main():
     ap.add_argument("--no-fuse", action="store_true", help="run the two layers as two kernels")
     ap.add_argument("--no-rotate", action="store_true", help="reuse one buffer set (stays in the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--per-layer", type=int, default=0, metavar="CFG",
+                    help="instead of the headline line, print a per-layer table (us, dense-equivalent TFLOP/s, "
+                         "algorithmic GB/s, roofline fraction) for config CFG in 2..5")
+    ap.add_argument("--only", type=str, default="", help="with --per-layer: comma-separated layer indices to run")
+    ap.add_argument("--reps", type=int, default=20, help="with --per-layer: timed launches per layer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -41,6 +48,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.per_layer:
+        return per_layer(args, torch, npas, helpers, configs)
     w = configs.config2(batch=args.batch)
     N, H, W, C = w.x_shape
     npx = N * H * W
@@ -140,6 +149,82 @@ def main():
                                "unit": "TFLOP/s (dense-equivalent)", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": "%d of %d pixels of the same stack, %d repetitions" % (sample_px, npx, reps)}
     print(json.dumps(out))
+
+
+def per_layer(args, torch, npas, helpers, configs):
+    """Per-layer timing of one config, every layer on its own buffers (rotated when small)."""
+    MFMA_PEAK, HBM_PEAK = 2500.0, 8000.0           # TFLOP/s (bf16 dense), GB/s
+    cfg = args.per_layer
+    w = {2: lambda: configs.config2(batch=args.batch), 3: configs.config3, 4: configs.config4,
+         5: lambda: configs.config5(batch=args.batch)}[cfg]()
+    stream = torch.cuda.current_stream().cuda_stream
+    shapes = {0: w.x_shape}
+    rows = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tot_us = tot_flop = tot_bytes = 0.0
+    only = set(int(t) for t in args.only.split(",") if t)
+    for i, L in enumerate(w.layers):
+        ishape = shapes[L.src]
+        oshape = helpers.out_shape(L, ishape)
+        shapes[i + 1] = oshape
+        if only and i not in only:
+            continue
+        esz = 4 if w.dtype == 0 else 2
+        nin, nout = int(np.prod(ishape)), int(np.prod(oshape))
+        packed = helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None
+        wbytes = packed.info()["device_bytes"] if packed else 0
+        abytes = (nin + nout + (nout if L.res >= 0 else 0)) * esz + wbytes
+        nsets = max(1, min(8, -(-600 * 2**20 // max(1, (nin + nout) * esz))))
+        td = torch.float32 if w.dtype == 0 else torch.int16
+        xs = [torch.randint(-3, 3, (nin,), device="cuda").to(td) if w.dtype else torch.randn(nin, device="cuda")
+              for _ in range(nsets)]
+        if w.dtype == 1:   # small finite bf16 values
+            xs = [(torch.randn(nin, device="cuda") ).to(torch.bfloat16).view(torch.int16) for _ in range(nsets)]
+        ys = [torch.empty(nout, dtype=td, device="cuda") for _ in range(nsets)]
+        rs = [torch.zeros(nout, dtype=td, device="cuda") for _ in range(nsets)] if L.res >= 0 else None
+
+        def run(k):
+            if L.kind == "conv":
+                N, H, W_, _ = ishape
+                npas.conv2d_sparse(packed, xs[k], ys[k], N, H, W_, L.stride, L.pad, None, rs[k] if rs else None, L.act, stream)
+            elif L.kind == "fc":
+                npas.fc_sparse(packed, xs[k], ys[k], ishape[0], None, L.act, stream)
+            elif L.kind == "maxpool":
+                N, H, W_, C = ishape
+                npas.maxpool3x3s2(xs[k], ys[k], N, H, W_, C, w.dtype, stream)
+            else:
+                N, H, W_, C = ishape
+                npas.global_avgpool(xs[k], ys[k], N, H, W_, C, w.dtype, stream)
+        reps = args.reps
+        for k in range(3):
+            run(k % nsets)
+        torch.cuda.synchronize()
+        e0.record()
+        for k in range(reps):
+            run(k % nsets)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        macs = 0
+        if L.kind == "conv":
+            macs = oshape[0] * oshape[1] * oshape[2] * L.F * L.C * L.KH * L.KW
+        elif L.kind == "fc":
+            macs = ishape[0] * L.F * L.C
+        flop = 2.0 * macs
+        t_hbm, t_mfma = abytes / (HBM_PEAK * 1e9) * 1e6, flop / (MFMA_PEAK * 1e12) * 1e6
+        bound = "hbm" if t_hbm >= t_mfma else "mfma"
+        frac = max(t_hbm, t_mfma) / us
+        var = packed.info()["variant"] if packed else -1
+        rows.append((i, L.name or L.kind, "x".join(map(str, ishape)), "x".join(map(str, oshape)), L.KH, L.stride, L.rate,
+                     var, us, flop / us / 1e6, abytes / us / 1e3, bound, frac))
+        tot_us += us; tot_flop += flop; tot_bytes += abytes
+        del xs, ys, rs
+        torch.cuda.empty_cache()
+    print("# config %d  %s  (us per launch; TFLOP/s dense-equivalent; GB/s algorithmic; frac = roofline floor / measured)" % (cfg, w.name))
+    print("%3s %-12s %-18s %-18s %2s %1s %4s %3s %9s %9s %9s %5s %6s" % ("i", "layer", "in", "out", "k", "s", "rate", "var", "us", "TFLOP/s", "GB/s", "bound", "frac"))
+    for r in rows:
+        print("%3d %-12s %-18s %-18s %2d %1d %4.1f %3d %9.2f %9.2f %9.1f %5s %6.3f" % r)
+    print("# total %.1f us  %.1f TFLOP/s dense-equivalent  %.1f GB/s algorithmic" % (tot_us, tot_flop / tot_us / 1e6, tot_bytes / tot_us / 1e3))
 
 
 if __name__ == "__main__":

@@ -12,12 +12,40 @@ namespace npas {
 
 static uint32_t magic_div(uint32_t d) { return d <= 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d); }
 
-static const size_t kLdsBudget = 64 * 1024;
+// Best output tile of at most `max_pix` pixels for one launch: candidates are scored by
+// how much of the MFMA columns and of the tile grid does useful work, then by halo
+// overhead.  `max_vec` bounds the 16-byte vectors of one staged patch chunk (0 = no bound).
+static bool pick_tile(const npas_packed *p, ConvGeom &g, int max_pix, int cols_small, size_t lds_budget, int nbuf,
+                      size_t extra_lds, int max_vec, double *cover_out)
+{
+    const bool pointwise = p->KH == 1 && p->KW == 1;
+    const int stride = g.stride;
+    double best = -1e30;
+    bool found = false;
+    for (int TW = 1; TW <= std::min(g.Wo, max_pix); ++TW)
+        for (int TH = 1; TH <= std::min(g.Ho, max_pix / TW); ++TH) {
+            int PH = pointwise ? TH : (TH - 1) * stride + p->KH;
+            int PW = pointwise ? TW : (TW - 1) * stride + p->KW;
+            size_t lds = (((size_t)PH * PW * g.pitch + 15) / 16 * 16) * nbuf + extra_lds;
+            if (lds > lds_budget) continue;
+            if (max_vec && (long)PH * PW * (p->fmt.CC / 8) > max_vec) continue;
+            int used_cols = TH * TW > cols_small ? max_pix : cols_small; // kernel instances walk fixed column counts
+            double cover = (double)g.Ho * g.Wo /
+                           ((double)((g.Ho + TH - 1) / TH) * ((g.Wo + TW - 1) / TW) * used_cols);
+            double halo = (double)PH * PW / ((double)TH * TW);
+            double score = cover - 0.05 * halo + 0.1 * ((double)used_cols / max_pix);
+            if (score > best) {
+                best = score;
+                found = true;
+                g.TH = TH; g.TW = TW; g.PH = PH; g.PW = PW;
+                if (cover_out) *cover_out = cover;
+            }
+        }
+    return found;
+}
 
-// Chooses the output tile of one launch.  A workgroup owns TH x TW output pixels
-// of one image (at most 128 = 8 MFMA column blocks) and stages the matching
-// input patch; candidates are scored by how much of the MFMA columns and of the
-// tile grid do useful work, then by halo overhead.
+// Plans one conv launch: tile shape, grid, LDS bytes.  A workgroup owns TH x TW output
+// pixels of one image and stages the matching input patch.
 int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, ConvPlan *out)
 {
     const DeviceFormat &d = p->fmt;
@@ -40,53 +68,73 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
     // LDS bytes per patch pixel: 16-byte aligned rows for the slab path's 16-byte reads,
     // rows displaced by 8 bytes for the element path's 2-byte gathers (bank spread)
     g.pitch = (d.CC * 2 + 15) / 16 * 16 + (slab ? 16 : 8);
-    g.koff_cap = slab ? 0 : std::min(512, std::max(32, d.max_list));
-    const size_t koff_bytes = (size_t)4 * g.koff_cap * 4;
 
-    double best = -1e30;
-    bool found = false;
-    for (int TW = 1; TW <= std::min(g.Wo, 128); ++TW)
-        for (int TH = 1; TH <= std::min(g.Ho, 128 / TW); ++TH) {
-            int PH = pointwise ? TH : (TH - 1) * stride + p->KH;
-            int PW = pointwise ? TW : (TW - 1) * stride + p->KW;
-            size_t lds = ((size_t)PH * PW * g.pitch + 15) / 16 * 16 + koff_bytes;
-            if (lds > kLdsBudget) continue;
-            int used_cols = TH * TW > 64 ? 128 : 64; // kernel instances walk 4 or 8 column blocks
-            double cover = (double)g.Ho * g.Wo /
-                           ((double)((g.Ho + TH - 1) / TH) * ((g.Wo + TW - 1) / TW) * used_cols);
-            double halo = (double)PH * PW / ((double)TH * TW);
-            double score = cover - 0.05 * halo + 0.1 * (used_cols / 128.0);
-            if (score > best) {
-                best = score;
-                found = true;
-                g.TH = TH; g.TW = TW; g.PH = PH; g.PW = PW;
-            }
+    if (slab) {
+        // persistent double-buffered kernel: two patch buffers, shapes listed at launch_slab_dt
+        const size_t budget = 96 * 1024;
+        const int max_vec = 256 * 8;
+        ConvGeom g128 = g, g64 = g;
+        double c128 = 0, c64 = 0;
+        if (d.NT == 2) {
+            g.shape = 2;
+            if (!pick_tile(p, g, 128, 128, budget, 2, 0, max_vec, nullptr)) goto nofit;
+        } else if (p->F <= 64) {
+            g.shape = 1;
+            if (!pick_tile(p, g, 128, 128, budget, 2, 0, max_vec, nullptr)) goto nofit;
+        } else {
+            bool ok128 = pick_tile(p, g128, 128, 128, budget, 2, 0, max_vec, &c128);
+            bool ok64 = pick_tile(p, g64, 64, 64, budget, 2, 0, max_vec, &c64);
+            if (!ok128 && !ok64) goto nofit;
+            long items128 = ok128 ? (long)g128.N * ((g128.Ho + g128.TH - 1) / g128.TH) * ((g128.Wo + g128.TW - 1) / g128.TW) : 0;
+            // the wider tile unless it wastes MFMA columns or leaves most of the chip idle
+            bool use64 = !ok128 || (ok64 && (c64 > 1.15 * c128 || items128 * ((p->F + 127) / 128) < 256));
+            g = use64 ? g64 : g128;
+            g.shape = use64 ? 3 : 0;
         }
-    if (!found) {
-        set_error("no output tile fits in LDS (kernel %dx%d stride %d)", p->KH, p->KW, stride);
-        return NPAS_E_SHAPE;
+        const int wgf = (g.shape == 0 || g.shape == 3) ? 2 : 1;
+        g.tilesY = (g.Ho + g.TH - 1) / g.TH;
+        g.tilesX = (g.Wo + g.TW - 1) / g.TW;
+        g.div_tw = magic_div(g.TW);
+        g.div_pw = magic_div(g.PW);
+        g.div_vec = magic_div(std::max(1, d.CC / 8));
+        g.div_pitch = magic_div(g.pitch);
+        g.nfsplit = (d.ntiles + wgf - 1) / wgf; // filter blocks per pixel tile
+        g.tiles_per_split = wgf;
+        const long items = (long)g.N * g.tilesY * g.tilesX * g.nfsplit;
+        out->g = g;
+        out->grid = (unsigned)std::min<long>(items, 512);
+        out->lds_bytes = (((size_t)g.PH * g.PW * g.pitch + 15) / 16 * 16) * 2;
+        return NPAS_OK;
     }
-    g.tilesY = (g.Ho + g.TH - 1) / g.TH;
-    g.tilesX = (g.Wo + g.TW - 1) / g.TW;
-    g.div_tw = magic_div(g.TW);
-    g.div_pw = magic_div(g.PW);
-    g.div_vec = magic_div(std::max(1, d.CC / 8));
-    const long ptiles = (long)g.N * g.tilesY * g.tilesX;
-    const int quads = (d.ntiles + 3) / 4; // filter tiles are walked four at a time (one per wave)
-    int nfsplit;
-    if (d.nchunks > 1) nfsplit = quads; // accumulators live across chunks: one quad per workgroup
-    else {
-        long want = (2048 + ptiles - 1) / ptiles; // aim for >= 2048 workgroups
-        nfsplit = (int)std::max(1L, std::min<long>(quads, want));
+    {
+        g.koff_cap = std::min(512, std::max(32, d.max_list));
+        const size_t koff_bytes = (size_t)4 * g.koff_cap * 4;
+        if (!pick_tile(p, g, 128, 64, 64 * 1024, 1, koff_bytes, 0, nullptr)) goto nofit;
+        g.tilesY = (g.Ho + g.TH - 1) / g.TH;
+        g.tilesX = (g.Wo + g.TW - 1) / g.TW;
+        g.div_tw = magic_div(g.TW);
+        g.div_pw = magic_div(g.PW);
+        g.div_vec = magic_div(std::max(1, d.CC / 8));
+        const long ptiles = (long)g.N * g.tilesY * g.tilesX;
+        const int quads = (d.ntiles + 3) / 4; // filter tiles are walked four at a time (one per wave)
+        int nfsplit;
+        if (d.nchunks > 1) nfsplit = quads; // accumulators live across chunks: one quad per workgroup
+        else {
+            long want = (2048 + ptiles - 1) / ptiles; // aim for >= 2048 workgroups
+            nfsplit = (int)std::max(1L, std::min<long>(quads, want));
+        }
+        int quads_per = (quads + nfsplit - 1) / nfsplit;
+        nfsplit = (quads + quads_per - 1) / quads_per;
+        g.nfsplit = nfsplit;
+        g.tiles_per_split = quads_per * 4;
+        out->g = g;
+        out->grid = (unsigned)(ptiles * nfsplit);
+        out->lds_bytes = ((size_t)g.PH * g.PW * g.pitch + 15) / 16 * 16 + koff_bytes;
+        return NPAS_OK;
     }
-    int quads_per = (quads + nfsplit - 1) / nfsplit;
-    nfsplit = (quads + quads_per - 1) / quads_per;
-    g.nfsplit = nfsplit;
-    g.tiles_per_split = quads_per * 4;
-    out->g = g;
-    out->grid = (unsigned)(ptiles * nfsplit);
-    out->lds_bytes = ((size_t)g.PH * g.PW * g.pitch + 15) / 16 * 16 + koff_bytes;
-    return NPAS_OK;
+nofit:
+    set_error("no output tile fits in LDS (kernel %dx%d stride %d)", p->KH, p->KW, stride);
+    return NPAS_E_SHAPE;
 }
 
 static int check_run(const npas_packed *p, const void *x, void *y, int N, int H, int W, int stride, int pad)

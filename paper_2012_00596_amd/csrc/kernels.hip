@@ -285,142 +285,253 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
 
 // ------------------------------------------------------------------------------
 // conv_slab_mfma: the same layers, gathered at 8-channel granularity.  A list entry is
-// an 8-channel slab at one tap; four slabs make one 32-deep MFMA step, and the B
-// operand of a step is one 16-byte LDS read per lane (lane quarter q reads slab 4*step+q
-// of its pixel).  A wave owns a super-tile of 16*NT filters and all S pixel blocks of the
-// workgroup's output tile, so a gathered fragment feeds NT MFMAs and a weight fragment S.
-template <int DT, int S, int NT>
+// an 8-channel slab at one tap; four slabs make one 32-deep MFMA step, and the B operand
+// of a step is one 16-byte LDS read per lane (lane quarter q reads slab 4*step+q of its
+// pixel).  The 4 waves of a workgroup form a WGF x (4/WGF) grid over a tile of
+// 16*WT*WGF filters x 16*WB*(4/WGF) output pixels; a wave reuses each gathered
+// activation fragment for its WT filter tiles and each weight fragment for its WB
+// pixel blocks.
+//
+// Workgroups are persistent: each walks work items (pixel tile, filter block) and,
+// inside an item, the layer's channel chunks.  The activation patch of the NEXT stage
+// is fetched from global memory into registers while the current one is multiplied out
+// of LDS, then written to the other LDS buffer: one barrier per stage, and global loads
+// in flight all the time (what an HBM-bound layer needs).
+constexpr int kSlabPrefetch = 8; // 16-byte vectors of the next patch a thread holds
+
+template <int WT, int WB, int WGF> struct SlabShape {
+    static constexpr int WGP = 4 / WGF;         // waves along pixels
+    static constexpr int TPB = WB * WGP;        // pixel blocks per workgroup tile
+    static constexpr int TFT = WT * WGF;        // filter tiles per workgroup tile
+};
+
+struct SlabItem {
+    int n, ty0, tx0, fb;
+};
+
+__device__ __forceinline__ SlabItem slab_item(const ConvGeom &g, uint32_t item)
+{
+    SlabItem it;
+    const uint32_t nfb = (uint32_t)g.nfsplit;
+    const uint32_t ptile = item / nfb;
+    it.fb = (int)(item - ptile * nfb);
+    const uint32_t tiles_img = (uint32_t)(g.tilesY * g.tilesX);
+    it.n = (int)(ptile / tiles_img);
+    const uint32_t trem = ptile - (uint32_t)it.n * tiles_img;
+    const uint32_t tyi = trem / (uint32_t)g.tilesX;
+    it.ty0 = (int)tyi * g.TH;
+    it.tx0 = (int)(trem - tyi * (uint32_t)g.tilesX) * g.TW;
+    return it;
+}
+
+// What one thread moves of every staged patch chunk: kSlabPrefetch 16-byte vectors.
+// Computed once per kernel (the patch geometry never changes), so that a stage costs an
+// add per vector instead of divisions: grel = element offset of the vector relative to
+// the patch origin pixel and the chunk's first channel, loff = byte offset in the LDS
+// buffer.  Vectors past the end of the patch repeat the last one (same load, same
+// store: harmless).
+struct SlabDesc {
+    int32_t grel[kSlabPrefetch];
+    uint32_t loff[kSlabPrefetch];
+};
+
+__device__ __forceinline__ void slab_desc_init(const ConvMfmaArgs &a, int tid, SlabDesc &d)
+{
+    const ConvGeom &g = a.g;
+    const uint32_t nvv = (uint32_t)a.CC >> 3;
+    const uint32_t total = (uint32_t)(g.PH * g.PW) * nvv;
+#pragma unroll
+    for (int i = 0; i < kSlabPrefetch; ++i) {
+        const uint32_t v = min((uint32_t)tid + 256u * i, total - 1u);
+        const uint32_t pix = fastdiv(v, g.div_vec), cv = v - pix * nvv;
+        const uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
+        d.grel[i] = (int32_t)(((py * g.pstep) * g.W + px * g.pstep) * g.C + cv * 8);
+        d.loff[i] = pix * (uint32_t)g.pitch + cv * 16;
+    }
+}
+
+// Issues the global loads of one patch chunk.  interior: the whole patch lies inside the
+// image and the chunk has all CC channels, so no vector needs a test.
+__device__ __forceinline__ void slab_patch_load(const ConvMfmaArgs &a, const uint8_t *xb, const SlabItem &it, int cc,
+                                                const SlabDesc &d, uint4 (&pf)[kSlabPrefetch])
+{
+    const ConvGeom &g = a.g;
+    const int c0 = cc * a.CC, ccount = min(a.CC, g.C - c0);
+    const int iy0 = (g.pstep > 1 ? it.ty0 * g.pstep : it.ty0 * g.stride) - g.pad;
+    const int ix0 = (g.pstep > 1 ? it.tx0 * g.pstep : it.tx0 * g.stride) - g.pad;
+    const int32_t base = ((it.n * g.H + iy0) * g.W + ix0) * g.C + c0; // may point before the image: only used where valid
+    const bool interior = ccount == a.CC && iy0 >= 0 && ix0 >= 0 && iy0 + (g.PH - 1) * g.pstep < g.H &&
+                          ix0 + (g.PW - 1) * g.pstep < g.W;
+    if (interior) {
+#pragma unroll
+        for (int i = 0; i < kSlabPrefetch; ++i)
+            pf[i] = *reinterpret_cast<const uint4 *>(xb + (uint32_t)(base + d.grel[i]) * 2u);
+    } else {
+#pragma unroll
+        for (int i = 0; i < kSlabPrefetch; ++i) {
+            // border items only: recover the patch pixel from the LDS offset
+            const uint32_t pix = fastdiv(d.loff[i], g.div_pitch), cb = d.loff[i] - pix * (uint32_t)g.pitch;
+            const uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
+            const int iy = iy0 + (int)py * g.pstep, ix = ix0 + (int)px * g.pstep;
+            const bool ok = (uint32_t)iy < (uint32_t)g.H && (uint32_t)ix < (uint32_t)g.W && (int)(cb >> 1) < ccount;
+            pf[i] = uint4{0u, 0u, 0u, 0u};
+            if (ok) pf[i] = *reinterpret_cast<const uint4 *>(xb + (uint32_t)(base + d.grel[i]) * 2u);
+        }
+    }
+}
+
+__device__ __forceinline__ void slab_patch_store(uint8_t *buf, const SlabDesc &d, const uint4 (&pf)[kSlabPrefetch])
+{
+#pragma unroll
+    for (int i = 0; i < kSlabPrefetch; ++i) *reinterpret_cast<uint4 *>(buf + d.loff[i]) = pf[i];
+}
+
+template <int DT, int WT, int WB, int WGF>
 __global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const ConvGeom &g = a.g;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
-
-    const uint32_t logical = xcd_remap(blockIdx.x, gridDim.x);
-    const uint32_t fsplit = logical % (uint32_t)g.nfsplit, ptile = logical / (uint32_t)g.nfsplit;
-    const uint32_t tiles_img = (uint32_t)(g.tilesY * g.tilesX);
-    const int n = (int)(ptile / tiles_img);
-    const uint32_t trem = ptile % tiles_img;
-    const int ty0 = (int)(trem / (uint32_t)g.tilesX) * g.TH, tx0 = (int)(trem % (uint32_t)g.tilesX) * g.TW;
-
+    const int wf = wave % WGF, wp = wave / WGF;
+    const uint32_t nwg = gridDim.x;
+    const uint32_t nitems = (uint32_t)(g.N * g.tilesY * g.tilesX * g.nfsplit);
+    const uint32_t buf_bytes = ((uint32_t)(g.PH * g.PW * g.pitch) + 15u) & ~15u;
+    const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
+    uint8_t *yb = reinterpret_cast<uint8_t *>(a.y);
+    const uint8_t *rb = reinterpret_cast<const uint8_t *>(a.residual);
     const int npix_tile = g.TH * g.TW;
-    uint32_t pixbase[S];
-    int32_t outoff[S];
-#pragma unroll
-    for (int s = 0; s < S; ++s) {
-        uint32_t m = (uint32_t)(s * 16 + n16);
-        uint32_t ty = fastdiv(m, g.div_tw), tx = m - ty * (uint32_t)g.TW;
-        int oy = ty0 + (int)ty, ox = tx0 + (int)tx;
-        bool valid = (int)m < npix_tile && oy < g.Ho && ox < g.Wo;
-        pixbase[s] = valid ? ((ty * g.lstep) * g.PW + tx * g.lstep) * (uint32_t)g.pitch : 0u;
-        outoff[s] = valid ? ((n * g.Ho + oy) * g.Wo + ox) * g.F : -1;
-    }
-    const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
-    const int iy0 = (g.pstep > 1 ? ty0 * g.pstep : ty0 * g.stride) - g.pad;
-    const int ix0 = (g.pstep > 1 ? tx0 * g.pstep : tx0 * g.stride) - g.pad;
+    const Clamp cl = clamp_of(g.act); // F is a multiple of 4 on this path: a lane's 4 outputs are one 8-byte store
 
-    const int st_begin = (int)fsplit * g.tiles_per_split;
-    const int st_end = min(st_begin + g.tiles_per_split, a.ntiles);
-    bool staged = false;
+    uint32_t item = xcd_remap(blockIdx.x, nwg);
+    if (item >= nitems) return;
+    SlabDesc desc;
+    slab_desc_init(a, tid, desc);
+    SlabItem it = slab_item(g, item);
+    uint4 pf[kSlabPrefetch];
+    slab_patch_load(a, xb, it, 0, desc, pf);
+    slab_patch_store(lds, desc, pf);
+    __syncthreads();
+    uint32_t bufoff = 0;
 
-    for (int stb = st_begin; stb < st_end; stb += 4) {
-        const int st = stb + wave;
-        const bool active = st < st_end;
-        f32x4 acc[NT][S];
+    for (;;) { // one work item per iteration
+        const int st = it.fb * WGF + wf; // this wave's super-tile
+        const bool active = st < a.ntiles;
+        const int fl = (st * WT) * 16 + 4 * q; // this lane's first filter in row tile 0
+        // Where this lane's pixel columns sit in the patch and in the output; accumulators
+        // start from bias + residual so that the epilogue only clamps, rounds and stores.
+        uint32_t pixbase[WB], obyte[WB];
+        f32x4 acc[WT][WB];
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+        for (int s = 0; s < WB; ++s) {
+            const uint32_t m = (uint32_t)((wp * WB + s) * 16 + n16);
+            const uint32_t ty = fastdiv(m, g.div_tw), tx = m - ty * (uint32_t)g.TW;
+            const int oy = it.ty0 + (int)ty, ox = it.tx0 + (int)tx;
+            const bool valid = (int)m < npix_tile && oy < g.Ho && ox < g.Wo;
+            pixbase[s] = valid ? ((ty * g.lstep) * g.PW + tx * g.lstep) * (uint32_t)g.pitch : 0u;
+            obyte[s] = valid ? (uint32_t)(((it.n * g.Ho + oy) * g.Wo + ox) * g.F + fl) * 2u : 0xffffffffu;
+        }
 #pragma unroll
-            for (int s = 0; s < S; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-        for (int cc = 0; cc < a.nchunks; ++cc) {
-            if (a.nchunks > 1 || !staged) {
-                __syncthreads();
-                stage_patch<true>(a, lds, x16, n, iy0, ix0, cc, tid);
-                staged = true;
-                __syncthreads();
+        for (int j = 0; j < WT; ++j) {
+            f32x4 b0 = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (a.bias && active) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (fl + 16 * j + i < g.F) b0[i] = a.bias[fl + 16 * j + i];
             }
-            if (!active) continue;
-            const int e0 = a.tc_ptr[st * a.nchunks + cc], e1 = a.tc_ptr[st * a.nchunks + cc + 1];
-            if (e0 >= e1) continue;
-            const uint4 *wf = reinterpret_cast<const uint4 *>(a.wfrag) + (size_t)(e0 >> 2) * NT * 64 + lane;
-            const uint32_t *kp = a.kent + e0 + q;
-            // software pipeline: fetch step i+1's list entry and weight fragments during step i
-            uint32_t ent = *kp;
-            uint4 wa[NT];
 #pragma unroll
-            for (int j = 0; j < NT; ++j) wa[j] = wf[j * 64];
-            for (int e = e0; e < e1; e += 4) {
-                const uint32_t koff = ((ent >> 24) * (uint32_t)g.PW + ((ent >> 16) & 255u)) * (uint32_t)g.pitch + (ent & 0xffffu) * 2u;
-                uint4 wc[NT];
-#pragma unroll
-                for (int j = 0; j < NT; ++j) wc[j] = wa[j];
-                if (e + 4 < e1) {
-                    kp += 4;
-                    wf += NT * 64;
-                    ent = *kp;
-#pragma unroll
-                    for (int j = 0; j < NT; ++j) wa[j] = wf[j * 64];
-                }
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    const uint4 b = *reinterpret_cast<const uint4 *>(lds + pixbase[s] + koff);
-#pragma unroll
-                    for (int j = 0; j < NT; ++j) acc[j][s] = mfma16<DT>(wc[j], b, acc[j][s]);
+            for (int s = 0; s < WB; ++s) {
+                acc[j][s] = b0;
+                if (rb && active && obyte[s] != 0xffffffffu && fl + 16 * j < g.F) {
+                    const uint2 r = *reinterpret_cast<const uint2 *>(rb + obyte[s] + 32u * j);
+                    acc[j][s][0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
+                    acc[j][s][1] += from_storage<DT>((uint16_t)(r.x >> 16));
+                    acc[j][s][2] += from_storage<DT>((uint16_t)(r.y & 0xffffu));
+                    acc[j][s][3] += from_storage<DT>((uint16_t)(r.y >> 16));
                 }
             }
         }
 
-        if (active) {
-            uint16_t *y16 = reinterpret_cast<uint16_t *>(a.y);
-            const uint16_t *r16 = reinterpret_cast<const uint16_t *>(a.residual);
-            const bool vec4 = (g.F & 3) == 0;
-            const Clamp cl = clamp_of(g.act);
+        uint32_t nitem = item + nwg;
+        bool more = nitem < nitems; // another item after this one?
+        SlabItem nit = it;
+        for (int cc = 0; cc < a.nchunks; ++cc) {
+            // ---- next stage's patch: global loads go out now, land while we multiply ----
+            const bool last = cc == a.nchunks - 1;
+            const bool has_next = !last || more;
+            if (has_next) {
+                if (last) nit = slab_item(g, nitem);
+                slab_patch_load(a, xb, last ? nit : it, last ? 0 : cc + 1, desc, pf);
+            }
+            // ---- multiply the current stage out of LDS ---------------------------------
+            if (active) {
+                const int e0 = a.tc_ptr[st * a.nchunks + cc], e1 = a.tc_ptr[st * a.nchunks + cc + 1];
+                if (e0 < e1) {
+                    const uint8_t *wfb = reinterpret_cast<const uint8_t *>(a.wfrag);
+                    const uint8_t *keb = reinterpret_cast<const uint8_t *>(a.kent);
+                    uint32_t wby = (uint32_t)(e0 >> 2) * (WT * 1024u) + (uint32_t)lane * 16u, kby = (uint32_t)(e0 + q) * 4u;
+                    uint32_t ent = *reinterpret_cast<const uint32_t *>(keb + kby);
+                    uint4 wa[WT];
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                const int f0 = (st * NT + j) * 16 + 4 * q;
-                if (f0 >= g.F) continue;
-                float bv[4] = {0.f, 0.f, 0.f, 0.f};
-                if (a.bias) {
+                    for (int j = 0; j < WT; ++j) wa[j] = *reinterpret_cast<const uint4 *>(wfb + wby + j * 1024u);
+                    for (int e = e0; e < e1; e += 4) {
+                        const uint32_t koff = bufoff + ((ent >> 24) * (uint32_t)g.PW + ((ent >> 16) & 255u)) * (uint32_t)g.pitch +
+                                              (ent & 0xffffu) * 2u;
+                        uint4 wc[WT];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (f0 + i < g.F) bv[i] = a.bias[f0 + i];
-                }
+                        for (int j = 0; j < WT; ++j) wc[j] = wa[j];
+                        if (e + 4 < e1) { // fetch the next step's entry and weight fragments during this step
+                            kby += 16u;
+                            wby += WT * 1024u;
+                            ent = *reinterpret_cast<const uint32_t *>(keb + kby);
 #pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    if (outoff[s] < 0) continue;
-                    const size_t o = (size_t)outoff[s] + f0;
-                    float v[4] = {acc[j][s][0] + bv[0], acc[j][s][1] + bv[1], acc[j][s][2] + bv[2], acc[j][s][3] + bv[3]};
-                    if (vec4) {
-                        if (r16) {
-                            uint2 r = *reinterpret_cast<const uint2 *>(r16 + o);
-                            v[0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
-                            v[1] += from_storage<DT>((uint16_t)(r.x >> 16));
-                            v[2] += from_storage<DT>((uint16_t)(r.y & 0xffffu));
-                            v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
+                            for (int j = 0; j < WT; ++j) wa[j] = *reinterpret_cast<const uint4 *>(wfb + wby + j * 1024u);
                         }
-                        uint2 out;
-                        out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-                        out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                        *reinterpret_cast<uint2 *>(y16 + o) = out;
-                    } else {
+                        uint4 b[WB];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (f0 + i < g.F) {
-                                float t = v[i];
-                                if (r16) t += from_storage<DT>(r16[o + i]);
-                                y16[o + i] = (uint16_t)(pack2<DT>(clampf(t, cl), 0.f) & 0xffffu);
-                            }
+                        for (int s = 0; s < WB; ++s) b[s] = *reinterpret_cast<const uint4 *>(lds + pixbase[s] + koff);
+#pragma unroll
+                        for (int s = 0; s < WB; ++s)
+#pragma unroll
+                            for (int j = 0; j < WT; ++j) acc[j][s] = mfma16<DT>(wc[j], b[s], acc[j][s]);
                     }
                 }
             }
+            if (has_next) slab_patch_store(lds + (bufoff ^ buf_bytes), desc, pf);
+            if (last && active) {
+                // ---- clamp (activation), round, store --------------------------------------
+#pragma unroll
+                for (int j = 0; j < WT; ++j) {
+                    const int f0 = fl + 16 * j;
+                    if (f0 >= g.F) continue;
+#pragma unroll
+                    for (int s = 0; s < WB; ++s) {
+                        if (obyte[s] == 0xffffffffu) continue;
+                        uint2 out;
+                        out.x = pack2<DT>(clampf(acc[j][s][0], cl), clampf(acc[j][s][1], cl));
+                        out.y = pack2<DT>(clampf(acc[j][s][2], cl), clampf(acc[j][s][3], cl));
+                        *reinterpret_cast<uint2 *>(yb + obyte[s] + 32u * j) = out;
+                    }
+                }
+            }
+            __syncthreads();
+            bufoff ^= buf_bytes;
         }
+        if (!more) break;
+        item = nitem;
+        it = nit;
     }
 }
 
-template <int DT, int S, int NT>
+template <int DT, int WT, int WB, int WGF>
 static int launch_slab_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
-    hipLaunchKernelGGL((conv_slab_mfma_kernel<DT, S, NT>), dim3(grid), dim3(256), lds_bytes, st, a);
+    auto kern = conv_slab_mfma_kernel<DT, WT, WB, WGF>;
+    static bool attr_done = false; // one flag per instantiation
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds_bytes, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("conv_slab_mfma launch failed: %s", hipGetErrorString(e));
@@ -429,15 +540,18 @@ static int launch_slab_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_byt
     return NPAS_OK;
 }
 
+// Workgroup shapes (filter tiles per wave, pixel blocks per wave, waves along filters):
+//   0: 4 x 4 x 2 -> 128 filters x 128 pixels     2: 2 x 2 x 1 -> 32 filters x 128 pixels
+//   1: 4 x 2 x 1 ->  64 filters x 128 pixels     3: 4 x 2 x 2 -> 128 filters x  64 pixels
 template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
-    const bool s8 = a.g.TH * a.g.TW > 64;
-    switch (a.NT) {
-    case 1: return s8 ? launch_slab_inst<DT, 8, 1>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 1>(a, grid, lds_bytes, st);
-    case 2: return s8 ? launch_slab_inst<DT, 8, 2>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 2>(a, grid, lds_bytes, st);
-    case 4: return s8 ? launch_slab_inst<DT, 8, 4>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 4>(a, grid, lds_bytes, st);
+    switch (a.g.shape) {
+    case 0: return launch_slab_inst<DT, 4, 4, 2>(a, grid, lds_bytes, st);
+    case 1: return launch_slab_inst<DT, 4, 2, 1>(a, grid, lds_bytes, st);
+    case 2: return launch_slab_inst<DT, 2, 2, 1>(a, grid, lds_bytes, st);
+    case 3: return launch_slab_inst<DT, 4, 2, 2>(a, grid, lds_bytes, st);
     }
-    set_error("conv_slab_mfma: unsupported tiles per wave %d", a.NT);
+    set_error("conv_slab_mfma: unknown workgroup shape %d", a.g.shape);
     return NPAS_E_SHAPE;
 }
 

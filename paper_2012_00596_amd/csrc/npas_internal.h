@@ -104,8 +104,9 @@ struct ConvGeom {
     int nfsplit;          // filter-tile splits (grid = pixel tiles x nfsplit)
     int tiles_per_split;  // filter tiles one workgroup walks through
     int koff_cap;         // per-wave capacity of the offset table, entries
-    uint32_t div_tw, div_pw, div_vec; // magic reciprocals (see fastdiv)
+    uint32_t div_tw, div_pw, div_vec, div_pitch; // magic reciprocals (see fastdiv)
     int vec;              // 1: 16-byte staging path (C and CC multiples of 8)
+    int shape;            // slab path: workgroup shape index (see launch_slab_dt)
 };
 
 struct ConvMfmaArgs {

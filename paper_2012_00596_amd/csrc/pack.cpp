@@ -181,14 +181,14 @@ static void build_mfma_gather(npas_packed *p, const uint8_t *m, const uint8_t *w
 
 
 // Slab format (see npas_internal.h).  NT = row tiles per wave: a wave reuses each
-// gathered activation fragment NT times, so wide layers take NT = 4.
+// gathered activation fragment NT times.
 static void build_mfma_slab(npas_packed *p, const uint8_t *m, const uint8_t *w)
 {
     DeviceFormat &d = p->fmt;
     const int F = p->F, C = p->C, KH = p->KH, KW = p->KW;
     d.variant = V_MFMA_SLAB;
-    d.NT = F >= 256 ? 4 : (F >= 128 ? 2 : 1);
-    d.CC = std::min(C, (KH == 1 && KW == 1) ? 128 : 64);
+    d.NT = F > 32 ? 4 : 2;
+    d.CC = std::min(C, 64);
     d.nchunks = (C + d.CC - 1) / d.CC;
     const int SF = 16 * d.NT;
     d.ntiles = (F + SF - 1) / SF;
@@ -304,10 +304,11 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         // Element gather skips exactly what a 16-filter tile's groups punch, at about four
         // times the operand-fetch cost per kept position of the slab path; it pays once
         // fewer than a quarter of a tile's positions survive, and it is the only path for
-        // channel counts that are not a multiple of 8.
+        // channel counts that are not a multiple of 8 or filter counts that are not a multiple of 4.
         const char *force = getenv("NPAS_FORCE_VARIANT"); // "gather" | "slab": benchmarking aid
-        bool gather = p->C % 8 != 0 || union_density(p, mask_full.data()) < 0.25;
-        if (force && p->C % 8 == 0) gather = strcmp(force, "gather") == 0;
+        const bool slab_ok = p->C % 8 == 0 && p->F % 4 == 0;
+        bool gather = !slab_ok || union_density(p, mask_full.data()) < 0.25;
+        if (force && slab_ok) gather = strcmp(force, "gather") == 0;
         if (gather) build_mfma_gather(p, mask_full.data(), (const uint8_t *)w_host);
         else build_mfma_slab(p, mask_full.data(), (const uint8_t *)w_host);
     }
