@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--per-layer", type=int, default=0, metavar="CFG",
                     help="instead of the headline line, print a per-layer table (us, dense-equivalent TFLOP/s, "
                          "algorithmic GB/s, roofline fraction) for config CFG in 2..5")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MB",
+                    help="instead of the benchmark, run 5 plain device copies of MB megabytes (known traffic for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--only", type=str, default="", help="with --per-layer: comma-separated layer indices to run")
     ap.add_argument("--reps", type=int, default=20, help="with --per-layer: timed launches per layer")
     args = ap.parse_args()
@@ -48,6 +51,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = args.copy_calibration * 2**20
+        src = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 5}))
+        return
     if args.per_layer:
         return per_layer(args, torch, npas, helpers, configs)
     w = configs.config2(batch=args.batch)

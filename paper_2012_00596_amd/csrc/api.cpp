@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 
@@ -88,6 +89,10 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
             long items128 = ok128 ? (long)g128.N * ((g128.Ho + g128.TH - 1) / g128.TH) * ((g128.Wo + g128.TW - 1) / g128.TW) : 0;
             // the wider tile unless it wastes MFMA columns or leaves most of the chip idle
             bool use64 = !ok128 || (ok64 && (c64 > 1.15 * c128 || items128 * ((p->F + 127) / 128) < 256));
+            if (const char *e = getenv("NPAS_SLAB_SHAPE")) { // TEMP tuning knob
+                if (atoi(e) == 3 && ok64) use64 = true;
+                if (atoi(e) == 0 && ok128) use64 = false;
+            }
             g = use64 ? g64 : g128;
             g.shape = use64 ? 3 : 0;
         }
@@ -102,7 +107,11 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
         g.tiles_per_split = wgf;
         const long items = (long)g.N * g.tilesY * g.tilesX * g.nfsplit;
         out->g = g;
-        out->grid = (unsigned)std::min<long>(items, 512);
+        {
+            const bool small = g.PH * g.PW * (d.CC / 8) <= 1024;
+            const int occ = g.shape == 0 ? 2 : (small ? (g.shape == 2 ? 4 : 3) : (g.shape == 2 ? 3 : 2));
+            out->grid = (unsigned)std::min<long>(items, 256L * occ);
+        }
         out->lds_bytes = (((size_t)g.PH * g.PW * g.pitch + 15) / 16 * 16) * 2;
         return NPAS_OK;
     }

@@ -297,7 +297,6 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
 // is fetched from global memory into registers while the current one is multiplied out
 // of LDS, then written to the other LDS buffer: one barrier per stage, and global loads
 // in flight all the time (what an HBM-bound layer needs).
-constexpr int kSlabPrefetch = 8; // 16-byte vectors of the next patch a thread holds
 
 template <int WT, int WB, int WGF> struct SlabShape {
     static constexpr int WGP = 4 / WGF;         // waves along pixels
@@ -324,24 +323,24 @@ __device__ __forceinline__ SlabItem slab_item(const ConvGeom &g, uint32_t item)
     return it;
 }
 
-// What one thread moves of every staged patch chunk: kSlabPrefetch 16-byte vectors.
+// What one thread moves of every staged patch chunk: NPF 16-byte vectors.
 // Computed once per kernel (the patch geometry never changes), so that a stage costs an
 // add per vector instead of divisions: grel = element offset of the vector relative to
 // the patch origin pixel and the chunk's first channel, loff = byte offset in the LDS
 // buffer.  Vectors past the end of the patch repeat the last one (same load, same
 // store: harmless).
-struct SlabDesc {
-    int32_t grel[kSlabPrefetch];
-    uint32_t loff[kSlabPrefetch];
+template <int NPF> struct SlabDesc { // NPF = 16-byte vectors of a patch chunk one thread moves
+    int32_t grel[NPF];
+    uint32_t loff[NPF];
 };
 
-__device__ __forceinline__ void slab_desc_init(const ConvMfmaArgs &a, int tid, SlabDesc &d)
+template <int NPF> __device__ __forceinline__ void slab_desc_init(const ConvMfmaArgs &a, int tid, SlabDesc<NPF> &d)
 {
     const ConvGeom &g = a.g;
     const uint32_t nvv = (uint32_t)a.CC >> 3;
     const uint32_t total = (uint32_t)(g.PH * g.PW) * nvv;
 #pragma unroll
-    for (int i = 0; i < kSlabPrefetch; ++i) {
+    for (int i = 0; i < NPF; ++i) {
         const uint32_t v = min((uint32_t)tid + 256u * i, total - 1u);
         const uint32_t pix = fastdiv(v, g.div_vec), cv = v - pix * nvv;
         const uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
@@ -352,8 +351,9 @@ __device__ __forceinline__ void slab_desc_init(const ConvMfmaArgs &a, int tid, S
 
 // Issues the global loads of one patch chunk.  interior: the whole patch lies inside the
 // image and the chunk has all CC channels, so no vector needs a test.
+template <int NPF>
 __device__ __forceinline__ void slab_patch_load(const ConvMfmaArgs &a, const uint8_t *xb, const SlabItem &it, int cc,
-                                                const SlabDesc &d, uint4 (&pf)[kSlabPrefetch])
+                                                const SlabDesc<NPF> &d, uint4 (&pf)[NPF])
 {
     const ConvGeom &g = a.g;
     const int c0 = cc * a.CC, ccount = min(a.CC, g.C - c0);
@@ -364,11 +364,11 @@ __device__ __forceinline__ void slab_patch_load(const ConvMfmaArgs &a, const uin
                           ix0 + (g.PW - 1) * g.pstep < g.W;
     if (interior) {
 #pragma unroll
-        for (int i = 0; i < kSlabPrefetch; ++i)
+        for (int i = 0; i < NPF; ++i)
             pf[i] = *reinterpret_cast<const uint4 *>(xb + (uint32_t)(base + d.grel[i]) * 2u);
     } else {
 #pragma unroll
-        for (int i = 0; i < kSlabPrefetch; ++i) {
+        for (int i = 0; i < NPF; ++i) {
             // border items only: recover the patch pixel from the LDS offset
             const uint32_t pix = fastdiv(d.loff[i], g.div_pitch), cb = d.loff[i] - pix * (uint32_t)g.pitch;
             const uint32_t py = fastdiv(pix, g.div_pw), px = pix - py * (uint32_t)g.PW;
@@ -380,14 +380,15 @@ __device__ __forceinline__ void slab_patch_load(const ConvMfmaArgs &a, const uin
     }
 }
 
-__device__ __forceinline__ void slab_patch_store(uint8_t *buf, const SlabDesc &d, const uint4 (&pf)[kSlabPrefetch])
+template <int NPF>
+__device__ __forceinline__ void slab_patch_store(uint8_t *buf, const SlabDesc<NPF> &d, const uint4 (&pf)[NPF])
 {
 #pragma unroll
-    for (int i = 0; i < kSlabPrefetch; ++i) *reinterpret_cast<uint4 *>(buf + d.loff[i]) = pf[i];
+    for (int i = 0; i < NPF; ++i) *reinterpret_cast<uint4 *>(buf + d.loff[i]) = pf[i];
 }
 
-template <int DT, int WT, int WB, int WGF>
-__global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
+template <int DT, int WT, int WB, int WGF, int NPF, int OCC>
+__global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const ConvGeom &g = a.g;
@@ -404,10 +405,10 @@ __global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
 
     uint32_t item = xcd_remap(blockIdx.x, nwg);
     if (item >= nitems) return;
-    SlabDesc desc;
+    SlabDesc<NPF> desc;
     slab_desc_init(a, tid, desc);
     SlabItem it = slab_item(g, item);
-    uint4 pf[kSlabPrefetch];
+    uint4 pf[NPF];
     slab_patch_load(a, xb, it, 0, desc, pf);
     slab_patch_store(lds, desc, pf);
     __syncthreads();
@@ -418,7 +419,7 @@ __global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
         const bool active = st < a.ntiles;
         const int fl = (st * WT) * 16 + 4 * q; // this lane's first filter in row tile 0
         // Where this lane's pixel columns sit in the patch and in the output; accumulators
-        // start from bias + residual so that the epilogue only clamps, rounds and stores.
+        // start from the bias.
         uint32_t pixbase[WB], obyte[WB];
         f32x4 acc[WT][WB];
 #pragma unroll
@@ -439,16 +440,7 @@ __global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
                     if (fl + 16 * j + i < g.F) b0[i] = a.bias[fl + 16 * j + i];
             }
 #pragma unroll
-            for (int s = 0; s < WB; ++s) {
-                acc[j][s] = b0;
-                if (rb && active && obyte[s] != 0xffffffffu && fl + 16 * j < g.F) {
-                    const uint2 r = *reinterpret_cast<const uint2 *>(rb + obyte[s] + 32u * j);
-                    acc[j][s][0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
-                    acc[j][s][1] += from_storage<DT>((uint16_t)(r.x >> 16));
-                    acc[j][s][2] += from_storage<DT>((uint16_t)(r.y & 0xffffu));
-                    acc[j][s][3] += from_storage<DT>((uint16_t)(r.y >> 16));
-                }
-            }
+            for (int s = 0; s < WB; ++s) acc[j][s] = b0;
         }
 
         uint32_t nitem = item + nwg;
@@ -461,6 +453,18 @@ __global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
             if (has_next) {
                 if (last) nit = slab_item(g, nitem);
                 slab_patch_load(a, xb, last ? nit : it, last ? 0 : cc + 1, desc, pf);
+            }
+            // ---- residual: fetched ahead of the item's last chunk, added after it -----------
+            uint2 res[WT][WB];
+            if (last && rb && active) {
+#pragma unroll
+                for (int j = 0; j < WT; ++j)
+#pragma unroll
+                    for (int s = 0; s < WB; ++s) {
+                        res[j][s] = uint2{0u, 0u};
+                        if (obyte[s] != 0xffffffffu && fl + 16 * j < g.F)
+                            res[j][s] = *reinterpret_cast<const uint2 *>(rb + obyte[s] + 32u * j);
+                    }
             }
             // ---- multiply the current stage out of LDS ---------------------------------
             if (active) {
@@ -506,6 +510,12 @@ __global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
 #pragma unroll
                     for (int s = 0; s < WB; ++s) {
                         if (obyte[s] == 0xffffffffu) continue;
+                        if (rb) {
+                            acc[j][s][0] += from_storage<DT>((uint16_t)(res[j][s].x & 0xffffu));
+                            acc[j][s][1] += from_storage<DT>((uint16_t)(res[j][s].x >> 16));
+                            acc[j][s][2] += from_storage<DT>((uint16_t)(res[j][s].y & 0xffffu));
+                            acc[j][s][3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
+                        }
                         uint2 out;
                         out.x = pack2<DT>(clampf(acc[j][s][0], cl), clampf(acc[j][s][1], cl));
                         out.y = pack2<DT>(clampf(acc[j][s][2], cl), clampf(acc[j][s][3], cl));
@@ -522,10 +532,10 @@ __global__ __launch_bounds__(256, 2) void conv_slab_mfma_kernel(ConvMfmaArgs a)
     }
 }
 
-template <int DT, int WT, int WB, int WGF>
+template <int DT, int WT, int WB, int WGF, int NPF, int OCC>
 static int launch_slab_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
-    auto kern = conv_slab_mfma_kernel<DT, WT, WB, WGF>;
+    auto kern = conv_slab_mfma_kernel<DT, WT, WB, WGF, NPF, OCC>;
     static bool attr_done = false; // one flag per instantiation
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
@@ -543,13 +553,15 @@ static int launch_slab_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_byt
 // Workgroup shapes (filter tiles per wave, pixel blocks per wave, waves along filters):
 //   0: 4 x 4 x 2 -> 128 filters x 128 pixels     2: 2 x 2 x 1 -> 32 filters x 128 pixels
 //   1: 4 x 2 x 1 ->  64 filters x 128 pixels     3: 4 x 2 x 2 -> 128 filters x  64 pixels
+// Each with 4 or 8 staged vectors per thread (patch chunk of up to 1024 / 2048 vectors).
 template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
+    const bool small = a.g.PH * a.g.PW * (a.CC / 8) <= 1024;
     switch (a.g.shape) {
-    case 0: return launch_slab_inst<DT, 4, 4, 2>(a, grid, lds_bytes, st);
-    case 1: return launch_slab_inst<DT, 4, 2, 1>(a, grid, lds_bytes, st);
-    case 2: return launch_slab_inst<DT, 2, 2, 1>(a, grid, lds_bytes, st);
-    case 3: return launch_slab_inst<DT, 4, 2, 2>(a, grid, lds_bytes, st);
+    case 0: return small ? launch_slab_inst<DT, 4, 4, 2, 4, 2>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 4, 2, 8, 2>(a, grid, lds_bytes, st);
+    case 1: return small ? launch_slab_inst<DT, 4, 2, 1, 4, 3>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 2, 1, 8, 2>(a, grid, lds_bytes, st);
+    case 2: return small ? launch_slab_inst<DT, 2, 2, 1, 4, 4>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 2, 2, 1, 8, 3>(a, grid, lds_bytes, st);
+    case 3: return small ? launch_slab_inst<DT, 4, 2, 2, 4, 3>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 2, 2, 8, 2>(a, grid, lds_bytes, st);
     }
     set_error("conv_slab_mfma: unknown workgroup shape %d", a.g.shape);
     return NPAS_E_SHAPE;
@@ -860,6 +872,46 @@ __global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const void *x, void *
     }
 }
 
+// 16-bit storage, C a multiple of 8: one thread owns 8 channels of one output pixel
+// (16-byte loads and stores).  Values are compared as floats; the winner's bits are kept.
+template <int DT>
+__global__ __launch_bounds__(256) void maxpool3x3s2_vec8_kernel(const uint4 *x, uint4 *y, int N, int H, int W, int C8,
+                                                                int Ho, int Wo)
+{
+    const uint32_t total = (uint32_t)(N * Ho * Wo * C8);
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < total; i += gridDim.x * 256u) {
+        const uint32_t c = i % (uint32_t)C8;
+        uint32_t t = i / (uint32_t)C8;
+        const int ox = (int)(t % (uint32_t)Wo);
+        t /= (uint32_t)Wo;
+        const int oy = (int)(t % (uint32_t)Ho), n = (int)(t / (uint32_t)Ho);
+        float m[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) m[k] = -INFINITY;
+        for (int kh = 0; kh < 3; ++kh) {
+            const int iy = 2 * oy + kh - 1;
+            if (iy < 0 || iy >= H) continue;
+            for (int kw = 0; kw < 3; ++kw) {
+                const int ix = 2 * ox + kw - 1;
+                if (ix < 0 || ix >= W) continue;
+                const uint4 v = x[(uint32_t)((n * H + iy) * W + ix) * (uint32_t)C8 + c];
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    m[2 * k] = fmaxf(m[2 * k], from_storage<DT>((uint16_t)(w[k] & 0xffffu)));
+                    m[2 * k + 1] = fmaxf(m[2 * k + 1], from_storage<DT>((uint16_t)(w[k] >> 16)));
+                }
+            }
+        }
+        uint4 o;
+        o.x = pack2<DT>(m[0], m[1]);
+        o.y = pack2<DT>(m[2], m[3]);
+        o.z = pack2<DT>(m[4], m[5]);
+        o.w = pack2<DT>(m[6], m[7]);
+        y[i] = o;
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(256) void global_avgpool_kernel(const void *x, void *y, int N, int HW, int C)
 {
@@ -877,7 +929,13 @@ int launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int dt, v
     const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
     size_t total = (size_t)N * Ho * Wo * C;
     unsigned grid = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 64);
-    if (dt == NPAS_F32) hipLaunchKernelGGL(maxpool3x3s2_kernel<NPAS_F32>, dim3(grid), dim3(256), 0, st, x, y, N, H, W, C, Ho, Wo);
+    if (dt != NPAS_F32 && C % 8 == 0) {
+        grid = (unsigned)std::min<size_t>((total / 8 + 255) / 256, 256 * 32);
+        if (dt == NPAS_BF16)
+            hipLaunchKernelGGL(maxpool3x3s2_vec8_kernel<NPAS_BF16>, dim3(grid), dim3(256), 0, st, (const uint4 *)x, (uint4 *)y, N, H, W, C / 8, Ho, Wo);
+        else
+            hipLaunchKernelGGL(maxpool3x3s2_vec8_kernel<NPAS_F16>, dim3(grid), dim3(256), 0, st, (const uint4 *)x, (uint4 *)y, N, H, W, C / 8, Ho, Wo);
+    } else if (dt == NPAS_F32) hipLaunchKernelGGL(maxpool3x3s2_kernel<NPAS_F32>, dim3(grid), dim3(256), 0, st, x, y, N, H, W, C, Ho, Wo);
     else if (dt == NPAS_BF16) hipLaunchKernelGGL(maxpool3x3s2_kernel<NPAS_BF16>, dim3(grid), dim3(256), 0, st, x, y, N, H, W, C, Ho, Wo);
     else hipLaunchKernelGGL(maxpool3x3s2_kernel<NPAS_F16>, dim3(grid), dim3(256), 0, st, x, y, N, H, W, C, Ho, Wo);
     hipError_t e = hipGetLastError();

@@ -225,12 +225,13 @@ def test_full_size_config4_sampled_images(npas, torch):
 
 
 def test_pools(npas, torch):
-    for dtype in (dtypes.BF16, dtypes.F32):
-        xs, xe = dtypes.quantize(prng.normal(9, 1, 2 * 9 * 11 * 24).reshape(2, 9, 11, 24), dtype)
+    # C = 24 takes the 8-channel vector path for 16-bit storage, C = 5 the scalar one
+    for dtype, C in ((dtypes.BF16, 24), (dtypes.F16, 24), (dtypes.BF16, 5), (dtypes.F32, 24)):
+        xs, xe = dtypes.quantize(prng.normal(9, 1, 2 * 9 * 11 * C).reshape(2, 9, 11, C), dtype)
         x = to_dev(xs, torch)
-        y = new_dev((2, 5, 6, 24), dtype, torch)
-        npas.maxpool3x3s2(x, y, 2, 9, 11, 24, dtype)
-        np.testing.assert_array_equal(from_dev(y, dtype).reshape(2, 5, 6, 24), oracle.maxpool3x3s2(xe))
-        z = new_dev((2, 24), dtype, torch)
-        npas.global_avgpool(x, z, 2, 9, 11, 24, dtype)
-        assert rel_err(from_dev(z, dtype).reshape(2, 24), oracle.round_to(oracle.global_avgpool(xe), dtype)) <= TOL[dtype]
+        y = new_dev((2, 5, 6, C), dtype, torch)
+        npas.maxpool3x3s2(x, y, 2, 9, 11, C, dtype)
+        np.testing.assert_array_equal(from_dev(y, dtype).reshape(2, 5, 6, C), oracle.maxpool3x3s2(xe))
+        z = new_dev((2, C), dtype, torch)
+        npas.global_avgpool(x, z, 2, 9, 11, C, dtype)
+        assert rel_err(from_dev(z, dtype).reshape(2, C), oracle.round_to(oracle.global_avgpool(xe), dtype)) <= TOL[dtype]
