@@ -76,7 +76,10 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
         const int max_vec = 256 * 8;
         ConvGeom g128 = g, g64 = g;
         double c128 = 0, c64 = 0;
-        if (d.NT == 2) {
+        if (d.NT == 2 && p->F > 32) { // 64 filters x 64 pixels, small accumulators, many workgroups per CU
+            g.shape = 4;
+            if (!pick_tile(p, g, 64, 64, budget, 2, 0, max_vec, nullptr)) goto nofit;
+        } else if (d.NT == 2) {
             g.shape = 2;
             if (!pick_tile(p, g, 128, 128, budget, 2, 0, max_vec, nullptr)) goto nofit;
         } else if (p->F <= 64) {
@@ -96,7 +99,7 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
             g = use64 ? g64 : g128;
             g.shape = use64 ? 3 : 0;
         }
-        const int wgf = (g.shape == 0 || g.shape == 3) ? 2 : 1;
+        const int wgf = (g.shape == 0 || g.shape == 3 || g.shape == 4) ? 2 : 1;
         g.tilesY = (g.Ho + g.TH - 1) / g.TH;
         g.tilesX = (g.Wo + g.TW - 1) / g.TW;
         g.div_tw = magic_div(g.TW);
@@ -109,7 +112,7 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
         out->g = g;
         {
             const bool small = g.PH * g.PW * (d.CC / 8) <= 1024;
-            const int occ = g.shape == 0 ? 2 : (small ? (g.shape == 2 ? 4 : 3) : (g.shape == 2 ? 3 : 2));
+            const int occ = g.shape == 4 ? 5 : g.shape == 0 ? 2 : (small ? (g.shape == 2 ? 4 : 3) : (g.shape == 2 ? 3 : 2));
             out->grid = (unsigned)std::min<long>(items, 256L * occ);
         }
         out->lds_bytes = (((size_t)g.PH * g.PW * g.pitch + 15) / 16 * 16) * 2;
@@ -188,6 +191,22 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.Ho = (H + 2 * pad - p->KH) / stride + 1; a.Wo = (W + 2 * pad - p->KW) / stride + 1;
         a.KH = p->KH; a.KW = p->KW; a.stride = stride; a.pad = pad; a.act = act;
         return launch_conv_valu(a, stream);
+    }
+    if (p->ring.present && pad == 0) { // streaming 1x1 path
+        RingArgs a;
+        a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
+        a.rg_ptr = p->dev.rg_ptr; a.rg_chunk = p->dev.rg_chunk; a.wimg = p->dev.wimg;
+        a.C = p->C; a.F = p->F;
+        a.H = H; a.W = W; a.stride = stride;
+        a.Ho = (H - 1) / stride + 1; a.Wo = (W - 1) / stride + 1;
+        a.M = N * a.Ho * a.Wo;
+        a.nptiles = (a.M + 255) / 256;
+        a.nfb = p->ring.nfb;
+        a.act = act;
+        a.flat = stride == 1;
+        a.div_howo = magic_div((uint32_t)(a.Ho * a.Wo));
+        a.div_wo = magic_div((uint32_t)a.Wo);
+        return launch_pointwise_ring(p->dtype, a, stream);
     }
     ConvPlan local;
     if (!plan) {

@@ -562,9 +562,290 @@ template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid
     case 1: return small ? launch_slab_inst<DT, 4, 2, 1, 4, 3>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 2, 1, 8, 2>(a, grid, lds_bytes, st);
     case 2: return small ? launch_slab_inst<DT, 2, 2, 1, 4, 4>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 2, 2, 1, 8, 3>(a, grid, lds_bytes, st);
     case 3: return small ? launch_slab_inst<DT, 4, 2, 2, 4, 3>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 2, 2, 8, 2>(a, grid, lds_bytes, st);
+    case 4: return small ? launch_slab_inst<DT, 2, 2, 2, 4, 5>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 2, 2, 2, 8, 3>(a, grid, lds_bytes, st);
     }
     set_error("conv_slab_mfma: unknown workgroup shape %d", a.g.shape);
     return NPAS_E_SHAPE;
+}
+
+// ------------------------------------------------------------------------------
+// pointwise_ring: 1x1 layers (and FC) with C a multiple of 64, streamed through a ring of
+// LDS stages that are filled by direct global->LDS loads (global_load_lds_dwordx4): no
+// registers hold data in flight, so two whole stages (96 KB per CU) are always on their
+// way while a third is multiplied — what an HBM-bound layer with little work per byte needs.
+//
+// Workgroup: 8 waves as 4 (pixels) x 2 (filters), tile 256 pixels x 128 filters, wave tile
+// 64 x 64.  Stage = 64 channels: 256 pixels x 128 B of activations (32 KB) + 16 weight
+// images of 1 KB (16 KB).  A wave issues 4 + 2 loads per stage; a load writes 64 lanes x 16 B
+// lane-linearly into one 1 KB LDS block.  Activations are stored unpadded with an XOR
+// swizzle: 16-byte vector cv of pixel p sits at p*128 + (cv ^ (p & 7))*16, so that the
+// MFMA B-operand reads (16 consecutive pixels, same cv) spread over the banks.
+// The loads are inline assembly (the compiler would otherwise drain the whole ring before
+// every LDS read); their completion is tracked by hand: vector-memory operations of a wave
+// return in order, so "at most 6 outstanding" means every stage but the newest has landed.
+constexpr int kRingStages = 3;
+constexpr uint32_t kRingPatchBytes = 32768, kRingStageBytes = 49152;
+
+__device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr)
+                 : "memory");
+}
+
+// 8-byte global load the compiler does not see (it would drain the ring before the use);
+// the caller waits for it by hand with ring_wait6.
+__device__ __forceinline__ uint2 asm_load8(const void *gptr)
+{
+    uint2 v;
+    asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(v) : "v"(gptr) : "memory");
+    return v;
+}
+
+// 8-byte global store the compiler does not see either: with every vector-memory operation
+// of the kernel issued by hand, the kernel can count them and wait for exactly the ones it needs.
+__device__ __forceinline__ uint4 asm_load16(const void *gptr)
+{
+    uint4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(gptr) : "memory");
+    return v;
+}
+
+__device__ __forceinline__ void asm_store8(void *gptr, uint2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(gptr), "v"(v) : "memory");
+}
+
+// Wait until at most n vector-memory operations of this wave are outstanding (they retire in
+// order, so everything but the n youngest has completed).  The instruction takes an immediate;
+// n is rounded down to the values the kernel's issue pattern produces (waiting for more than
+// asked is always safe).
+__device__ __forceinline__ void ring_wait(uint32_t n)
+{
+    if (n >= 54u) asm volatile("s_waitcnt vmcnt(54)" ::: "memory");
+    else if (n >= 38u) asm volatile("s_waitcnt vmcnt(38)" ::: "memory");
+    else if (n >= 22u) asm volatile("s_waitcnt vmcnt(22)" ::: "memory");
+    else if (n >= 6u) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// "At most 6 vector-memory operations outstanding", tied to 16 values loaded with asm_load8
+// so that no use of them can move above the wait.
+__device__ __forceinline__ void ring_wait6(uint2 (&r)[4][4])
+{
+    asm volatile("s_waitcnt vmcnt(6)"
+                 : "+v"(r[0][0]), "+v"(r[0][1]), "+v"(r[0][2]), "+v"(r[0][3]), "+v"(r[1][0]), "+v"(r[1][1]), "+v"(r[1][2]),
+                   "+v"(r[1][3]), "+v"(r[2][0]), "+v"(r[2][1]), "+v"(r[2][2]), "+v"(r[2][3]), "+v"(r[3][0]), "+v"(r[3][1]),
+                   "+v"(r[3][2]), "+v"(r[3][3])
+                 :
+                 : "memory");
+}
+// Same for four 16-byte values: the wait, then an empty statement that "redefines" their
+// 16 dwords so that no use can be scheduled above it.
+#define NPAS_RING_WAIT6_X4(b)                                                                                          \
+    do {                                                                                                               \
+        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");                                                               \
+        asm volatile(""                                                                                                \
+                     : "+v"(b[0].x), "+v"(b[0].y), "+v"(b[0].z), "+v"(b[0].w), "+v"(b[1].x), "+v"(b[1].y), "+v"(b[1].z), \
+                       "+v"(b[1].w), "+v"(b[2].x), "+v"(b[2].y), "+v"(b[2].z), "+v"(b[2].w), "+v"(b[3].x), "+v"(b[3].y), \
+                       "+v"(b[3].z), "+v"(b[3].w)                                                                      \
+                     :                                                                                                 \
+                     : "memory");                                                                                      \
+    } while (0)
+
+template <int DT>
+__global__ __launch_bounds__(512) void pointwise_ring_kernel(RingArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint32_t lbase = (uint32_t)(uintptr_t)lds;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
+    const int wp = wave >> 1, wf = wave & 1;
+    const uint32_t nwg = gridDim.x, nitems = (uint32_t)(a.nptiles * a.nfb);
+    const int nst = a.C >> 6; // stages (64-channel chunks) per item
+    const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
+    const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg);
+    uint8_t *yb = reinterpret_cast<uint8_t *>(a.y);
+    const uint8_t *rb = reinterpret_cast<const uint8_t *>(a.residual);
+    const Clamp cl = clamp_of(a.act);
+
+    // byte offset in x of output pixel m's input pixel
+    auto in_byte = [&](uint32_t m) -> uint32_t {
+        m = min(m, (uint32_t)a.M - 1u);
+        if (a.flat) return m * (uint32_t)a.C * 2u;
+        const uint32_t n = fastdiv(m, a.div_howo), r = m - n * (uint32_t)(a.Ho * a.Wo);
+        const uint32_t oy = fastdiv(r, a.div_wo), ox = r - oy * (uint32_t)a.Wo;
+        return ((n * a.H + oy * a.stride) * a.W + ox * a.stride) * (uint32_t)a.C * 2u;
+    };
+
+    // ---- producer: which (item, chunk) the next issued stage is --------------------------
+    uint32_t p_item = xcd_remap(blockIdx.x, nwg);
+    if (p_item >= nitems) return;
+    int p_t = 0;
+    uint32_t p_fb = 0;
+    uint32_t ppix[4];
+    const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u; // which 16-byte vector of the pixel this lane fetches
+    auto producer_item = [&]() {
+        const uint32_t ptile = p_item / (uint32_t)a.nfb;
+        p_fb = p_item - ptile * (uint32_t)a.nfb;
+        p_t = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ppix[i] = in_byte(ptile * 256u + (uint32_t)((wave * 4 + i) * 8 + (lane >> 3)));
+    };
+    producer_item();
+    bool p_done = false;
+    // Issue accounting (wave-uniform): `issued` counts this wave's vector-memory operations,
+    // mark_* remember the count right after the loads of the stage in each ring slot.
+    uint32_t issued = 0, mark_cur = 0, mark_nxt = 0;
+    auto produce = [&](uint32_t slot) { // always issues its 6 loads; past the end it repeats the last stage
+        const uint32_t sbase = lbase + slot * kRingStageBytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lds_dma16(xb + ppix[i] + (uint32_t)p_t * 128u + pcv, sbase + (uint32_t)(wave * 4 + i) * 1024u);
+        const uint8_t *wsrc = wb + (size_t)(p_fb * (uint32_t)nst + (uint32_t)p_t) * 16384u + (uint32_t)(wave * 2) * 1024u + (uint32_t)lane * 16u;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) lds_dma16(wsrc + i * 1024, sbase + kRingPatchBytes + (uint32_t)(wave * 2 + i) * 1024u);
+        issued += 6u;
+        if (!p_done) {
+            if (p_t + 1 < nst) ++p_t;
+            else if (p_item + nwg < nitems) {
+                p_item += nwg;
+                producer_item();
+            } else p_done = true;
+        }
+    };
+    produce(0);
+    mark_cur = issued;
+    produce(1);
+    mark_nxt = issued;
+
+    // ---- consumer ------------------------------------------------------------------
+    uint32_t c_item = xcd_remap(blockIdx.x, nwg);
+    const uint32_t brow = (uint32_t)((wp * 64 + n16) * 128), arow = (uint32_t)(wf * 4) * 1024u + (uint32_t)lane * 16u;
+    uint32_t stage = 0;
+    for (;;) { // one item per iteration
+        const uint32_t ptile = c_item / (uint32_t)a.nfb, fb = c_item - ptile * (uint32_t)a.nfb;
+        const int fl = (int)fb * 128 + wf * 64 + 4 * q; // this lane's first filter in row tile 0
+        uint32_t obyte[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t m = ptile * 256u + (uint32_t)(wp * 64 + s * 16 + n16);
+            obyte[s] = m < (uint32_t)a.M ? (m * (uint32_t)a.F + (uint32_t)fl) * 2u : 0xffffffffu;
+        }
+        f32x4 acc[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        uint2 res[4][4];
+        uint4 bia[4];
+        for (int t = 0; t < nst; ++t, ++stage) {
+            ring_wait(__builtin_amdgcn_readfirstlane(issued - mark_cur)); // this stage's loads (own wave) have landed
+            __builtin_amdgcn_s_barrier();  // ... and everyone's; and everyone is done with the stage before
+            asm volatile("" ::: "memory");
+            if (rb && t == nst - 1) { // residual: asked for before the newest stage, used after the multiply
+                issued += 16u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        const bool ok = obyte[s] != 0xffffffffu && fl + 16 * j < a.F;
+                        res[j][s] = asm_load8(rb + (ok ? obyte[s] + 32u * j : 0u));
+                    }
+            }
+            if (a.bias && t == nst - 1) { // bias of this lane's 4 x 4 filters (F is a multiple of 4)
+                issued += 4u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bia[j] = asm_load16(a.bias + (fl + 16 * j < a.F ? fl + 16 * j : 0));
+            }
+            produce((stage + 2) % kRingStages);
+            mark_cur = mark_nxt;
+            mark_nxt = issued;
+            const uint8_t *sb = lds + (stage % kRingStages) * kRingStageBytes;
+#pragma unroll
+            for (int step = 0; step < 2; ++step) {
+                uint4 A[4], B[4];
+                const uint8_t *ap = sb + kRingPatchBytes + (uint32_t)(step * 8) * 1024u + arow;
+                const uint8_t *bp = sb + brow + (uint32_t)(((step * 4 + q) ^ (n16 & 7)) * 16);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) A[j] = *reinterpret_cast<const uint4 *>(ap + j * 1024);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) B[s] = *reinterpret_cast<const uint4 *>(bp + s * 2048);
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[j][s] = mfma16<DT>(A[j], B[s], acc[j][s]);
+            }
+        }
+        // ---- bias, residual, clamp (activation), round, store -----------------------------
+        if (rb) ring_wait6(res); // the 6 loads issued after the residual's may stay in flight
+        if (a.bias) NPAS_RING_WAIT6_X4(bia);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (fl + 16 * j >= a.F) continue;
+            float bv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (a.bias) {
+                bv[0] = __uint_as_float(bia[j].x);
+                bv[1] = __uint_as_float(bia[j].y);
+                bv[2] = __uint_as_float(bia[j].z);
+                bv[3] = __uint_as_float(bia[j].w);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (obyte[s] == 0xffffffffu) continue;
+                float v[4] = {acc[j][s][0] + bv[0], acc[j][s][1] + bv[1], acc[j][s][2] + bv[2], acc[j][s][3] + bv[3]};
+                if (rb) {
+                    v[0] += from_storage<DT>((uint16_t)(res[j][s].x & 0xffffu));
+                    v[1] += from_storage<DT>((uint16_t)(res[j][s].x >> 16));
+                    v[2] += from_storage<DT>((uint16_t)(res[j][s].y & 0xffffu));
+                    v[3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
+                }
+                uint2 out;
+                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
+                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                asm_store8(yb + obyte[s] + 32u * j, out);
+            }
+        }
+        {   // stores just issued by this wave: one per (row tile, pixel block) that has any valid lane
+            const int fw = (int)fb * 128 + wf * 64, mw = (int)(ptile * 256u) + wp * 64;
+            const int nj = max(0, min(4, (a.F - fw + 15) >> 4)), ns = max(0, min(4, (a.M - mw + 15) >> 4));
+            issued += (uint32_t)(nj * ns);
+        }
+        if (c_item + nwg >= nitems) break;
+        c_item += nwg;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70); // drain the (repeated) loads still in flight before the wave ends
+}
+
+int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds_bytes = (size_t)kRingStages * kRingStageBytes;
+    const unsigned grid = (unsigned)std::min<long>((long)a.nptiles * a.nfb, 256);
+    static bool attr_done[2] = {false, false};
+    if (dtype == NPAS_BF16) {
+        auto kern = pointwise_ring_kernel<NPAS_BF16>;
+        if (!attr_done[0]) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            attr_done[0] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds_bytes, st, a);
+    } else if (dtype == NPAS_F16) {
+        auto kern = pointwise_ring_kernel<NPAS_F16>;
+        if (!attr_done[1]) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            attr_done[1] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds_bytes, st, a);
+    } else {
+        set_error("pointwise_ring needs a 16-bit storage type");
+        return NPAS_E_DTYPE;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("pointwise_ring launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
 }
 
 static bool g_lds_attr_set[2][2] = {{false, false}, {false, false}};

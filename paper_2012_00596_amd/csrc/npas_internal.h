@@ -61,6 +61,20 @@ struct DeviceFormat {
     int max_list = 0; // longest per-(tile,chunk) list, entries
 };
 
+// ---- ring format: extra execution format of 1x1 layers with C % 64 == 0 ---------
+// Filters in blocks of 128, channels in chunks of 64, every (block, chunk) present (the
+// kernel walks chunk t at stage t; rg_ptr / rg_chunk record that for inspection).  Per
+// (block, chunk) wimg holds 16 A-operand images of 1 KB: image step*8 + tile, lane
+// 16*q + r, value i = W[128 fb + 16 tile + r][64 chunk + 32 step + 8 q + i] (zero where
+// pruned or past F).
+struct RingFormat {
+    bool present = false;
+    int nfb = 0;
+    std::vector<int32_t> rg_ptr;
+    std::vector<uint32_t> rg_chunk;
+    std::vector<uint16_t> wimg;
+};
+
 struct DeviceCopy {
     int device = -1;
     void *blob = nullptr; // one allocation holding everything below
@@ -71,6 +85,9 @@ struct DeviceCopy {
     const int32_t *vg_ptr = nullptr, *vg_f0 = nullptr;
     const uint32_t *vkent = nullptr;
     const float *vw = nullptr;
+    const int32_t *rg_ptr = nullptr;
+    const uint32_t *rg_chunk = nullptr;
+    const void *wimg = nullptr;
 };
 
 } // namespace npas
@@ -85,6 +102,7 @@ struct npas_packed {
     std::vector<uint8_t> library, pat_id, w4;
     // execution format
     npas::DeviceFormat fmt;
+    npas::RingFormat ring;
     npas::DeviceCopy dev;
 };
 
@@ -133,6 +151,23 @@ struct ConvValuArgs {
     int N, H, W, C, F, Ho, Wo, KH, KW, stride, pad, act;
 };
 
+struct RingArgs {
+    const void *x;
+    void *y;
+    const void *residual;
+    const float *bias;
+    const int32_t *rg_ptr;
+    const uint32_t *rg_chunk;
+    const void *wimg;
+    int M;                      // output pixels N*Ho*Wo
+    int C, F;
+    int H, W, Ho, Wo, stride;   // input / output geometry (stride > 1: subsampled input pixels)
+    int nptiles, nfb;           // 256-pixel tiles, 128-filter blocks
+    int act;
+    int flat;                   // 1: stride 1, input pixel index == output pixel index
+    uint32_t div_howo, div_wo;  // magic reciprocals of Ho*Wo and Wo
+};
+
 // Host-side plan of one conv launch (tile shape, grid, LDS bytes).
 struct ConvPlan {
     ConvGeom g;
@@ -147,6 +182,7 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
 // launchers (kernels.hip)
 int launch_conv_mfma(int dtype, int variant, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream);
 int launch_conv_valu(const ConvValuArgs &a, void *stream);
+int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream);
 bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
                                 int act1, int act2, uint32_t use0, uint32_t use1, void *stream);

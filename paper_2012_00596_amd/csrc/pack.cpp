@@ -188,6 +188,7 @@ static void build_mfma_slab(npas_packed *p, const uint8_t *m, const uint8_t *w)
     const int F = p->F, C = p->C, KH = p->KH, KW = p->KW;
     d.variant = V_MFMA_SLAB;
     d.NT = F > 32 ? 4 : 2;
+    if (const char *e = getenv("NPAS_FORCE_NT")) d.NT = atoi(e) == 2 ? 2 : d.NT; // TEMP tuning knob
     d.CC = std::min(C, 64);
     d.nchunks = (C + d.CC - 1) / d.CC;
     const int SF = 16 * d.NT;
@@ -259,6 +260,37 @@ static double union_density(const npas_packed *p, const uint8_t *m)
     return total ? (double)kept / (double)total : 1.0;
 }
 
+// Ring format (see npas_internal.h): what pointwise_ring_kernel streams through LDS.
+static void build_ring(npas_packed *p, const uint8_t *m, const uint8_t *w)
+{
+    RingFormat &r = p->ring;
+    const int F = p->F, C = p->C;
+    r.present = true;
+    r.nfb = (F + 127) / 128;
+    r.rg_ptr.assign(r.nfb + 1, 0);
+    r.rg_chunk.clear();
+    r.wimg.clear();
+    const uint16_t *w16 = reinterpret_cast<const uint16_t *>(w);
+    for (int fb = 0; fb < r.nfb; ++fb) {
+        r.rg_ptr[fb] = (int32_t)r.rg_chunk.size();
+        const int f0 = 128 * fb;
+        for (int cc = 0; cc < C / 64; ++cc) { // every chunk is listed: stage t of a block is chunk t
+            r.rg_chunk.push_back((uint32_t)cc);
+            size_t w0 = r.wimg.size();
+            r.wimg.resize(w0 + 16 * 512, 0);
+            for (int step = 0; step < 2; ++step)
+                for (int tile = 0; tile < 8; ++tile)
+                    for (int lane = 0; lane < 64; ++lane)
+                        for (int i = 0; i < 8; ++i) {
+                            int rr = lane & 15, q = lane >> 4, f = f0 + 16 * tile + rr, c = 64 * cc + 32 * step + 8 * q + i;
+                            if (f < F && m[(size_t)f * C + c])
+                                r.wimg[w0 + (size_t)(step * 8 + tile) * 512 + lane * 8 + i] = w16[(size_t)f * C + c];
+                        }
+        }
+    }
+    r.rg_ptr[r.nfb] = (int32_t)r.rg_chunk.size();
+}
+
 static void build_valu_f32(npas_packed *p, const uint8_t *m, const uint8_t *w)
 {
     (void)m;
@@ -311,6 +343,10 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         if (force && slab_ok) gather = strcmp(force, "gather") == 0;
         if (gather) build_mfma_gather(p, mask_full.data(), (const uint8_t *)w_host);
         else build_mfma_slab(p, mask_full.data(), (const uint8_t *)w_host);
+        // 1x1 layers with whole 64-channel chunks also get the streaming (ring) format, which
+        // the run calls prefer whenever the layer is run without padding
+        if (p->KH == 1 && p->KW == 1 && p->C % 64 == 0 && p->F % 4 == 0 && !(force && strcmp(force, "noring") == 0))
+            build_ring(p, mask_full.data(), (const uint8_t *)w_host);
     }
     return NPAS_OK;
 }
@@ -339,6 +375,7 @@ int upload(npas_packed *p)
     size_t o_tc = place(blob, d.tc_ptr), o_ke = place(blob, d.kent), o_wf = place(blob, d.wfrag);
     size_t o_vp = place(blob, d.vg_ptr), o_vf = place(blob, d.vg_f0), o_vk = place(blob, d.vkent),
            o_vw = place(blob, d.vw);
+    size_t o_rp = place(blob, p->ring.rg_ptr), o_rc = place(blob, p->ring.rg_chunk), o_ri = place(blob, p->ring.wimg);
     blob.resize((blob.size() + 255) / 256 * 256 + 256);
     void *ptr = nullptr;
     hipError_t e = hipMalloc(&ptr, blob.size());
@@ -363,6 +400,9 @@ int upload(npas_packed *p)
     p->dev.vg_f0 = (const int32_t *)(b + o_vf);
     p->dev.vkent = (const uint32_t *)(b + o_vk);
     p->dev.vw = (const float *)(b + o_vw);
+    p->dev.rg_ptr = (const int32_t *)(b + o_rp);
+    p->dev.rg_chunk = (const uint32_t *)(b + o_rc);
+    p->dev.wimg = b + o_ri;
     return NPAS_OK;
 }
 
@@ -504,6 +544,8 @@ int npas_packed_info(const npas_packed *p, int64_t info[16])
     const DeviceFormat &d = p->fmt;
     size_t dev_bytes = d.tc_ptr.size() * 4 + d.kent.size() * 4 + d.wfrag.size() * 2 + d.vg_ptr.size() * 4 +
                        d.vg_f0.size() * 4 + d.vkent.size() * 4 + d.vw.size() * 4;
+    if (p->ring.present) // the format the run calls use for this layer
+        dev_bytes = p->ring.rg_ptr.size() * 4 + p->ring.rg_chunk.size() * 4 + p->ring.wimg.size() * 2;
     int64_t v[16] = {p->scheme, p->dtype, p->F, p->C, p->KH, p->KW, p->Bf, p->Bc, p->G,
                      (int64_t)p->k_pos.size(), p->n_pat, p->dev.device >= 0, d.variant,
                      (int64_t)dev_bytes, (int64_t)p->w_compact.size(), 0};
