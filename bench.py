@@ -58,7 +58,27 @@ def main():
         for _ in range(5):
             dst.copy_(src)
         torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 5}))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        e0.record()
+        for _ in range(5):
+            dst.zero_()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_w = e0.elapsed_time(e1) / 5
+        e0.record()
+        for _ in range(5):
+            src.sum()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_r = e0.elapsed_time(e1) / 5
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 10,
+                          "copy_GBps": 2 * n / ms / 1e6, "fill_GBps": n / ms_w / 1e6, "read_sum_GBps": n / ms_r / 1e6}))
         return
     if args.per_layer:
         return per_layer(args, torch, npas, helpers, configs)
@@ -129,6 +149,14 @@ def main():
         kern_ms = max(per)
         kname = "conv_gather_mfma(layer %d of 2)" % (per.index(kern_ms) + 1)
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+    # HBM bytes per launch of the fused kernel as measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE scaled by a
+    # plain copy); only valid for the default workload and launch configuration
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "fused_pointwise_pair_cfg2_hbm_traffic.md")
+    if launches == 1 and N == 64 and os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
 
     out = {
         "metric": "dense-equivalent TFLOP/s and per-layer us for block-punched sparse conv at 1 GPU",
@@ -143,7 +171,7 @@ def main():
                                % N, "launches_per_step": launches, "buffer_sets": nsets,
                    "dense_equiv_gflop_per_step": dense_flop / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kname,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kname,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_ms},
     }
 
