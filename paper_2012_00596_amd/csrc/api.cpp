@@ -4,7 +4,10 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <array>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <memory>
 
 #include "npas_internal.h"
@@ -76,10 +79,7 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
         const int max_vec = 256 * 8;
         ConvGeom g128 = g, g64 = g;
         double c128 = 0, c64 = 0;
-        if (d.NT == 2 && p->F > 32) { // 64 filters x 64 pixels, small accumulators, many workgroups per CU
-            g.shape = 4;
-            if (!pick_tile(p, g, 64, 64, budget, 2, 0, max_vec, nullptr)) goto nofit;
-        } else if (d.NT == 2) {
+        if (d.NT == 2) {
             g.shape = 2;
             if (!pick_tile(p, g, 128, 128, budget, 2, 0, max_vec, nullptr)) goto nofit;
         } else if (p->F <= 64) {
@@ -92,14 +92,10 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
             long items128 = ok128 ? (long)g128.N * ((g128.Ho + g128.TH - 1) / g128.TH) * ((g128.Wo + g128.TW - 1) / g128.TW) : 0;
             // the wider tile unless it wastes MFMA columns or leaves most of the chip idle
             bool use64 = !ok128 || (ok64 && (c64 > 1.15 * c128 || items128 * ((p->F + 127) / 128) < 256));
-            if (const char *e = getenv("NPAS_SLAB_SHAPE")) { // TEMP tuning knob
-                if (atoi(e) == 3 && ok64) use64 = true;
-                if (atoi(e) == 0 && ok128) use64 = false;
-            }
             g = use64 ? g64 : g128;
             g.shape = use64 ? 3 : 0;
         }
-        const int wgf = (g.shape == 0 || g.shape == 3 || g.shape == 4) ? 2 : 1;
+        const int wgf = (g.shape == 0 || g.shape == 3) ? 2 : 1;
         g.tilesY = (g.Ho + g.TH - 1) / g.TH;
         g.tilesX = (g.Wo + g.TW - 1) / g.TW;
         g.div_tw = magic_div(g.TW);
@@ -112,7 +108,7 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
         out->g = g;
         {
             const bool small = g.PH * g.PW * (d.CC / 8) <= 1024;
-            const int occ = g.shape == 4 ? 5 : g.shape == 0 ? 2 : (small ? (g.shape == 2 ? 4 : 3) : (g.shape == 2 ? 3 : 2));
+            const int occ = g.shape == 0 ? 2 : (small ? (g.shape == 2 ? 4 : 3) : (g.shape == 2 ? 3 : 2));
             out->grid = (unsigned)std::min<long>(items, 256L * occ);
         }
         out->lds_bytes = (((size_t)g.PH * g.PW * g.pitch + 15) / 16 * 16) * 2;
@@ -175,6 +171,81 @@ static int check_run(const npas_packed *p, const void *x, void *y, int N, int H,
     return NPAS_OK;
 }
 
+// Output tile of the k x k streaming kernel: NI images x TH x TW output pixels (at most 256,
+// the MFMA columns of a workgroup) whose halo patch fits the kernel's limits.  Picks the
+// plan with the best ratio of useful to computed columns, then the smaller halo.  Returns
+// false when no plan exists or the launch would leave most of the chip idle (the slab
+// kernel's smaller tiles serve those cases better).
+static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, bool force, SpatialRingArgs *a);
+
+// The search is a few thousand candidates; its result depends only on the shapes, so it is
+// kept per shape (launches of a stack repeat the same few shapes).
+bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a)
+{
+    static std::mutex mu;
+    static std::map<std::array<int, 10>, std::pair<bool, SpatialRingArgs>> cache;
+    // NPAS_FORCE_VARIANT=spatial (tests): take this kernel whenever a plan exists
+    const char *fv = std::getenv("NPAS_FORCE_VARIANT");
+    const int force = fv && std::strcmp(fv, "spatial") == 0;
+    const std::array<int, 10> key = {p->KH, p->KW, p->C, p->F, p->ring.nfb, N, H, W, pad, force};
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(key);
+    if (it == cache.end()) {
+        SpatialRingArgs g;
+        std::memset(&g, 0, sizeof g);
+        const bool ok = plan_spatial_search(p, N, H, W, pad, force != 0, &g);
+        it = cache.emplace(key, std::make_pair(ok, g)).first;
+    }
+    *a = it->second.second;
+    return it->second.first;
+}
+
+static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, bool force, SpatialRingArgs *a)
+{
+    const int KH = p->KH, KW = p->KW, T = KH * KW;
+    const int Ho = H + 2 * pad - KH + 1, Wo = W + 2 * pad - KW + 1;
+    const int lds_total = 160 * 1024 - 2048 /* bias buffers */ - 2048 /* pixel table */, wstage = 16384;
+    const int max_npb = (lds_total - 3 * wstage) / 2048;
+    if (T < 2 || p->C % 64 != 0) return false;
+    double best = -1.0;
+    int bNI = 0, bTH = 0, bTW = 0;
+    for (int TH = 1; TH <= std::min(Ho, 255); ++TH)
+        for (int TW = 1; TW <= std::min(Wo, 255) && TH * TW <= 256; ++TW) {
+            const int PH = TH + KH - 1, PW = TW + KW - 1;
+            const long ty = (Ho + TH - 1) / TH, tx = (Wo + TW - 1) / TW;
+            const int maxNI = std::min(N, 256 / (TH * TW));
+            for (int NI = 1; NI <= maxNI; ++NI) {
+                const int npb = (NI * PH * PW + 7) / 8;
+                if (npb > max_npb) break;
+                const long tn = (N + NI - 1) / NI;
+                const int depth = std::min(6, (lds_total - 2048 * npb) / wstage);
+                const double eff = (double)N * Ho * Wo / ((double)tn * ty * tx * 256.0);
+                const double halo = (double)(NI * PH * PW) / (double)(NI * TH * TW);
+                const double score = eff - 0.02 * halo + 0.02 * (depth - 3);
+                if (score > best) {
+                    best = score;
+                    bNI = NI; bTH = TH; bTW = TW;
+                }
+            }
+        }
+    if (best < 0) return false;
+    a->N = N; a->H = H; a->W = W; a->C = p->C; a->F = p->F; a->Ho = Ho; a->Wo = Wo;
+    a->KH = KH; a->KW = KW; a->pad = pad;
+    a->NI = bNI; a->TH = bTH; a->TW = bTW; a->PH = bTH + KH - 1; a->PW = bTW + KW - 1;
+    a->tilesN = (N + bNI - 1) / bNI; a->tilesY = (Ho + bTH - 1) / bTH; a->tilesX = (Wo + bTW - 1) / bTW;
+    a->nfb = p->ring.nfb;
+    a->npb = (bNI * a->PH * a->PW + 7) / 8;
+    a->depth = std::min(6, (lds_total - 2048 * a->npb) / wstage);
+    a->div_tw = magic_div((uint32_t)bTW); a->div_pw = magic_div((uint32_t)a->PW);
+    a->div_thtw = magic_div((uint32_t)(bTH * bTW)); a->div_phpw = magic_div((uint32_t)(a->PH * a->PW));
+    const long items = (long)a->tilesN * a->tilesY * a->tilesX * a->nfb;
+    const double eff = (double)N * Ho * Wo / ((double)a->tilesN * a->tilesY * a->tilesX * 256.0);
+    // worth it when the launch fills most of the chip and neither the 256 pixel columns nor the
+    // 128 filter rows of a workgroup are mostly padding (measured against the slab kernel)
+    const double fill = (double)p->F / (128.0 * a->nfb);
+    return force || (items >= 192 && eff >= 0.6 && fill >= 0.75);
+}
+
 int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y, int N, int H, int W, int stride,
              int pad, const void *bias, const void *residual, int act, void *stream)
 {
@@ -192,7 +263,7 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.KH = p->KH; a.KW = p->KW; a.stride = stride; a.pad = pad; a.act = act;
         return launch_conv_valu(a, stream);
     }
-    if (p->ring.present && pad == 0) { // streaming 1x1 path
+    if (p->ring.present && p->KH == 1 && p->KW == 1 && pad == 0) { // streaming 1x1 path
         RingArgs a;
         a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
         a.rg_ptr = p->dev.rg_ptr; a.rg_chunk = p->dev.rg_chunk; a.wimg = p->dev.wimg;
@@ -207,6 +278,15 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.div_howo = magic_div((uint32_t)(a.Ho * a.Wo));
         a.div_wo = magic_div((uint32_t)a.Wo);
         return launch_pointwise_ring(p->dtype, a, stream);
+    }
+    if (p->ring.present && stride == 1) { // k x k streaming path, when a tile plan fills the chip
+        SpatialRingArgs a;
+        if (plan_spatial(p, N, H, W, pad, &a)) {
+            a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
+            a.wimg = p->dev.wimg; a.zeros = p->dev.zeros;
+            a.act = act;
+            return launch_spatial_ring(p->dtype, a, stream);
+        }
     }
     ConvPlan local;
     if (!plan) {

@@ -562,7 +562,6 @@ template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid
     case 1: return small ? launch_slab_inst<DT, 4, 2, 1, 4, 3>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 2, 1, 8, 2>(a, grid, lds_bytes, st);
     case 2: return small ? launch_slab_inst<DT, 2, 2, 1, 4, 4>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 2, 2, 1, 8, 3>(a, grid, lds_bytes, st);
     case 3: return small ? launch_slab_inst<DT, 4, 2, 2, 4, 3>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 4, 2, 2, 8, 2>(a, grid, lds_bytes, st);
-    case 4: return small ? launch_slab_inst<DT, 2, 2, 2, 4, 5>(a, grid, lds_bytes, st) : launch_slab_inst<DT, 2, 2, 2, 8, 3>(a, grid, lds_bytes, st);
     }
     set_error("conv_slab_mfma: unknown workgroup shape %d", a.g.shape);
     return NPAS_E_SHAPE;
@@ -595,7 +594,7 @@ __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
 }
 
 // 8-byte global load the compiler does not see (it would drain the ring before the use);
-// the caller waits for it by hand with ring_wait6.
+// the caller waits for it by hand and then ties the value with ring_tie.
 __device__ __forceinline__ uint2 asm_load8(const void *gptr)
 {
     uint2 v;
@@ -619,33 +618,41 @@ __device__ __forceinline__ void asm_store8(void *gptr, uint2 v)
 
 // Wait until at most n vector-memory operations of this wave are outstanding (they retire in
 // order, so everything but the n youngest has completed).  The instruction takes an immediate;
-// n is rounded down to the values the kernel's issue pattern produces (waiting for more than
-// asked is always safe).
+// n is rounded down to the nearest value listed here (waiting for more than asked is always safe).
 __device__ __forceinline__ void ring_wait(uint32_t n)
 {
-    if (n >= 54u) asm volatile("s_waitcnt vmcnt(54)" ::: "memory");
-    else if (n >= 38u) asm volatile("s_waitcnt vmcnt(38)" ::: "memory");
-    else if (n >= 22u) asm volatile("s_waitcnt vmcnt(22)" ::: "memory");
-    else if (n >= 6u) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#define NPAS_W(k) else if (n >= k##u) asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory");
+    if (n < 4u) { // the steady state of the rings: a stage or two in flight behind the awaited one
+        if (n == 3u) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else if (n == 2u) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else if (n == 1u) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else if (n < 8u) {
+        if (n == 6u) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else if (n == 7u) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
+        else if (n == 5u) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    }
+    NPAS_W(60) NPAS_W(54) NPAS_W(48) NPAS_W(42) NPAS_W(38) NPAS_W(32) NPAS_W(28) NPAS_W(24) NPAS_W(22) NPAS_W(20) NPAS_W(18)
+    NPAS_W(16) NPAS_W(14) NPAS_W(12) NPAS_W(10) NPAS_W(9)
+    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+#undef NPAS_W
 }
 
-// "At most 6 vector-memory operations outstanding", tied to 16 values loaded with asm_load8
-// so that no use of them can move above the wait.
-__device__ __forceinline__ void ring_wait6(uint2 (&r)[4][4])
+// Empty statement that "redefines" 16 values loaded with asm_load8, placed after the wait
+// that covers them, so that no use of them can be scheduled above that wait.
+__device__ __forceinline__ void ring_tie(uint2 (&r)[4][4])
 {
-    asm volatile("s_waitcnt vmcnt(6)"
+    asm volatile(""
                  : "+v"(r[0][0]), "+v"(r[0][1]), "+v"(r[0][2]), "+v"(r[0][3]), "+v"(r[1][0]), "+v"(r[1][1]), "+v"(r[1][2]),
                    "+v"(r[1][3]), "+v"(r[2][0]), "+v"(r[2][1]), "+v"(r[2][2]), "+v"(r[2][3]), "+v"(r[3][0]), "+v"(r[3][1]),
                    "+v"(r[3][2]), "+v"(r[3][3])
                  :
                  : "memory");
 }
-// Same for four 16-byte values: the wait, then an empty statement that "redefines" their
-// 16 dwords so that no use can be scheduled above it.
-#define NPAS_RING_WAIT6_X4(b)                                                                                          \
+// Same for four 16-byte values (their 16 dwords).
+#define NPAS_RING_TIE_X4(b)                                                                                             \
     do {                                                                                                               \
-        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");                                                               \
         asm volatile(""                                                                                                \
                      : "+v"(b[0].x), "+v"(b[0].y), "+v"(b[0].z), "+v"(b[0].w), "+v"(b[1].x), "+v"(b[1].y), "+v"(b[1].z), \
                        "+v"(b[1].w), "+v"(b[2].x), "+v"(b[2].y), "+v"(b[2].z), "+v"(b[2].w), "+v"(b[3].x), "+v"(b[3].y), \
@@ -777,8 +784,9 @@ __global__ __launch_bounds__(512) void pointwise_ring_kernel(RingArgs a)
             }
         }
         // ---- bias, residual, clamp (activation), round, store -----------------------------
-        if (rb) ring_wait6(res); // the 6 loads issued after the residual's may stay in flight
-        if (a.bias) NPAS_RING_WAIT6_X4(bia);
+        if (rb || a.bias) asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); // the stage issued after them may stay in flight
+        if (rb) ring_tie(res);
+        if (a.bias) NPAS_RING_TIE_X4(bia);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (fl + 16 * j >= a.F) continue;
@@ -814,6 +822,314 @@ __global__ __launch_bounds__(512) void pointwise_ring_kernel(RingArgs a)
         c_item += nwg;
     }
     __builtin_amdgcn_s_waitcnt(0x0F70); // drain the (repeated) loads still in flight before the wave ends
+}
+
+// ------------------------------------------------------------------------------
+// spatial_ring: k x k layers at stride 1 with C a multiple of 64.  A stage is one tap of one
+// 64-channel chunk (two MFMA steps); its 16 weight images (16 KB) go through a ring of `depth`
+// LDS slots.  The activations of a chunk are the halo patch of the output tile
+// ([patch pixel][64 channels], 128 B per pixel, XOR-swizzled by the patch pixel index),
+// double-buffered: while the KH*KW taps of chunk c are multiplied out of one buffer, the
+// patch of chunk c+1 is fetched into the other.  Padding pixels are fetched from a block of
+// zeros.  A tile is NI images x TH x TW output pixels (several images per tile keep the 256
+// MFMA columns busy on 7x7 and 14x14 maps).
+//
+// The workgroup has three kinds of waves, because a wave's vector-memory operations retire
+// in order: a patch load (HBM latency) issued ahead of a weight load (L2 latency) would
+// hold it back, and either would hold back a multiplying wave.
+//   waves 0-7   multiply: 4 pixel groups x 2 filter groups, 64 x 64 outputs each; no
+//               global loads in their main loop
+//   waves 8-9   fetch the weight stages, depth-1 stages ahead
+//   waves 10-11 fetch the patches, a few blocks per stage, finishing well before the chunk ends
+// One s_barrier per stage, executed by all twelve: a fetching wave first waits for the loads
+// of the stage about to be multiplied; after the barrier the slot (or patch buffer) of the
+// stage before is free to be refilled.
+constexpr uint32_t kSpatialWStage = 16384;
+constexpr int kSpatialThreads = 12 * 64;
+
+struct SpatialItem {
+    int n0, ty0, tx0, fb;
+};
+
+__device__ __forceinline__ SpatialItem spatial_item(const SpatialRingArgs &a, uint32_t item)
+{
+    SpatialItem it;
+    uint32_t rest = item / (uint32_t)a.nfb;
+    it.fb = (int)(item - rest * (uint32_t)a.nfb);
+    const uint32_t txi = rest % (uint32_t)a.tilesX;
+    rest /= (uint32_t)a.tilesX;
+    const uint32_t tyi = rest % (uint32_t)a.tilesY;
+    it.n0 = (int)(rest / (uint32_t)a.tilesY) * a.NI;
+    it.ty0 = (int)tyi * a.TH;
+    it.tx0 = (int)txi * a.TW;
+    return it;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRingArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint32_t lbase = (uint32_t)(uintptr_t)lds;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
+    const uint32_t nwg = gridDim.x;
+    const uint32_t nitems = (uint32_t)(a.tilesN * a.tilesY * a.tilesX * a.nfb);
+    const int T = a.KH * a.KW, nch = a.C >> 6;
+    const uint32_t ppb = (uint32_t)a.npb * 1024u;      // bytes of one patch buffer
+    const uint32_t wring = 2u * ppb;                   // LDS offset of the weight ring
+    const uint32_t D = (uint32_t)a.depth;              // weight stages in the ring
+    const uint32_t lbias = wring + D * kSpatialWStage; // two 1 KB bias buffers (item parity)
+    const uint32_t ltab = lbias + 2048u;               // patch pixel -> (image, row, column), 4 B each
+    uint32_t c_item = xcd_remap(blockIdx.x, nwg);
+    if (c_item >= nitems) return;
+    SpatialItem it = spatial_item(a, c_item);
+    const int phpw = a.PH * a.PW;
+
+    // patch pixel table (the same for every item): img << 20 | row << 10 | column, ~0 past the end
+    for (int pp = tid; pp < a.npb * 8; pp += kSpatialThreads) {
+        const uint32_t img = fastdiv((uint32_t)pp, a.div_phpw), r = (uint32_t)pp - img * (uint32_t)phpw;
+        const uint32_t py = fastdiv(r, a.div_pw), px = r - py * (uint32_t)a.PW;
+        reinterpret_cast<uint32_t *>(lds + ltab)[pp] = (int)img < a.NI ? (img << 20 | py << 10 | px) : 0xffffffffu;
+    }
+    __syncthreads();
+
+    if (wave >= 10) {
+        // ---- patch fetch ------------------------------------------------------------------
+        const int wl = wave - 10;
+        const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
+        const uint8_t *zb = reinterpret_cast<const uint8_t *>(a.zeros) + (uint32_t)(lane & 7) * 16u;
+        const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u;
+        const int nblk = (a.npb - wl + 1) >> 1;                 // this wave's blocks: wl, wl + 2, ...
+        const int per = (nblk + max(1, T - 3) - 1) / max(1, T - 3); // blocks per stage: done 3 stages early
+        // blocks [k0, k1) of this wave's share of the patch of (item pi, chunk cc)
+        auto patch = [&](const SpatialItem &pi, int cc, uint32_t buf, int k0, int k1) {
+            for (int k = k0; k < min(k1, nblk); ++k) {
+                const int blk = wl + 2 * k;
+                const uint32_t e = reinterpret_cast<const uint32_t *>(lds + ltab)[blk * 8 + (lane >> 3)];
+                const int n = pi.n0 + (int)(e >> 20), iy = pi.ty0 - a.pad + (int)((e >> 10) & 1023u), ix = pi.tx0 - a.pad + (int)(e & 1023u);
+                const bool inb = e != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
+                const uint8_t *src = inb ? xb + ((uint32_t)((n * a.H + iy) * a.W + ix) * (uint32_t)a.C + (uint32_t)cc * 64u) * 2u + pcv : zb;
+                lds_dma16(src, lbase + buf * ppb + (uint32_t)blk * 1024u);
+            }
+        };
+        // bias of an item's 128 filters (512 B; lanes 32-63 fetch a copy that nobody reads)
+        auto bias_block = [&](const SpatialItem &pi, uint32_t buf) {
+            if (!a.bias || wl != 0) return;
+            const int f = pi.fb * 128 + (lane & 31) * 4;
+            lds_dma16(a.bias + (f < a.F ? f : 0), lbase + lbias + buf * 1024u);
+        };
+        patch(it, 0, 0, 0, nblk);
+        bias_block(it, 0);
+        uint32_t pbuf = 0, bbuf = 0;
+        for (;;) {
+            const bool more_items = c_item + nwg < nitems;
+            SpatialItem nit = it;
+            if (more_items) nit = spatial_item(a, c_item + nwg);
+            for (int cc = 0; cc < nch; ++cc) {
+                const bool within = cc + 1 < nch;
+                for (int tap = 0; tap < T; ++tap) {
+                    if (tap == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this chunk's patch has landed
+                    __builtin_amdgcn_s_barrier();
+                    if (within) patch(it, cc + 1, pbuf ^ 1u, tap * per, (tap + 1) * per);
+                    else if (more_items) {
+                        patch(nit, 0, pbuf ^ 1u, tap * per, (tap + 1) * per);
+                        if (tap == 0) bias_block(nit, bbuf ^ 1u);
+                    }
+                }
+                pbuf ^= 1u;
+            }
+            if (!more_items) break;
+            c_item += nwg;
+            it = nit;
+            bbuf ^= 1u;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+
+    if (wave >= 8) {
+        // ---- weight stage fetch: images wl*8 .. wl*8+7 of every stage ------------------------
+        const int wl = wave - 8;
+        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)(wl * 8) * 1024u + (uint32_t)lane * 16u;
+        uint32_t p_item = c_item, p_slot = 0;
+        int p_fb = it.fb, p_cc = 0, p_tap = 0;
+        bool p_done = false;
+        auto produce_w = [&]() { // always issues its 8 loads; past the end it repeats the last stage
+            const uint8_t *wsrc = wb + (size_t)((p_fb * nch + p_cc) * T + p_tap) * kSpatialWStage;
+            const uint32_t dst = lbase + wring + p_slot * kSpatialWStage + (uint32_t)(wl * 8) * 1024u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) lds_dma16(wsrc + i * 1024, dst + (uint32_t)i * 1024u);
+            if (++p_slot == D) p_slot = 0;
+            if (!p_done) {
+                if (++p_tap == T) {
+                    p_tap = 0;
+                    if (++p_cc == nch) {
+                        p_cc = 0;
+                        if (p_item + nwg < nitems) {
+                            p_item += nwg;
+                            p_fb = spatial_item(a, p_item).fb;
+                        } else {
+                            p_done = true;
+                            p_cc = nch - 1;
+                            p_tap = T - 1;
+                        }
+                    }
+                }
+            }
+        };
+        for (uint32_t i = 0; i + 1 < D; ++i) produce_w();
+        for (;;) {
+            const bool more_items = c_item + nwg < nitems;
+            for (int st = 0; st < nch * T; ++st) {
+                // at most the D-2 stages issued after the one about to be multiplied stay in flight
+                if (D == 3) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else if (D == 4) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+                else if (D == 5) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                produce_w(); // the stage D-1 ahead, into the slot the barrier freed
+            }
+            if (!more_items) break;
+            c_item += nwg;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+
+    // ---- multiply ------------------------------------------------------------------------
+    const int wp = wave >> 1, wf = wave & 1;
+    const Clamp cl = clamp_of(a.act);
+    const int thtw = a.TH * a.TW;
+    // per-lane tile geometry (the same for every item)
+    uint32_t pb0[4], mt[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const uint32_t m = (uint32_t)(wp * 64 + s * 16 + n16);
+        const uint32_t img = fastdiv(m, a.div_thtw), r = m - img * (uint32_t)thtw;
+        const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
+        const bool valid = (int)m < a.NI * thtw;
+        pb0[s] = valid ? img * (uint32_t)phpw + ty * (uint32_t)a.PW + tx : 0u;
+        mt[s] = valid ? (img << 16 | ty << 8 | tx) : 0xffffffffu;
+    }
+    uint32_t c_slot = 0, pbuf = 0, bbuf = 0;
+    const uint32_t arow = (uint32_t)(wf * 4) * 1024u + (uint32_t)lane * 16u;
+
+    for (;;) { // one item per iteration
+        f32x4 acc[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const bool more_items = c_item + nwg < nitems;
+
+        for (int cc = 0; cc < nch; ++cc) {
+            const uint8_t *pbp = lds + pbuf * ppb;
+            for (int tap = 0; tap < T; ++tap) {
+                __builtin_amdgcn_s_barrier(); // this stage's weights (and, at tap 0, the chunk's patch) are in LDS
+                asm volatile("" ::: "memory");
+                const uint8_t *wsp = lds + wring + c_slot * kSpatialWStage + arow;
+                if (++c_slot == D) c_slot = 0;
+                const uint32_t kh = (uint32_t)tap / (uint32_t)a.KW, kw = (uint32_t)tap - kh * (uint32_t)a.KW;
+                const uint32_t toff = kh * (uint32_t)a.PW + kw;
+                // the 8 B fragments of the stage (2 steps x 4 pixel blocks) in use order, fetched
+                // three ahead of their use; A fragments one step ahead
+                uint32_t baddr[8];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const uint32_t pp = pb0[s] + toff;
+                    baddr[s] = pp * 128u + ((((uint32_t)q) ^ (pp & 7u)) << 4);
+                    baddr[4 + s] = pp * 128u + ((((uint32_t)(4 + q)) ^ (pp & 7u)) << 4);
+                }
+                uint4 A[2][4], B[8];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) A[0][j] = *reinterpret_cast<const uint4 *>(wsp + j * 1024);
+#pragma unroll
+                for (int i = 0; i < 3; ++i) B[i] = *reinterpret_cast<const uint4 *>(pbp + baddr[i]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (i + 3 < 8) B[i + 3] = *reinterpret_cast<const uint4 *>(pbp + baddr[i + 3]);
+                    if (i == 1) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) A[1][j] = *reinterpret_cast<const uint4 *>(wsp + 8192 + j * 1024);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[j][i & 3] = mfma16<DT>(A[i >> 2][j], B[i], acc[j][i & 3]);
+                }
+            }
+            pbuf ^= 1u;
+        }
+        // ---- bias (from LDS), residual, clamp (activation), round, store ---------------------
+        const int fl = it.fb * 128 + wf * 64 + 4 * q; // this lane's first filter in row tile 0
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int n = it.n0 + (int)(mt[s] >> 16), oy = it.ty0 + (int)((mt[s] >> 8) & 255u), ox = it.tx0 + (int)(mt[s] & 255u);
+            if (mt[s] == 0xffffffffu || n >= a.N || oy >= a.Ho || ox >= a.Wo) continue;
+            const size_t o = (size_t)((n * a.Ho + oy) * a.Wo + ox) * (size_t)a.F + (size_t)fl;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (fl + 16 * j >= a.F) continue;
+                float v[4] = {acc[j][s][0], acc[j][s][1], acc[j][s][2], acc[j][s][3]};
+                if (a.bias) {
+                    const float4 b4 = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 16 * j + 4 * q) * 4u);
+                    v[0] += b4.x;
+                    v[1] += b4.y;
+                    v[2] += b4.z;
+                    v[3] += b4.w;
+                }
+                if (a.residual) {
+                    const uint2 r = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.residual) + o + 16 * j);
+                    v[0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
+                    v[1] += from_storage<DT>((uint16_t)(r.x >> 16));
+                    v[2] += from_storage<DT>((uint16_t)(r.y & 0xffffu));
+                    v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
+                }
+                uint2 out;
+                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
+                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o + 16 * j) = out;
+            }
+        }
+        if (!more_items) break;
+        c_item += nwg;
+        it = spatial_item(a, c_item);
+        bbuf ^= 1u;
+    }
+}
+
+int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds_bytes = (size_t)2 * a.npb * 1024 + (size_t)a.depth * kSpatialWStage + 2048 + (size_t)a.npb * 32;
+    const long items = (long)a.tilesN * a.tilesY * a.tilesX * a.nfb;
+    const unsigned grid = (unsigned)std::min<long>(items, 256);
+    static bool attr_done[2] = {false, false};
+    if (lds_bytes > 160 * 1024 || a.depth < 3 || a.depth > 6 || a.NI * a.TH * a.TW > 256 || a.TH > 255 || a.TW > 255 || a.PH > 1023 || a.PW > 1023) {
+        set_error("spatial_ring: tile plan does not fit the kernel");
+        return NPAS_E_SHAPE;
+    }
+    if (dtype == NPAS_BF16) {
+        auto kern = spatial_ring_kernel<NPAS_BF16>;
+        if (!attr_done[0]) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            attr_done[0] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kSpatialThreads), lds_bytes, st, a);
+    } else if (dtype == NPAS_F16) {
+        auto kern = spatial_ring_kernel<NPAS_F16>;
+        if (!attr_done[1]) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            attr_done[1] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kSpatialThreads), lds_bytes, st, a);
+    } else {
+        set_error("spatial_ring needs a 16-bit storage type");
+        return NPAS_E_DTYPE;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("spatial_ring launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
 }
 
 int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream)
@@ -1032,7 +1348,6 @@ int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *w
     // more than kFppBlocksPerWave blocks
     const int min_grid = (nblk + 4 * kFppBlocksPerWave - 1) / (4 * kFppBlocksPerWave);
     unsigned grid = (unsigned)std::max(min_grid, std::min((nblk + 3) / 4, 512));
-    if (const char *e = getenv("NPAS_FPP_GRID")) grid = (unsigned)std::max(min_grid, atoi(e)); // TEMP tuning knob
 #define NPAS_FPP_CASE(N1, N2)                                                              \
     if (nt1 == N1 && nt2 == N2) {                                                          \
         if (dtype == NPAS_BF16) fpp_launch<NPAS_BF16, N1, N2>(a, grid, st);                \

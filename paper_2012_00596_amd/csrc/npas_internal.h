@@ -62,14 +62,15 @@ struct DeviceFormat {
 };
 
 // ---- ring format: extra execution format of 1x1 layers with C % 64 == 0 ---------
-// Filters in blocks of 128, channels in chunks of 64, every (block, chunk) present (the
-// kernel walks chunk t at stage t; rg_ptr / rg_chunk record that for inspection).  Per
-// (block, chunk) wimg holds 16 A-operand images of 1 KB: image step*8 + tile, lane
-// 16*q + r, value i = W[128 fb + 16 tile + r][64 chunk + 32 step + 8 q + i] (zero where
-// pruned or past F).
+// (also built for k x k layers with C % 64 == 0, which run it at stride 1.)
+// Filters in blocks of 128, channels in chunks of 64, taps kh*KW + kw; every (block,
+// chunk, tap) present: the kernels walk them in that order, one ring stage each
+// (rg_ptr / rg_chunk record the chunk order for inspection).  Per (block, chunk, tap) wimg
+// holds 16 A-operand images of 1 KB: image step*8 + tile, lane 16*q + r, value i =
+// W[128 fb + 16 tile + r][64 chunk + 32 step + 8 q + i][tap] (zero where pruned or past F).
 struct RingFormat {
     bool present = false;
-    int nfb = 0;
+    int nfb = 0, taps = 1;
     std::vector<int32_t> rg_ptr;
     std::vector<uint32_t> rg_chunk;
     std::vector<uint16_t> wimg;
@@ -88,6 +89,7 @@ struct DeviceCopy {
     const int32_t *rg_ptr = nullptr;
     const uint32_t *rg_chunk = nullptr;
     const void *wimg = nullptr;
+    const void *zeros = nullptr; // 256 bytes of zeros
 };
 
 } // namespace npas
@@ -168,6 +170,24 @@ struct RingArgs {
     uint32_t div_howo, div_wo;  // magic reciprocals of Ho*Wo and Wo
 };
 
+struct SpatialRingArgs {
+    const void *x;
+    void *y;
+    const void *residual;
+    const float *bias;
+    const void *wimg;
+    const void *zeros;          // >= 16 bytes of zeros on the device (source of padding pixels)
+    int N, H, W, C, F, Ho, Wo;
+    int KH, KW, pad;            // stride 1
+    int NI, TH, TW;             // tile: NI images x TH x TW output pixels (<= 256)
+    int PH, PW;                 // patch of one image of the tile
+    int tilesN, tilesY, tilesX, nfb;
+    int npb;                    // 1 KB blocks (8 pixels) of one patch chunk
+    int depth;                  // weight stages in the LDS ring (3..6)
+    int act;
+    uint32_t div_tw, div_pw, div_thtw, div_phpw; // magic reciprocals
+};
+
 // Host-side plan of one conv launch (tile shape, grid, LDS bytes).
 struct ConvPlan {
     ConvGeom g;
@@ -183,6 +203,9 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
 int launch_conv_mfma(int dtype, int variant, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream);
 int launch_conv_valu(const ConvValuArgs &a, void *stream);
 int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream);
+// Tile plan of the k x k streaming kernel (geometry fields of *a); false: use another kernel.
+bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a);
+int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream);
 bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
                                 int act1, int act2, uint32_t use0, uint32_t use1, void *stream);

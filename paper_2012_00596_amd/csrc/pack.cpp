@@ -188,7 +188,6 @@ static void build_mfma_slab(npas_packed *p, const uint8_t *m, const uint8_t *w)
     const int F = p->F, C = p->C, KH = p->KH, KW = p->KW;
     d.variant = V_MFMA_SLAB;
     d.NT = F > 32 ? 4 : 2;
-    if (const char *e = getenv("NPAS_FORCE_NT")) d.NT = atoi(e) == 2 ? 2 : d.NT; // TEMP tuning knob
     d.CC = std::min(C, 64);
     d.nchunks = (C + d.CC - 1) / d.CC;
     const int SF = 16 * d.NT;
@@ -260,32 +259,34 @@ static double union_density(const npas_packed *p, const uint8_t *m)
     return total ? (double)kept / (double)total : 1.0;
 }
 
-// Ring format (see npas_internal.h): what pointwise_ring_kernel streams through LDS.
+// Ring format (see npas_internal.h): what the ring kernels stream through LDS.
 static void build_ring(npas_packed *p, const uint8_t *m, const uint8_t *w)
 {
     RingFormat &r = p->ring;
-    const int F = p->F, C = p->C;
+    const int F = p->F, C = p->C, T = p->KH * p->KW;
     r.present = true;
+    r.taps = T;
     r.nfb = (F + 127) / 128;
     r.rg_ptr.assign(r.nfb + 1, 0);
     r.rg_chunk.clear();
-    r.wimg.clear();
+    r.wimg.assign((size_t)r.nfb * (C / 64) * T * 16 * 512, 0);
     const uint16_t *w16 = reinterpret_cast<const uint16_t *>(w);
+    size_t w0 = 0;
     for (int fb = 0; fb < r.nfb; ++fb) {
         r.rg_ptr[fb] = (int32_t)r.rg_chunk.size();
         const int f0 = 128 * fb;
-        for (int cc = 0; cc < C / 64; ++cc) { // every chunk is listed: stage t of a block is chunk t
+        for (int cc = 0; cc < C / 64; ++cc) {
             r.rg_chunk.push_back((uint32_t)cc);
-            size_t w0 = r.wimg.size();
-            r.wimg.resize(w0 + 16 * 512, 0);
-            for (int step = 0; step < 2; ++step)
-                for (int tile = 0; tile < 8; ++tile)
-                    for (int lane = 0; lane < 64; ++lane)
-                        for (int i = 0; i < 8; ++i) {
-                            int rr = lane & 15, q = lane >> 4, f = f0 + 16 * tile + rr, c = 64 * cc + 32 * step + 8 * q + i;
-                            if (f < F && m[(size_t)f * C + c])
-                                r.wimg[w0 + (size_t)(step * 8 + tile) * 512 + lane * 8 + i] = w16[(size_t)f * C + c];
-                        }
+            for (int tap = 0; tap < T; ++tap, w0 += 16 * 512)
+                for (int step = 0; step < 2; ++step)
+                    for (int tile = 0; tile < 8; ++tile)
+                        for (int lane = 0; lane < 64; ++lane)
+                            for (int i = 0; i < 8; ++i) {
+                                int rr = lane & 15, q = lane >> 4, f = f0 + 16 * tile + rr, c = 64 * cc + 32 * step + 8 * q + i;
+                                if (f >= F) continue;
+                                size_t wi = ((size_t)f * C + c) * T + tap;
+                                if (m[wi]) r.wimg[w0 + (size_t)(step * 8 + tile) * 512 + lane * 8 + i] = w16[wi];
+                            }
         }
     }
     r.rg_ptr[r.nfb] = (int32_t)r.rg_chunk.size();
@@ -337,15 +338,16 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         // times the operand-fetch cost per kept position of the slab path; it pays once
         // fewer than a quarter of a tile's positions survive, and it is the only path for
         // channel counts that are not a multiple of 8 or filter counts that are not a multiple of 4.
-        const char *force = getenv("NPAS_FORCE_VARIANT"); // "gather" | "slab": benchmarking aid
+        const char *force = getenv("NPAS_FORCE_VARIANT"); // "gather" | "slab" | "noring": testing aid
         const bool slab_ok = p->C % 8 == 0 && p->F % 4 == 0;
         bool gather = !slab_ok || union_density(p, mask_full.data()) < 0.25;
-        if (force && slab_ok) gather = strcmp(force, "gather") == 0;
+        if (force && slab_ok && (strcmp(force, "gather") == 0 || strcmp(force, "slab") == 0)) gather = strcmp(force, "gather") == 0;
         if (gather) build_mfma_gather(p, mask_full.data(), (const uint8_t *)w_host);
         else build_mfma_slab(p, mask_full.data(), (const uint8_t *)w_host);
-        // 1x1 layers with whole 64-channel chunks also get the streaming (ring) format, which
-        // the run calls prefer whenever the layer is run without padding
-        if (p->KH == 1 && p->KW == 1 && p->C % 64 == 0 && p->F % 4 == 0 && !(force && strcmp(force, "noring") == 0))
+        // layers with whole 64-channel chunks also get the streaming (ring) format, which the run
+        // calls prefer for 1x1 layers without padding and k x k layers at stride 1
+        if (p->C % 64 == 0 && p->F % 4 == 0 && (double)((p->F + 127) / 128) * p->C * p->KH * p->KW * 256.0 < 256e6 &&
+            !(force && strcmp(force, "noring") == 0))
             build_ring(p, mask_full.data(), (const uint8_t *)w_host);
     }
     return NPAS_OK;
@@ -403,6 +405,7 @@ int upload(npas_packed *p)
     p->dev.rg_ptr = (const int32_t *)(b + o_rp);
     p->dev.rg_chunk = (const uint32_t *)(b + o_rc);
     p->dev.wimg = b + o_ri;
+    p->dev.zeros = b + blob.size() - 256; // the blob ends with 256 zero bytes
     return NPAS_OK;
 }
 

@@ -95,8 +95,7 @@ EDGE = [
 ]
 
 
-@pytest.mark.parametrize("case", EDGE, ids=[c[0] for c in EDGE])
-def test_edge_cases(npas, torch, case):
+def _run_edge_case(npas, torch, case):
     name, N, H, W, C, F, KH, KW, stride, pad, Bf, Bc, rate, dtype, act, use_res, use_bias = case
     print(f"edge {name}", flush=True)
     xs, xe = dtypes.quantize(prng.normal(7, 1, N * H * W * C).reshape(N, H, W, C), dtype)
@@ -122,6 +121,36 @@ def test_edge_cases(npas, torch, case):
     y2 = run_layer_gpu(npas, torch, L, p, to_dev(xs, torch), (N, H, W, C), dtype,
                        None if rs is None else to_dev(rs, torch), None if bias is None else to_dev(bias, torch))
     assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("case", EDGE, ids=[c[0] for c in EDGE])
+def test_edge_cases(npas, torch, case):
+    _run_edge_case(npas, torch, case)
+
+
+# k x k, stride 1, whole 64-channel chunks: the streaming kernel (forced, so that small
+# problems take it too): several images per tile, ragged tiles in every direction, filter
+# counts off the 128-filter block, more work items than workgroups.
+SPATIAL = [
+    ("sp_7x7_images_per_tile", 11, 7, 7, 64, 136, 3, 3, 1, 1, 8, 4, 3, dtypes.BF16, 1, True, True),
+    ("sp_14x14_two_chunks", 3, 14, 14, 128, 64, 3, 3, 1, 1, 8, 4, 2, dtypes.BF16, 2, False, True),
+    ("sp_ragged_tiles", 2, 30, 29, 64, 260, 3, 3, 1, 1, 4, 4, 2, dtypes.BF16, 0, True, False),
+    ("sp_pad0_fp16", 2, 12, 12, 64, 32, 3, 3, 1, 0, 4, 4, 2, dtypes.F16, 1, False, False),
+    ("sp_kernel_5x3", 2, 12, 17, 128, 32, 5, 3, 1, 2, 4, 4, 2, dtypes.BF16, 0, False, False),
+    ("sp_more_items_than_workgroups", 70, 16, 16, 64, 512, 3, 3, 1, 1, 8, 4, 4, dtypes.BF16, 1, True, True),
+]
+
+
+@pytest.mark.parametrize("case", SPATIAL, ids=[c[0] for c in SPATIAL])
+def test_spatial_streaming_kernel(npas, torch, case, monkeypatch):
+    monkeypatch.setenv("NPAS_FORCE_VARIANT", "spatial")
+    _run_edge_case(npas, torch, case)
+
+
+def test_config4_pattern_small_streaming_kernel(npas, torch, monkeypatch):
+    monkeypatch.setenv("NPAS_FORCE_VARIANT", "spatial")
+    print("config4 small, streaming kernel", flush=True)
+    layerwise(npas, torch, configs.config4(batch=3, HW=12))
 
 
 def test_group_with_everything_pruned_gives_bias_only(npas, torch):
