@@ -839,13 +839,16 @@ __global__ __launch_bounds__(512) void pointwise_ring_kernel(RingArgs a)
 // hold it back, and either would hold back a multiplying wave.
 //   waves 0-7   multiply: 4 pixel groups x 2 filter groups, 64 x 64 outputs each; no
 //               global loads in their main loop
-//   waves 8-9   fetch the weight stages, depth-1 stages ahead
-//   waves 10-11 fetch the patches, a few blocks per stage, finishing well before the chunk ends
-// One s_barrier per stage, executed by all twelve: a fetching wave first waits for the loads
+//   waves 8-11  fetch the weight stages, depth-1 stages ahead
+//   waves 12-15 fetch the patches, a few blocks per stage, finishing well before the chunk ends
+// (four of each: one wave gets a global->LDS load issued only every ~160 cycles, measured, so
+// the 16 loads of a weight stage have to come from several waves to keep up with the matrix cores)
+// One s_barrier per stage, executed by all sixteen: a fetching wave first waits for the loads
 // of the stage about to be multiplied; after the barrier the slot (or patch buffer) of the
 // stage before is free to be refilled.
 constexpr uint32_t kSpatialWStage = 16384;
-constexpr int kSpatialThreads = 12 * 64;
+constexpr int kSpatialThreads = 16 * 64;
+constexpr int kSpatialFetchWaves = 4; // of each kind
 
 struct SpatialItem {
     int n0, ty0, tx0, fb;
@@ -892,18 +895,18 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
     }
     __syncthreads();
 
-    if (wave >= 10) {
+    if (wave >= 8 + kSpatialFetchWaves) {
         // ---- patch fetch ------------------------------------------------------------------
-        const int wl = wave - 10;
+        const int wl = wave - 8 - kSpatialFetchWaves;
         const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
         const uint8_t *zb = reinterpret_cast<const uint8_t *>(a.zeros) + (uint32_t)(lane & 7) * 16u;
         const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u;
-        const int nblk = (a.npb - wl + 1) >> 1;                 // this wave's blocks: wl, wl + 2, ...
+        const int nblk = (a.npb - wl + kSpatialFetchWaves - 1) / kSpatialFetchWaves; // this wave's blocks: wl, wl + 4, ...
         const int per = (nblk + max(1, T - 3) - 1) / max(1, T - 3); // blocks per stage: done 3 stages early
         // blocks [k0, k1) of this wave's share of the patch of (item pi, chunk cc)
         auto patch = [&](const SpatialItem &pi, int cc, uint32_t buf, int k0, int k1) {
             for (int k = k0; k < min(k1, nblk); ++k) {
-                const int blk = wl + 2 * k;
+                const int blk = wl + kSpatialFetchWaves * k;
                 const uint32_t e = reinterpret_cast<const uint32_t *>(lds + ltab)[blk * 8 + (lane >> 3)];
                 const int n = pi.n0 + (int)(e >> 20), iy = pi.ty0 - a.pad + (int)((e >> 10) & 1023u), ix = pi.tx0 - a.pad + (int)(e & 1023u);
                 const bool inb = e != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
@@ -947,17 +950,18 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
     }
 
     if (wave >= 8) {
-        // ---- weight stage fetch: images wl*8 .. wl*8+7 of every stage ------------------------
+        // ---- weight stage fetch: images wl*4 .. wl*4+3 of every stage ------------------------
         const int wl = wave - 8;
-        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)(wl * 8) * 1024u + (uint32_t)lane * 16u;
+        constexpr int kImgs = 16 / kSpatialFetchWaves;
+        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)(wl * kImgs) * 1024u + (uint32_t)lane * 16u;
         uint32_t p_item = c_item, p_slot = 0;
         int p_fb = it.fb, p_cc = 0, p_tap = 0;
         bool p_done = false;
-        auto produce_w = [&]() { // always issues its 8 loads; past the end it repeats the last stage
+        auto produce_w = [&]() { // always issues its 4 loads; past the end it repeats the last stage
             const uint8_t *wsrc = wb + (size_t)((p_fb * nch + p_cc) * T + p_tap) * kSpatialWStage;
-            const uint32_t dst = lbase + wring + p_slot * kSpatialWStage + (uint32_t)(wl * 8) * 1024u;
+            const uint32_t dst = lbase + wring + p_slot * kSpatialWStage + (uint32_t)(wl * kImgs) * 1024u;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) lds_dma16(wsrc + i * 1024, dst + (uint32_t)i * 1024u);
+            for (int i = 0; i < kImgs; ++i) lds_dma16(wsrc + i * 1024, dst + (uint32_t)i * 1024u);
             if (++p_slot == D) p_slot = 0;
             if (!p_done) {
                 if (++p_tap == T) {
@@ -981,10 +985,11 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
             const bool more_items = c_item + nwg < nitems;
             for (int st = 0; st < nch * T; ++st) {
                 // at most the D-2 stages issued after the one about to be multiplied stay in flight
-                if (D == 3) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-                else if (D == 4) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-                else if (D == 5) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+                static_assert(kImgs == 4, "the waits below count 4 loads per stage");
+                if (D == 3) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                else if (D == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else if (D == 5) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 produce_w(); // the stage D-1 ahead, into the slot the barrier freed
             }
