@@ -195,7 +195,7 @@ def per_layer(args, torch, npas, helpers, configs):
     """Per-layer timing of one config, every layer on its own buffers (rotated when small)."""
     MFMA_PEAK, HBM_PEAK = 2500.0, 8000.0           # TFLOP/s (bf16 dense), GB/s
     cfg = args.per_layer
-    w = {2: lambda: configs.config2(batch=args.batch), 3: configs.config3, 4: configs.config4,
+    w = {1: configs.config1, 2: lambda: configs.config2(batch=args.batch), 3: configs.config3, 4: configs.config4,
          5: lambda: configs.config5(batch=args.batch)}[cfg]()
     stream = torch.cuda.current_stream().cuda_stream
     shapes = {0: w.x_shape}
@@ -251,19 +251,25 @@ def per_layer(args, torch, npas, helpers, configs):
         elif L.kind == "fc":
             macs = ishape[0] * L.F * L.C
         flop = 2.0 * macs
-        t_hbm, t_mfma = abytes / (HBM_PEAK * 1e9) * 1e6, flop / (MFMA_PEAK * 1e12) * 1e6
-        bound = "hbm" if t_hbm >= t_mfma else "mfma"
+        peak = 157.3 if w.dtype == 0 else MFMA_PEAK    # fp32 layers run on the vector ALUs
+        t_hbm, t_mfma = abytes / (HBM_PEAK * 1e9) * 1e6, flop / (peak * 1e12) * 1e6
+        bound = "hbm" if t_hbm >= t_mfma else ("alu" if w.dtype == 0 else "mfma")
         frac = max(t_hbm, t_mfma) / us
-        var = packed.info()["variant"] if packed else -1
+        if L.kind == "conv":
+            kern = npas.conv2d_kernel_name(packed, ishape[0], ishape[1], ishape[2], L.stride, L.pad)
+        elif L.kind == "fc":
+            kern = npas.conv2d_kernel_name(packed, ishape[0], 1, 1, 1, 0)
+        else:
+            kern = L.kind
         rows.append((i, L.name or L.kind, "x".join(map(str, ishape)), "x".join(map(str, oshape)), L.KH, L.stride, L.rate,
-                     var, us, flop / us / 1e6, abytes / us / 1e3, bound, frac))
+                     kern.replace("conv_", ""), us, flop / us / 1e6, abytes / us / 1e3, bound, frac))
         tot_us += us; tot_flop += flop; tot_bytes += abytes
         del xs, ys, rs
         torch.cuda.empty_cache()
     print("# config %d  %s  (us per launch; TFLOP/s dense-equivalent; GB/s algorithmic; frac = roofline floor / measured)" % (cfg, w.name))
-    print("%3s %-12s %-18s %-18s %2s %1s %4s %3s %9s %9s %9s %5s %6s" % ("i", "layer", "in", "out", "k", "s", "rate", "var", "us", "TFLOP/s", "GB/s", "bound", "frac"))
+    print("%3s %-12s %-18s %-18s %2s %1s %4s %-14s %9s %9s %9s %5s %6s" % ("i", "layer", "in", "out", "k", "s", "rate", "kernel", "us", "TFLOP/s", "GB/s", "bound", "frac"))
     for r in rows:
-        print("%3d %-12s %-18s %-18s %2d %1d %4.1f %3d %9.2f %9.2f %9.1f %5s %6.3f" % r)
+        print("%3d %-12s %-18s %-18s %2d %1d %4.1f %-14s %9.2f %9.2f %9.1f %5s %6.3f" % r)
     print("# total %.1f us  %.1f TFLOP/s dense-equivalent  %.1f GB/s algorithmic" % (tot_us, tot_flop / tot_us / 1e6, tot_bytes / tot_us / 1e3))
 
 

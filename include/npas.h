@@ -126,6 +126,12 @@ int npas_conv2d_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int
                        int stride, int pad, const void *bias_dev, const void *residual_dev,
                        npas_act act, void *hip_stream);
 
+/* Name of the kernel npas_conv2d_sparse launches for this layer and geometry
+ * ("conv_valu_f32", "conv_gather_mfma", "conv_slab_mfma", "pointwise_ring",
+ * "spatial_ring"); a static string, NULL for a NULL handle.  For reports and tests:
+ * the choice depends on the packed format and on how well the problem fills the chip. */
+const char *npas_conv2d_kernel_name(const npas_packed *p, int N, int H, int W, int stride, int pad);
+
 /* Sparse fully-connected layer: x_dev [B][IN] -> y_dev [B][OUT]; the handle comes
  * from npas_pack_fc_block (or any 1x1 packed layer). */
 int npas_fc_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int B, const void *bias_dev,

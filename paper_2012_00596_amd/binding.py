@@ -22,7 +22,8 @@ OK, E_NULL, E_SHAPE, E_MASK_NOT_BLOCK_UNIFORM, E_MASK_NOT_IN_LIBRARY, E_DTYPE, E
 
 EXPORTS = [
     "npas_last_error", "npas_pack_block_punched", "npas_pack_fc_block", "npas_pack_pattern",
-    "npas_packed_info", "npas_packed_export", "npas_free", "npas_conv2d_sparse", "npas_fc_sparse",
+    "npas_packed_info", "npas_packed_export", "npas_free", "npas_conv2d_sparse", "npas_conv2d_kernel_name",
+    "npas_fc_sparse",
     "npas_maxpool3x3s2", "npas_global_avgpool", "npas_stack_create", "npas_stack_workspace_bytes",
     "npas_run_stack", "npas_stack_num_launches", "npas_stack_free",
 ]
@@ -73,6 +74,8 @@ def lib():
         L.npas_free.argtypes = [vp]
         L.npas_free.restype = None
         L.npas_conv2d_sparse.argtypes = [vp, vp, vp, ip, ip, ip, ip, ip, vp, vp, ip, vp]
+        L.npas_conv2d_kernel_name.argtypes = [vp, ip, ip, ip, ip, ip]
+        L.npas_conv2d_kernel_name.restype = C.c_char_p
         L.npas_fc_sparse.argtypes = [vp, vp, vp, ip, vp, ip, vp]
         L.npas_maxpool3x3s2.argtypes = [vp, vp, ip, ip, ip, ip, ip, vp]
         L.npas_global_avgpool.argtypes = [vp, vp, ip, ip, ip, ip, ip, vp]
@@ -178,6 +181,11 @@ def pack_pattern(w, mask, library, dtype, stream=None):
 def conv2d_sparse(packed, x, y, N, H, W, stride, pad, bias=None, residual=None, act=ACT_NONE, stream=None):
     _check(lib().npas_conv2d_sparse(packed.handle, _dev(x), _dev(y), N, H, W, stride, pad, _dev(bias),
                                     _dev(residual), act, stream))
+
+
+def conv2d_kernel_name(packed, N, H, W, stride, pad):
+    name = lib().npas_conv2d_kernel_name(packed.handle, N, H, W, stride, pad)
+    return name.decode() if name else None
 
 
 def fc_sparse(packed, x, y, B, bias=None, act=ACT_NONE, stream=None):

@@ -246,6 +246,29 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     return force || (items >= 192 && eff >= 0.6 && fill >= 0.75);
 }
 
+// Which kernel a run call launches for this layer and geometry.
+enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SLAB, R_GATHER };
+
+static Route choose_route(const npas_packed *p, int N, int H, int W, int stride, int pad, SpatialRingArgs *sp)
+{
+    if (p->fmt.variant == V_VALU_F32) return R_VALU;
+    if (p->ring.present && p->KH == 1 && p->KW == 1 && pad == 0) return R_POINTWISE_RING;
+    if (p->ring.present && stride == 1 && plan_spatial(p, N, H, W, pad, sp)) return R_SPATIAL_RING;
+    return p->fmt.variant == V_MFMA_SLAB ? R_SLAB : R_GATHER;
+}
+
+const char *route_name(const npas_packed *p, int N, int H, int W, int stride, int pad)
+{
+    SpatialRingArgs sp;
+    switch (choose_route(p, N, H, W, stride, pad, &sp)) {
+    case R_VALU: return "conv_valu_f32";
+    case R_POINTWISE_RING: return "pointwise_ring";
+    case R_SPATIAL_RING: return "spatial_ring";
+    case R_SLAB: return "conv_slab_mfma";
+    default: return "conv_gather_mfma";
+    }
+}
+
 int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y, int N, int H, int W, int stride,
              int pad, const void *bias, const void *residual, int act, void *stream)
 {
@@ -253,7 +276,9 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         set_error("unknown activation %d", act);
         return NPAS_E_SHAPE;
     }
-    if (p->fmt.variant == V_VALU_F32) {
+    SpatialRingArgs sp;
+    const Route route = choose_route(p, N, H, W, stride, pad, &sp);
+    if (route == R_VALU) {
         ConvValuArgs a;
         a.x = (const float *)x; a.y = (float *)y; a.residual = (const float *)residual; a.bias = (const float *)bias;
         a.vg_ptr = p->dev.vg_ptr; a.vg_f0 = p->dev.vg_f0; a.vkent = p->dev.vkent; a.vw = p->dev.vw;
@@ -263,7 +288,7 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.KH = p->KH; a.KW = p->KW; a.stride = stride; a.pad = pad; a.act = act;
         return launch_conv_valu(a, stream);
     }
-    if (p->ring.present && p->KH == 1 && p->KW == 1 && pad == 0) { // streaming 1x1 path
+    if (route == R_POINTWISE_RING) { // streaming 1x1 path
         RingArgs a;
         a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
         a.rg_ptr = p->dev.rg_ptr; a.rg_chunk = p->dev.rg_chunk; a.wimg = p->dev.wimg;
@@ -279,14 +304,12 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.div_wo = magic_div((uint32_t)a.Wo);
         return launch_pointwise_ring(p->dtype, a, stream);
     }
-    if (p->ring.present && stride == 1) { // k x k streaming path, when a tile plan fills the chip
-        SpatialRingArgs a;
-        if (plan_spatial(p, N, H, W, pad, &a)) {
-            a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
-            a.wimg = p->dev.wimg; a.zeros = p->dev.zeros;
-            a.act = act;
-            return launch_spatial_ring(p->dtype, a, stream);
-        }
+    if (route == R_SPATIAL_RING) { // k x k streaming path, when a tile plan fills the chip
+        SpatialRingArgs &a = sp;
+        a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
+        a.wimg = p->dev.wimg; a.zeros = p->dev.zeros;
+        a.act = act;
+        return launch_spatial_ring(p->dtype, a, stream);
     }
     ConvPlan local;
     if (!plan) {
@@ -470,6 +493,12 @@ int npas_conv2d_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int
     int rc = check_run(p, x_dev, y_dev, N, H, W, stride, pad);
     if (rc) return rc;
     return run_conv(p, nullptr, x_dev, y_dev, N, H, W, stride, pad, bias_dev, residual_dev, act, hip_stream);
+}
+
+const char *npas_conv2d_kernel_name(const npas_packed *p, int N, int H, int W, int stride, int pad)
+{
+    if (!p || N <= 0 || H <= 0 || W <= 0 || stride <= 0 || pad < 0) return nullptr;
+    return route_name(p, N, H, W, stride, pad);
 }
 
 int npas_fc_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int B, const void *bias_dev, npas_act act,

@@ -573,17 +573,25 @@ template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid
 // registers hold data in flight, so two whole stages (96 KB per CU) are always on their
 // way while a third is multiplied — what an HBM-bound layer with little work per byte needs.
 //
-// Workgroup: 8 waves as 4 (pixels) x 2 (filters), tile 256 pixels x 128 filters, wave tile
-// 64 x 64.  Stage = 64 channels: 256 pixels x 128 B of activations (32 KB) + 16 weight
-// images of 1 KB (16 KB).  A wave issues 4 + 2 loads per stage; a load writes 64 lanes x 16 B
-// lane-linearly into one 1 KB LDS block.  Activations are stored unpadded with an XOR
-// swizzle: 16-byte vector cv of pixel p sits at p*128 + (cv ^ (p & 7))*16, so that the
-// MFMA B-operand reads (16 consecutive pixels, same cv) spread over the banks.
-// The loads are inline assembly (the compiler would otherwise drain the whole ring before
-// every LDS read); their completion is tracked by hand: vector-memory operations of a wave
-// return in order, so "at most 6 outstanding" means every stage but the newest has landed.
+// Tile 256 pixels x 128 filters.  Stage = 64 channels: 256 pixels x 128 B of activations
+// (32 KB) + 16 weight images of 1 KB (16 KB).  A load writes 64 lanes x 16 B lane-linearly
+// into one 1 KB LDS block.  Activations are stored unpadded with an XOR swizzle: 16-byte
+// vector cv of pixel p sits at p*128 + (cv ^ (p & 7))*16, so that the MFMA B-operand reads
+// (16 consecutive pixels, same cv) spread over the banks.
+//
+// Twelve waves: 0-7 multiply (4 pixel groups x 2 filter groups, 64 x 64 outputs each),
+// 8 fetches the weight images, 9-11 the activations.  The loads are inline assembly (the
+// compiler would otherwise drain the whole ring before every LDS read) and a fetching wave
+// tracks their completion by hand: a wave's vector-memory operations return in order, so "at
+// most one stage's worth outstanding" means every stage but the newest has landed.  The
+// multiplying waves issue no such loads; their residual / bias loads and their stores are
+// ordinary code the compiler waits for exactly.  One s_barrier per stage, executed by all.
 constexpr int kRingStages = 3;
 constexpr uint32_t kRingPatchBytes = 32768, kRingStageBytes = 49152;
+constexpr int kPointwiseThreads = 12 * 64;
+constexpr int kPointwiseXWaves = 3;                        // waves 9.. fetch activations
+constexpr int kPointwiseWWaves = 4 - kPointwiseXWaves;     // waves 8.. fetch weights
+constexpr int kPointwiseXLoads = (32 + kPointwiseXWaves - 1) / kPointwiseXWaves, kPointwiseWLoads = 16 / kPointwiseWWaves;
 
 __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
 {
@@ -593,149 +601,149 @@ __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
                  : "memory");
 }
 
-// 8-byte global load the compiler does not see (it would drain the ring before the use);
-// the caller waits for it by hand and then ties the value with ring_tie.
-__device__ __forceinline__ uint2 asm_load8(const void *gptr)
-{
-    uint2 v;
-    asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(v) : "v"(gptr) : "memory");
-    return v;
-}
+struct PointwiseItem {
+    uint32_t ptile, fb; // 256-pixel tile, 128-filter block
+};
 
-// 8-byte global store the compiler does not see either: with every vector-memory operation
-// of the kernel issued by hand, the kernel can count them and wait for exactly the ones it needs.
-__device__ __forceinline__ uint4 asm_load16(const void *gptr)
+__device__ __forceinline__ PointwiseItem pointwise_item(uint32_t nfb, uint32_t item)
 {
-    uint4 v;
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(gptr) : "memory");
-    return v;
+    PointwiseItem it;
+    it.ptile = item / nfb;
+    it.fb = item - it.ptile * nfb;
+    return it;
 }
-
-__device__ __forceinline__ void asm_store8(void *gptr, uint2 v)
-{
-    asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(gptr), "v"(v) : "memory");
-}
-
-// Wait until at most n vector-memory operations of this wave are outstanding (they retire in
-// order, so everything but the n youngest has completed).  The instruction takes an immediate;
-// n is rounded down to the nearest value listed here (waiting for more than asked is always safe).
-__device__ __forceinline__ void ring_wait(uint32_t n)
-{
-#define NPAS_W(k) else if (n >= k##u) asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory");
-    if (n < 4u) { // the steady state of the rings: a stage or two in flight behind the awaited one
-        if (n == 3u) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-        else if (n == 2u) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        else if (n == 1u) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    } else if (n < 8u) {
-        if (n == 6u) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else if (n == 7u) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
-        else if (n == 5u) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    }
-    NPAS_W(60) NPAS_W(54) NPAS_W(48) NPAS_W(42) NPAS_W(38) NPAS_W(32) NPAS_W(28) NPAS_W(24) NPAS_W(22) NPAS_W(20) NPAS_W(18)
-    NPAS_W(16) NPAS_W(14) NPAS_W(12) NPAS_W(10) NPAS_W(9)
-    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-#undef NPAS_W
-}
-
-// Empty statement that "redefines" 16 values loaded with asm_load8, placed after the wait
-// that covers them, so that no use of them can be scheduled above that wait.
-__device__ __forceinline__ void ring_tie(uint2 (&r)[4][4])
-{
-    asm volatile(""
-                 : "+v"(r[0][0]), "+v"(r[0][1]), "+v"(r[0][2]), "+v"(r[0][3]), "+v"(r[1][0]), "+v"(r[1][1]), "+v"(r[1][2]),
-                   "+v"(r[1][3]), "+v"(r[2][0]), "+v"(r[2][1]), "+v"(r[2][2]), "+v"(r[2][3]), "+v"(r[3][0]), "+v"(r[3][1]),
-                   "+v"(r[3][2]), "+v"(r[3][3])
-                 :
-                 : "memory");
-}
-// Same for four 16-byte values (their 16 dwords).
-#define NPAS_RING_TIE_X4(b)                                                                                             \
-    do {                                                                                                               \
-        asm volatile(""                                                                                                \
-                     : "+v"(b[0].x), "+v"(b[0].y), "+v"(b[0].z), "+v"(b[0].w), "+v"(b[1].x), "+v"(b[1].y), "+v"(b[1].z), \
-                       "+v"(b[1].w), "+v"(b[2].x), "+v"(b[2].y), "+v"(b[2].z), "+v"(b[2].w), "+v"(b[3].x), "+v"(b[3].y), \
-                       "+v"(b[3].z), "+v"(b[3].w)                                                                      \
-                     :                                                                                                 \
-                     : "memory");                                                                                      \
-    } while (0)
 
 template <int DT>
-__global__ __launch_bounds__(512) void pointwise_ring_kernel(RingArgs a)
+__global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lbase = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
-    const int wp = wave >> 1, wf = wave & 1;
     const uint32_t nwg = gridDim.x, nitems = (uint32_t)(a.nptiles * a.nfb);
     const int nst = a.C >> 6; // stages (64-channel chunks) per item
-    const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
-    const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg);
+    const uint32_t nfb = (uint32_t)a.nfb;
+    const uint32_t lbias = (uint32_t)kRingStages * kRingStageBytes; // two 1 KB bias buffers (item parity)
+    uint32_t c_item = xcd_remap(blockIdx.x, nwg);
+    if (c_item >= nitems) return;
+
+    if (wave >= 8 + kPointwiseWWaves) {
+        // ---- activation fetch: blocks wl, wl + X, wl + 2X, ... (8 pixels each) of every stage ------
+        const int wl = wave - 8 - kPointwiseWWaves;
+        const int nld = (32 - wl + kPointwiseXWaves - 1) / kPointwiseXWaves; // this wave's loads per stage
+        const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
+        const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u; // which 16-byte vector of its pixel this lane fetches
+        auto in_byte = [&](uint32_t m) __attribute__((always_inline)) -> uint32_t { // byte offset in x of output pixel m's input pixel
+            m = min(m, (uint32_t)a.M - 1u);
+            if (a.flat) return m * (uint32_t)a.C * 2u;
+            const uint32_t n = fastdiv(m, a.div_howo), r = m - n * (uint32_t)(a.Ho * a.Wo);
+            const uint32_t oy = fastdiv(r, a.div_wo), ox = r - oy * (uint32_t)a.Wo;
+            return ((n * a.H + oy * a.stride) * a.W + ox * a.stride) * (uint32_t)a.C * 2u;
+        };
+        uint32_t p_item = c_item, p_slot = 0, ppix[kPointwiseXLoads];
+        int p_t = 0;
+        bool p_done = false;
+        auto producer_item = [&]() __attribute__((always_inline)) {
+            const PointwiseItem pi = pointwise_item(nfb, p_item);
+            p_t = 0;
+#pragma unroll
+            for (int i = 0; i < kPointwiseXLoads; ++i) ppix[i] = in_byte(pi.ptile * 256u + (uint32_t)((wl + kPointwiseXWaves * i) * 8 + (lane >> 3))) + pcv;
+        };
+        producer_item();
+        auto produce = [&]() __attribute__((always_inline)) { // always issues its nld loads; past the end it repeats the last stage
+            const uint32_t dst = lbase + p_slot * kRingStageBytes + (uint32_t)wl * 1024u;
+#pragma unroll
+            for (int i = 0; i < kPointwiseXLoads; ++i)
+                if (i < nld) lds_dma16(xb + ppix[i] + (uint32_t)p_t * 128u, dst + (uint32_t)(kPointwiseXWaves * i) * 1024u);
+            if (++p_slot == (uint32_t)kRingStages) p_slot = 0;
+            if (!p_done) {
+                if (p_t + 1 < nst) ++p_t;
+                else if (p_item + nwg < nitems) {
+                    p_item += nwg;
+                    producer_item();
+                } else p_done = true;
+            }
+        };
+        for (int i = 0; i + 1 < kRingStages; ++i) produce();
+        for (;;) {
+            for (int t = 0; t < nst; ++t) {
+                static_assert(kRingStages == 3 && kPointwiseXLoads == 11, "the wait below leaves one stage (nld loads) in flight");
+                if (nld == 11) asm volatile("s_waitcnt vmcnt(11)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                produce(); // two stages ahead, into the slot the barrier freed
+            }
+            if (c_item + nwg >= nitems) break;
+            c_item += nwg;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+
+    if (wave >= 8) {
+        // ---- weight fetch: the 16 images of every stage, and each item's bias ----------------------
+        const int wl = wave - 8;
+        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)(wl * kPointwiseWLoads) * 1024u + (uint32_t)lane * 16u;
+        uint32_t p_item = c_item, p_slot = 0;
+        PointwiseItem pi = pointwise_item(nfb, p_item);
+        int p_t = 0;
+        bool p_done = false;
+        auto produce = [&]() __attribute__((always_inline)) { // always issues its loads; past the end it repeats the last stage
+            const uint8_t *wsrc = wb + (size_t)(pi.fb * (uint32_t)nst + (uint32_t)p_t) * 16384u;
+            const uint32_t dst = lbase + p_slot * kRingStageBytes + kRingPatchBytes + (uint32_t)(wl * kPointwiseWLoads) * 1024u;
+#pragma unroll
+            for (int i = 0; i < kPointwiseWLoads; ++i) lds_dma16(wsrc + i * 1024, dst + (uint32_t)i * 1024u);
+            if (++p_slot == (uint32_t)kRingStages) p_slot = 0;
+            if (!p_done) {
+                if (p_t + 1 < nst) ++p_t;
+                else if (p_item + nwg < nitems) {
+                    p_item += nwg;
+                    pi = pointwise_item(nfb, p_item);
+                    p_t = 0;
+                } else p_done = true;
+            }
+        };
+        // bias of an item's 128 filters (512 B; lanes 32-63 fetch a copy that nobody reads)
+        auto bias_block = [&](uint32_t fb, uint32_t buf) __attribute__((always_inline)) {
+            if (!a.bias || wl != 0) return;
+            const int f = (int)fb * 128 + (lane & 31) * 4;
+            lds_dma16(a.bias + (f < a.F ? f : 0), lbase + lbias + buf * 1024u);
+        };
+        uint32_t bbuf = 0;
+        bias_block(pi.fb, 0);
+        for (int i = 0; i + 1 < kRingStages; ++i) produce();
+        for (;;) {
+            const bool more = c_item + nwg < nitems;
+            for (int t = 0; t < nst; ++t) {
+                // one stage (16 loads) may stay in flight; a bias load in between only makes this stricter
+                static_assert(kPointwiseWLoads == 16, "the wait below counts 16 loads per stage");
+                asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                // the other bias buffer was last read in the epilogue before this item's first barrier
+                if (t == 0 && more) bias_block(pointwise_item(nfb, c_item + nwg).fb, bbuf ^ 1u);
+                produce();
+            }
+            if (!more) break;
+            c_item += nwg;
+            bbuf ^= 1u;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+
+    // ---- multiply ------------------------------------------------------------------------
+    const int wp = wave >> 1, wf = wave & 1;
     uint8_t *yb = reinterpret_cast<uint8_t *>(a.y);
     const uint8_t *rb = reinterpret_cast<const uint8_t *>(a.residual);
     const Clamp cl = clamp_of(a.act);
-
-    // byte offset in x of output pixel m's input pixel
-    auto in_byte = [&](uint32_t m) -> uint32_t {
-        m = min(m, (uint32_t)a.M - 1u);
-        if (a.flat) return m * (uint32_t)a.C * 2u;
-        const uint32_t n = fastdiv(m, a.div_howo), r = m - n * (uint32_t)(a.Ho * a.Wo);
-        const uint32_t oy = fastdiv(r, a.div_wo), ox = r - oy * (uint32_t)a.Wo;
-        return ((n * a.H + oy * a.stride) * a.W + ox * a.stride) * (uint32_t)a.C * 2u;
-    };
-
-    // ---- producer: which (item, chunk) the next issued stage is --------------------------
-    uint32_t p_item = xcd_remap(blockIdx.x, nwg);
-    if (p_item >= nitems) return;
-    int p_t = 0;
-    uint32_t p_fb = 0;
-    uint32_t ppix[4];
-    const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u; // which 16-byte vector of the pixel this lane fetches
-    auto producer_item = [&]() {
-        const uint32_t ptile = p_item / (uint32_t)a.nfb;
-        p_fb = p_item - ptile * (uint32_t)a.nfb;
-        p_t = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) ppix[i] = in_byte(ptile * 256u + (uint32_t)((wave * 4 + i) * 8 + (lane >> 3)));
-    };
-    producer_item();
-    bool p_done = false;
-    // Issue accounting (wave-uniform): `issued` counts this wave's vector-memory operations,
-    // mark_* remember the count right after the loads of the stage in each ring slot.
-    uint32_t issued = 0, mark_cur = 0, mark_nxt = 0;
-    auto produce = [&](uint32_t slot) { // always issues its 6 loads; past the end it repeats the last stage
-        const uint32_t sbase = lbase + slot * kRingStageBytes;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) lds_dma16(xb + ppix[i] + (uint32_t)p_t * 128u + pcv, sbase + (uint32_t)(wave * 4 + i) * 1024u);
-        const uint8_t *wsrc = wb + (size_t)(p_fb * (uint32_t)nst + (uint32_t)p_t) * 16384u + (uint32_t)(wave * 2) * 1024u + (uint32_t)lane * 16u;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) lds_dma16(wsrc + i * 1024, sbase + kRingPatchBytes + (uint32_t)(wave * 2 + i) * 1024u);
-        issued += 6u;
-        if (!p_done) {
-            if (p_t + 1 < nst) ++p_t;
-            else if (p_item + nwg < nitems) {
-                p_item += nwg;
-                producer_item();
-            } else p_done = true;
-        }
-    };
-    produce(0);
-    mark_cur = issued;
-    produce(1);
-    mark_nxt = issued;
-
-    // ---- consumer ------------------------------------------------------------------
-    uint32_t c_item = xcd_remap(blockIdx.x, nwg);
     const uint32_t brow = (uint32_t)((wp * 64 + n16) * 128), arow = (uint32_t)(wf * 4) * 1024u + (uint32_t)lane * 16u;
-    uint32_t stage = 0;
+    uint32_t c_slot = 0, bbuf = 0;
     for (;;) { // one item per iteration
-        const uint32_t ptile = c_item / (uint32_t)a.nfb, fb = c_item - ptile * (uint32_t)a.nfb;
-        const int fl = (int)fb * 128 + wf * 64 + 4 * q; // this lane's first filter in row tile 0
+        const PointwiseItem it = pointwise_item(nfb, c_item);
+        const int fl = (int)it.fb * 128 + wf * 64 + 4 * q; // this lane's first filter in row tile 0
         uint32_t obyte[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const uint32_t m = ptile * 256u + (uint32_t)(wp * 64 + s * 16 + n16);
+            const uint32_t m = it.ptile * 256u + (uint32_t)(wp * 64 + s * 16 + n16);
             obyte[s] = m < (uint32_t)a.M ? (m * (uint32_t)a.F + (uint32_t)fl) * 2u : 0xffffffffu;
         }
         f32x4 acc[4][4];
@@ -744,30 +752,23 @@ __global__ __launch_bounds__(512) void pointwise_ring_kernel(RingArgs a)
 #pragma unroll
             for (int s = 0; s < 4; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
         uint2 res[4][4];
-        uint4 bia[4];
-        for (int t = 0; t < nst; ++t, ++stage) {
-            ring_wait(__builtin_amdgcn_readfirstlane(issued - mark_cur)); // this stage's loads (own wave) have landed
-            __builtin_amdgcn_s_barrier();  // ... and everyone's; and everyone is done with the stage before
+        for (int t = 0; t < nst; ++t) {
+            __builtin_amdgcn_s_barrier(); // this stage has landed; everyone is done with the stage before
             asm volatile("" ::: "memory");
-            if (rb && t == nst - 1) { // residual: asked for before the newest stage, used after the multiply
-                issued += 16u;
+            if (rb && t == nst - 1) { // residual: asked for before the last multiply, used after it
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int s = 0; s < 4; ++s) {
+                    uint32_t ob = obyte[s];
+                    asm volatile("" : "+v"(ob)); // keeps the 16 addresses from being formed (and held) outside the loop
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) {
-                        const bool ok = obyte[s] != 0xffffffffu && fl + 16 * j < a.F;
-                        res[j][s] = asm_load8(rb + (ok ? obyte[s] + 32u * j : 0u));
+                    for (int j = 0; j < 4; ++j) {
+                        const bool ok = ob != 0xffffffffu && fl + 16 * j < a.F;
+                        res[j][s] = *reinterpret_cast<const uint2 *>(rb + (ok ? ob + 32u * j : 0u));
                     }
+                }
             }
-            if (a.bias && t == nst - 1) { // bias of this lane's 4 x 4 filters (F is a multiple of 4)
-                issued += 4u;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) bia[j] = asm_load16(a.bias + (fl + 16 * j < a.F ? fl + 16 * j : 0));
-            }
-            produce((stage + 2) % kRingStages);
-            mark_cur = mark_nxt;
-            mark_nxt = issued;
-            const uint8_t *sb = lds + (stage % kRingStages) * kRingStageBytes;
+            const uint8_t *sb = lds + c_slot * kRingStageBytes;
+            if (++c_slot == (uint32_t)kRingStages) c_slot = 0;
 #pragma unroll
             for (int step = 0; step < 2; ++step) {
                 uint4 A[4], B[4];
@@ -784,44 +785,33 @@ __global__ __launch_bounds__(512) void pointwise_ring_kernel(RingArgs a)
             }
         }
         // ---- bias, residual, clamp (activation), round, store -----------------------------
-        if (rb || a.bias) asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); // the stage issued after them may stay in flight
-        if (rb) ring_tie(res);
-        if (a.bias) NPAS_RING_TIE_X4(bia);
+        {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (fl + 16 * j >= a.F) continue;
-            float bv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (a.bias) {
-                bv[0] = __uint_as_float(bia[j].x);
-                bv[1] = __uint_as_float(bia[j].y);
-                bv[2] = __uint_as_float(bia[j].z);
-                bv[3] = __uint_as_float(bia[j].w);
-            }
+            for (int j = 0; j < 4; ++j) {
+                if (fl + 16 * j >= a.F) continue;
+                float4 bv = float4{0.f, 0.f, 0.f, 0.f};
+                if (a.bias) bv = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 16 * j + 4 * q) * 4u);
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                if (obyte[s] == 0xffffffffu) continue;
-                float v[4] = {acc[j][s][0] + bv[0], acc[j][s][1] + bv[1], acc[j][s][2] + bv[2], acc[j][s][3] + bv[3]};
-                if (rb) {
-                    v[0] += from_storage<DT>((uint16_t)(res[j][s].x & 0xffffu));
-                    v[1] += from_storage<DT>((uint16_t)(res[j][s].x >> 16));
-                    v[2] += from_storage<DT>((uint16_t)(res[j][s].y & 0xffffu));
-                    v[3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
+                for (int s = 0; s < 4; ++s) {
+                    if (obyte[s] == 0xffffffffu) continue;
+                    float v[4] = {acc[j][s][0] + bv.x, acc[j][s][1] + bv.y, acc[j][s][2] + bv.z, acc[j][s][3] + bv.w};
+                    if (rb) {
+                        v[0] += from_storage<DT>((uint16_t)(res[j][s].x & 0xffffu));
+                        v[1] += from_storage<DT>((uint16_t)(res[j][s].x >> 16));
+                        v[2] += from_storage<DT>((uint16_t)(res[j][s].y & 0xffffu));
+                        v[3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
+                    }
+                    uint2 out;
+                    out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
+                    out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                    *reinterpret_cast<uint2 *>(yb + obyte[s] + 32u * j) = out;
                 }
-                uint2 out;
-                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                asm_store8(yb + obyte[s] + 32u * j, out);
             }
-        }
-        {   // stores just issued by this wave: one per (row tile, pixel block) that has any valid lane
-            const int fw = (int)fb * 128 + wf * 64, mw = (int)(ptile * 256u) + wp * 64;
-            const int nj = max(0, min(4, (a.F - fw + 15) >> 4)), ns = max(0, min(4, (a.M - mw + 15) >> 4));
-            issued += (uint32_t)(nj * ns);
         }
         if (c_item + nwg >= nitems) break;
         c_item += nwg;
+        bbuf ^= 1u;
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70); // drain the (repeated) loads still in flight before the wave ends
 }
 
 // ------------------------------------------------------------------------------
@@ -904,7 +894,7 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
         const int nblk = (a.npb - wl + kSpatialFetchWaves - 1) / kSpatialFetchWaves; // this wave's blocks: wl, wl + 4, ...
         const int per = (nblk + max(1, T - 3) - 1) / max(1, T - 3); // blocks per stage: done 3 stages early
         // blocks [k0, k1) of this wave's share of the patch of (item pi, chunk cc)
-        auto patch = [&](const SpatialItem &pi, int cc, uint32_t buf, int k0, int k1) {
+        auto patch = [&](const SpatialItem &pi, int cc, uint32_t buf, int k0, int k1) __attribute__((always_inline)) {
             for (int k = k0; k < min(k1, nblk); ++k) {
                 const int blk = wl + kSpatialFetchWaves * k;
                 const uint32_t e = reinterpret_cast<const uint32_t *>(lds + ltab)[blk * 8 + (lane >> 3)];
@@ -915,7 +905,7 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
             }
         };
         // bias of an item's 128 filters (512 B; lanes 32-63 fetch a copy that nobody reads)
-        auto bias_block = [&](const SpatialItem &pi, uint32_t buf) {
+        auto bias_block = [&](const SpatialItem &pi, uint32_t buf) __attribute__((always_inline)) {
             if (!a.bias || wl != 0) return;
             const int f = pi.fb * 128 + (lane & 31) * 4;
             lds_dma16(a.bias + (f < a.F ? f : 0), lbase + lbias + buf * 1024u);
@@ -957,7 +947,7 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
         uint32_t p_item = c_item, p_slot = 0;
         int p_fb = it.fb, p_cc = 0, p_tap = 0;
         bool p_done = false;
-        auto produce_w = [&]() { // always issues its 4 loads; past the end it repeats the last stage
+        auto produce_w = [&]() __attribute__((always_inline)) { // always issues its 4 loads; past the end it repeats the last stage
             const uint8_t *wsrc = wb + (size_t)((p_fb * nch + p_cc) * T + p_tap) * kSpatialWStage;
             const uint32_t dst = lbase + wring + p_slot * kSpatialWStage + (uint32_t)(wl * kImgs) * 1024u;
 #pragma unroll
@@ -1140,7 +1130,7 @@ int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
 int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds_bytes = (size_t)kRingStages * kRingStageBytes;
+    const size_t lds_bytes = (size_t)kRingStages * kRingStageBytes + 2048;
     const unsigned grid = (unsigned)std::min<long>((long)a.nptiles * a.nfb, 256);
     static bool attr_done[2] = {false, false};
     if (dtype == NPAS_BF16) {
@@ -1149,14 +1139,14 @@ int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream)
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
             attr_done[0] = true;
         }
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds_bytes, st, a);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kPointwiseThreads), lds_bytes, st, a);
     } else if (dtype == NPAS_F16) {
         auto kern = pointwise_ring_kernel<NPAS_F16>;
         if (!attr_done[1]) {
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
             attr_done[1] = true;
         }
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds_bytes, st, a);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kPointwiseThreads), lds_bytes, st, a);
     } else {
         set_error("pointwise_ring needs a 16-bit storage type");
         return NPAS_E_DTYPE;

@@ -92,6 +92,7 @@ struct DeviceCopy {
     const void *zeros = nullptr; // 256 bytes of zeros
 };
 
+
 } // namespace npas
 
 struct npas_packed {
@@ -203,6 +204,7 @@ int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, Co
 int launch_conv_mfma(int dtype, int variant, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream);
 int launch_conv_valu(const ConvValuArgs &a, void *stream);
 int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream);
+const char *route_name(const npas_packed *p, int N, int H, int W, int stride, int pad);
 // Tile plan of the k x k streaming kernel (geometry fields of *a); false: use another kernel.
 bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a);
 int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream);

@@ -95,7 +95,7 @@ EDGE = [
 ]
 
 
-def _run_edge_case(npas, torch, case):
+def _run_edge_case(npas, torch, case, expect_kernel=None):
     name, N, H, W, C, F, KH, KW, stride, pad, Bf, Bc, rate, dtype, act, use_res, use_bias = case
     print(f"edge {name}", flush=True)
     xs, xe = dtypes.quantize(prng.normal(7, 1, N * H * W * C).reshape(N, H, W, C), dtype)
@@ -111,6 +111,8 @@ def _run_edge_case(npas, torch, case):
                                                re, act), dtype)
     p = pack_layer(npas, L, dtype)
     helpers.check_metadata(oracle, L, p, dtype)
+    if expect_kernel is not None:
+        assert npas.conv2d_kernel_name(p, N, H, W, stride, pad) == expect_kernel
     y = run_layer_gpu(npas, torch, L, p, to_dev(xs, torch), (N, H, W, C), dtype,
                       None if rs is None else to_dev(rs, torch), None if bias is None else to_dev(bias, torch))
     got = from_dev(y, dtype).reshape(oshape)
@@ -144,7 +146,7 @@ SPATIAL = [
 @pytest.mark.parametrize("case", SPATIAL, ids=[c[0] for c in SPATIAL])
 def test_spatial_streaming_kernel(npas, torch, case, monkeypatch):
     monkeypatch.setenv("NPAS_FORCE_VARIANT", "spatial")
-    _run_edge_case(npas, torch, case)
+    _run_edge_case(npas, torch, case, expect_kernel="spatial_ring")
 
 
 def test_config4_pattern_small_streaming_kernel(npas, torch, monkeypatch):
