@@ -298,6 +298,12 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.M = N * a.Ho * a.Wo;
         a.nptiles = (a.M + 255) / 256;
         a.nfb = p->ring.nfb;
+        a.small = 0;
+        if ((long)a.nptiles * a.nfb < 96) { // most CUs would get no tile: smaller tiles, deeper ring
+            a.small = 1;
+            a.nptiles = (a.M + 63) / 64;
+            a.nfb = (p->F + 63) / 64;
+        }
         a.act = act;
         a.flat = stride == 1;
         a.div_howo = magic_div((uint32_t)(a.Ho * a.Wo));

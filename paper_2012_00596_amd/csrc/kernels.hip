@@ -570,28 +570,39 @@ template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid
 // ------------------------------------------------------------------------------
 // pointwise_ring: 1x1 layers (and FC) with C a multiple of 64, streamed through a ring of
 // LDS stages that are filled by direct global->LDS loads (global_load_lds_dwordx4): no
-// registers hold data in flight, so two whole stages (96 KB per CU) are always on their
-// way while a third is multiplied — what an HBM-bound layer with little work per byte needs.
+// registers hold data in flight, so whole stages are always on their way while one is
+// multiplied — what an HBM-bound layer with little work per byte needs.
 //
-// Tile 256 pixels x 128 filters.  Stage = 64 channels: 256 pixels x 128 B of activations
-// (32 KB) + 16 weight images of 1 KB (16 KB).  A load writes 64 lanes x 16 B lane-linearly
+// Tile (PW * 64) pixels x (FW * 64) filters.  Stage = 64 channels: 128 B per pixel of
+// activations + FW * 8 weight images of 1 KB.  A load writes 64 lanes x 16 B lane-linearly
 // into one 1 KB LDS block.  Activations are stored unpadded with an XOR swizzle: 16-byte
 // vector cv of pixel p sits at p*128 + (cv ^ (p & 7))*16, so that the MFMA B-operand reads
 // (16 consecutive pixels, same cv) spread over the banks.
 //
-// Twelve waves: 0-7 multiply (4 pixel groups x 2 filter groups, 64 x 64 outputs each),
-// 8 fetches the weight images, 9-11 the activations.  The loads are inline assembly (the
-// compiler would otherwise drain the whole ring before every LDS read) and a fetching wave
-// tracks their completion by hand: a wave's vector-memory operations return in order, so "at
-// most one stage's worth outstanding" means every stage but the newest has landed.  The
-// multiplying waves issue no such loads; their residual / bias loads and their stores are
+// Waves 0 .. PW*FW-1 multiply (PW pixel groups x FW filter groups, 64 x 64 outputs each), the
+// next WW fetch the weight images, the last XW the activations.  The loads are inline assembly
+// (the compiler would otherwise drain the whole ring before every LDS read) and a fetching
+// wave tracks their completion by hand: a wave's vector-memory operations return in order, so
+// "at most D-2 stages' worth outstanding" means the stage about to be multiplied has landed.
+// The multiplying waves issue no such loads; their residual / bias loads and their stores are
 // ordinary code the compiler waits for exactly.  One s_barrier per stage, executed by all.
-constexpr int kRingStages = 3;
-constexpr uint32_t kRingPatchBytes = 32768, kRingStageBytes = 49152;
-constexpr int kPointwiseThreads = 12 * 64;
-constexpr int kPointwiseXWaves = 3;                        // waves 9.. fetch activations
-constexpr int kPointwiseWWaves = 4 - kPointwiseXWaves;     // waves 8.. fetch weights
-constexpr int kPointwiseXLoads = (32 + kPointwiseXWaves - 1) / kPointwiseXWaves, kPointwiseWLoads = 16 / kPointwiseWWaves;
+//
+// Two configurations: 256 x 128 tiles with a 3-stage ring (throughput: most bytes in flight
+// per CU, most reuse of the weights), and 64 x 64 tiles with an 8-stage ring for launches
+// that would leave most CUs without a tile (small batches): more, smaller items, and a whole
+// layer's channel loop in flight at once instead of one load latency per stage.
+template <int PW_, int FW_, int XW_, int WW_, int D_> struct PointwiseCfg {
+    static constexpr int PW = PW_, FW = FW_, XW = XW_, WW = WW_, D = D_;
+    static constexpr int kComputeWaves = PW * FW;
+    static constexpr int kThreads = (kComputeWaves + XW + WW) * 64;
+    static constexpr uint32_t kXBytes = PW * 8192, kWBytes = FW * 8192, kStageBytes = kXBytes + kWBytes;
+    static constexpr int kXBlocks = PW * 8, kWImages = FW * 8;             // 1 KB loads per stage
+    static constexpr int kXLoads = (kXBlocks + XW - 1) / XW, kWLoads = (kWImages + WW - 1) / WW; // per fetch wave, at most
+    static constexpr size_t kLdsBytes = (size_t)D * kStageBytes + 2048;    // + two bias buffers
+    static_assert(D >= 3 && kXLoads * (D - 1) <= 63 && kWLoads * (D - 1) <= 63, "a wave can have 63 loads in flight");
+};
+using PointwiseBig = PointwiseCfg<4, 2, 3, 1, 3>;
+using PointwiseSmall = PointwiseCfg<1, 1, 2, 2, 8>;
 
 __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
 {
@@ -601,8 +612,26 @@ __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
                  : "memory");
 }
 
+// "At most n vector-memory operations of this wave outstanding" for a wave-uniform n < 64
+// (the instruction takes an immediate).
+__device__ __forceinline__ void wait_vmcnt(uint32_t n)
+{
+#define NPAS_W(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
+    switch (n) {
+        NPAS_W(0) NPAS_W(1) NPAS_W(2) NPAS_W(3) NPAS_W(4) NPAS_W(5) NPAS_W(6) NPAS_W(7) NPAS_W(8) NPAS_W(9) NPAS_W(10)
+        NPAS_W(11) NPAS_W(12) NPAS_W(13) NPAS_W(14) NPAS_W(15) NPAS_W(16) NPAS_W(17) NPAS_W(18) NPAS_W(19) NPAS_W(20)
+        NPAS_W(21) NPAS_W(22) NPAS_W(23) NPAS_W(24) NPAS_W(25) NPAS_W(26) NPAS_W(27) NPAS_W(28) NPAS_W(29) NPAS_W(30)
+        NPAS_W(31) NPAS_W(32) NPAS_W(33) NPAS_W(34) NPAS_W(35) NPAS_W(36) NPAS_W(37) NPAS_W(38) NPAS_W(39) NPAS_W(40)
+        NPAS_W(41) NPAS_W(42) NPAS_W(43) NPAS_W(44) NPAS_W(45) NPAS_W(46) NPAS_W(47) NPAS_W(48) NPAS_W(49) NPAS_W(50)
+        NPAS_W(51) NPAS_W(52) NPAS_W(53) NPAS_W(54) NPAS_W(55) NPAS_W(56) NPAS_W(57) NPAS_W(58) NPAS_W(59) NPAS_W(60)
+        NPAS_W(61) NPAS_W(62)
+    default: asm volatile("s_waitcnt vmcnt(63)" ::: "memory"); break;
+    }
+#undef NPAS_W
+}
+
 struct PointwiseItem {
-    uint32_t ptile, fb; // 256-pixel tile, 128-filter block
+    uint32_t ptile, fb; // pixel tile, filter block (in units of the configuration's tile)
 };
 
 __device__ __forceinline__ PointwiseItem pointwise_item(uint32_t nfb, uint32_t item)
@@ -613,23 +642,24 @@ __device__ __forceinline__ PointwiseItem pointwise_item(uint32_t nfb, uint32_t i
     return it;
 }
 
-template <int DT>
-__global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingArgs a)
+template <int DT, typename Cfg>
+__global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs a)
 {
+    constexpr int PW = Cfg::PW, FW = Cfg::FW, XW = Cfg::XW, WW = Cfg::WW, D = Cfg::D, NC = Cfg::kComputeWaves;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lbase = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
     const uint32_t nwg = gridDim.x, nitems = (uint32_t)(a.nptiles * a.nfb);
     const int nst = a.C >> 6; // stages (64-channel chunks) per item
     const uint32_t nfb = (uint32_t)a.nfb;
-    const uint32_t lbias = (uint32_t)kRingStages * kRingStageBytes; // two 1 KB bias buffers (item parity)
+    const uint32_t lbias = (uint32_t)D * Cfg::kStageBytes; // two 1 KB bias buffers (item parity)
     uint32_t c_item = xcd_remap(blockIdx.x, nwg);
     if (c_item >= nitems) return;
 
-    if (wave >= 8 + kPointwiseWWaves) {
-        // ---- activation fetch: blocks wl, wl + X, wl + 2X, ... (8 pixels each) of every stage ------
-        const int wl = wave - 8 - kPointwiseWWaves;
-        const int nld = (32 - wl + kPointwiseXWaves - 1) / kPointwiseXWaves; // this wave's loads per stage
+    if (wave >= NC + WW) {
+        // ---- activation fetch: blocks wl, wl + XW, wl + 2 XW, ... (8 pixels each) of every stage ----
+        const int wl = wave - NC - WW;
+        const int nld = (Cfg::kXBlocks - wl + XW - 1) / XW; // this wave's loads per stage
         const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
         const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u; // which 16-byte vector of its pixel this lane fetches
         auto in_byte = [&](uint32_t m) __attribute__((always_inline)) -> uint32_t { // byte offset in x of output pixel m's input pixel
@@ -639,22 +669,22 @@ __global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingA
             const uint32_t oy = fastdiv(r, a.div_wo), ox = r - oy * (uint32_t)a.Wo;
             return ((n * a.H + oy * a.stride) * a.W + ox * a.stride) * (uint32_t)a.C * 2u;
         };
-        uint32_t p_item = c_item, p_slot = 0, ppix[kPointwiseXLoads];
+        uint32_t p_item = c_item, p_slot = 0, ppix[Cfg::kXLoads];
         int p_t = 0;
         bool p_done = false;
         auto producer_item = [&]() __attribute__((always_inline)) {
             const PointwiseItem pi = pointwise_item(nfb, p_item);
             p_t = 0;
 #pragma unroll
-            for (int i = 0; i < kPointwiseXLoads; ++i) ppix[i] = in_byte(pi.ptile * 256u + (uint32_t)((wl + kPointwiseXWaves * i) * 8 + (lane >> 3))) + pcv;
+            for (int i = 0; i < Cfg::kXLoads; ++i) ppix[i] = in_byte(pi.ptile * (uint32_t)(PW * 64) + (uint32_t)((wl + XW * i) * 8 + (lane >> 3))) + pcv;
         };
         producer_item();
         auto produce = [&]() __attribute__((always_inline)) { // always issues its nld loads; past the end it repeats the last stage
-            const uint32_t dst = lbase + p_slot * kRingStageBytes + (uint32_t)wl * 1024u;
+            const uint32_t dst = lbase + p_slot * Cfg::kStageBytes + (uint32_t)wl * 1024u;
 #pragma unroll
-            for (int i = 0; i < kPointwiseXLoads; ++i)
-                if (i < nld) lds_dma16(xb + ppix[i] + (uint32_t)p_t * 128u, dst + (uint32_t)(kPointwiseXWaves * i) * 1024u);
-            if (++p_slot == (uint32_t)kRingStages) p_slot = 0;
+            for (int i = 0; i < Cfg::kXLoads; ++i)
+                if (i < nld) lds_dma16(xb + ppix[i] + (uint32_t)p_t * 128u, dst + (uint32_t)(XW * i) * 1024u);
+            if (++p_slot == (uint32_t)D) p_slot = 0;
             if (!p_done) {
                 if (p_t + 1 < nst) ++p_t;
                 else if (p_item + nwg < nitems) {
@@ -663,14 +693,13 @@ __global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingA
                 } else p_done = true;
             }
         };
-        for (int i = 0; i + 1 < kRingStages; ++i) produce();
+        for (int i = 0; i + 1 < D; ++i) produce();
+        const uint32_t allow = (uint32_t)(nld * (D - 2)); // the D-2 stages issued after the awaited one may stay in flight
         for (;;) {
             for (int t = 0; t < nst; ++t) {
-                static_assert(kRingStages == 3 && kPointwiseXLoads == 11, "the wait below leaves one stage (nld loads) in flight");
-                if (nld == 11) asm volatile("s_waitcnt vmcnt(11)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+                wait_vmcnt(allow);
                 __builtin_amdgcn_s_barrier();
-                produce(); // two stages ahead, into the slot the barrier freed
+                produce(); // D-1 stages ahead, into the slot the barrier freed
             }
             if (c_item + nwg >= nitems) break;
             c_item += nwg;
@@ -679,20 +708,30 @@ __global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingA
         return;
     }
 
-    if (wave >= 8) {
-        // ---- weight fetch: the 16 images of every stage, and each item's bias ----------------------
-        const int wl = wave - 8;
-        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)(wl * kPointwiseWLoads) * 1024u + (uint32_t)lane * 16u;
+    if (wave >= NC) {
+        // ---- weight fetch: images wl, wl + WW, ... of every stage, and each item's bias --------------
+        // A stage's images in the packed format are [step 0..1][filter half 0..1][row tile 0..3]; a
+        // 64-filter tile (FW == 1) takes the four row tiles of its half in each step.
+        const int wl = wave - NC;
+        const int nld = (Cfg::kWImages - wl + WW - 1) / WW;
+        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)lane * 16u;
         uint32_t p_item = c_item, p_slot = 0;
         PointwiseItem pi = pointwise_item(nfb, p_item);
         int p_t = 0;
         bool p_done = false;
         auto produce = [&]() __attribute__((always_inline)) { // always issues its loads; past the end it repeats the last stage
-            const uint8_t *wsrc = wb + (size_t)(pi.fb * (uint32_t)nst + (uint32_t)p_t) * 16384u;
-            const uint32_t dst = lbase + p_slot * kRingStageBytes + kRingPatchBytes + (uint32_t)(wl * kPointwiseWLoads) * 1024u;
+            const uint32_t fb128 = FW == 2 ? pi.fb : pi.fb >> 1, half = FW == 2 ? 0u : pi.fb & 1u;
+            const uint8_t *wsrc = wb + (size_t)(fb128 * (uint32_t)nst + (uint32_t)p_t) * 16384u;
+            const uint32_t dst = lbase + p_slot * Cfg::kStageBytes + Cfg::kXBytes;
 #pragma unroll
-            for (int i = 0; i < kPointwiseWLoads; ++i) lds_dma16(wsrc + i * 1024, dst + (uint32_t)i * 1024u);
-            if (++p_slot == (uint32_t)kRingStages) p_slot = 0;
+            for (int i = 0; i < Cfg::kWLoads; ++i) {
+                const int img = wl + WW * i; // local image: step * (FW * 4) + (filter group) * 4 + row tile
+                if (i < nld) {
+                    const uint32_t src_img = FW == 2 ? (uint32_t)img : (uint32_t)((img >> 2) * 8 + (img & 3)) + half * 4u;
+                    lds_dma16(wsrc + src_img * 1024u, dst + (uint32_t)img * 1024u);
+                }
+            }
+            if (++p_slot == (uint32_t)D) p_slot = 0;
             if (!p_done) {
                 if (p_t + 1 < nst) ++p_t;
                 else if (p_item + nwg < nitems) {
@@ -702,21 +741,21 @@ __global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingA
                 } else p_done = true;
             }
         };
-        // bias of an item's 128 filters (512 B; lanes 32-63 fetch a copy that nobody reads)
+        // bias of an item's filters (lanes past the tile fetch a copy that nobody reads)
         auto bias_block = [&](uint32_t fb, uint32_t buf) __attribute__((always_inline)) {
             if (!a.bias || wl != 0) return;
-            const int f = (int)fb * 128 + (lane & 31) * 4;
+            const int f = (int)fb * (FW * 64) + (lane & (FW * 16 - 1)) * 4;
             lds_dma16(a.bias + (f < a.F ? f : 0), lbase + lbias + buf * 1024u);
         };
         uint32_t bbuf = 0;
         bias_block(pi.fb, 0);
-        for (int i = 0; i + 1 < kRingStages; ++i) produce();
+        for (int i = 0; i + 1 < D; ++i) produce();
+        // a bias load in between only makes the wait stricter (one more completion than needed)
+        const uint32_t allow = (uint32_t)(nld * (D - 2));
         for (;;) {
             const bool more = c_item + nwg < nitems;
             for (int t = 0; t < nst; ++t) {
-                // one stage (16 loads) may stay in flight; a bias load in between only makes this stricter
-                static_assert(kPointwiseWLoads == 16, "the wait below counts 16 loads per stage");
-                asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+                wait_vmcnt(allow);
                 __builtin_amdgcn_s_barrier();
                 // the other bias buffer was last read in the epilogue before this item's first barrier
                 if (t == 0 && more) bias_block(pointwise_item(nfb, c_item + nwg).fb, bbuf ^ 1u);
@@ -731,7 +770,7 @@ __global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingA
     }
 
     // ---- multiply ------------------------------------------------------------------------
-    const int wp = wave >> 1, wf = wave & 1;
+    const int wp = wave / FW, wf = wave % FW;
     uint8_t *yb = reinterpret_cast<uint8_t *>(a.y);
     const uint8_t *rb = reinterpret_cast<const uint8_t *>(a.residual);
     const Clamp cl = clamp_of(a.act);
@@ -739,11 +778,11 @@ __global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingA
     uint32_t c_slot = 0, bbuf = 0;
     for (;;) { // one item per iteration
         const PointwiseItem it = pointwise_item(nfb, c_item);
-        const int fl = (int)it.fb * 128 + wf * 64 + 4 * q; // this lane's first filter in row tile 0
+        const int fl = (int)it.fb * (FW * 64) + wf * 64 + 4 * q; // this lane's first filter in row tile 0
         uint32_t obyte[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const uint32_t m = it.ptile * 256u + (uint32_t)(wp * 64 + s * 16 + n16);
+            const uint32_t m = it.ptile * (uint32_t)(PW * 64) + (uint32_t)(wp * 64 + s * 16 + n16);
             obyte[s] = m < (uint32_t)a.M ? (m * (uint32_t)a.F + (uint32_t)fl) * 2u : 0xffffffffu;
         }
         f32x4 acc[4][4];
@@ -767,12 +806,12 @@ __global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingA
                     }
                 }
             }
-            const uint8_t *sb = lds + c_slot * kRingStageBytes;
-            if (++c_slot == (uint32_t)kRingStages) c_slot = 0;
+            const uint8_t *sb = lds + c_slot * Cfg::kStageBytes;
+            if (++c_slot == (uint32_t)D) c_slot = 0;
 #pragma unroll
             for (int step = 0; step < 2; ++step) {
                 uint4 A[4], B[4];
-                const uint8_t *ap = sb + kRingPatchBytes + (uint32_t)(step * 8) * 1024u + arow;
+                const uint8_t *ap = sb + Cfg::kXBytes + (uint32_t)(step * FW * 4) * 1024u + arow;
                 const uint8_t *bp = sb + brow + (uint32_t)(((step * 4 + q) ^ (n16 & 7)) * 16);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) A[j] = *reinterpret_cast<const uint4 *>(ap + j * 1024);
@@ -785,27 +824,25 @@ __global__ __launch_bounds__(kPointwiseThreads) void pointwise_ring_kernel(RingA
             }
         }
         // ---- bias, residual, clamp (activation), round, store -----------------------------
-        {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (fl + 16 * j >= a.F) continue;
-                float4 bv = float4{0.f, 0.f, 0.f, 0.f};
-                if (a.bias) bv = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 16 * j + 4 * q) * 4u);
+        for (int j = 0; j < 4; ++j) {
+            if (fl + 16 * j >= a.F) continue;
+            float4 bv = float4{0.f, 0.f, 0.f, 0.f};
+            if (a.bias) bv = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 16 * j + 4 * q) * 4u);
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    if (obyte[s] == 0xffffffffu) continue;
-                    float v[4] = {acc[j][s][0] + bv.x, acc[j][s][1] + bv.y, acc[j][s][2] + bv.z, acc[j][s][3] + bv.w};
-                    if (rb) {
-                        v[0] += from_storage<DT>((uint16_t)(res[j][s].x & 0xffffu));
-                        v[1] += from_storage<DT>((uint16_t)(res[j][s].x >> 16));
-                        v[2] += from_storage<DT>((uint16_t)(res[j][s].y & 0xffffu));
-                        v[3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
-                    }
-                    uint2 out;
-                    out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-                    out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                    *reinterpret_cast<uint2 *>(yb + obyte[s] + 32u * j) = out;
+            for (int s = 0; s < 4; ++s) {
+                if (obyte[s] == 0xffffffffu) continue;
+                float v[4] = {acc[j][s][0] + bv.x, acc[j][s][1] + bv.y, acc[j][s][2] + bv.z, acc[j][s][3] + bv.w};
+                if (rb) {
+                    v[0] += from_storage<DT>((uint16_t)(res[j][s].x & 0xffffu));
+                    v[1] += from_storage<DT>((uint16_t)(res[j][s].x >> 16));
+                    v[2] += from_storage<DT>((uint16_t)(res[j][s].y & 0xffffu));
+                    v[3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
                 }
+                uint2 out;
+                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
+                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                *reinterpret_cast<uint2 *>(yb + obyte[s] + 32u * j) = out;
             }
         }
         if (c_item + nwg >= nitems) break;
@@ -1127,26 +1164,28 @@ int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
     return NPAS_OK;
 }
 
+template <int DT, typename Cfg> static void launch_pointwise_cfg(const RingArgs &a, hipStream_t st)
+{
+    static bool attr_done = false;
+    auto kern = pointwise_ring_kernel<DT, Cfg>;
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
+        attr_done = true;
+    }
+    const unsigned grid = (unsigned)std::min<long>((long)a.nptiles * a.nfb, 256);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::kThreads), Cfg::kLdsBytes, st, a);
+}
+
+// a.small selects the 64 x 64 configuration; a.nptiles / a.nfb count that configuration's tiles.
 int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds_bytes = (size_t)kRingStages * kRingStageBytes + 2048;
-    const unsigned grid = (unsigned)std::min<long>((long)a.nptiles * a.nfb, 256);
-    static bool attr_done[2] = {false, false};
     if (dtype == NPAS_BF16) {
-        auto kern = pointwise_ring_kernel<NPAS_BF16>;
-        if (!attr_done[0]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-            attr_done[0] = true;
-        }
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kPointwiseThreads), lds_bytes, st, a);
+        if (a.small) launch_pointwise_cfg<NPAS_BF16, PointwiseSmall>(a, st);
+        else launch_pointwise_cfg<NPAS_BF16, PointwiseBig>(a, st);
     } else if (dtype == NPAS_F16) {
-        auto kern = pointwise_ring_kernel<NPAS_F16>;
-        if (!attr_done[1]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-            attr_done[1] = true;
-        }
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kPointwiseThreads), lds_bytes, st, a);
+        if (a.small) launch_pointwise_cfg<NPAS_F16, PointwiseSmall>(a, st);
+        else launch_pointwise_cfg<NPAS_F16, PointwiseBig>(a, st);
     } else {
         set_error("pointwise_ring needs a 16-bit storage type");
         return NPAS_E_DTYPE;

@@ -165,7 +165,8 @@ struct RingArgs {
     int M;                      // output pixels N*Ho*Wo
     int C, F;
     int H, W, Ho, Wo, stride;   // input / output geometry (stride > 1: subsampled input pixels)
-    int nptiles, nfb;           // 256-pixel tiles, 128-filter blocks
+    int nptiles, nfb;           // pixel tiles and filter blocks of the chosen configuration
+    int small;                  // 0: 256 x 128 tiles, 3-stage ring; 1: 64 x 64 tiles, 8-stage ring
     int act;
     int flat;                   // 1: stride 1, input pixel index == output pixel index
     uint32_t div_howo, div_wo;  // magic reciprocals of Ho*Wo and Wo
