@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MB",
                     help="instead of the benchmark, run 5 plain device copies of MB megabytes (known traffic for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--stack", type=int, default=0, metavar="CFG",
+                    help="time npas_run_stack end to end on config CFG (2 or 5) at --batch instead of the headline line")
     ap.add_argument("--only", type=str, default="", help="with --per-layer: comma-separated layer indices to run")
     ap.add_argument("--reps", type=int, default=20, help="with --per-layer: timed launches per layer")
     args = ap.parse_args()
@@ -82,6 +84,8 @@ def main():
         return
     if args.per_layer:
         return per_layer(args, torch, npas, helpers, configs)
+    if args.stack:
+        return stack_mode(args, torch, npas, helpers, configs)
     w = configs.config2(batch=args.batch)
     N, H, W, C = w.x_shape
     npx = N * H * W
@@ -147,7 +151,7 @@ def main():
             torch.cuda.synchronize()
             per.append(e0.elapsed_time(e1) / args.steps)
         kern_ms = max(per)
-        kname = "conv_gather_mfma(layer %d of 2)" % (per.index(kern_ms) + 1)
+        kname = "%s (layer %d of 2)" % (npas.conv2d_kernel_name(packed[per.index(kern_ms)], N, H, W, 1, 0), per.index(kern_ms) + 1)
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     # HBM bytes per launch of the fused kernel as measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE scaled by a
     # plain copy); only valid for the default workload and launch configuration
@@ -189,6 +193,37 @@ def main():
                                "unit": "TFLOP/s (dense-equivalent)", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": "%d of %d pixels of the same stack, %d repetitions" % (sample_px, npx, reps)}
     print(json.dumps(out))
+
+
+def stack_mode(args, torch, npas, helpers, configs):
+    """npas_run_stack end to end: one call runs every layer of the config on one stream."""
+    cfg = args.stack
+    w = {2: lambda: configs.config2(batch=args.batch), 5: lambda: configs.config5(batch=args.batch)}[cfg]()
+    N, H, W, C = w.x_shape
+    packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None for L in w.layers]
+    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W, npas.STACK_FUSE_POINTWISE)
+    wsb = st.workspace_bytes(N)
+    x = helpers.to_dev(w.x_store, torch)
+    shapes = {0: w.x_shape}
+    for i, L in enumerate(w.layers):
+        shapes[i + 1] = helpers.out_shape(L, shapes[L.src])
+    y = helpers.new_dev(shapes[len(w.layers)], w.dtype, torch, fill=0)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(5):
+        st.run(x, y, N, ws, wsb, stream)
+    torch.cuda.synchronize()
+    reps = args.reps
+    e0.record()
+    for _ in range(reps):
+        st.run(x, y, N, ws, wsb, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    flop = 2.0 * w.dense_macs()
+    print("# config %d %s batch %d: npas_run_stack %.1f us per call, %d launches, workspace %.1f MB, %.1f TFLOP/s dense-equivalent, %.1f images/s"
+          % (cfg, w.name, N, us, st.num_launches(), wsb / 2**20, flop / us / 1e6, N / us * 1e6))
 
 
 def per_layer(args, torch, npas, helpers, configs):

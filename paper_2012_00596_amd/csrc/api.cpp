@@ -317,11 +317,21 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.act = act;
         return launch_spatial_ring(p->dtype, a, stream);
     }
-    ConvPlan local;
-    if (!plan) {
-        int rc = plan_conv(p, N, H, W, stride, pad, &local);
-        if (rc) return rc;
-        plan = &local;
+    std::shared_ptr<const ConvPlan> cached;
+    if (!plan) { // plans are kept per handle and geometry: a stack repeats the same launches call after call
+        const std::array<int, 5> key = {N, H, W, stride, pad};
+        std::lock_guard<std::mutex> lock(p->plan_mu);
+        for (const auto &e : p->plans)
+            if (e.first == key) cached = e.second;
+        if (!cached) {
+            auto fresh = std::make_shared<ConvPlan>();
+            int rc = plan_conv(p, N, H, W, stride, pad, fresh.get());
+            if (rc) return rc;
+            if (p->plans.size() >= 16) p->plans.erase(p->plans.begin());
+            p->plans.emplace_back(key, fresh);
+            cached = fresh;
+        }
+        plan = cached.get();
     }
     ConvMfmaArgs a;
     a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
@@ -354,6 +364,10 @@ struct npas_stack {
     unsigned flags = 0;
     // per-tensor placement for a given N is computed on the fly (sizes scale with N)
     std::vector<int> last_use; // last layer reading tensor t
+    mutable std::mutex place_mu;
+    mutable int place_N = -1;
+    mutable size_t place_need = 0;
+    mutable std::vector<size_t> place_off;
 };
 
 namespace npas {
@@ -707,7 +721,16 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
         return NPAS_E_SHAPE;
     }
     std::vector<size_t> off;
-    size_t need = place_tensors(s, N, &off);
+    size_t need;
+    {   // placement depends on N only; keep the last one
+        std::lock_guard<std::mutex> lock(s->place_mu);
+        if (s->place_N != N) {
+            s->place_need = place_tensors(s, N, &s->place_off);
+            s->place_N = N;
+        }
+        off = s->place_off;
+        need = s->place_need;
+    }
     if (need > 0 && (!workspace_dev || workspace_bytes < need || ((uintptr_t)workspace_dev & 255))) {
         set_error("workspace: need %zu bytes, 256-byte aligned; got %zu at %p", need, workspace_bytes, workspace_dev);
         return NPAS_E_WORKSPACE;

@@ -3,7 +3,11 @@
 #pragma once
 #include <cstddef>
 #include <cstdint>
+#include <array>
+#include <memory>
+#include <mutex>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/npas.h"
@@ -92,6 +96,7 @@ struct DeviceCopy {
     const void *zeros = nullptr; // 256 bytes of zeros
 };
 
+struct ConvPlan; // host-side plan of one conv launch, defined below
 
 } // namespace npas
 
@@ -107,6 +112,9 @@ struct npas_packed {
     npas::DeviceFormat fmt;
     npas::RingFormat ring;
     npas::DeviceCopy dev;
+    // launch plans already computed for this layer, by geometry (filled by the run calls)
+    mutable std::mutex plan_mu;
+    mutable std::vector<std::pair<std::array<int, 5>, std::shared_ptr<const npas::ConvPlan>>> plans;
 };
 
 namespace npas {
