@@ -38,6 +38,8 @@ def main():
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--stack", type=int, default=0, metavar="CFG",
                     help="time npas_run_stack end to end on config CFG (2 or 5) at --batch instead of the headline line")
+    ap.add_argument("--sweep", type=str, default="", choices=["", "rate", "block"],
+                    help="rate: 3x3 conv 56x56x256->256 over pruning schemes and rates; block: residual stack over block sizes at 6x")
     ap.add_argument("--only", type=str, default="", help="with --per-layer: comma-separated layer indices to run")
     ap.add_argument("--reps", type=int, default=20, help="with --per-layer: timed launches per layer")
     args = ap.parse_args()
@@ -86,6 +88,8 @@ def main():
         return per_layer(args, torch, npas, helpers, configs)
     if args.stack:
         return stack_mode(args, torch, npas, helpers, configs)
+    if args.sweep:
+        return sweep_mode(args, torch, npas, helpers)
     w = configs.config2(batch=args.batch)
     N, H, W, C = w.x_shape
     npx = N * H * W
@@ -195,10 +199,8 @@ def main():
     print(json.dumps(out))
 
 
-def stack_mode(args, torch, npas, helpers, configs):
-    """npas_run_stack end to end: one call runs every layer of the config on one stream."""
-    cfg = args.stack
-    w = {2: lambda: configs.config2(batch=args.batch), 5: lambda: configs.config5(batch=args.batch)}[cfg]()
+def time_stack(w, reps, torch, npas, helpers):
+    """(us per npas_run_stack call, launches, workspace bytes) for workload w."""
     N, H, W, C = w.x_shape
     packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None for L in w.layers]
     st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W, npas.STACK_FUSE_POINTWISE)
@@ -214,16 +216,65 @@ def stack_mode(args, torch, npas, helpers, configs):
     for _ in range(5):
         st.run(x, y, N, ws, wsb, stream)
     torch.cuda.synchronize()
-    reps = args.reps
     e0.record()
     for _ in range(reps):
         st.run(x, y, N, ws, wsb, stream)
     e1.record()
     torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / reps
+    return e0.elapsed_time(e1) * 1e3 / reps, st.num_launches(), wsb
+
+
+def stack_mode(args, torch, npas, helpers, configs):
+    """npas_run_stack end to end: one call runs every layer of the config on one stream."""
+    cfg = args.stack
+    w = {2: lambda: configs.config2(batch=args.batch), 5: lambda: configs.config5(batch=args.batch)}[cfg]()
+    us, launches, wsb = time_stack(w, args.reps, torch, npas, helpers)
     flop = 2.0 * w.dense_macs()
     print("# config %d %s batch %d: npas_run_stack %.1f us per call, %d launches, workspace %.1f MB, %.1f TFLOP/s dense-equivalent, %.1f images/s"
-          % (cfg, w.name, N, us, st.num_launches(), wsb / 2**20, flop / us / 1e6, N / us * 1e6))
+          % (cfg, w.name, w.x_shape[0], us, launches, wsb / 2**20, flop / us / 1e6, w.x_shape[0] / us * 1e6))
+
+
+def sweep_mode(args, torch, npas, helpers):
+    """The paper's two design-space sweeps (section 4) on synthetic layers: latency only."""
+    from workloads import sweeps
+    stream = torch.cuda.current_stream().cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if args.sweep == "block":
+        print("# residual stack, every pruned layer at 6x, batch %d: npas_run_stack per call" % args.batch)
+        print("%-9s %10s %12s" % ("Bf x Bc", "us", "images/s"))
+        for Bf, Bc in sweeps.BLOCK_SIZES:
+            w = sweeps.block_sweep_stack(Bf, Bc, batch=args.batch)
+            us, _, _ = time_stack(w, args.reps, torch, npas, helpers)
+            print("%-9s %10.1f %12.1f" % ("%dx%d" % (Bf, Bc), us, args.batch / us * 1e6), flush=True)
+        return
+    print("# 3x3 conv 56x56x256 -> 256, stride 1, batch %d, bf16; us per launch (dense-equivalent TFLOP/s of the unpruned layer)" % args.batch)
+    print("%-14s" % "scheme" + "".join("%22s" % ("%gx" % r) for r in sweeps.RATES))
+    dense_flop = 2.0 * args.batch * 56 * 56 * 256 * 256 * 9
+    for scheme in sweeps.RATE_SCHEMES:
+        cells, kerns = [], set()
+        for r in sweeps.RATES:
+            if scheme == "pattern" and r < 2.25:
+                cells.append("%22s" % "-")
+                continue
+            w = sweeps.rate_sweep_layer(scheme, r, batch=args.batch)
+            L = w.layers[0]
+            packed = helpers.pack_layer(npas, L, w.dtype)
+            N, H, W_, C = w.x_shape
+            x = helpers.to_dev(w.x_store, torch)
+            y = helpers.new_dev((N, H, W_, L.F), w.dtype, torch, fill=0)
+            for _ in range(3):
+                npas.conv2d_sparse(packed, x, y, N, H, W_, 1, 1, None, None, 0, stream)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(args.reps):
+                npas.conv2d_sparse(packed, x, y, N, H, W_, 1, 1, None, None, 0, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / args.reps
+            kerns.add(npas.conv2d_kernel_name(packed, N, H, W_, 1, 1).replace("conv_", ""))
+            cells.append("%22s" % ("%.1f (%.0f)" % (us, dense_flop / us / 1e6)))
+            del packed, x, y
+        print("%-14s" % scheme + "".join(cells) + "   " + ",".join(sorted(kerns)), flush=True)
 
 
 def per_layer(args, torch, npas, helpers, configs):

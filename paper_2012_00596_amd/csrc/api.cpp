@@ -252,9 +252,14 @@ enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SLAB, R_GATHER };
 static Route choose_route(const npas_packed *p, int N, int H, int W, int stride, int pad, SpatialRingArgs *sp)
 {
     if (p->fmt.variant == V_VALU_F32) return R_VALU;
-    if (p->ring.present && p->KH == 1 && p->KW == 1 && pad == 0) return R_POINTWISE_RING;
-    if (p->ring.present && stride == 1 && plan_spatial(p, N, H, W, pad, sp)) return R_SPATIAL_RING;
-    return p->fmt.variant == V_MFMA_SLAB ? R_SLAB : R_GATHER;
+    // A gather-format layer (few surviving positions) leaves the ring kernels, which multiply
+    // everything, only the launches they win (measured on the 3x3 256 -> 256 rate sweep and the
+    // 16 x 32-block FC layer): those above 1/8 density.
+    const bool gather = p->fmt.variant == V_MFMA_GATHER;
+    const bool ring_ok = p->ring.present && (!gather || p->fmt.density >= 0.125);
+    if (ring_ok && p->KH == 1 && p->KW == 1 && pad == 0) return R_POINTWISE_RING;
+    if (ring_ok && stride == 1 && (p->KH > 1 || p->KW > 1) && plan_spatial(p, N, H, W, pad, sp)) return R_SPATIAL_RING;
+    return gather ? R_GATHER : R_SLAB;
 }
 
 const char *route_name(const npas_packed *p, int N, int H, int W, int stride, int pad)

@@ -63,6 +63,7 @@ struct DeviceFormat {
     std::vector<uint32_t> vkent;
     std::vector<float> vw;
     int max_list = 0; // longest per-(tile,chunk) list, entries
+    double density = 1.0; // kept share of a 16-filter tile's (channel, tap) positions, union over its groups
 };
 
 // ---- ring format: extra execution format of 1x1 layers with C % 64 == 0 ---------

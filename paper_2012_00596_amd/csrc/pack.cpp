@@ -340,14 +340,15 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         // channel counts that are not a multiple of 8 or filter counts that are not a multiple of 4.
         const char *force = getenv("NPAS_FORCE_VARIANT"); // "gather" | "slab" | "noring": testing aid
         const bool slab_ok = p->C % 8 == 0 && p->F % 4 == 0;
-        bool gather = !slab_ok || union_density(p, mask_full.data()) < 0.25;
+        p->fmt.density = union_density(p, mask_full.data());
+        bool gather = !slab_ok || p->fmt.density < 0.25;
         if (force && slab_ok && (strcmp(force, "gather") == 0 || strcmp(force, "slab") == 0)) gather = strcmp(force, "gather") == 0;
         if (gather) build_mfma_gather(p, mask_full.data(), (const uint8_t *)w_host);
         else build_mfma_slab(p, mask_full.data(), (const uint8_t *)w_host);
-        // slab-format layers with whole 64-channel chunks also get the streaming (ring) format, which the
-        // run calls prefer for 1x1 layers without padding and k x k layers at stride 1 (it multiplies every
-        // position, so layers sparse enough for the gather format keep to that)
-        if (!gather && p->C % 64 == 0 && p->F % 4 == 0 && (double)((p->F + 127) / 128) * p->C * p->KH * p->KW * 256.0 < 256e6 &&
+        // layers with whole 64-channel chunks also get the streaming (ring) format, which the run calls
+        // prefer for 1x1 layers without padding and k x k layers at stride 1 unless the layer is sparse
+        // enough for the gather kernel to win (the ring multiplies every position)
+        if (p->C % 64 == 0 && p->F % 4 == 0 && (double)((p->F + 127) / 128) * p->C * p->KH * p->KW * 256.0 < 256e6 &&
             !(force && strcmp(force, "noring") == 0))
             build_ring(p, mask_full.data(), (const uint8_t *)w_host);
     }

@@ -155,6 +155,25 @@ def test_config4_pattern_small_streaming_kernel(npas, torch, monkeypatch):
     layerwise(npas, torch, configs.config4(batch=3, HW=12))
 
 
+SWEEP_CASES = [(sch, r) for sch in ("block_punched", "unstructured", "whole_tensor", "pattern", "filter")
+               for r in (2.5, 10) if not (sch == "pattern" and r < 2.25)]
+
+
+@pytest.mark.parametrize("scheme,rate", SWEEP_CASES, ids=["%s_r%s" % c for c in SWEEP_CASES])
+def test_rate_sweep_layer_kinds(npas, torch, scheme, rate):
+    """The layer kinds of the rate sweep (bench.py --sweep rate), at a size the oracle finishes quickly."""
+    from workloads import sweeps
+    print(f"sweep {scheme} rate {rate}", flush=True)
+    layerwise(npas, torch, sweeps.rate_sweep_layer(scheme, rate, batch=2, HW=11, C=64, F=72))
+
+
+def test_block_sweep_stack_reduced(npas, torch):
+    """The block-size sweep's stack (bench.py --sweep block) at 16x8 blocks, reduced input size."""
+    from workloads import sweeps
+    print("block sweep 16x8", flush=True)
+    layerwise(npas, torch, sweeps.block_sweep_stack(16, 8, batch=1, HW=32), check_meta=False)
+
+
 def test_group_with_everything_pruned_gives_bias_only(npas, torch):
     F, C = 32, 16
     m = masks.block_punched_mask(F, C, 3, 3, 8, 4, 2, 5)

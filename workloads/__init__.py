@@ -2,4 +2,4 @@
 benchmark.  Input generation only: no pruning-scheme validation, packing or
 layer arithmetic lives in this package, and it imports neither the oracle nor
 the HIP library."""
-from . import configs, dtypes, masks, prng  # noqa: F401
+from . import configs, dtypes, masks, prng, sweeps  # noqa: F401
