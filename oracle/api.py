@@ -155,6 +155,19 @@ def conv2d_pattern(X, w4, pat_id, library, stride=1, pad=1, bias=None, act=ACT_N
     return Y
 
 
+def dwconv3x3(X, W, stride=1, bias=None, residual=None, act=ACT_NONE):
+    """Depthwise 3x3 convolution, padding 1; W is [C][3][3]."""
+    X, W, bias, residual = _f64(X), _f64(W), _f64(bias), _f64(residual)
+    N, H, Wd, Cc = X.shape
+    assert W.shape == (Cc, 3, 3)
+    Y = np.empty((N, (H - 1) // stride + 1, (Wd - 1) // stride + 1, Cc), dtype=np.float64)
+    if residual is not None:
+        assert residual.shape == Y.shape
+    rc = lib().oracle_dwconv3x3(_p(X), _p(W), _p(bias), _p(residual), N, H, Wd, Cc, stride, act, _p(Y))
+    assert rc == 0, rc
+    return Y
+
+
 def maxpool3x3s2(X):
     X = _f64(X)
     N, H, Wd, Cc = X.shape
@@ -180,6 +193,9 @@ def run_layer(L, tensors, dtype):
         return conv2d_masked(x, L.w_exact, L.mask, L.stride, L.pad, None, res, L.act)
     if L.kind == "fc":
         return fc_masked(x, L.w_exact, L.mask, None, L.act)
+    if L.kind == "dwconv":
+        res = tensors[L.res] if L.res >= 0 else None
+        return dwconv3x3(x, L.w_exact, L.stride, None, res, L.act)
     if L.kind == "maxpool":
         return maxpool3x3s2(x)
     if L.kind == "avgpool":

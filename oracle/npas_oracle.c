@@ -310,6 +310,38 @@ int oracle_conv2d_pattern(const double *X, const double *w4, const uint8_t *pat_
     return ORACLE_OK;
 }
 
+/* ---------------------------------------------------------------------------
+ * Depthwise 3x3 convolution (the "3x3 DW" of the search space's cascades,
+ * section 5.1.1): every channel is filtered by its own 3x3 kernel, padding 1,
+ *   Y[n,y,x,c] = act( bias[c] + sum_{kh,kw} W[c,kh,kw] * X[n, y*s+kh-1, x*s+kw-1, c]
+ *                     + residual[n,y,x,c] )
+ * out-of-range input taken as 0, Ho = (H + 2 - 3)/s + 1 (floor).  bias and
+ * residual may be NULL.
+ * ------------------------------------------------------------------------- */
+int oracle_dwconv3x3(const double *X, const double *W, const double *bias, const double *residual,
+                     int N, int H, int Wd, int C, int stride, int act, double *Y)
+{
+    if (!X || !W || !Y || N <= 0 || H <= 0 || Wd <= 0 || C <= 0 || stride <= 0) return ORACLE_E_ARG;
+    int Ho = (H + 2 - 3) / stride + 1, Wo = (Wd + 2 - 3) / stride + 1;
+    if (Ho <= 0 || Wo <= 0) return ORACLE_E_ARG;
+    for (int n = 0; n < N; ++n)
+        for (int y = 0; y < Ho; ++y)
+            for (int x = 0; x < Wo; ++x)
+                for (int c = 0; c < C; ++c) {
+                    double acc = bias ? bias[c] : 0.0;
+                    for (int kh = 0; kh < 3; ++kh)
+                        for (int kw = 0; kw < 3; ++kw) {
+                            int iy = y * stride + kh - 1, ix = x * stride + kw - 1;
+                            if (iy < 0 || iy >= H || ix < 0 || ix >= Wd) continue;
+                            acc += W[((size_t)c * 3 + kh) * 3 + kw] * X[(((size_t)n * H + iy) * Wd + ix) * C + c];
+                        }
+                    size_t o = (((size_t)n * Ho + y) * Wo + x) * C + c;
+                    if (residual) acc += residual[o];
+                    Y[o] = activate(acc, act);
+                }
+    return ORACLE_OK;
+}
+
 /* 3x3 stride-2 max pooling with padding 1 (padded cells never win). */
 int oracle_maxpool3x3s2(const double *X, int N, int H, int Wd, int C, double *Y)
 {

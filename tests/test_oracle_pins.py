@@ -184,6 +184,47 @@ def test_pools_match_library():
     assert (oracle.maxpool3x3s2(Xneg) < 0).all()
 
 
+@pytest.mark.parametrize("N,H,W,C,stride", [(2, 7, 9, 5, 1), (1, 8, 8, 16, 2), (2, 9, 6, 3, 2), (1, 1, 1, 4, 1), (1, 2, 5, 8, 1)])
+def test_depthwise_matches_float64_grouped_library_convolution(N, H, W, C, stride):
+    x = prng.normal(31, 1, N * H * W * C).reshape(N, H, W, C)
+    w = prng.normal(31, 2, C * 9, 0.3).reshape(C, 3, 3)
+    b = prng.normal(31, 3, C)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2), torch.from_numpy(w).reshape(C, 1, 3, 3),
+                                     torch.from_numpy(b), stride=stride, padding=1, groups=C).permute(0, 2, 3, 1).numpy()
+    got = oracle.dwconv3x3(x, w, stride, b)
+    assert got.shape == ref.shape
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_depthwise_closed_forms():
+    C, H, W = 4, 5, 6
+    w = prng.normal(32, 1, C * 9).reshape(C, 3, 3)
+    # unit impulse in channel c0 at (y0, x0): the output is that channel's kernel, mirrored around the impulse,
+    # and every other channel stays zero (channels do not mix)
+    x = np.zeros((1, H, W, C))
+    y0, x0, c0 = 2, 3, 1
+    x[0, y0, x0, c0] = 1.0
+    y = oracle.dwconv3x3(x, w)
+    for oy in range(H):
+        for ox in range(W):
+            kh, kw = y0 - oy + 1, x0 - ox + 1
+            want = w[c0, kh, kw] if 0 <= kh < 3 and 0 <= kw < 3 else 0.0
+            assert y[0, oy, ox, c0] == want
+    assert np.all(y[..., [0, 2, 3]] == 0.0)
+    # all-ones input: interior = sum of the kernel, a corner = sum of the 2x2 taps that stay inside
+    y = oracle.dwconv3x3(np.ones((1, H, W, C)), w)
+    np.testing.assert_allclose(y[0, 2, 2], w.sum(axis=(1, 2)), rtol=1e-13)
+    np.testing.assert_allclose(y[0, 0, 0], w[:, 1:, 1:].sum(axis=(1, 2)), rtol=1e-13)
+    # it is the masked dense convolution whose weight tensor is diagonal in (filter, channel)
+    xr = prng.normal(32, 2, 2 * H * W * C).reshape(2, H, W, C)
+    dense = np.zeros((C, C, 3, 3))
+    dense[np.arange(C), np.arange(C)] = w
+    res = prng.normal(32, 3, 2 * 3 * 3 * C).reshape(2, 3, 3, C)
+    a = oracle.dwconv3x3(xr, w, 2, None, res, oracle.ACT_RELU6)
+    b = oracle.conv2d_masked(xr, dense, (dense != 0).astype(np.uint8), 2, 1, None, res, oracle.ACT_RELU6)
+    np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-13)
+
+
 def test_rounding_matches_library_types_and_ties_to_even():
     v = np.concatenate([rnd(101, (20000,), 3.0), rnd(102, (2000,), 1e-39), rnd(103, (2000,), 1e30),
                         [1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -8 + 2 ** -30, -1.0 - 2 ** -8, 0.0, 65520.0]])
