@@ -202,7 +202,7 @@ def main():
 def time_stack(w, reps, torch, npas, helpers):
     """(us per npas_run_stack call, launches, workspace bytes) for workload w."""
     N, H, W, C = w.x_shape
-    packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None for L in w.layers]
+    packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
     st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W, npas.STACK_FUSE_POINTWISE)
     wsb = st.workspace_bytes(N)
     x = helpers.to_dev(w.x_store, torch)

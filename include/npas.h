@@ -51,7 +51,8 @@ typedef struct npas_stack npas_stack;   /* a wired list of layers */
 
 typedef enum { NPAS_F32 = 0, NPAS_BF16 = 1, NPAS_F16 = 2 } npas_dtype;
 typedef enum { NPAS_ACT_NONE = 0, NPAS_ACT_RELU = 1, NPAS_ACT_RELU6 = 2 } npas_act;
-typedef enum { NPAS_SCHEME_BLOCK_PUNCHED = 0, NPAS_SCHEME_FC_BLOCK = 1, NPAS_SCHEME_PATTERN = 2 } npas_scheme;
+typedef enum { NPAS_SCHEME_BLOCK_PUNCHED = 0, NPAS_SCHEME_FC_BLOCK = 1, NPAS_SCHEME_PATTERN = 2,
+               NPAS_SCHEME_DEPTHWISE = 3 } npas_scheme;
 
 typedef enum {
     NPAS_OK = 0,
@@ -93,6 +94,12 @@ int npas_pack_fc_block(const void *w_host, const uint8_t *mask_host, int OUT, in
 int npas_pack_pattern(const void *w_host, const uint8_t *mask_host, int F, int C,
                       const uint8_t *library_host, int n_pat, npas_dtype dt, void *hip_stream,
                       npas_packed **out);
+
+/* Depthwise 3x3 weights W[C][3][3]: the "3x3 DW" member of the layer cascades in the search
+ * space (section 5.1.1), one 3x3 kernel per channel, not pruned.  The handle reports scheme
+ * NPAS_SCHEME_DEPTHWISE with F = C; npas_packed_export returns the weights in w_compact
+ * ([C][9], storage type); it runs through npas_depthwise3x3 or a DEPTHWISE3X3 stack layer. */
+int npas_pack_depthwise3x3(const void *w_host, int C, npas_dtype dt, void *hip_stream, npas_packed **out);
 
 /* info[0..15] = { scheme, dtype, F, C, KH, KW, Bf, Bc, G (filter groups),
  *                 K_total (length of k_pos), n_pat, device_ready, kernel variant,
@@ -137,6 +144,14 @@ const char *npas_conv2d_kernel_name(const npas_packed *p, int N, int H, int W, i
 int npas_fc_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int B, const void *bias_dev,
                    npas_act act, void *hip_stream);
 
+/* Depthwise 3x3 convolution, padding 1, stride >= 1: x_dev [N][H][W][C] -> y_dev
+ * [N][(H-1)/stride+1][(W-1)/stride+1][C],
+ *   y[n,oy,ox,c] = act(bias[c] + sum_{kh,kw} W[c,kh,kw] x[n, oy*stride+kh-1, ox*stride+kw-1, c] + residual),
+ * out-of-range input = 0, fp32 accumulation.  bias_dev (fp32) and residual_dev (y's shape and
+ * type) are nullable.  Errors as npas_conv2d_sparse; a handle of another scheme -> NPAS_E_SHAPE. */
+int npas_depthwise3x3(const npas_packed *p, const void *x_dev, void *y_dev, int N, int H, int W, int stride,
+                      const void *bias_dev, const void *residual_dev, npas_act act, void *hip_stream);
+
 /* Glue layers a residual stack needs around the pruned ones (not pruned
  * themselves): 3x3 stride-2 max-pool with padding 1 (padding never wins), and
  * global average pool [N][H][W][C] -> [N][C] (fp32 mean, rounded on store). */
@@ -148,16 +163,16 @@ int npas_global_avgpool(const void *x_dev, void *y_dev, int N, int H, int W, int
 /* ---- running a stack ------------------------------------------------------ */
 
 typedef enum { NPAS_LAYER_CONV = 0, NPAS_LAYER_FC = 1, NPAS_LAYER_MAXPOOL3X3S2 = 2,
-               NPAS_LAYER_GLOBAL_AVGPOOL = 3 } npas_layer_kind;
+               NPAS_LAYER_GLOBAL_AVGPOOL = 3, NPAS_LAYER_DEPTHWISE3X3 = 4 } npas_layer_kind;
 
 /* Tensor 0 is the stack input; layer i writes tensor i+1; the last layer's
  * tensor is the stack output.  `src` and `res` name earlier tensors (res = -1:
  * no residual).  `packed` must outlive the stack. */
 typedef struct {
     int kind;                  /* npas_layer_kind */
-    const npas_packed *packed; /* CONV / FC; NULL otherwise */
-    int stride, pad;           /* CONV */
-    int act;                   /* npas_act, CONV / FC */
+    const npas_packed *packed; /* CONV / FC / DEPTHWISE3X3; NULL otherwise */
+    int stride, pad;           /* CONV; DEPTHWISE3X3: stride (pad is 1) */
+    int act;                   /* npas_act, CONV / FC / DEPTHWISE3X3 */
     int src;
     int res;
     const void *bias_dev;      /* nullable */

@@ -14,14 +14,15 @@ HEADER = os.path.join(os.path.dirname(_HERE), "include", "npas.h")
 
 F32, BF16, F16 = 0, 1, 2
 ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
-SCHEME_BLOCK_PUNCHED, SCHEME_FC_BLOCK, SCHEME_PATTERN = 0, 1, 2
-LAYER_CONV, LAYER_FC, LAYER_MAXPOOL3X3S2, LAYER_GLOBAL_AVGPOOL = 0, 1, 2, 3
+SCHEME_BLOCK_PUNCHED, SCHEME_FC_BLOCK, SCHEME_PATTERN, SCHEME_DEPTHWISE = 0, 1, 2, 3
+LAYER_CONV, LAYER_FC, LAYER_MAXPOOL3X3S2, LAYER_GLOBAL_AVGPOOL, LAYER_DEPTHWISE3X3 = 0, 1, 2, 3, 4
 STACK_FUSE_POINTWISE = 1
 OK, E_NULL, E_SHAPE, E_MASK_NOT_BLOCK_UNIFORM, E_MASK_NOT_IN_LIBRARY, E_DTYPE, E_WORKSPACE, E_HIP, E_MASK_VALUE = \
     0, -1, -2, -3, -4, -5, -6, -7, -8
 
 EXPORTS = [
     "npas_last_error", "npas_pack_block_punched", "npas_pack_fc_block", "npas_pack_pattern",
+    "npas_pack_depthwise3x3", "npas_depthwise3x3",
     "npas_packed_info", "npas_packed_export", "npas_free", "npas_conv2d_sparse", "npas_conv2d_kernel_name",
     "npas_fc_sparse",
     "npas_maxpool3x3s2", "npas_global_avgpool", "npas_stack_create", "npas_stack_workspace_bytes",
@@ -69,6 +70,8 @@ def lib():
         L.npas_pack_block_punched.argtypes = [vp, vp, ip, ip, ip, ip, ip, ip, ip, vp, C.POINTER(vp)]
         L.npas_pack_fc_block.argtypes = [vp, vp, ip, ip, ip, ip, ip, vp, C.POINTER(vp)]
         L.npas_pack_pattern.argtypes = [vp, vp, ip, ip, vp, ip, ip, vp, C.POINTER(vp)]
+        L.npas_pack_depthwise3x3.argtypes = [vp, ip, ip, vp, C.POINTER(vp)]
+        L.npas_depthwise3x3.argtypes = [vp, vp, vp, ip, ip, ip, ip, vp, vp, ip, vp]
         L.npas_packed_info.argtypes = [vp, vp]
         L.npas_packed_export.argtypes = [vp, vp, vp, vp, vp, vp]
         L.npas_free.argtypes = [vp]
@@ -144,7 +147,8 @@ class Packed:
         i = self.info()
         grp = np.zeros(i["G"] + 1, dtype=np.int32)
         kpos = np.zeros(i["K_total"], dtype=np.int32)
-        wc = np.zeros((i["K_total"], i["Bf"]), dtype=_np_storage(i["dtype"]))
+        wc = np.zeros((i["C"], 9) if i["scheme"] == SCHEME_DEPTHWISE else (i["K_total"], i["Bf"]),
+                      dtype=_np_storage(i["dtype"]))
         out = {"grp_ptr": grp, "k_pos": kpos, "w_compact": wc}
         pat = w4 = None
         if i["scheme"] == SCHEME_PATTERN:
@@ -176,6 +180,20 @@ def pack_pattern(w, mask, library, dtype, stream=None):
     _check(lib().npas_pack_pattern(_host(w), _host(mask), F, Cc, _host(library), library.shape[0], dtype, stream,
                                    C.byref(h)))
     return Packed(h)
+
+
+def pack_depthwise3x3(w, dtype, stream=None):
+    """w: [C][3][3] in the storage type (float32, or uint16 bit patterns)."""
+    w = np.ascontiguousarray(w, dtype=_np_storage(dtype))
+    assert w.ndim == 3 and w.shape[1:] == (3, 3)
+    h = C.c_void_p()
+    _check(lib().npas_pack_depthwise3x3(_host(w), w.shape[0], dtype, stream, C.byref(h)))
+    return Packed(h)
+
+
+def depthwise3x3(packed, x, y, N, H, W, stride, bias=None, residual=None, act=ACT_NONE, stream=None):
+    _check(lib().npas_depthwise3x3(packed.handle, _dev(x), _dev(y), N, H, W, stride, _dev(bias), _dev(residual), act,
+                                   stream))
 
 
 def conv2d_sparse(packed, x, y, N, H, W, stride, pad, bias=None, residual=None, act=ACT_NONE, stream=None):

@@ -151,6 +151,10 @@ static int check_run(const npas_packed *p, const void *x, void *y, int N, int H,
         set_error("NULL argument (handle=%p x_dev=%p y_dev=%p)", (const void *)p, x, y);
         return NPAS_E_NULL;
     }
+    if (p->scheme == NPAS_SCHEME_DEPTHWISE) {
+        set_error("a depthwise handle runs through npas_depthwise3x3, not the convolution / FC calls");
+        return NPAS_E_SHAPE;
+    }
     if (N <= 0 || H <= 0 || W <= 0 || stride <= 0 || pad < 0) {
         set_error("bad geometry N=%d H=%d W=%d stride=%d pad=%d", N, H, W, stride, pad);
         return NPAS_E_SHAPE;
@@ -538,6 +542,39 @@ int npas_fc_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int B, 
     return run_conv(p, nullptr, x_dev, y_dev, B, 1, 1, 1, 0, bias_dev, nullptr, act, hip_stream);
 }
 
+static int run_depthwise(const npas_packed *p, const void *x, void *y, int N, int H, int W, int stride, const void *bias,
+                         const void *residual, int act, void *stream)
+{
+    if (!p || !x || !y) {
+        set_error("NULL argument (handle=%p x_dev=%p y_dev=%p)", (const void *)p, x, y);
+        return NPAS_E_NULL;
+    }
+    if (p->scheme != NPAS_SCHEME_DEPTHWISE) {
+        set_error("npas_depthwise3x3 needs a handle from npas_pack_depthwise3x3 (scheme %d)", p->scheme);
+        return NPAS_E_SHAPE;
+    }
+    if (N <= 0 || H <= 0 || W <= 0 || stride <= 0 || (double)N * H * W * p->C > 2147483647.0) {
+        set_error("bad geometry N=%d H=%d W=%d stride=%d", N, H, W, stride);
+        return NPAS_E_SHAPE;
+    }
+    if (act != NPAS_ACT_NONE && act != NPAS_ACT_RELU && act != NPAS_ACT_RELU6) {
+        set_error("unknown activation %d", act);
+        return NPAS_E_SHAPE;
+    }
+    if (p->dev.device < 0) {
+        set_error("packed layer has no device copy (packed on a machine without a GPU)");
+        return NPAS_E_HIP;
+    }
+    const void *w = p->dtype == NPAS_F32 ? (const void *)p->dev.vw : p->dev.wfrag;
+    return launch_depthwise3x3(p->dtype, x, y, w, (const float *)bias, residual, N, H, W, p->C, stride, act, stream);
+}
+
+int npas_depthwise3x3(const npas_packed *p, const void *x_dev, void *y_dev, int N, int H, int W, int stride,
+                      const void *bias_dev, const void *residual_dev, npas_act act, void *hip_stream)
+{
+    return run_depthwise(p, x_dev, y_dev, N, H, W, stride, bias_dev, residual_dev, act, hip_stream);
+}
+
 static int check_pool(const void *x, void *y, int N, int H, int W, int C, int dt)
 {
     if (!x || !y) {
@@ -592,7 +629,8 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             return NPAS_E_SHAPE;
         }
         const bool pruned = d.kind == NPAS_LAYER_CONV || d.kind == NPAS_LAYER_FC;
-        if (pruned && !d.packed) {
+        const bool weighted = pruned || d.kind == NPAS_LAYER_DEPTHWISE3X3;
+        if (weighted && !d.packed) {
             set_error("layer %d has no packed handle", i);
             return NPAS_E_NULL;
         }
@@ -636,6 +674,13 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             nd.H = nd.W = 1; nd.C = d.packed->C;
             nd.Ho = nd.Wo = 1; nd.F = d.packed->F;
             break;
+        case NPAS_LAYER_DEPTHWISE3X3:
+            if (d.packed->scheme != NPAS_SCHEME_DEPTHWISE || d.packed->C != in.C || d.stride <= 0) {
+                set_error("layer %d: depthwise layer does not fit its input (%dx%dx%d)", i, in.H, in.W, in.C);
+                return NPAS_E_SHAPE;
+            }
+            nd.Ho = (in.H - 1) / d.stride + 1; nd.Wo = (in.W - 1) / d.stride + 1; nd.F = in.C;
+            break;
         case NPAS_LAYER_MAXPOOL3X3S2:
             nd.Ho = (in.H - 1) / 2 + 1; nd.Wo = (in.W - 1) / 2 + 1; nd.F = in.C;
             break;
@@ -646,13 +691,17 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             set_error("layer %d: unknown kind %d", i, d.kind);
             return NPAS_E_SHAPE;
         }
-        if (pruned && d.packed->dtype != s->dtype) {
+        if (d.kind == NPAS_LAYER_CONV && d.packed->scheme == NPAS_SCHEME_DEPTHWISE) {
+            set_error("layer %d: a depthwise handle needs a DEPTHWISE3X3 layer", i);
+            return NPAS_E_SHAPE;
+        }
+        if (weighted && d.packed->dtype != s->dtype) {
             set_error("layer %d: storage type %d differs from the stack's %d", i, d.packed->dtype, s->dtype);
             return NPAS_E_DTYPE;
         }
         if (d.res >= 0) {
             const Dim r = dims[d.res];
-            if (d.kind != NPAS_LAYER_CONV || r.H != nd.Ho || r.W != nd.Wo || r.C != nd.F) {
+            if ((d.kind != NPAS_LAYER_CONV && d.kind != NPAS_LAYER_DEPTHWISE3X3) || r.H != nd.Ho || r.W != nd.Wo || r.C != nd.F) {
                 set_error("layer %d: residual tensor %d has the wrong shape", i, d.res);
                 return NPAS_E_SHAPE;
             }
@@ -772,6 +821,10 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
         case NPAS_LAYER_FC:
             rc = check_run(n.d.packed, x, y, N, 1, 1, 1, 0);
             if (!rc) rc = run_conv(n.d.packed, nullptr, x, y, N, 1, 1, 1, 0, n.d.bias_dev, nullptr, n.d.act, hip_stream);
+            break;
+        case NPAS_LAYER_DEPTHWISE3X3:
+            rc = run_depthwise(n.d.packed, x, y, N, n.H, n.W, n.d.stride, n.d.bias_dev, n.d.res >= 0 ? tensor(n.d.res) : nullptr,
+                               n.d.act, hip_stream);
             break;
         case NPAS_LAYER_MAXPOOL3X3S2:
             rc = launch_maxpool(x, y, N, n.H, n.W, n.C, n.dtype, hip_stream);

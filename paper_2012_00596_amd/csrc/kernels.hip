@@ -16,6 +16,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstdlib>
+#include <type_traits>
 
 #include "npas_internal.h"
 
@@ -1551,6 +1552,99 @@ __global__ __launch_bounds__(256) void global_avgpool_kernel(const void *x, void
     double s = 0.0; // fp64 sum: the mean of an fp32 map stays within 1e-5 of the exact one
     for (int p = 0; p < HW; ++p) s += (double)ld_act<DT>(x, ((size_t)n * HW + p) * C + c);
     st_act<DT>(y, (size_t)i, (float)(s / (double)HW));
+}
+
+// ------------------------------------------------------------------------------
+// Depthwise 3x3, padding 1: one thread per (output pixel, vector of V channels); V * element
+// size = 16 bytes when the channel count allows it, so every load and store is one 16-byte
+// access, coalesced along the channels.  HBM-bound: the nine taps of a pixel come from L1 / L2.
+// fp32 storage accumulates in fp64, like the fp32 convolution kernel (products of two fp32
+// values are exact in fp64, so the stored result is the correctly rounded one).
+template <int DT, int V>
+__global__ __launch_bounds__(256) void depthwise3x3_kernel(const void *x, void *y, const void *w, const float *bias,
+                                                           const void *residual, int N, int H, int W, int C, int Ho,
+                                                           int Wo, int stride, int act)
+{
+    const int CV = C / V;
+    const size_t total = (size_t)N * Ho * Wo * CV;
+    const Clamp cl = clamp_of(act);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int cv = (int)(i % CV);
+        size_t r = i / CV;
+        const int ox = (int)(r % Wo);
+        r /= Wo;
+        const int oy = (int)(r % Ho), n = (int)(r / Ho);
+        using Acc = typename std::conditional<DT == NPAS_F32, double, float>::type;
+        Acc acc[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) acc[k] = bias ? (Acc)bias[cv * V + k] : (Acc)0;
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+            const int iy = oy * stride + kh - 1;
+            if (iy < 0 || iy >= H) continue;
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const int ix = ox * stride + kw - 1;
+                if (ix < 0 || ix >= W) continue;
+                const size_t xo = ((size_t)(n * H + iy) * W + ix) * C + (size_t)cv * V;
+                const size_t wo = (size_t)(kh * 3 + kw) * C + (size_t)cv * V;
+                if (V == 8) { // 16-bit storage, 8 channels
+                    const uint4 xv = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(x) + xo);
+                    const uint4 wv = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(w) + wo);
+                    const uint32_t xs[4] = {xv.x, xv.y, xv.z, xv.w}, ws[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        acc[2 * k] += from_storage<DT>((uint16_t)(xs[k] & 0xffffu)) * from_storage<DT>((uint16_t)(ws[k] & 0xffffu));
+                        acc[2 * k + 1] += from_storage<DT>((uint16_t)(xs[k] >> 16)) * from_storage<DT>((uint16_t)(ws[k] >> 16));
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < V; ++k) acc[k] += (Acc)ld_act<DT>(x, xo + k) * (Acc)ld_act<DT>(w, wo + k);
+                }
+            }
+        }
+        const size_t yo = ((size_t)(n * Ho + oy) * Wo + ox) * C + (size_t)cv * V;
+        if (residual) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) acc[k] += (Acc)ld_act<DT>(residual, yo + k);
+        }
+        if (V == 8) {
+            uint4 out;
+            out.x = pack2<DT>(clampf((float)acc[0], cl), clampf((float)acc[1], cl));
+            out.y = pack2<DT>(clampf((float)acc[2], cl), clampf((float)acc[3], cl));
+            out.z = pack2<DT>(clampf((float)acc[4], cl), clampf((float)acc[5], cl));
+            out.w = pack2<DT>(clampf((float)acc[6], cl), clampf((float)acc[7], cl));
+            *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(y) + yo) = out;
+        } else {
+#pragma unroll
+            for (int k = 0; k < V; ++k) st_act<DT>(y, yo + k, clampf((float)acc[k], cl));
+        }
+    }
+}
+
+int launch_depthwise3x3(int dt, const void *x, void *y, const void *w, const float *bias, const void *residual, int N, int H,
+                        int W, int C, int stride, int act, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const int Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
+    const bool vec = dt != NPAS_F32 && C % 8 == 0;
+    const size_t total = (size_t)N * Ho * Wo * (vec ? C / 8 : C);
+    const unsigned grid = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 32);
+#define NPAS_DW(DT, V) hipLaunchKernelGGL((depthwise3x3_kernel<DT, V>), dim3(grid), dim3(256), 0, st, x, y, w, bias, residual, N, H, W, C, Ho, Wo, stride, act)
+    if (dt == NPAS_BF16) {
+        if (vec) NPAS_DW(NPAS_BF16, 8);
+        else NPAS_DW(NPAS_BF16, 1);
+    } else if (dt == NPAS_F16) {
+        if (vec) NPAS_DW(NPAS_F16, 8);
+        else NPAS_DW(NPAS_F16, 1);
+    } else NPAS_DW(NPAS_F32, 1);
+#undef NPAS_DW
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("depthwise3x3 launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
 }
 
 int launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream)

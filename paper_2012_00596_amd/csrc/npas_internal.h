@@ -23,6 +23,7 @@ enum Variant {
     V_VALU_F32 = 0,    // fp32 storage: one thread per (pixel, filter sub-group), scalar-broadcast weights
     V_MFMA_GATHER = 1, // 16-bit storage: 16-filter tiles, element-gathered activations, MFMA 16x16x32
     V_MFMA_SLAB = 2,   // 16-bit storage: 16*NT-filter super-tiles, 8-channel slabs gathered with one 16-byte LDS read
+    V_DEPTHWISE = 3,   // depthwise 3x3: weights tap-major [9][C] in the storage type (wfrag for 16-bit, vw for fp32)
 };
 
 // ---- device execution format for V_MFMA_GATHER -------------------------------
@@ -221,6 +222,8 @@ int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream);
 bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
                                 int act1, int act2, uint32_t use0, uint32_t use1, void *stream);
+int launch_depthwise3x3(int dt, const void *x, void *y, const void *w, const float *bias, const void *residual, int N, int H,
+                        int W, int C, int stride, int act, void *stream);
 int launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream);
 int launch_avgpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream);
 

@@ -540,6 +540,51 @@ int npas_pack_pattern(const void *w_host, const uint8_t *mask_host, int F, int C
     return finish_pack(p, mask, w_host, out);
 }
 
+int npas_pack_depthwise3x3(const void *w_host, int C, npas_dtype dt, void *hip_stream, npas_packed **out)
+{
+    (void)hip_stream;
+    if (!w_host || !out) {
+        set_error("NULL argument (w_host=%p out=%p)", w_host, (void *)out);
+        return NPAS_E_NULL;
+    }
+    *out = nullptr;
+    if (C <= 0 || C > 65535) {
+        set_error("bad channel count %d", C);
+        return NPAS_E_SHAPE;
+    }
+    if (dt != NPAS_F32 && dt != NPAS_BF16 && dt != NPAS_F16) {
+        set_error("unknown storage type %d", (int)dt);
+        return NPAS_E_DTYPE;
+    }
+    npas_packed *p = new npas_packed;
+    p->scheme = NPAS_SCHEME_DEPTHWISE;
+    p->dtype = dt;
+    p->F = C; p->C = C; p->KH = 3; p->KW = 3; p->Bf = 1; p->Bc = 1; p->G = 0;
+    p->grp_ptr.assign(1, 0);
+    const size_t esz = dt == NPAS_F32 ? 4 : 2;
+    p->w_compact.assign((const uint8_t *)w_host, (const uint8_t *)w_host + (size_t)C * 9 * esz);
+    // device order: tap-major [9][C], so that a thread's channel vector of one tap is one 16-byte load
+    p->fmt.variant = V_DEPTHWISE;
+    if (dt == NPAS_F32) {
+        const float *w = (const float *)w_host;
+        p->fmt.vw.resize((size_t)9 * C);
+        for (int c = 0; c < C; ++c)
+            for (int t = 0; t < 9; ++t) p->fmt.vw[(size_t)t * C + c] = w[(size_t)c * 9 + t];
+    } else {
+        const uint16_t *w = (const uint16_t *)w_host;
+        p->fmt.wfrag.resize((size_t)9 * C);
+        for (int c = 0; c < C; ++c)
+            for (int t = 0; t < 9; ++t) p->fmt.wfrag[(size_t)t * C + c] = w[(size_t)c * 9 + t];
+    }
+    int rc = upload(p);
+    if (rc != NPAS_OK) {
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return NPAS_OK;
+}
+
 int npas_packed_info(const npas_packed *p, int64_t info[16])
 {
     if (!p || !info) {

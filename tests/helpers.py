@@ -42,6 +42,8 @@ def from_dev(t, dtype):
 
 
 def pack_layer(npas, L, dtype):
+    if L.kind == "dwconv":
+        return npas.pack_depthwise3x3(L.w_store, dtype)
     if L.scheme == "block_punched":
         return npas.pack_block_punched(L.w_store, L.mask, L.Bf, L.Bc, dtype)
     if L.scheme == "fc_block":
@@ -58,6 +60,9 @@ def out_shape(L, in_shape):
         return (N, (H + 2 * L.pad - L.KH) // L.stride + 1, (W + 2 * L.pad - L.KW) // L.stride + 1, L.F)
     if L.kind == "fc":
         return (in_shape[0], L.F)
+    if L.kind == "dwconv":
+        N, H, W, C = in_shape
+        return (N, (H - 1) // L.stride + 1, (W - 1) // L.stride + 1, C)
     if L.kind == "maxpool":
         N, H, W, C = in_shape
         return (N, (H - 1) // 2 + 1, (W - 1) // 2 + 1, C)
@@ -76,6 +81,9 @@ def run_layer_gpu(npas, torch, L, packed, x_dev, in_shape, dtype, res_dev=None, 
         npas.conv2d_sparse(packed, x_dev, y, N, H, W, L.stride, L.pad, bias_dev, res_dev, L.act)
     elif L.kind == "fc":
         npas.fc_sparse(packed, x_dev, y, in_shape[0], bias_dev, L.act)
+    elif L.kind == "dwconv":
+        N, H, W, _ = in_shape
+        npas.depthwise3x3(packed, x_dev, y, N, H, W, L.stride, bias_dev, res_dev, L.act)
     elif L.kind == "maxpool":
         N, H, W, C = in_shape
         npas.maxpool3x3s2(x_dev, y, N, H, W, C, dtype)
@@ -88,7 +96,7 @@ def run_layer_gpu(npas, torch, L, packed, x_dev, in_shape, dtype, res_dev=None, 
 
 def stack_descs(npas, layers, packed):
     kinds = {"conv": npas.LAYER_CONV, "fc": npas.LAYER_FC, "maxpool": npas.LAYER_MAXPOOL3X3S2,
-             "avgpool": npas.LAYER_GLOBAL_AVGPOOL}
+             "avgpool": npas.LAYER_GLOBAL_AVGPOOL, "dwconv": npas.LAYER_DEPTHWISE3X3}
     return [dict(kind=kinds[L.kind], packed=packed[i], stride=L.stride, pad=L.pad, act=L.act, src=L.src, res=L.res)
             for i, L in enumerate(layers)]
 

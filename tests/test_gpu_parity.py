@@ -28,8 +28,8 @@ def layerwise(npas, torch, w, check_meta=True):
     for i, L in enumerate(w.layers):
         in_shape = shapes[L.src]
         shapes[i + 1] = helpers.out_shape(L, in_shape)
-        packed = pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None
-        if packed is not None and check_meta:
+        packed = pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None
+        if packed is not None and check_meta and L.kind != "dwconv":
             helpers.check_metadata(oracle, L, packed, w.dtype)
             assert packed.info()["device_ready"] == 1
         xs, _ = dtypes.quantize(rounded[L.src], w.dtype)
@@ -174,6 +174,65 @@ def test_block_sweep_stack_reduced(npas, torch):
     layerwise(npas, torch, sweeps.block_sweep_stack(16, 8, batch=1, HW=32), check_meta=False)
 
 
+DW_CASES = [
+    # name, N, H, W, C, stride, dtype, act, use_res, use_bias
+    ("dw_bf16_vec", 2, 13, 11, 144, 1, dtypes.BF16, 2, False, True),
+    ("dw_bf16_stride2_odd", 3, 15, 14, 24, 2, dtypes.BF16, 2, False, False),
+    ("dw_bf16_scalar_channels", 1, 9, 9, 12, 1, dtypes.BF16, 1, True, True),
+    ("dw_fp16_res", 2, 8, 10, 32, 1, dtypes.F16, 0, True, False),
+    ("dw_fp32", 1, 7, 8, 10, 2, dtypes.F32, 2, True, True),
+    ("dw_one_pixel", 1, 1, 1, 16, 1, dtypes.BF16, 0, False, False),
+]
+
+
+@pytest.mark.parametrize("case", DW_CASES, ids=[c[0] for c in DW_CASES])
+def test_depthwise3x3(npas, torch, case):
+    name, N, H, W, C, stride, dtype, act, use_res, use_bias = case
+    print(f"depthwise {name}", flush=True)
+    xs, xe = dtypes.quantize(prng.normal(17, 1, N * H * W * C).reshape(N, H, W, C), dtype)
+    ws, we = dtypes.quantize(prng.normal(17, 2, C * 9, 0.3).reshape(C, 3, 3), dtype)
+    L = configs.Layer("dwconv", "", C, C, 3, 3, stride, 1, 1, 1, 1.0, act, w_store=ws, w_exact=we)
+    oshape = helpers.out_shape(L, (N, H, W, C))
+    bias = prng.normal(17, 3, C).astype(np.float32) if use_bias else None
+    rs = re = None
+    if use_res:
+        rs, re = dtypes.quantize(prng.normal(17, 4, int(np.prod(oshape))).reshape(oshape), dtype)
+    ref = oracle.round_to(oracle.dwconv3x3(xe, we, stride, None if bias is None else bias.astype(np.float64), re, act), dtype)
+    p = pack_layer(npas, L, dtype)
+    info = p.info()
+    assert info["scheme"] == npas.SCHEME_DEPTHWISE and info["C"] == C and info["device_ready"] == 1
+    np.testing.assert_array_equal(p.export()["w_compact"], np.asarray(ws).reshape(C, 9))    # bit-exact round trip
+    y = run_layer_gpu(npas, torch, L, p, to_dev(xs, torch), (N, H, W, C), dtype,
+                      None if rs is None else to_dev(rs, torch), None if bias is None else to_dev(bias, torch))
+    err = rel_err(from_dev(y, dtype).reshape(oshape), ref)
+    print(f"  err={err:.3e}", flush=True)
+    assert err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_inverted_residual_block_layerwise_and_stack(npas, torch, stride):
+    """1x1 -> depthwise 3x3 -> 1x1 (+ input): each layer against the oracle, then the stack call end to end."""
+    from workloads import sweeps
+    w = sweeps.inverted_residual_block(batch=2, HW=13, stride=stride)
+    print(f"inverted residual block, stride {stride}", flush=True)
+    layerwise(npas, torch, w)
+    rounded, _ = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+    for flags in (0, 1):
+        got, st = _run_stack_gpu(npas, torch, w, flags)
+        err = rel_err(got, rounded[-1])
+        print(f"  run_stack flags={flags} launches={st.num_launches()} err={err:.3e}", flush=True)
+        assert err <= 2e-2          # three roundings of bf16 activations compound
+
+
+def test_depthwise_handle_is_rejected_by_the_convolution_call(npas, torch):
+    ws, _ = dtypes.quantize(prng.normal(18, 1, 16 * 9).reshape(16, 3, 3), dtypes.BF16)
+    p = npas.pack_depthwise3x3(ws, dtypes.BF16)
+    x = new_dev((1, 4, 4, 16), dtypes.BF16, torch, fill=0)
+    y = new_dev((1, 4, 4, 16), dtypes.BF16, torch, fill=0)
+    with pytest.raises(npas.NpasError):
+        npas.conv2d_sparse(p, x, y, 1, 4, 4, 1, 1)
+
+
 def test_group_with_everything_pruned_gives_bias_only(npas, torch):
     F, C = 32, 16
     m = masks.block_punched_mask(F, C, 3, 3, 8, 4, 2, 5)
@@ -204,7 +263,7 @@ def test_garbage_under_the_mask_changes_nothing(npas, torch):
 
 
 def _run_stack_gpu(npas, torch, w, flags=0):
-    packed = [pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None for L in w.layers]
+    packed = [pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
     st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), w.x_shape[1], w.x_shape[2], flags)
     N = w.x_shape[0]
     shape = w.x_shape

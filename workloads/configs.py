@@ -25,7 +25,7 @@ ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
 
 @dataclass
 class Layer:
-    kind: str                      # "conv" | "fc" | "maxpool" | "avgpool"
+    kind: str                      # "conv" | "fc" | "dwconv" (depthwise 3x3, pad 1, w [C][3][3]) | "maxpool" | "avgpool"
     scheme: str = ""               # "block_punched" | "fc_block" | "pattern"
     C: int = 0
     F: int = 0
@@ -72,6 +72,11 @@ class Workload:
                 B = s[0]
                 total += B * L.F * L.C
                 shapes[i + 1] = (B, L.F)
+            elif L.kind == "dwconv":
+                N, H, W, C = s
+                Ho, Wo = (H - 1) // L.stride + 1, (W - 1) // L.stride + 1
+                total += N * Ho * Wo * C * 9
+                shapes[i + 1] = (N, Ho, Wo, C)
             elif L.kind == "maxpool":
                 N, H, W, C = s
                 shapes[i + 1] = (N, (H + 2 - 3) // 2 + 1, (W + 2 - 3) // 2 + 1, C)
