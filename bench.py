@@ -32,12 +32,13 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--per-layer", type=int, default=0, metavar="CFG",
                     help="instead of the headline line, print a per-layer table (us, dense-equivalent TFLOP/s, "
-                         "algorithmic GB/s, roofline fraction) for config CFG in 2..5")
+                         "algorithmic GB/s, roofline fraction) for config CFG in 1..5 (BASELINE.json's configs[CFG-1]); "
+                         "6 = the inverted-residual block 1x1, depthwise 3x3, 1x1 of workloads/sweeps.py")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MB",
                     help="instead of the benchmark, run 5 plain device copies of MB megabytes (known traffic for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--stack", type=int, default=0, metavar="CFG",
-                    help="time npas_run_stack end to end on config CFG (2 or 5) at --batch instead of the headline line")
+                    help="time npas_run_stack end to end on config CFG (2, 5, or 6 = inverted-residual block) at --batch")
     ap.add_argument("--sweep", type=str, default="", choices=["", "rate", "block"],
                     help="rate: 3x3 conv 56x56x256->256 over pruning schemes and rates; block: residual stack over block sizes at 6x")
     ap.add_argument("--only", type=str, default="", help="with --per-layer: comma-separated layer indices to run")
@@ -199,11 +200,12 @@ def main():
     print(json.dumps(out))
 
 
-def time_stack(w, reps, torch, npas, helpers):
+def time_stack(w, reps, torch, npas, helpers, fuse=True):
     """(us per npas_run_stack call, launches, workspace bytes) for workload w."""
     N, H, W, C = w.x_shape
     packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
-    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W, npas.STACK_FUSE_POINTWISE)
+    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W,
+                    npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL if fuse else 0)
     wsb = st.workspace_bytes(N)
     x = helpers.to_dev(w.x_store, torch)
     shapes = {0: w.x_shape}
@@ -227,8 +229,10 @@ def time_stack(w, reps, torch, npas, helpers):
 def stack_mode(args, torch, npas, helpers, configs):
     """npas_run_stack end to end: one call runs every layer of the config on one stream."""
     cfg = args.stack
-    w = {2: lambda: configs.config2(batch=args.batch), 5: lambda: configs.config5(batch=args.batch)}[cfg]()
-    us, launches, wsb = time_stack(w, args.reps, torch, npas, helpers)
+    from workloads import sweeps
+    w = {2: lambda: configs.config2(batch=args.batch), 5: lambda: configs.config5(batch=args.batch),
+         6: lambda: sweeps.inverted_residual_block(batch=args.batch)}[cfg]()
+    us, launches, wsb = time_stack(w, args.reps, torch, npas, helpers, fuse=not args.no_fuse)
     flop = 2.0 * w.dense_macs()
     print("# config %d %s batch %d: npas_run_stack %.1f us per call, %d launches, workspace %.1f MB, %.1f TFLOP/s dense-equivalent, %.1f images/s"
           % (cfg, w.name, w.x_shape[0], us, launches, wsb / 2**20, flop / us / 1e6, w.x_shape[0] / us * 1e6))
@@ -281,8 +285,9 @@ def per_layer(args, torch, npas, helpers, configs):
     """Per-layer timing of one config, every layer on its own buffers (rotated when small)."""
     MFMA_PEAK, HBM_PEAK = 2500.0, 8000.0           # TFLOP/s (bf16 dense), GB/s
     cfg = args.per_layer
+    from workloads import sweeps
     w = {1: configs.config1, 2: lambda: configs.config2(batch=args.batch), 3: configs.config3, 4: configs.config4,
-         5: lambda: configs.config5(batch=args.batch)}[cfg]()
+         5: lambda: configs.config5(batch=args.batch), 6: lambda: sweeps.inverted_residual_block(batch=args.batch)}[cfg]()
     stream = torch.cuda.current_stream().cuda_stream
     shapes = {0: w.x_shape}
     rows = []
@@ -297,8 +302,10 @@ def per_layer(args, torch, npas, helpers, configs):
             continue
         esz = 4 if w.dtype == 0 else 2
         nin, nout = int(np.prod(ishape)), int(np.prod(oshape))
-        packed = helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc") else None
+        packed = helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None
         wbytes = packed.info()["device_bytes"] if packed else 0
+        if L.kind == "dwconv":
+            wbytes = L.C * 9 * 2
         abytes = (nin + nout + (nout if L.res >= 0 else 0)) * esz + wbytes
         nsets = max(1, min(8, -(-600 * 2**20 // max(1, (nin + nout) * esz))))
         td = torch.float32 if w.dtype == 0 else torch.int16
@@ -315,6 +322,9 @@ def per_layer(args, torch, npas, helpers, configs):
                 npas.conv2d_sparse(packed, xs[k], ys[k], N, H, W_, L.stride, L.pad, None, rs[k] if rs else None, L.act, stream)
             elif L.kind == "fc":
                 npas.fc_sparse(packed, xs[k], ys[k], ishape[0], None, L.act, stream)
+            elif L.kind == "dwconv":
+                N, H, W_, _ = ishape
+                npas.depthwise3x3(packed, xs[k], ys[k], N, H, W_, L.stride, None, rs[k] if rs else None, L.act, stream)
             elif L.kind == "maxpool":
                 N, H, W_, C = ishape
                 npas.maxpool3x3s2(xs[k], ys[k], N, H, W_, C, w.dtype, stream)
@@ -336,10 +346,12 @@ def per_layer(args, torch, npas, helpers, configs):
             macs = oshape[0] * oshape[1] * oshape[2] * L.F * L.C * L.KH * L.KW
         elif L.kind == "fc":
             macs = ishape[0] * L.F * L.C
+        elif L.kind == "dwconv":
+            macs = oshape[0] * oshape[1] * oshape[2] * L.C * 9
         flop = 2.0 * macs
-        peak = 157.3 if w.dtype == 0 else MFMA_PEAK    # fp32 layers run on the vector ALUs
+        peak = 157.3 if (w.dtype == 0 or L.kind == "dwconv") else MFMA_PEAK    # fp32 and depthwise layers run on the vector ALUs
         t_hbm, t_mfma = abytes / (HBM_PEAK * 1e9) * 1e6, flop / (peak * 1e12) * 1e6
-        bound = "hbm" if t_hbm >= t_mfma else ("alu" if w.dtype == 0 else "mfma")
+        bound = "hbm" if t_hbm >= t_mfma else ("alu" if (w.dtype == 0 or L.kind == "dwconv") else "mfma")
         frac = max(t_hbm, t_mfma) / us
         if L.kind == "conv":
             kern = npas.conv2d_kernel_name(packed, ishape[0], ishape[1], ishape[2], L.stride, L.pad)

@@ -178,7 +178,10 @@ typedef struct {
     const void *bias_dev;      /* nullable */
 } npas_layer_desc;
 
-enum { NPAS_STACK_FUSE_POINTWISE = 1 }; /* allow a 1x1 -> act -> 1x1 pair to run as one kernel */
+enum {
+    NPAS_STACK_FUSE_POINTWISE = 1,         /* allow a 1x1 -> act -> 1x1 pair to run as one kernel */
+    NPAS_STACK_FUSE_INVERTED_RESIDUAL = 2  /* allow 1x1 -> depthwise 3x3 (stride 1) -> 1x1 (+ block input) to run as one kernel */
+};
 
 /* Builds a stack for inputs of H x W x C (C is taken from the first layer).
  * Checks wiring, shapes and types (NPAS_E_SHAPE / NPAS_E_DTYPE). */

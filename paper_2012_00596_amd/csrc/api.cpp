@@ -366,6 +366,10 @@ struct npas_stack {
         int fpp_nt1 = 0;                  // live intermediate tiles of that pair
         uint32_t fpp_use[2] = {0, 0};     // chunk masks of that pair
         bool fused_away = false;          // second layer of a fused pair: runs inside the first
+        // first layer of a fused 1x1 -> depthwise 3x3 -> 1x1 block: device images and tile
+        const void *ir_w1 = nullptr, *ir_w3 = nullptr;
+        const float *ir_wdw = nullptr;
+        int ir_nslots = 0, ir_TH = 0, ir_TW = 0, ir_residual = 0;
     };
     std::vector<Node> nodes;
     std::vector<void *> blobs; // device allocations owned by the stack (fused-pair weight images)
@@ -400,7 +404,8 @@ static size_t place_tensors(const npas_stack *s, int N, std::vector<size_t> *off
     size_t total = 0;
     const int esz = dtype_size(s->dtype);
     for (int t = 1; t < nt - 1; ++t) { // tensor t is written by layer t-1
-        if (s->nodes[t - 1].fused_blob) continue; // intermediate of a fused pair never reaches memory
+        if (s->nodes[t - 1].fused_blob || s->nodes[t - 1].ir_w1) continue; // intermediate of a fused pair / block never reaches memory
+        if (t >= 2 && s->nodes[t - 2].ir_w1) continue;                      // nor does the second one of a fused block
         sz[t] = (tensor_elems_per_image(s, t) * N * esz + 255) / 256 * 256;
         // drop tensors whose last reader ran before layer t-1
         live.erase(std::remove_if(live.begin(), live.end(), [&](const Live &l) { return l.until < t - 1; }),
@@ -504,6 +509,92 @@ static FppPlan build_fpp(const npas_packed *p1, const npas_packed *p2)
                         plan.blob[((size_t)(nt1 + u * nch + j) * 64 + lane) * 8 + i] = d2[(size_t)f * p2->C + c];
                 }
     return plan;
+}
+
+// Storage bits -> float on the host (bf16: the upper half of a float; fp16 by its fields).
+static float storage_to_float(uint16_t b, int dtype)
+{
+    uint32_t u;
+    if (dtype == NPAS_BF16) u = (uint32_t)b << 16;
+    else {
+        const uint32_t sign = (uint32_t)(b >> 15) << 31, e = (b >> 10) & 31u, m = b & 1023u;
+        if (e == 0) {
+            if (m == 0) u = sign;
+            else { // subnormal: value m * 2^-24
+                float f = (float)m * 5.9604644775390625e-8f;
+                std::memcpy(&u, &f, 4);
+                u |= sign;
+            }
+        } else if (e == 31) u = sign | 0x7f800000u | (m << 13);
+        else u = sign | ((e + 112u) << 23) | (m << 13);
+    }
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+// Plan and weight images of a fused inverted-residual block (layouts: see fused_inverted_residual_kernel).
+struct IrPlan {
+    int nslots = 0;                 // live intermediate channels, padded to a multiple of 32
+    std::vector<uint16_t> w1, w3;   // A-operand images
+    std::vector<float> wdw;         // [9][nslots]
+};
+
+static IrPlan build_ir(const npas_packed *p1, const npas_packed *pdw, const npas_packed *p3)
+{
+    IrPlan plan;
+    const int mid = p1->F, nt3 = (p3->F + 15) / 16;
+    std::vector<uint8_t> live(mid, 0); // intermediate channels some filter of layer 3 keeps
+    for (int g = 0; g < p3->G; ++g)
+        for (int k = p3->grp_ptr[g]; k < p3->grp_ptr[g + 1]; ++k) live[p3->k_pos[k]] = 1;
+    std::vector<int> perm;
+    for (int c = 0; c < mid; ++c)
+        if (live[c]) perm.push_back(c);
+    perm.resize(std::max<size_t>(32, (perm.size() + 31) / 32 * 32), -1);
+    plan.nslots = (int)perm.size();
+    const int nt1 = plan.nslots / 16, nk = plan.nslots / 32;
+    std::vector<uint16_t> d1 = dense_pointwise(p1), d3 = dense_pointwise(p3);
+    plan.w1.assign((size_t)nt1 * 512, 0);
+    for (int t = 0; t < nt1; ++t)
+        for (int lane = 0; lane < 64; ++lane)
+            for (int i = 0; i < 8; ++i) {
+                const int r = lane & 15, q = lane >> 4, f = perm[16 * t + r], c = 8 * q + i;
+                if (f >= 0 && c < p1->C) plan.w1[((size_t)t * 64 + lane) * 8 + i] = d1[(size_t)f * p1->C + c];
+            }
+    plan.w3.assign((size_t)nt3 * nk * 512, 0);
+    for (int u = 0; u < nt3; ++u)
+        for (int k = 0; k < nk; ++k)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int i = 0; i < 8; ++i) {
+                    const int r = lane & 15, q = lane >> 4, f = 16 * u + r, c = perm[32 * k + 8 * q + i];
+                    if (f < p3->F && c >= 0) plan.w3[((size_t)(u * nk + k) * 64 + lane) * 8 + i] = d3[(size_t)f * p3->C + c];
+                }
+    plan.wdw.assign((size_t)9 * plan.nslots, 0.f);
+    const uint16_t *wd = reinterpret_cast<const uint16_t *>(pdw->w_compact.data());
+    for (int s = 0; s < plan.nslots; ++s)
+        if (perm[s] >= 0)
+            for (int t = 0; t < 9; ++t) plan.wdw[(size_t)t * plan.nslots + s] = storage_to_float(wd[(size_t)perm[s] * 9 + t], pdw->dtype);
+    return plan;
+}
+
+// Output tile of the fused block for an H x W map: the shape that costs least, counting the
+// halo pixels expanded (cheap) and the 16-pixel blocks of depthwise work (about four times dearer),
+// among those whose LDS footprint leaves room for several workgroups per CU.
+static void plan_ir_tile(int H, int W, int nslots, int *TH, int *TW)
+{
+    double best = 1e300;
+    *TH = 1; *TW = 1;
+    for (int th = 1; th <= 32; ++th)
+        for (int tw = 1; tw <= 64; ++tw) {
+            if (th * tw > 256 || (th + 2) * (tw + 2) > 512 || tw + 2 > 1023) continue;
+            if (fused_ir_lds_bytes(th, tw, nslots) > 64 * 1024) continue;
+            const double tiles = (double)((H + th - 1) / th) * ((W + tw - 1) / tw);
+            const double cost = tiles * (1.0 * (((th + 2) * (tw + 2) + 15) / 16) + 4.0 * ((th * tw + 15) / 16) + 2.0);
+            if (cost < best) {
+                best = cost;
+                *TH = th; *TW = tw;
+            }
+        }
 }
 
 static bool is_plain_pointwise(const npas_layer_desc &d)
@@ -711,6 +802,51 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
         dims[i + 1] = {nd.Ho, nd.Wo, nd.F};
         s->nodes.push_back(nd);
     }
+    if (flags & NPAS_STACK_FUSE_INVERTED_RESIDUAL) {
+        int ndev = 0;
+        bool have_dev = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
+        if (!have_dev) (void)hipGetLastError();
+        for (int i = 0; i + 2 < n_layers && have_dev; ++i) {
+            npas_stack::Node &a = s->nodes[i], &b = s->nodes[i + 1], &c = s->nodes[i + 2];
+            if (a.fused_away || !is_plain_pointwise(a.d) || !is_plain_pointwise(c.d) || a.d.res >= 0) continue;
+            if (b.d.kind != NPAS_LAYER_DEPTHWISE3X3 || b.d.stride != 1 || b.d.bias_dev || b.d.res >= 0) continue;
+            if (b.d.src != i + 1 || c.d.src != i + 2 || (c.d.res >= 0 && c.d.res != a.d.src)) continue;
+            bool other_reader = false; // the two tensors inside the block must have no reader outside it
+            for (int j = i + 1; j < n_layers; ++j) {
+                const npas_layer_desc &dj = s->nodes[j].d;
+                if ((j != i + 1 && dj.src == i + 1) || dj.res == i + 1) other_reader = true;
+                if ((j != i + 2 && dj.src == i + 2) || dj.res == i + 2) other_reader = true;
+            }
+            if (other_reader) continue;
+            const npas_packed *p1 = a.d.packed, *p3 = c.d.packed;
+            if (p1->C > 32 || p1->C % 8 || p3->F % 4 || p3->F > 32 || (c.d.res >= 0 && p3->F != p1->C)) continue;
+            IrPlan ip = build_ir(p1, b.d.packed, p3);
+            int th, tw;
+            plan_ir_tile(a.H, a.W, ip.nslots, &th, &tw);
+            if (fused_ir_lds_bytes(th, tw, ip.nslots) > 64 * 1024) continue;
+            const size_t b1 = ip.w1.size() * 2, b3 = ip.w3.size() * 2, bd = ip.wdw.size() * 4;
+            const size_t o3 = (b1 + 255) / 256 * 256, od = o3 + (b3 + 255) / 256 * 256;
+            std::vector<uint8_t> blob(od + bd);
+            std::memcpy(blob.data(), ip.w1.data(), b1);
+            std::memcpy(blob.data() + o3, ip.w3.data(), b3);
+            std::memcpy(blob.data() + od, ip.wdw.data(), bd);
+            void *dptr = nullptr;
+            if (hipMalloc(&dptr, blob.size()) != hipSuccess ||
+                hipMemcpy(dptr, blob.data(), blob.size(), hipMemcpyHostToDevice) != hipSuccess) {
+                if (dptr) (void)hipFree(dptr);
+                set_error("could not upload the fused-block weight images");
+                for (void *q : s->blobs) (void)hipFree(q);
+                return NPAS_E_HIP;
+            }
+            s->blobs.push_back(dptr);
+            a.ir_w1 = dptr;
+            a.ir_w3 = (const uint8_t *)dptr + o3;
+            a.ir_wdw = (const float *)((const uint8_t *)dptr + od);
+            a.ir_nslots = ip.nslots; a.ir_TH = th; a.ir_TW = tw; a.ir_residual = c.d.res >= 0;
+            b.fused_away = true;
+            c.fused_away = true;
+        }
+    }
     if (flags & NPAS_STACK_FUSE_POINTWISE) {
         int ndev = 0;
         bool have_dev = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
@@ -801,6 +937,16 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
         const void *x = tensor(n.d.src);
         void *y = tensor(i + 1);
         int rc = NPAS_OK;
+        if (n.ir_w1) { // this layer and the next two as one kernel; the tensors between them are never stored
+            const npas_packed *p1 = n.d.packed, *p3 = s->nodes[i + 2].d.packed;
+            rc = check_run(p1, x, tensor(i + 3), N, n.H, n.W, 1, 0);
+            if (!rc)
+                rc = launch_fused_inverted_residual(p1->dtype, x, tensor(i + 3), n.ir_w1, n.ir_w3, n.ir_wdw, N, n.H, n.W, p1->C,
+                                                    p3->F, n.ir_nslots, n.ir_TH, n.ir_TW, n.d.act, s->nodes[i + 1].d.act,
+                                                    s->nodes[i + 2].d.act, n.ir_residual, hip_stream);
+            if (rc) return rc;
+            continue;
+        }
         if (n.fused_blob) { // this layer and the next as one kernel; the tensor between them is never stored
             const npas_packed *p1 = n.d.packed, *p2 = s->nodes[i + 1].d.packed;
             rc = check_run(p1, x, tensor(i + 2), N, n.H, n.W, 1, 0);

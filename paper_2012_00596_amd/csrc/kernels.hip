@@ -1555,6 +1555,187 @@ __global__ __launch_bounds__(256) void global_avgpool_kernel(const void *x, void
 }
 
 // ------------------------------------------------------------------------------
+// fused_inverted_residual: y = act3(W3 . act2(DW3x3(act1(W1 . x))) + x) for the cascade 1x1 -> 3x3
+// depthwise (stride 1) -> 1x1 of the search space (section 5.1.1) when the two wide tensors
+// between the layers have no other reader.  They never leave the CU: HBM sees x once and y once.
+//
+// A workgroup (4 waves) owns an output tile of TH x TW pixels.
+//   1. Expansion: for the tile plus a one-pixel halo, 16 pixels at a time, layer 1's MFMAs
+//      (K = C1 <= 32 in one step) produce 16 x 16 output tiles that are clamped, rounded and written
+//      to LDS as [halo pixel][slot] in the storage type.  Halo pixels outside the image read x as
+//      zero, which gives zero (the layers carry no bias here), as the padding of the depthwise
+//      layer must be.  A slot is an intermediate channel some filter of layer 3 keeps; channels
+//      nobody keeps are dead and are never computed (the pruning of layer 3 pays in layers 1 and 2).
+//   2. Depthwise + projection, 16 output pixels at a time: lane (q, n) forms the depthwise output
+//      of pixel n for 8 slots (nine 16-byte LDS reads of activations, fp32 weights from an LDS
+//      table, fp32 accumulate, clamp, round): exactly the B operand of layer 3's MFMA step for
+//      those 32 slots.  After all steps: residual (x again, 8 bytes per lane), clamp, round, store.
+// Bound: vector ALUs (the depthwise arithmetic and the unpacking of 16-bit pairs), not HBM.
+struct IrArgs {
+    const void *x;
+    void *y;
+    const void *w1;      // [nt1][64 lanes][8] layer-1 A-operand images, rows in slot order
+    const void *w3;      // [nt3][nk][64 lanes][8] layer-3 A-operand images, K in slot order
+    const float *wdw;    // [9][nslots] depthwise weights in slot order
+    int N, H, W, C1, F3;
+    int nt1, nk, nt3;    // slots / 16, slots / 32, ceil(F3 / 16)
+    int TH, TW, tilesY, tilesX;
+    int act1, act2, act3;
+    int residual;        // 1: add the block input (needs F3 == C1)
+    uint32_t div_tw, div_pw;
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
+    const int PH = a.TH + 2, PW = a.TW + 2, nslots = a.nt1 * 16;
+    const int nhb = (PH * PW + 15) >> 4, nob = (a.TH * a.TW + 15) >> 4; // 16-pixel blocks of the halo tile / the tile
+    const uint32_t pitch = (uint32_t)nslots * 2u + 16u;                  // bytes per halo pixel (+16: spreads the banks)
+    uint8_t *y1 = lds;
+    float *dww = reinterpret_cast<float *>(lds + (size_t)nhb * 16 * pitch);
+
+    uint32_t tile = blockIdx.x;
+    const int txi = (int)(tile % (uint32_t)a.tilesX);
+    tile /= (uint32_t)a.tilesX;
+    const int tyi = (int)(tile % (uint32_t)a.tilesY), n = (int)(tile / (uint32_t)a.tilesY);
+    const int ty0 = tyi * a.TH, tx0 = txi * a.TW;
+
+    for (int i = tid; i < 9 * nslots; i += 256) dww[i] = a.wdw[i];
+
+    // ---- 1. expansion into LDS ------------------------------------------------------------
+    const Clamp cl1 = clamp_of(a.act1);
+    const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
+    const uint4 *w1 = reinterpret_cast<const uint4 *>(a.w1) + lane;
+    for (int hb = wave; hb < nhb; hb += 4) {
+        const uint32_t hp = (uint32_t)(hb * 16 + n16);
+        const uint32_t py = fastdiv(hp, a.div_pw), px = hp - py * (uint32_t)PW;
+        const int iy = ty0 - 1 + (int)py, ix = tx0 - 1 + (int)px;
+        const bool inb = (int)py < PH && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W && 8 * q < a.C1;
+        uint4 xv = uint4{0u, 0u, 0u, 0u};
+        if (inb) xv = *reinterpret_cast<const uint4 *>(x16 + ((size_t)(n * a.H + iy) * a.W + ix) * a.C1 + 8 * q);
+        uint8_t *dst = y1 + (size_t)hp * pitch + (uint32_t)(4 * q) * 2u;
+        for (int t = 0; t < a.nt1; ++t) {
+            const f32x4 d = mfma16<DT>(w1[t * 64], xv, f32x4{0.f, 0.f, 0.f, 0.f});
+            uint2 o;
+            o.x = pack2<DT>(clampf(d[0], cl1), clampf(d[1], cl1));
+            o.y = pack2<DT>(clampf(d[2], cl1), clampf(d[3], cl1));
+            *reinterpret_cast<uint2 *>(dst + t * 32) = o;
+        }
+    }
+    __syncthreads();
+
+    // ---- 2. depthwise + projection ---------------------------------------------------------
+    const Clamp cl2 = clamp_of(a.act2), cl3 = clamp_of(a.act3);
+    const uint4 *w3 = reinterpret_cast<const uint4 *>(a.w3) + lane;
+    uint16_t *y16 = reinterpret_cast<uint16_t *>(a.y);
+    for (int ob = wave; ob < nob; ob += 4) {
+        const uint32_t m = (uint32_t)(ob * 16 + n16);
+        const uint32_t ty = fastdiv(m, a.div_tw), tx = m - ty * (uint32_t)a.TW;
+        const int oy = ty0 + (int)ty, ox = tx0 + (int)tx;
+        const bool valid = (int)ty < a.TH && oy < a.H && ox < a.W;
+        const uint8_t *base = y1 + (valid ? (size_t)(ty * (uint32_t)PW + tx) * pitch : 0) + (uint32_t)(8 * q) * 2u;
+        f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < a.nk; ++k) {
+            float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int tap = 0; tap < 9; ++tap) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(base + (size_t)((tap / 3) * PW + tap % 3) * pitch + k * 64);
+                const float4 wa = *reinterpret_cast<const float4 *>(dww + tap * nslots + 32 * k + 8 * q);
+                const float4 wb = *reinterpret_cast<const float4 *>(dww + tap * nslots + 32 * k + 8 * q + 4);
+                s[0] += from_storage<DT>((uint16_t)(v.x & 0xffffu)) * wa.x;
+                s[1] += from_storage<DT>((uint16_t)(v.x >> 16)) * wa.y;
+                s[2] += from_storage<DT>((uint16_t)(v.y & 0xffffu)) * wa.z;
+                s[3] += from_storage<DT>((uint16_t)(v.y >> 16)) * wa.w;
+                s[4] += from_storage<DT>((uint16_t)(v.z & 0xffffu)) * wb.x;
+                s[5] += from_storage<DT>((uint16_t)(v.z >> 16)) * wb.y;
+                s[6] += from_storage<DT>((uint16_t)(v.w & 0xffffu)) * wb.z;
+                s[7] += from_storage<DT>((uint16_t)(v.w >> 16)) * wb.w;
+            }
+            uint4 b;
+            b.x = pack2<DT>(clampf(s[0], cl2), clampf(s[1], cl2));
+            b.y = pack2<DT>(clampf(s[2], cl2), clampf(s[3], cl2));
+            b.z = pack2<DT>(clampf(s[4], cl2), clampf(s[5], cl2));
+            b.w = pack2<DT>(clampf(s[6], cl2), clampf(s[7], cl2));
+            acc0 = mfma16<DT>(w3[k * 64], b, acc0);
+            if (a.nt3 == 2) acc1 = mfma16<DT>(w3[(a.nk + k) * 64], b, acc1);
+        }
+        if (!valid) continue;
+        const size_t pix = (size_t)(n * a.H + oy) * a.W + ox;
+        for (int u = 0; u < a.nt3; ++u) {
+            const int f = 16 * u + 4 * q;
+            if (f >= a.F3) continue;
+            const f32x4 d = u == 0 ? acc0 : acc1;
+            float v[4] = {d[0], d[1], d[2], d[3]};
+            if (a.residual) {
+                const uint2 r = *reinterpret_cast<const uint2 *>(x16 + pix * a.C1 + f);
+                v[0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
+                v[1] += from_storage<DT>((uint16_t)(r.x >> 16));
+                v[2] += from_storage<DT>((uint16_t)(r.y & 0xffffu));
+                v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
+            }
+            uint2 o;
+            o.x = pack2<DT>(clampf(v[0], cl3), clampf(v[1], cl3));
+            o.y = pack2<DT>(clampf(v[2], cl3), clampf(v[3], cl3));
+            *reinterpret_cast<uint2 *>(y16 + pix * a.F3 + f) = o;
+        }
+    }
+}
+
+size_t fused_ir_lds_bytes(int TH, int TW, int nslots)
+{
+    const int nhb = ((TH + 2) * (TW + 2) + 15) / 16;
+    return (size_t)nhb * 16 * ((size_t)nslots * 2 + 16) + (size_t)9 * nslots * 4;
+}
+
+int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void *w1, const void *w3, const float *wdw, int N,
+                                   int H, int W, int C1, int F3, int nslots, int TH, int TW, int act1, int act2, int act3,
+                                   int residual, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    IrArgs a;
+    a.x = x; a.y = y; a.w1 = w1; a.w3 = w3; a.wdw = wdw;
+    a.N = N; a.H = H; a.W = W; a.C1 = C1; a.F3 = F3;
+    a.nt1 = nslots / 16; a.nk = nslots / 32; a.nt3 = (F3 + 15) / 16;
+    a.TH = TH; a.TW = TW; a.tilesY = (H + TH - 1) / TH; a.tilesX = (W + TW - 1) / TW;
+    a.act1 = act1; a.act2 = act2; a.act3 = act3; a.residual = residual;
+    a.div_tw = TW <= 1 ? 0u : (uint32_t)(((1ull << 32) + TW - 1) / TW);
+    a.div_pw = (uint32_t)(((1ull << 32) + (TW + 2) - 1) / (TW + 2));
+    const size_t lds_bytes = fused_ir_lds_bytes(TH, TW, nslots);
+    if (nslots <= 0 || nslots % 32 || a.nt3 < 1 || a.nt3 > 2 || C1 > 32 || C1 % 8 || F3 % 4 || lds_bytes > 160 * 1024 || (residual && F3 != C1)) {
+        set_error("fused inverted residual: unsupported shape (slots %d, C1 %d, F3 %d, LDS %zu)", nslots, C1, F3, lds_bytes);
+        return NPAS_E_SHAPE;
+    }
+    const long grid = (long)N * a.tilesY * a.tilesX;
+    static bool attr_done[2] = {false, false};
+    if (dtype == NPAS_BF16) {
+        auto kern = fused_inverted_residual_kernel<NPAS_BF16>;
+        if (!attr_done[0]) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            attr_done[0] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, st, a);
+    } else if (dtype == NPAS_F16) {
+        auto kern = fused_inverted_residual_kernel<NPAS_F16>;
+        if (!attr_done[1]) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            attr_done[1] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, st, a);
+    } else {
+        set_error("fused inverted residual needs a 16-bit storage type");
+        return NPAS_E_DTYPE;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("fused_inverted_residual launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+// ------------------------------------------------------------------------------
 // Depthwise 3x3, padding 1: one thread per (output pixel, vector of V channels); V * element
 // size = 16 bytes when the channel count allows it, so every load and store is one 16-byte
 // access, coalesced along the channels.  HBM-bound: the nine taps of a pixel come from L1 / L2.

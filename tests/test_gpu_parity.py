@@ -217,8 +217,9 @@ def test_inverted_residual_block_layerwise_and_stack(npas, torch, stride):
     print(f"inverted residual block, stride {stride}", flush=True)
     layerwise(npas, torch, w)
     rounded, _ = oracle.run_stack(w.x_exact, w.layers, w.dtype)
-    for flags in (0, 1):
+    for flags in (0, 1, 3):          # per layer; pointwise-pair fusion (not applicable); whole-block fusion
         got, st = _run_stack_gpu(npas, torch, w, flags)
+        assert st.num_launches() == (1 if flags == 3 and stride == 1 else 3)
         err = rel_err(got, rounded[-1])
         print(f"  run_stack flags={flags} launches={st.num_launches()} err={err:.3e}", flush=True)
         assert err <= 2e-2          # three roundings of bf16 activations compound
