@@ -368,7 +368,7 @@ struct npas_stack {
         bool fused_away = false;          // second layer of a fused pair: runs inside the first
         // first layer of a fused 1x1 -> depthwise 3x3 -> 1x1 block: device images and tile
         const void *ir_w1 = nullptr, *ir_w3 = nullptr;
-        const float *ir_wdw = nullptr;
+        const uint32_t *ir_wdw = nullptr;
         int ir_nslots = 0, ir_TH = 0, ir_TW = 0, ir_residual = 0;
     };
     std::vector<Node> nodes;
@@ -511,33 +511,11 @@ static FppPlan build_fpp(const npas_packed *p1, const npas_packed *p2)
     return plan;
 }
 
-// Storage bits -> float on the host (bf16: the upper half of a float; fp16 by its fields).
-static float storage_to_float(uint16_t b, int dtype)
-{
-    uint32_t u;
-    if (dtype == NPAS_BF16) u = (uint32_t)b << 16;
-    else {
-        const uint32_t sign = (uint32_t)(b >> 15) << 31, e = (b >> 10) & 31u, m = b & 1023u;
-        if (e == 0) {
-            if (m == 0) u = sign;
-            else { // subnormal: value m * 2^-24
-                float f = (float)m * 5.9604644775390625e-8f;
-                std::memcpy(&u, &f, 4);
-                u |= sign;
-            }
-        } else if (e == 31) u = sign | 0x7f800000u | (m << 13);
-        else u = sign | ((e + 112u) << 23) | (m << 13);
-    }
-    float f;
-    std::memcpy(&f, &u, 4);
-    return f;
-}
-
 // Plan and weight images of a fused inverted-residual block (layouts: see fused_inverted_residual_kernel).
 struct IrPlan {
     int nslots = 0;                 // live intermediate channels, padded to a multiple of 32
     std::vector<uint16_t> w1, w3;   // A-operand images
-    std::vector<float> wdw;         // [9][nslots]
+    std::vector<uint32_t> wdw;      // [9][nslots]: the weight's storage bits in the low (even slot) or high (odd slot) half
 };
 
 static IrPlan build_ir(const npas_packed *p1, const npas_packed *pdw, const npas_packed *p3)
@@ -569,11 +547,11 @@ static IrPlan build_ir(const npas_packed *p1, const npas_packed *pdw, const npas
                     const int r = lane & 15, q = lane >> 4, f = 16 * u + r, c = perm[32 * k + 8 * q + i];
                     if (f < p3->F && c >= 0) plan.w3[((size_t)(u * nk + k) * 64 + lane) * 8 + i] = d3[(size_t)f * p3->C + c];
                 }
-    plan.wdw.assign((size_t)9 * plan.nslots, 0.f);
+    plan.wdw.assign((size_t)9 * plan.nslots, 0u);
     const uint16_t *wd = reinterpret_cast<const uint16_t *>(pdw->w_compact.data());
     for (int s = 0; s < plan.nslots; ++s)
         if (perm[s] >= 0)
-            for (int t = 0; t < 9; ++t) plan.wdw[(size_t)t * plan.nslots + s] = storage_to_float(wd[(size_t)perm[s] * 9 + t], pdw->dtype);
+            for (int t = 0; t < 9; ++t) plan.wdw[(size_t)t * plan.nslots + s] = (uint32_t)wd[(size_t)perm[s] * 9 + t] << (s & 1 ? 16 : 0);
     return plan;
 }
 
@@ -841,7 +819,7 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             s->blobs.push_back(dptr);
             a.ir_w1 = dptr;
             a.ir_w3 = (const uint8_t *)dptr + o3;
-            a.ir_wdw = (const float *)((const uint8_t *)dptr + od);
+            a.ir_wdw = (const uint32_t *)((const uint8_t *)dptr + od);
             a.ir_nslots = ip.nslots; a.ir_TH = th; a.ir_TW = tw; a.ir_residual = c.d.res >= 0;
             b.fused_away = true;
             c.fused_away = true;

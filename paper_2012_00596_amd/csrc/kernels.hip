@@ -1567,16 +1567,29 @@ __global__ __launch_bounds__(256) void global_avgpool_kernel(const void *x, void
 //      layer must be.  A slot is an intermediate channel some filter of layer 3 keeps; channels
 //      nobody keeps are dead and are never computed (the pruning of layer 3 pays in layers 1 and 2).
 //   2. Depthwise + projection, 16 output pixels at a time: lane (q, n) forms the depthwise output
-//      of pixel n for 8 slots (nine 16-byte LDS reads of activations, fp32 weights from an LDS
-//      table, fp32 accumulate, clamp, round): exactly the B operand of layer 3's MFMA step for
+//      of pixel n for 8 slots (nine 16-byte LDS reads of activations, weights from an LDS table,
+//      one dot2 instruction per multiply-add on the packed pairs, fp32 accumulate, clamp, round):
+//      exactly the B operand of layer 3's MFMA step for
 //      those 32 slots.  After all steps: residual (x again, 8 bytes per lane), clamp, round, store.
 // Bound: vector ALUs (the depthwise arithmetic and the unpacking of 16-bit pairs), not HBM.
+// c + x.lo * w.lo + x.hi * w.hi on two packed 16-bit pairs (v_dot2c_f32_bf16 / v_dot2_f32_f16).  With one half of
+// w zero this is a multiply-add on the other half without unpacking it (the zero half adds an exact zero as long
+// as the activation beside it is finite).
+template <int DT> __device__ __forceinline__ float dot2acc(uint32_t x, uint32_t w, float c)
+{
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    if (DT == NPAS_BF16) return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x), __builtin_bit_cast(bf16x2, w), c, false);
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, x), __builtin_bit_cast(f16x2, w), c, false);
+}
+
 struct IrArgs {
     const void *x;
     void *y;
     const void *w1;      // [nt1][64 lanes][8] layer-1 A-operand images, rows in slot order
     const void *w3;      // [nt3][nk][64 lanes][8] layer-3 A-operand images, K in slot order
-    const float *wdw;    // [9][nslots] depthwise weights in slot order
+    const uint32_t *wdw; // [9][nslots] depthwise weights in slot order, each alone in its half of a 16-bit pair
+                         // (even slots low, odd slots high, the other half zero)
     int N, H, W, C1, F3;
     int nt1, nk, nt3;    // slots / 16, slots / 32, ceil(F3 / 16)
     int TH, TW, tilesY, tilesX;
@@ -1594,7 +1607,7 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
     const int nhb = (PH * PW + 15) >> 4, nob = (a.TH * a.TW + 15) >> 4; // 16-pixel blocks of the halo tile / the tile
     const uint32_t pitch = (uint32_t)nslots * 2u + 16u;                  // bytes per halo pixel (+16: spreads the banks)
     uint8_t *y1 = lds;
-    float *dww = reinterpret_cast<float *>(lds + (size_t)nhb * 16 * pitch);
+    uint32_t *dww = reinterpret_cast<uint32_t *>(lds + (size_t)nhb * 16 * pitch);
 
     uint32_t tile = blockIdx.x;
     const int txi = (int)(tile % (uint32_t)a.tilesX);
@@ -1639,19 +1652,23 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
         f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int k = 0; k < a.nk; ++k) {
             float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            uint4 vt[9]; // all nine taps asked for before the first is used
+#pragma unroll
+            for (int tap = 0; tap < 9; ++tap)
+                vt[tap] = *reinterpret_cast<const uint4 *>(base + (size_t)((tap / 3) * PW + tap % 3) * pitch + k * 64);
 #pragma unroll
             for (int tap = 0; tap < 9; ++tap) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(base + (size_t)((tap / 3) * PW + tap % 3) * pitch + k * 64);
-                const float4 wa = *reinterpret_cast<const float4 *>(dww + tap * nslots + 32 * k + 8 * q);
-                const float4 wb = *reinterpret_cast<const float4 *>(dww + tap * nslots + 32 * k + 8 * q + 4);
-                s[0] += from_storage<DT>((uint16_t)(v.x & 0xffffu)) * wa.x;
-                s[1] += from_storage<DT>((uint16_t)(v.x >> 16)) * wa.y;
-                s[2] += from_storage<DT>((uint16_t)(v.y & 0xffffu)) * wa.z;
-                s[3] += from_storage<DT>((uint16_t)(v.y >> 16)) * wa.w;
-                s[4] += from_storage<DT>((uint16_t)(v.z & 0xffffu)) * wb.x;
-                s[5] += from_storage<DT>((uint16_t)(v.z >> 16)) * wb.y;
-                s[6] += from_storage<DT>((uint16_t)(v.w & 0xffffu)) * wb.z;
-                s[7] += from_storage<DT>((uint16_t)(v.w >> 16)) * wb.w;
+                const uint4 v = vt[tap];
+                const uint4 wa = *reinterpret_cast<const uint4 *>(dww + tap * nslots + 32 * k + 8 * q);
+                const uint4 wb = *reinterpret_cast<const uint4 *>(dww + tap * nslots + 32 * k + 8 * q + 4);
+                s[0] = dot2acc<DT>(v.x, wa.x, s[0]);
+                s[1] = dot2acc<DT>(v.x, wa.y, s[1]);
+                s[2] = dot2acc<DT>(v.y, wa.z, s[2]);
+                s[3] = dot2acc<DT>(v.y, wa.w, s[3]);
+                s[4] = dot2acc<DT>(v.z, wb.x, s[4]);
+                s[5] = dot2acc<DT>(v.z, wb.y, s[5]);
+                s[6] = dot2acc<DT>(v.w, wb.z, s[6]);
+                s[7] = dot2acc<DT>(v.w, wb.w, s[7]);
             }
             uint4 b;
             b.x = pack2<DT>(clampf(s[0], cl2), clampf(s[1], cl2));
@@ -1689,7 +1706,7 @@ size_t fused_ir_lds_bytes(int TH, int TW, int nslots)
     return (size_t)nhb * 16 * ((size_t)nslots * 2 + 16) + (size_t)9 * nslots * 4;
 }
 
-int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void *w1, const void *w3, const float *wdw, int N,
+int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void *w1, const void *w3, const uint32_t *wdw, int N,
                                    int H, int W, int C1, int F3, int nslots, int TH, int TW, int act1, int act2, int act3,
                                    int residual, void *stream)
 {

@@ -223,7 +223,7 @@ bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
                                 int act1, int act2, uint32_t use0, uint32_t use1, void *stream);
 size_t fused_ir_lds_bytes(int TH, int TW, int nslots);
-int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void *w1, const void *w3, const float *wdw, int N,
+int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void *w1, const void *w3, const uint32_t *wdw, int N,
                                    int H, int W, int C1, int F3, int nslots, int TH, int TW, int act1, int act2, int act3,
                                    int residual, void *stream);
 int launch_depthwise3x3(int dt, const void *x, void *y, const void *w, const float *bias, const void *residual, int N, int H,
