@@ -564,7 +564,7 @@ static void plan_ir_tile(int H, int W, int nslots, int *TH, int *TW)
     *TH = 1; *TW = 1;
     for (int th = 1; th <= 32; ++th)
         for (int tw = 1; tw <= 64; ++tw) {
-            if (th * tw > 256 || (th + 2) * (tw + 2) > 512 || tw + 2 > 1023) continue;
+            if ((th + 2) * (tw + 2) > 256) continue; // four 16-pixel halo blocks per wave at most
             if (fused_ir_lds_bytes(th, tw, nslots) > 64 * 1024) continue;
             const double tiles = (double)((H + th - 1) / th) * ((W + tw - 1) / tw);
             const double cost = tiles * (1.0 * (((th + 2) * (tw + 2) + 15) / 16) + 4.0 * ((th * tw + 15) / 16) + 2.0);
@@ -799,6 +799,7 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             const npas_packed *p1 = a.d.packed, *p3 = c.d.packed;
             if (p1->C > 32 || p1->C % 8 || p3->F % 4 || p3->F > 32 || (c.d.res >= 0 && p3->F != p1->C)) continue;
             IrPlan ip = build_ir(p1, b.d.packed, p3);
+            if (ip.nslots > 192) continue;
             int th, tw;
             plan_ir_tile(a.H, a.W, ip.nslots, &th, &tw);
             if (fused_ir_lds_bytes(th, tw, ip.nslots) > 64 * 1024) continue;

@@ -1583,6 +1583,10 @@ template <int DT> __device__ __forceinline__ float dot2acc(uint32_t x, uint32_t 
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, x), __builtin_bit_cast(f16x2, w), c, false);
 }
 
+// Padding of a halo pixel's row in LDS: 32 bytes measured best among 16 .. 144 for 96 slots (a 256-byte row
+// pitch, i.e. 64, is the worst case: every pixel on the same banks).
+constexpr uint32_t kIrPad = 32;
+
 struct IrArgs {
     const void *x;
     void *y;
@@ -1605,7 +1609,7 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
     const int PH = a.TH + 2, PW = a.TW + 2, nslots = a.nt1 * 16;
     const int nhb = (PH * PW + 15) >> 4, nob = (a.TH * a.TW + 15) >> 4; // 16-pixel blocks of the halo tile / the tile
-    const uint32_t pitch = (uint32_t)nslots * 2u + 16u;                  // bytes per halo pixel (+16: spreads the banks)
+    const uint32_t pitch = (uint32_t)nslots * 2u + kIrPad;               // bytes per halo pixel
     uint8_t *y1 = lds;
     uint32_t *dww = reinterpret_cast<uint32_t *>(lds + (size_t)nhb * 16 * pitch);
 
@@ -1621,20 +1625,34 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
     const Clamp cl1 = clamp_of(a.act1);
     const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
     const uint4 *w1 = reinterpret_cast<const uint4 *>(a.w1) + lane;
-    for (int hb = wave; hb < nhb; hb += 4) {
+    // every load of this phase is issued before the first MFMA: the wave's activation vectors (up to four
+    // 16-pixel blocks) and layer 1's images, so that one memory latency is paid instead of one per block and image
+    uint4 xv[4], w1r[12];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int hb = wave + 4 * r;
         const uint32_t hp = (uint32_t)(hb * 16 + n16);
         const uint32_t py = fastdiv(hp, a.div_pw), px = hp - py * (uint32_t)PW;
         const int iy = ty0 - 1 + (int)py, ix = tx0 - 1 + (int)px;
-        const bool inb = (int)py < PH && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W && 8 * q < a.C1;
-        uint4 xv = uint4{0u, 0u, 0u, 0u};
-        if (inb) xv = *reinterpret_cast<const uint4 *>(x16 + ((size_t)(n * a.H + iy) * a.W + ix) * a.C1 + 8 * q);
-        uint8_t *dst = y1 + (size_t)hp * pitch + (uint32_t)(4 * q) * 2u;
-        for (int t = 0; t < a.nt1; ++t) {
-            const f32x4 d = mfma16<DT>(w1[t * 64], xv, f32x4{0.f, 0.f, 0.f, 0.f});
-            uint2 o;
-            o.x = pack2<DT>(clampf(d[0], cl1), clampf(d[1], cl1));
-            o.y = pack2<DT>(clampf(d[2], cl1), clampf(d[3], cl1));
-            *reinterpret_cast<uint2 *>(dst + t * 32) = o;
+        const bool inb = hb < nhb && (int)py < PH && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W && 8 * q < a.C1;
+        xv[r] = uint4{0u, 0u, 0u, 0u};
+        if (inb) xv[r] = *reinterpret_cast<const uint4 *>(x16 + ((size_t)(n * a.H + iy) * a.W + ix) * a.C1 + 8 * q);
+    }
+#pragma unroll
+    for (int t = 0; t < 12; ++t) w1r[t] = t < a.nt1 ? w1[t * 64] : uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int hb = wave + 4 * r;
+        uint8_t *dst = y1 + (size_t)(hb * 16 + n16) * pitch + (uint32_t)(4 * q) * 2u;
+#pragma unroll
+        for (int t = 0; t < 12; ++t) {
+            if (hb < nhb && t < a.nt1) {
+                const f32x4 d = mfma16<DT>(w1r[t], xv[r], f32x4{0.f, 0.f, 0.f, 0.f});
+                uint2 o;
+                o.x = pack2<DT>(clampf(d[0], cl1), clampf(d[1], cl1));
+                o.y = pack2<DT>(clampf(d[2], cl1), clampf(d[3], cl1));
+                *reinterpret_cast<uint2 *>(dst + t * 32) = o;
+            }
         }
     }
     __syncthreads();
@@ -1651,6 +1669,7 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
         const uint8_t *base = y1 + (valid ? (size_t)(ty * (uint32_t)PW + tx) * pitch : 0) + (uint32_t)(8 * q) * 2u;
         f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int k = 0; k < a.nk; ++k) {
+            const uint4 w3a = w3[k * 64], w3b = a.nt3 == 2 ? w3[(a.nk + k) * 64] : uint4{0u, 0u, 0u, 0u}; // asked for before the taps
             float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             uint4 vt[9]; // all nine taps asked for before the first is used
 #pragma unroll
@@ -1675,8 +1694,8 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
             b.y = pack2<DT>(clampf(s[2], cl2), clampf(s[3], cl2));
             b.z = pack2<DT>(clampf(s[4], cl2), clampf(s[5], cl2));
             b.w = pack2<DT>(clampf(s[6], cl2), clampf(s[7], cl2));
-            acc0 = mfma16<DT>(w3[k * 64], b, acc0);
-            if (a.nt3 == 2) acc1 = mfma16<DT>(w3[(a.nk + k) * 64], b, acc1);
+            acc0 = mfma16<DT>(w3a, b, acc0);
+            if (a.nt3 == 2) acc1 = mfma16<DT>(w3b, b, acc1);
         }
         if (!valid) continue;
         const size_t pix = (size_t)(n * a.H + oy) * a.W + ox;
@@ -1703,7 +1722,7 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
 size_t fused_ir_lds_bytes(int TH, int TW, int nslots)
 {
     const int nhb = ((TH + 2) * (TW + 2) + 15) / 16;
-    return (size_t)nhb * 16 * ((size_t)nslots * 2 + 16) + (size_t)9 * nslots * 4;
+    return (size_t)nhb * 16 * ((size_t)nslots * 2 + kIrPad) + (size_t)9 * nslots * 4;
 }
 
 int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void *w1, const void *w3, const uint32_t *wdw, int N,
@@ -1720,7 +1739,7 @@ int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void
     a.div_tw = TW <= 1 ? 0u : (uint32_t)(((1ull << 32) + TW - 1) / TW);
     a.div_pw = (uint32_t)(((1ull << 32) + (TW + 2) - 1) / (TW + 2));
     const size_t lds_bytes = fused_ir_lds_bytes(TH, TW, nslots);
-    if (nslots <= 0 || nslots % 32 || a.nt3 < 1 || a.nt3 > 2 || C1 > 32 || C1 % 8 || F3 % 4 || lds_bytes > 160 * 1024 || (residual && F3 != C1)) {
+    if (nslots <= 0 || nslots % 32 || nslots > 192 || (TH + 2) * (TW + 2) > 256 || a.nt3 < 1 || a.nt3 > 2 || C1 > 32 || C1 % 8 || F3 % 4 || lds_bytes > 160 * 1024 || (residual && F3 != C1)) {
         set_error("fused inverted residual: unsupported shape (slots %d, C1 %d, F3 %d, LDS %zu)", nslots, C1, F3, lds_bytes);
         return NPAS_E_SHAPE;
     }
