@@ -234,6 +234,32 @@ def test_depthwise_handle_is_rejected_by_the_convolution_call(npas, torch):
         npas.conv2d_sparse(p, x, y, 1, 4, 4, 1, 1)
 
 
+def test_fc_with_rows_and_columns_pruned_inside_blocks(npas, torch):
+    """Block-based FC pruning allows whole rows as well as whole columns of a block to go (section 3)."""
+    B, IN, OUT, Br, Bcol = 37, 192, 88, 16, 32
+    m = masks.fc_block_mask(OUT, IN, Br, Bcol, 3, 41).copy()
+    keys = prng.u64(41, 9, OUT * (IN // Bcol)).reshape(OUT, IN // Bcol)
+    rowdrop = (keys % np.uint64(4)) == 0                      # a quarter of the (row, block) pairs lose their row
+    m[np.repeat(rowdrop, Bcol, axis=1)] = 0
+    assert oracle.validate_fc_block(m, Br, Bcol) == 0
+    xs, xe = dtypes.quantize(prng.normal(41, 1, B * IN).reshape(B, IN), dtypes.BF16)
+    ws, we = dtypes.quantize(prng.normal(41, 2, OUT * IN, 0.1).reshape(OUT, IN, 1, 1), dtypes.BF16)
+    L = configs.Layer("fc", "fc_block", IN, OUT, 1, 1, 1, 0, Br, Bcol, 3.0, 1, w_store=ws, w_exact=we,
+                      mask=m.reshape(OUT, IN, 1, 1))
+    p = pack_layer(npas, L, dtypes.BF16)
+    helpers.check_metadata(oracle, L, p, dtypes.BF16)
+    y = run_layer_gpu(npas, torch, L, p, to_dev(xs, torch), (B, IN), dtypes.BF16)
+    ref = oracle.round_to(oracle.fc_masked(xe, we, L.mask, None, 1), dtypes.BF16)
+    err = rel_err(from_dev(y, dtypes.BF16).reshape(B, OUT), ref)
+    print(f"  err={err:.3e}", flush=True)
+    assert err <= 1e-2
+
+
+def test_block_punched_5x5(npas, torch):
+    _run_edge_case(npas, torch, ("kernel_5x5", 2, 17, 19, 16, 24, 5, 5, 1, 2, 8, 4, 3, dtypes.BF16, 1, False, True))
+    _run_edge_case(npas, torch, ("kernel_5x5_wide", 2, 12, 12, 64, 72, 5, 5, 1, 2, 8, 4, 2, dtypes.BF16, 0, True, False))
+
+
 def test_group_with_everything_pruned_gives_bias_only(npas, torch):
     F, C = 32, 16
     m = masks.block_punched_mask(F, C, 3, 3, 8, 4, 2, 5)
