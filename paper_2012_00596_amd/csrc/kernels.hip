@@ -779,31 +779,32 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
     uint32_t c_slot = 0, bbuf = 0;
     for (;;) { // one item per iteration
         const PointwiseItem it = pointwise_item(nfb, c_item);
-        const int fl = (int)it.fb * (FW * 64) + wf * 64 + 4 * q; // this lane's first filter in row tile 0
-        uint32_t obyte[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint32_t m = it.ptile * (uint32_t)(PW * 64) + (uint32_t)(wp * 64 + s * 16 + n16);
-            obyte[s] = m < (uint32_t)a.M ? (m * (uint32_t)a.F + (uint32_t)fl) * 2u : 0xffffffffu;
-        }
+        // The activations are the MFMA's row operand and the weight images its column operand, and
+        // row r of weight tile j is filter 4r + j of the wave's 64: result register i of (j, s)
+        // is pixel 16s + 4q + i, filter 4 n16 + j.  A lane therefore owns 4 consecutive filters
+        // of a pixel, and the 16 lanes of a quarter wave one whole 128-byte run of its row.
+        const int fcol = (int)it.fb * (FW * 64) + wf * 64 + 4 * n16;
+        const uint32_t m0 = it.ptile * (uint32_t)(PW * 64) + (uint32_t)(wp * 64 + 4 * q);
+        const uint32_t obase = (m0 * (uint32_t)a.F + (uint32_t)fcol) * 2u; // byte offset of (pixel m0, filter fcol)
+        const uint32_t rows_left = fcol < a.F && m0 < (uint32_t)a.M ? (uint32_t)a.M - m0 : 0u; // valid pixels from m0 on
         f32x4 acc[4][4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int s = 0; s < 4; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
-        uint2 res[4][4];
+        uint2 res[4][4]; // [s][i]
         for (int t = 0; t < nst; ++t) {
             __builtin_amdgcn_s_barrier(); // this stage has landed; everyone is done with the stage before
             asm volatile("" ::: "memory");
             if (rb && t == nst - 1) { // residual: asked for before the last multiply, used after it
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    uint32_t ob = obyte[s];
+                    uint32_t ob = obase;
                     asm volatile("" : "+v"(ob)); // keeps the 16 addresses from being formed (and held) outside the loop
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const bool ok = ob != 0xffffffffu && fl + 16 * j < a.F;
-                        res[j][s] = *reinterpret_cast<const uint2 *>(rb + (ok ? ob + 32u * j : 0u));
+                    for (int i = 0; i < 4; ++i) {
+                        const bool ok = (uint32_t)(16 * s + i) < rows_left;
+                        res[s][i] = *reinterpret_cast<const uint2 *>(rb + (ok ? ob + (uint32_t)(16 * s + i) * (uint32_t)a.F * 2u : 0u));
                     }
                 }
             }
@@ -821,31 +822,29 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[j][s] = mfma16<DT>(A[j], B[s], acc[j][s]);
+                    for (int j = 0; j < 4; ++j) acc[j][s] = mfma16<DT>(B[s], A[j], acc[j][s]);
             }
         }
         // ---- bias, residual, clamp (activation), round, store -----------------------------
+        float4 bv = float4{0.f, 0.f, 0.f, 0.f};
+        if (a.bias) bv = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 4 * n16) * 4u);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (fl + 16 * j >= a.F) continue;
-            float4 bv = float4{0.f, 0.f, 0.f, 0.f};
-            if (a.bias) bv = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 16 * j + 4 * q) * 4u);
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                if (obyte[s] == 0xffffffffu) continue;
-                float v[4] = {acc[j][s][0] + bv.x, acc[j][s][1] + bv.y, acc[j][s][2] + bv.z, acc[j][s][3] + bv.w};
+            for (int i = 0; i < 4; ++i) {
+                if ((uint32_t)(16 * s + i) >= rows_left) continue;
+                float v[4] = {acc[0][s][i] + bv.x, acc[1][s][i] + bv.y, acc[2][s][i] + bv.z, acc[3][s][i] + bv.w};
                 if (rb) {
-                    v[0] += from_storage<DT>((uint16_t)(res[j][s].x & 0xffffu));
-                    v[1] += from_storage<DT>((uint16_t)(res[j][s].x >> 16));
-                    v[2] += from_storage<DT>((uint16_t)(res[j][s].y & 0xffffu));
-                    v[3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
+                    v[0] += from_storage<DT>((uint16_t)(res[s][i].x & 0xffffu));
+                    v[1] += from_storage<DT>((uint16_t)(res[s][i].x >> 16));
+                    v[2] += from_storage<DT>((uint16_t)(res[s][i].y & 0xffffu));
+                    v[3] += from_storage<DT>((uint16_t)(res[s][i].y >> 16));
                 }
                 uint2 out;
                 out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
                 out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                *reinterpret_cast<uint2 *>(yb + obyte[s] + 32u * j) = out;
+                *reinterpret_cast<uint2 *>(yb + obase + (uint32_t)(16 * s + i) * (uint32_t)a.F * 2u) = out;
             }
-        }
         if (c_item + nwg >= nitems) break;
         c_item += nwg;
         bbuf ^= 1u;
@@ -1032,8 +1031,8 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
     const int wp = wave >> 1, wf = wave & 1;
     const Clamp cl = clamp_of(a.act);
     const int thtw = a.TH * a.TW;
-    // per-lane tile geometry (the same for every item)
-    uint32_t pb0[4], mt[4];
+    // where this lane's operand rows (tile pixels 64 wp + 16 s + n16) sit in the patch (the same for every item)
+    uint32_t pb0[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         const uint32_t m = (uint32_t)(wp * 64 + s * 16 + n16);
@@ -1041,7 +1040,6 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
         const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
         const bool valid = (int)m < a.NI * thtw;
         pb0[s] = valid ? img * (uint32_t)phpw + ty * (uint32_t)a.PW + tx : 0u;
-        mt[s] = valid ? (img << 16 | ty << 8 | tx) : 0xffffffffu;
     }
     uint32_t c_slot = 0, pbuf = 0, bbuf = 0;
     const uint32_t arow = (uint32_t)(wf * 4) * 1024u + (uint32_t)lane * 16u;
@@ -1085,42 +1083,43 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
                         for (int j = 0; j < 4; ++j) A[1][j] = *reinterpret_cast<const uint4 *>(wsp + 8192 + j * 1024);
                     }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[j][i & 3] = mfma16<DT>(A[i >> 2][j], B[i], acc[j][i & 3]);
+                    for (int j = 0; j < 4; ++j) acc[j][i & 3] = mfma16<DT>(B[i], A[i >> 2][j], acc[j][i & 3]);
                 }
             }
             pbuf ^= 1u;
         }
         // ---- bias (from LDS), residual, clamp (activation), round, store ---------------------
-        const int fl = it.fb * 128 + wf * 64 + 4 * q; // this lane's first filter in row tile 0
+        // The patch is the MFMA's row operand and the weight images its column operand, and row r
+        // of weight tile j is filter 4r + j of the wave's 64: result register i of (j, s) is tile
+        // pixel 64 wp + 16 s + 4q + i, filter 4 n16 + j.  A lane writes 4 consecutive filters of a
+        // pixel, the 16 lanes of a quarter wave one whole 128-byte run of its row.
+        const int fcol = it.fb * 128 + wf * 64 + 4 * n16;
+        float4 b4 = float4{0.f, 0.f, 0.f, 0.f};
+        if (a.bias) b4 = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 4 * n16) * 4u);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int n = it.n0 + (int)(mt[s] >> 16), oy = it.ty0 + (int)((mt[s] >> 8) & 255u), ox = it.tx0 + (int)(mt[s] & 255u);
-            if (mt[s] == 0xffffffffu || n >= a.N || oy >= a.Ho || ox >= a.Wo) continue;
-            const size_t o = (size_t)((n * a.Ho + oy) * a.Wo + ox) * (size_t)a.F + (size_t)fl;
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (fl + 16 * j >= a.F) continue;
-                float v[4] = {acc[j][s][0], acc[j][s][1], acc[j][s][2], acc[j][s][3]};
-                if (a.bias) {
-                    const float4 b4 = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 16 * j + 4 * q) * 4u);
-                    v[0] += b4.x;
-                    v[1] += b4.y;
-                    v[2] += b4.z;
-                    v[3] += b4.w;
-                }
+            for (int i = 0; i < 4; ++i) {
+                uint32_t m = (uint32_t)(wp * 64 + s * 16 + 4 * q + i);
+                asm volatile("" : "+v"(m)); // or the 16 pixel decodes are done (and held) ahead of the item loop
+                const uint32_t img = fastdiv(m, a.div_thtw), r = m - img * (uint32_t)thtw;
+                const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
+                const int n = it.n0 + (int)img, oy = it.ty0 + (int)ty, ox = it.tx0 + (int)tx;
+                if ((int)m >= a.NI * thtw || n >= a.N || oy >= a.Ho || ox >= a.Wo || fcol >= a.F) continue;
+                const size_t o = (size_t)((n * a.Ho + oy) * a.Wo + ox) * (size_t)a.F + (size_t)fcol;
+                float v[4] = {acc[0][s][i] + b4.x, acc[1][s][i] + b4.y, acc[2][s][i] + b4.z, acc[3][s][i] + b4.w};
                 if (a.residual) {
-                    const uint2 r = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.residual) + o + 16 * j);
-                    v[0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
-                    v[1] += from_storage<DT>((uint16_t)(r.x >> 16));
-                    v[2] += from_storage<DT>((uint16_t)(r.y & 0xffffu));
-                    v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
+                    const uint2 r2 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.residual) + o);
+                    v[0] += from_storage<DT>((uint16_t)(r2.x & 0xffffu));
+                    v[1] += from_storage<DT>((uint16_t)(r2.x >> 16));
+                    v[2] += from_storage<DT>((uint16_t)(r2.y & 0xffffu));
+                    v[3] += from_storage<DT>((uint16_t)(r2.y >> 16));
                 }
                 uint2 out;
                 out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
                 out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o + 16 * j) = out;
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o) = out;
             }
-        }
         if (!more_items) break;
         c_item += nwg;
         it = spatial_item(a, c_item);

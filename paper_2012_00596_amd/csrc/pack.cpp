@@ -282,7 +282,10 @@ static void build_ring(npas_packed *p, const uint8_t *m, const uint8_t *w)
                     for (int tile = 0; tile < 8; ++tile)
                         for (int lane = 0; lane < 64; ++lane)
                             for (int i = 0; i < 8; ++i) {
-                                int rr = lane & 15, q = lane >> 4, f = f0 + 16 * tile + rr, c = 64 * cc + 32 * step + 8 * q + i;
+                                // row rr of tile (h, j) is filter 64 h + 4 rr + j of the block: the four tiles of a
+                                // 64-filter half give each MFMA result column four consecutive filters
+                                int rr = lane & 15, q = lane >> 4, f = f0 + 64 * (tile >> 2) + 4 * rr + (tile & 3);
+                                int c = 64 * cc + 32 * step + 8 * q + i;
                                 if (f >= F) continue;
                                 size_t wi = ((size_t)f * C + c) * T + tap;
                                 if (m[wi]) r.wimg[w0 + (size_t)(step * 8 + tile) * 512 + lane * 8 + i] = w16[wi];
