@@ -402,7 +402,7 @@ __global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a
     uint8_t *yb = reinterpret_cast<uint8_t *>(a.y);
     const uint8_t *rb = reinterpret_cast<const uint8_t *>(a.residual);
     const int npix_tile = g.TH * g.TW;
-    const Clamp cl = clamp_of(g.act);
+    const Clamp cl = clamp_of(g.act); // F is a multiple of 4 on this path: a lane's 4 outputs are one 8-byte store
 
     uint32_t item = xcd_remap(blockIdx.x, nwg);
     if (item >= nitems) return;
@@ -418,14 +418,10 @@ __global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a
     for (;;) { // one work item per iteration
         const int st = it.fb * WGF + wf; // this wave's super-tile
         const bool active = st < a.ntiles;
-        // The patch is the MFMA's row operand and the weight fragments its column operand, and row r of
-        // row tile j is filter WT r + j of the super-tile: result register i of (j, s) is tile pixel
-        // 16 (wp WB + s) + 4q + i, filter WT n16 + j.  A lane owns WT consecutive filters of a pixel and
-        // the 16 lanes of a quarter wave one contiguous run of its output row.
-        const int fcol = st * (WT * 16) + WT * n16;
-        const bool fok = active && fcol < g.F; // F is a multiple of 4 on this path: all WT filters or none
-        // Where this lane's operand rows sit in the patch; accumulators start from the bias.
-        uint32_t pixbase[WB];
+        const int fl = (st * WT) * 16 + 4 * q; // this lane's first filter in row tile 0
+        // Where this lane's pixel columns sit in the patch and in the output; accumulators
+        // start from the bias.
+        uint32_t pixbase[WB], obyte[WB];
         f32x4 acc[WT][WB];
 #pragma unroll
         for (int s = 0; s < WB; ++s) {
@@ -434,12 +430,18 @@ __global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a
             const int oy = it.ty0 + (int)ty, ox = it.tx0 + (int)tx;
             const bool valid = (int)m < npix_tile && oy < g.Ho && ox < g.Wo;
             pixbase[s] = valid ? ((ty * g.lstep) * g.PW + tx * g.lstep) * (uint32_t)g.pitch : 0u;
+            obyte[s] = valid ? (uint32_t)(((it.n * g.Ho + oy) * g.Wo + ox) * g.F + fl) * 2u : 0xffffffffu;
         }
 #pragma unroll
         for (int j = 0; j < WT; ++j) {
-            const float b0 = a.bias && fok ? a.bias[fcol + j] : 0.f;
+            f32x4 b0 = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (a.bias && active) {
 #pragma unroll
-            for (int s = 0; s < WB; ++s) acc[j][s] = f32x4{b0, b0, b0, b0};
+                for (int i = 0; i < 4; ++i)
+                    if (fl + 16 * j + i < g.F) b0[i] = a.bias[fl + 16 * j + i];
+            }
+#pragma unroll
+            for (int s = 0; s < WB; ++s) acc[j][s] = b0;
         }
 
         uint32_t nitem = item + nwg;
@@ -452,6 +454,18 @@ __global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a
             if (has_next) {
                 if (last) nit = slab_item(g, nitem);
                 slab_patch_load(a, xb, last ? nit : it, last ? 0 : cc + 1, desc, pf);
+            }
+            // ---- residual: fetched ahead of the item's last chunk, added after it -----------
+            uint2 res[WT][WB];
+            if (last && rb && active) {
+#pragma unroll
+                for (int j = 0; j < WT; ++j)
+#pragma unroll
+                    for (int s = 0; s < WB; ++s) {
+                        res[j][s] = uint2{0u, 0u};
+                        if (obyte[s] != 0xffffffffu && fl + 16 * j < g.F)
+                            res[j][s] = *reinterpret_cast<const uint2 *>(rb + obyte[s] + 32u * j);
+                    }
             }
             // ---- multiply the current stage out of LDS ---------------------------------
             if (active) {
@@ -483,46 +497,32 @@ __global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a
 #pragma unroll
                         for (int s = 0; s < WB; ++s)
 #pragma unroll
-                            for (int j = 0; j < WT; ++j) acc[j][s] = mfma16<DT>(b[s], wc[j], acc[j][s]);
+                            for (int j = 0; j < WT; ++j) acc[j][s] = mfma16<DT>(wc[j], b[s], acc[j][s]);
                     }
                 }
             }
             if (has_next) slab_patch_store(lds + (bufoff ^ buf_bytes), desc, pf);
             if (last && active) {
-                // ---- residual, clamp (activation), round, store ------------------------------
+                // ---- clamp (activation), round, store --------------------------------------
 #pragma unroll
-                for (int s = 0; s < WB; ++s)
+                for (int j = 0; j < WT; ++j) {
+                    const int f0 = fl + 16 * j;
+                    if (f0 >= g.F) continue;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        uint32_t m = (uint32_t)((wp * WB + s) * 16 + 4 * q + i);
-                        asm volatile("" : "+v"(m)); // or the pixel decodes are done (and held) ahead of the chunk loop
-                        const uint32_t ty = fastdiv(m, g.div_tw), tx = m - ty * (uint32_t)g.TW;
-                        const int oy = it.ty0 + (int)ty, ox = it.tx0 + (int)tx;
-                        if (!fok || (int)m >= npix_tile || oy >= g.Ho || ox >= g.Wo) continue;
-                        const uint32_t ob = (uint32_t)(((it.n * g.Ho + oy) * g.Wo + ox) * g.F + fcol) * 2u;
-                        uint32_t res[WT / 2];
+                    for (int s = 0; s < WB; ++s) {
+                        if (obyte[s] == 0xffffffffu) continue;
                         if (rb) {
-                            if (WT == 4) {
-                                const uint2 r2 = *reinterpret_cast<const uint2 *>(rb + ob);
-                                res[0] = r2.x;
-                                res[WT / 2 - 1] = r2.y;
-                            } else {
-                                res[0] = *reinterpret_cast<const uint32_t *>(rb + ob);
-                            }
+                            acc[j][s][0] += from_storage<DT>((uint16_t)(res[j][s].x & 0xffffu));
+                            acc[j][s][1] += from_storage<DT>((uint16_t)(res[j][s].x >> 16));
+                            acc[j][s][2] += from_storage<DT>((uint16_t)(res[j][s].y & 0xffffu));
+                            acc[j][s][3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
                         }
-                        uint32_t out[WT / 2];
-#pragma unroll
-                        for (int h = 0; h < WT / 2; ++h) {
-                            float v0 = acc[2 * h][s][i], v1 = acc[2 * h + 1][s][i];
-                            if (rb) {
-                                v0 += from_storage<DT>((uint16_t)(res[h] & 0xffffu));
-                                v1 += from_storage<DT>((uint16_t)(res[h] >> 16));
-                            }
-                            out[h] = pack2<DT>(clampf(v0, cl), clampf(v1, cl));
-                        }
-                        if (WT == 4) *reinterpret_cast<uint2 *>(yb + ob) = uint2{out[0], out[WT / 2 - 1]};
-                        else *reinterpret_cast<uint32_t *>(yb + ob) = out[0];
+                        uint2 out;
+                        out.x = pack2<DT>(clampf(acc[j][s][0], cl), clampf(acc[j][s][1], cl));
+                        out.y = pack2<DT>(clampf(acc[j][s][2], cl), clampf(acc[j][s][3], cl));
+                        *reinterpret_cast<uint2 *>(yb + obyte[s] + 32u * j) = out;
                     }
+                }
             }
             __syncthreads();
             bufoff ^= buf_bytes;

@@ -227,14 +227,12 @@ static void build_mfma_slab(npas_packed *p, const uint8_t *m, const uint8_t *w)
             const size_t cstride = (size_t)KH * KW; // channel stride in W[F][C][KH][KW]
             for (size_t e = 0; e < n; ++e) {
                 size_t step = e / 4, q = e % 4;
-                // row r of row tile j is filter NT r + j of the super-tile: the kernel multiplies with the
-                // activations as the row operand, and a result column then holds NT consecutive filters
                 for (int j = 0; j < d.NT; ++j)
                     for (int r = 0; r < 16; ++r) {
-                        int fl = d.NT * r + j, f = f0 + fl;
+                        int f = f0 + 16 * j + r;
                         if (f >= F) continue;
                         for (int i = 0; i < 8; ++i) {
-                            size_t wi = base[e] + (size_t)fl * fstride + (size_t)i * cstride;
+                            size_t wi = base[e] + (size_t)(16 * j + r) * fstride + (size_t)i * cstride;
                             if (m[wi]) d.wfrag[w0 + (step * d.NT + j) * 512 + (q * 16 + r) * 8 + i] = w16[wi];
                         }
                     }
