@@ -1838,12 +1838,142 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(const void *x, void *
     }
 }
 
+// 16-bit storage, C a multiple of 8: one thread owns 8 channels of kDwRows consecutive output rows
+// of one output column.  It walks down the input rows once (each input vector is loaded once per
+// thread and feeds up to three output rows), keeps the 9 tap weights of its channels in registers
+// for its whole life, and multiplies on packed pairs: dot2(x pair, weight pair with the other half
+// zeroed) adds exactly one product in fp32, with no unpacking of the activations.  Consecutive
+// lanes are consecutive 16-byte channel vectors of a pixel, then consecutive pixels of a row.
+constexpr int kDwRows = 4;
+
+struct DwArgs {
+    const void *x;
+    void *y;
+    const void *w;        // [9][C] storage type, tap-major
+    const float *bias;
+    const void *residual;
+    int N, H, W, C, Ho, Wo, act;
+    uint32_t CV, nyb, total;            // channel vectors, row blocks per image, threads
+    uint32_t div_cv, div_wo, div_nyb;   // fastdiv magics
+};
+
+template <int DT, int STRIDE>
+__global__ __launch_bounds__(256, 3) void depthwise3x3_rows_kernel(DwArgs a)
+{
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.total) return;
+    uint32_t t = fastdiv(idx, a.div_cv);
+    const uint32_t cv = idx - t * a.CV;
+    uint32_t t2 = fastdiv(t, a.div_wo);
+    const int ox = (int)(t - t2 * (uint32_t)a.Wo);
+    const uint32_t n = fastdiv(t2, a.div_nyb);
+    const int oy0 = (int)(t2 - n * a.nyb) * kDwRows;
+    const Clamp cl = clamp_of(a.act);
+    const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
+    const uint16_t *w16 = reinterpret_cast<const uint16_t *>(a.w);
+
+    uint32_t wlo[9][4], whi[9][4]; // each pair of weights with the upper / the lower one zeroed
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+        const uint4 wv = *reinterpret_cast<const uint4 *>(w16 + (size_t)tap * a.C + (size_t)cv * 8);
+        const uint32_t ws[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            wlo[tap][k] = ws[k] & 0xffffu;
+            whi[tap][k] = ws[k] & 0xffff0000u;
+        }
+    }
+    float acc[kDwRows][8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float b = a.bias ? a.bias[cv * 8 + k] : 0.f;
+#pragma unroll
+        for (int j = 0; j < kDwRows; ++j) acc[j][k] = b;
+    }
+    constexpr int NR = (kDwRows - 1) * STRIDE + 3; // input rows this thread reads
+    const int ix0 = ox * STRIDE - 1, iy0 = oy0 * STRIDE - 1;
+    const size_t img = (size_t)n * a.H;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const int iy = iy0 + r;
+        const bool rowok = iy >= 0 && iy < a.H; // zero padding above and below the image
+        uint4 xv[3];
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            const int ix = ix0 + kw;
+            const bool ok = rowok && ix >= 0 && ix < a.W;
+            xv[kw] = uint4{0u, 0u, 0u, 0u};
+            if (ok) xv[kw] = *reinterpret_cast<const uint4 *>(x16 + ((img + (size_t)iy) * a.W + (size_t)ix) * a.C + (size_t)cv * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < kDwRows; ++j) {
+            const int kh = r - j * STRIDE; // compile-time after unrolling
+            if (kh < 0 || kh > 2) continue;
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const uint32_t xs[4] = {xv[kw].x, xv[kw].y, xv[kw].z, xv[kw].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    acc[j][2 * k] = dot2acc<DT>(xs[k], wlo[kh * 3 + kw][k], acc[j][2 * k]);
+                    acc[j][2 * k + 1] = dot2acc<DT>(xs[k], whi[kh * 3 + kw][k], acc[j][2 * k + 1]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kDwRows; ++j) {
+        const int oy = oy0 + j;
+        if (oy >= a.Ho) continue;
+        const size_t yo = (((size_t)n * a.Ho + (size_t)oy) * a.Wo + (size_t)ox) * a.C + (size_t)cv * 8;
+        if (a.residual) {
+            const uint4 rv = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(a.residual) + yo);
+            const uint32_t rs[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                acc[j][2 * k] += from_storage<DT>((uint16_t)(rs[k] & 0xffffu));
+                acc[j][2 * k + 1] += from_storage<DT>((uint16_t)(rs[k] >> 16));
+            }
+        }
+        uint4 out;
+        out.x = pack2<DT>(clampf(acc[j][0], cl), clampf(acc[j][1], cl));
+        out.y = pack2<DT>(clampf(acc[j][2], cl), clampf(acc[j][3], cl));
+        out.z = pack2<DT>(clampf(acc[j][4], cl), clampf(acc[j][5], cl));
+        out.w = pack2<DT>(clampf(acc[j][6], cl), clampf(acc[j][7], cl));
+        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(a.y) + yo) = out;
+    }
+}
+
+static uint32_t magic32(uint32_t d) { return d <= 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d); }
+
 int launch_depthwise3x3(int dt, const void *x, void *y, const void *w, const float *bias, const void *residual, int N, int H,
                         int W, int C, int stride, int act, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     const int Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
     const bool vec = dt != NPAS_F32 && C % 8 == 0;
+    if (vec && (stride == 1 || stride == 2)) {
+        const uint32_t CV = (uint32_t)C / 8, nyb = (uint32_t)((Ho + kDwRows - 1) / kDwRows);
+        const double threads = (double)N * nyb * Wo * CV;
+        // the index decode divides by CV, Wo and nyb with 32-bit reciprocals: exact while index * divisor < 2^32
+        if (threads * std::max({CV, (uint32_t)Wo, nyb}) < 4294967296.0) {
+            DwArgs a{x, y, w, bias, residual, N, H, W, C, Ho, Wo, act, CV, nyb, (uint32_t)threads,
+                     magic32(CV), magic32((uint32_t)Wo), magic32(nyb)};
+            const unsigned grid = (a.total + 255u) / 256u;
+            if (dt == NPAS_BF16) {
+                if (stride == 1) hipLaunchKernelGGL((depthwise3x3_rows_kernel<NPAS_BF16, 1>), dim3(grid), dim3(256), 0, st, a);
+                else hipLaunchKernelGGL((depthwise3x3_rows_kernel<NPAS_BF16, 2>), dim3(grid), dim3(256), 0, st, a);
+            } else {
+                if (stride == 1) hipLaunchKernelGGL((depthwise3x3_rows_kernel<NPAS_F16, 1>), dim3(grid), dim3(256), 0, st, a);
+                else hipLaunchKernelGGL((depthwise3x3_rows_kernel<NPAS_F16, 2>), dim3(grid), dim3(256), 0, st, a);
+            }
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) {
+                set_error("depthwise3x3_rows launch failed: %s", hipGetErrorString(e));
+                return NPAS_E_HIP;
+            }
+            return NPAS_OK;
+        }
+    }
     const size_t total = (size_t)N * Ho * Wo * (vec ? C / 8 : C);
     const unsigned grid = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 32);
 #define NPAS_DW(DT, V) hipLaunchKernelGGL((depthwise3x3_kernel<DT, V>), dim3(grid), dim3(256), 0, st, x, y, w, bias, residual, N, H, W, C, Ho, Wo, stride, act)
