@@ -251,11 +251,48 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
 }
 
 // Which kernel a run call launches for this layer and geometry.
-enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SLAB, R_GATHER };
+enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SMALLC, R_SLAB, R_GATHER };
 
-static Route choose_route(const npas_packed *p, int N, int H, int W, int stride, int pad, SpatialRingArgs *sp)
+// Tile and patch of a small-channel launch: TH x TW = 256 output pixels with the fewest computed-but-
+// unused ones, the patch within 48 KB of LDS.  False when no tile shape fits.
+static bool plan_smallc(const npas_packed *p, int N, int H, int W, int stride, int pad, SmallCArgs *a)
+{
+    const int Ho = (H + 2 * pad - p->KH) / stride + 1, Wo = (W + 2 * pad - p->KW) / stride + 1;
+    if (Ho <= 0 || Wo <= 0) return false;
+    long best = -1;
+    for (int th = 1; th <= 256; th *= 2) {
+        const int tw = 256 / th;
+        const int ph = (th - 1) * stride + p->KH, pw = (tw - 1) * stride + p->KW;
+        const int pitch = (pw * p->C * 2 + 3) / 4 * 4 + 4;
+        if ((long)ph * pitch > 48 * 1024 || (long)ph * pw * p->C > 256 * 24) continue; // LDS, and 24 staged values per thread
+        const int ty = (Ho + th - 1) / th, tx = (Wo + tw - 1) / tw;
+        const long cost = (long)ty * tx * 4096 + std::abs(th - tw); // tiles first, then the squarer shape (smaller patch)
+        if (best < 0 || cost < best) {
+            best = cost;
+            a->TH = th; a->TW = tw; a->tilesY = ty; a->tilesX = tx; a->PH = ph; a->PW = pw; a->pitch = pitch;
+        }
+    }
+    if (best < 0) return false;
+    a->N = N; a->H = H; a->W = W; a->C = p->C; a->F = p->F; a->Ho = Ho; a->Wo = Wo;
+    a->KH = p->KH; a->KW = p->KW; a->stride = stride; a->pad = pad;
+    a->K = p->C * p->KH * p->KW; a->nsteps = p->smallc.nsteps;
+    a->nitems = (uint32_t)N * (uint32_t)(a->tilesY * a->tilesX);
+    a->div_tw = magic_div((uint32_t)a->TW);
+    a->div_kwc = magic_div((uint32_t)(p->KW * p->C));
+    a->div_rowlen = magic_div((uint32_t)(a->PW * p->C));
+    a->row2 = (a->PW * p->C + 2) / 2; // the row's values plus one of slack for an odd start, in words
+    a->div_row2 = magic_div((uint32_t)a->row2);
+    a->div_tiles = magic_div((uint32_t)(a->tilesY * a->tilesX));
+    a->div_tx = magic_div((uint32_t)a->tilesX);
+    return true;
+}
+
+static Route choose_route(const npas_packed *p, int N, int H, int W, int stride, int pad, SpatialRingArgs *sp,
+                          SmallCArgs *sc = nullptr)
 {
     if (p->fmt.variant == V_VALU_F32) return R_VALU;
+    SmallCArgs sc_local;
+    if (p->smallc.present && plan_smallc(p, N, H, W, stride, pad, sc ? sc : &sc_local)) return R_SMALLC;
     // A gather-format layer (few surviving positions) leaves the ring kernels, which multiply
     // everything, only the launches they win (measured on the 3x3 256 -> 256 rate sweep and the
     // 16 x 32-block FC layer): those above 1/8 density.
@@ -273,6 +310,7 @@ const char *route_name(const npas_packed *p, int N, int H, int W, int stride, in
     case R_VALU: return "conv_valu_f32";
     case R_POINTWISE_RING: return "pointwise_ring";
     case R_SPATIAL_RING: return "spatial_ring";
+    case R_SMALLC: return "conv_smallc_mfma";
     case R_SLAB: return "conv_slab_mfma";
     default: return "conv_gather_mfma";
     }
@@ -286,7 +324,14 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         return NPAS_E_SHAPE;
     }
     SpatialRingArgs sp;
-    const Route route = choose_route(p, N, H, W, stride, pad, &sp);
+    SmallCArgs sc;
+    const Route route = choose_route(p, N, H, W, stride, pad, &sp, &sc);
+    if (route == R_SMALLC) { // fewer than 8 input channels: whole reduction in a few MFMA steps
+        sc.x = x; sc.y = y; sc.residual = residual; sc.bias = (const float *)bias;
+        sc.wimg = p->dev.scimg;
+        sc.act = act;
+        return launch_conv_smallc(p->dtype, sc, stream);
+    }
     if (route == R_VALU) {
         ConvValuArgs a;
         a.x = (const float *)x; a.y = (float *)y; a.residual = (const float *)residual; a.bias = (const float *)bias;

@@ -1238,6 +1238,214 @@ int launch_conv_mfma(int dtype, int variant, const ConvMfmaArgs &a, unsigned gri
 }
 
 // ------------------------------------------------------------------------------
+// conv_smallc_mfma: k x k layers with fewer than 8 input channels (the stem of an image network)
+// and at most 64 filters.  The reduction index k = (kh*KW + kw)*C + c runs over the whole patch of
+// an output pixel (147 for 7 x 7 x 3), so the layer is NS = ceil(K / 32) MFMA steps and its weight
+// images (NS x 4 of 1 KB, the column operand) stay in registers for the life of a wave.  The
+// activations are the row operand: a workgroup stages the input patch of a 256-pixel output tile
+// in LDS as rows of PW*C contiguous values, and a lane gathers its 8 values of a step with eight
+// 2-byte reads at pixel base + per-lane offset (consecutive k are consecutive addresses within one
+// patch row).  Each gathered fragment feeds the four 16-filter tiles.  Result register i of tile j
+// is pixel 4q + i of the 16-pixel block, filter 4 n16 + j: a lane writes four consecutive filters
+// of a pixel, a quarter wave one contiguous 2F-byte output row.  Pruned weights are zeros in the
+// images: with so few channels every position is kept by some filter of the 64 anyway.
+// The patch of the next tile is fetched into registers (kSmallCLoads values per thread at most)
+// while the current one is multiplied: fetched inside the tile loop without that, every tile paid
+// one load latency per 256 values.  WIDE (an input row is an even number of values, so all rows
+// of a patch start at the same 4-byte phase): the patch is fetched and staged as aligned 4-byte
+// words, one value of slack in front of each LDS row when the tile starts on an odd value;
+// otherwise value by value.
+constexpr int kSmallCLoads = 24;
+
+template <int DT, int NS, bool WIDE>
+__global__ __launch_bounds__(256) void conv_smallc_mfma_kernel(SmallCArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
+    const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
+    uint16_t *lds16 = reinterpret_cast<uint16_t *>(lds);
+    const Clamp cl = clamp_of(a.act);
+
+    uint4 wreg[NS][4];
+#pragma unroll
+    for (int st = 0; st < NS; ++st)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wreg[st][j] = reinterpret_cast<const uint4 *>(a.wimg)[(st * 4 + j) * 64 + lane];
+    // byte offset of this lane's value i of step st from its pixel's patch origin, two to a
+    // register (the patch is below 64 KB); slots past K alias the last real one (their weights are zero)
+    uint32_t koff2[NS][4];
+    const uint32_t kwc = (uint32_t)(a.KW * a.C);
+#pragma unroll
+    for (int st = 0; st < NS; ++st)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t k = min((uint32_t)(32 * st + 8 * q + i), (uint32_t)a.K - 1u);
+            const uint32_t kh = fastdiv(k, a.div_kwc);
+            const uint32_t off = kh * (uint32_t)a.pitch + (k - kh * kwc) * 2u;
+            if (i & 1) koff2[st][i >> 1] |= off << 16;
+            else koff2[st][i >> 1] = off;
+        }
+    const int fcol = 4 * n16;
+    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (a.bias && fcol < a.F) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bv[j] = a.bias[fcol + j];
+    }
+    const uint32_t rowlen = (uint32_t)(a.PW * a.C), patch_elems = (uint32_t)a.PH * rowlen;
+    const uint32_t tiles_img = (uint32_t)(a.tilesY * a.tilesX);
+
+    constexpr int NPV = WIDE ? kSmallCLoads / 2 : kSmallCLoads;
+    using PV = typename std::conditional<WIDE, uint32_t, uint16_t>::type;
+    PV pv[NPV];
+    const uint32_t row2 = (uint32_t)a.row2, patch_words = (uint32_t)a.PH * row2;
+    auto fetch_patch = [&](uint32_t item) __attribute__((always_inline)) {
+        const uint32_t n = fastdiv(item, a.div_tiles), trem = item - n * tiles_img;
+        const uint32_t tyi = fastdiv(trem, a.div_tx), txi = trem - tyi * (uint32_t)a.tilesX;
+        const int iy0 = (int)tyi * a.TH * a.stride - a.pad, ixe0 = ((int)txi * a.TW * a.stride - a.pad) * a.C; // first row, first value of a row
+        const uint16_t *xn = x16 + (size_t)n * a.H * (size_t)(a.W * a.C);
+#pragma unroll
+        for (int i = 0; i < NPV; ++i) {
+            const uint32_t e = (uint32_t)tid + 256u * i;
+            pv[i] = 0; // zero padding
+            if (WIDE) {
+                const uint32_t py = fastdiv(e, a.div_row2), pd = e - py * row2;
+                const int iy = iy0 + (int)py, ixe = (ixe0 & ~1) + 2 * (int)pd; // an even value index: both of the pair in the row or neither
+                if (e < patch_words && iy >= 0 && iy < a.H && ixe >= 0 && ixe < a.W * a.C)
+                    pv[i] = (PV) * reinterpret_cast<const uint32_t *>(xn + (uint32_t)(iy * (a.W * a.C) + ixe));
+            } else {
+                const uint32_t py = fastdiv(e, a.div_rowlen), pe = e - py * rowlen;
+                const int iy = iy0 + (int)py, ixe = ixe0 + (int)pe;
+                if (e < patch_elems && iy >= 0 && iy < a.H && ixe >= 0 && ixe < a.W * a.C) pv[i] = (PV)xn[(uint32_t)(iy * (a.W * a.C) + ixe)];
+            }
+        }
+    };
+    uint32_t item = blockIdx.x;
+    if (item < a.nitems) fetch_patch(item);
+    while (item < a.nitems) {
+        const uint32_t n = fastdiv(item, a.div_tiles), trem = item - n * tiles_img;
+        const uint32_t tyi = fastdiv(trem, a.div_tx), txi = trem - tyi * (uint32_t)a.tilesX;
+        const int ty0 = (int)tyi * a.TH, tx0 = (int)txi * a.TW;
+        __syncthreads(); // the tile before has been read
+#pragma unroll
+        for (int i = 0; i < NPV; ++i) {
+            const uint32_t e = (uint32_t)tid + 256u * i;
+            if (WIDE) {
+                const uint32_t py = fastdiv(e, a.div_row2), pd = e - py * row2;
+                if (e < patch_words) reinterpret_cast<uint32_t *>(lds)[py * (uint32_t)(a.pitch >> 2) + pd] = (uint32_t)pv[i];
+            } else {
+                const uint32_t py = fastdiv(e, a.div_rowlen), pe = e - py * rowlen;
+                if (e < patch_elems) lds16[py * (uint32_t)(a.pitch >> 1) + pe] = (uint16_t)pv[i];
+            }
+        }
+        __syncthreads();
+        // WIDE: the tile's first value sits one value into its LDS rows when it is an odd one
+        const uint32_t phase2 = WIDE ? (uint32_t)((((int)txi * a.TW * a.stride - a.pad) * a.C) & 1) * 2u : 0u;
+        const uint32_t next = item + gridDim.x;
+        if (next < a.nitems) fetch_patch(next); // lands while this tile is multiplied
+#pragma unroll 1
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t m = (uint32_t)((wave * 4 + s) * 16 + n16); // this lane's operand row
+            const uint32_t ty = fastdiv(m, a.div_tw), tx = m - ty * (uint32_t)a.TW;
+            const uint8_t *pp = lds + (ty * (uint32_t)a.stride) * (uint32_t)a.pitch + (tx * (uint32_t)(a.stride * a.C)) * 2u + phase2;
+            f32x4 acc[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = f32x4{bv[j], bv[j], bv[j], bv[j]};
+#pragma unroll
+            for (int st = 0; st < NS; ++st) {
+                uint4 af;
+                uint32_t h[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    h[i] = *reinterpret_cast<const uint16_t *>(pp + ((i & 1) ? koff2[st][i >> 1] >> 16 : koff2[st][i >> 1] & 0xffffu));
+                af.x = h[0] | h[1] << 16;
+                af.y = h[2] | h[3] << 16;
+                af.z = h[4] | h[5] << 16;
+                af.w = h[6] | h[7] << 16;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = mfma16<DT>(af, wreg[st][j], acc[j]);
+            }
+            // ---- residual, clamp (activation), round, store -------------------------------------
+            const uint32_t m0 = (uint32_t)((wave * 4 + s) * 16 + 4 * q);
+            uint32_t oty = fastdiv(m0, a.div_tw), otx = m0 - oty * (uint32_t)a.TW;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (i > 0 && ++otx == (uint32_t)a.TW) { // the next pixel of the tile, row-major
+                    otx = 0;
+                    ++oty;
+                }
+                const int oy = ty0 + (int)oty, ox = tx0 + (int)otx;
+                if (oy >= a.Ho || ox >= a.Wo || fcol >= a.F) continue;
+                const size_t o = (((size_t)n * a.Ho + (size_t)oy) * a.Wo + (size_t)ox) * (size_t)a.F + (size_t)fcol;
+                float v[4] = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+                if (a.residual) {
+                    const uint2 r2 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.residual) + o);
+                    v[0] += from_storage<DT>((uint16_t)(r2.x & 0xffffu));
+                    v[1] += from_storage<DT>((uint16_t)(r2.x >> 16));
+                    v[2] += from_storage<DT>((uint16_t)(r2.y & 0xffffu));
+                    v[3] += from_storage<DT>((uint16_t)(r2.y >> 16));
+                }
+                uint2 out;
+                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
+                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o) = out;
+            }
+        }
+        item = next;
+    }
+}
+
+// Persistent workgroups, exactly as many as are resident at once (a workgroup that had to wait for
+// a free slot would start its share of the tiles when the others are done with theirs).
+template <typename K> static void launch_smallc_inst(K kern, const SmallCArgs &a, size_t lds_bytes, hipStream_t st)
+{
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds_bytes) != hipSuccess || per_cu < 1) per_cu = 1;
+    const unsigned grid = (unsigned)std::min<uint32_t>(a.nitems, 256u * (unsigned)std::min(per_cu, 4));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds_bytes, st, a);
+}
+
+template <int DT> static int launch_smallc_dt(const SmallCArgs &a, size_t lds_bytes, hipStream_t st)
+{
+    const bool wide = (a.W * a.C) % 2 == 0;
+#define NPAS_SC(N_)                                                                        \
+    case N_:                                                                               \
+        if (wide) launch_smallc_inst(conv_smallc_mfma_kernel<DT, N_, true>, a, lds_bytes, st); \
+        else launch_smallc_inst(conv_smallc_mfma_kernel<DT, N_, false>, a, lds_bytes, st);     \
+        break;
+    switch (a.nsteps) {
+        NPAS_SC(1) NPAS_SC(2) NPAS_SC(3) NPAS_SC(4) NPAS_SC(5)
+    default: set_error("conv_smallc_mfma: %d reduction steps (at most 5)", a.nsteps); return NPAS_E_SHAPE;
+    }
+#undef NPAS_SC
+    return NPAS_OK;
+}
+
+int launch_conv_smallc(int dtype, const SmallCArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds_bytes = (size_t)a.PH * a.pitch;
+    if (a.TH * a.TW != 256 || lds_bytes > 48 * 1024 || a.PH * a.PW * a.C > 256 * kSmallCLoads ||
+        a.PH * a.row2 > 128 * kSmallCLoads || a.row2 * 4 > a.pitch || a.F > 64 || a.F % 4 != 0 || a.K > 32 * a.nsteps || a.K < 1) {
+        set_error("conv_smallc_mfma: plan does not fit the kernel");
+        return NPAS_E_SHAPE;
+    }
+    int rc;
+    if (dtype == NPAS_BF16) rc = launch_smallc_dt<NPAS_BF16>(a, lds_bytes, st);
+    else if (dtype == NPAS_F16) rc = launch_smallc_dt<NPAS_F16>(a, lds_bytes, st);
+    else {
+        set_error("conv_smallc_mfma needs a 16-bit storage type");
+        return NPAS_E_DTYPE;
+    }
+    if (rc) return rc;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("conv_smallc_mfma launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+// ------------------------------------------------------------------------------
 // Fused pointwise pair: y = act2(W2 * act1(W1 * x + b1) + b2) for two 1x1 layers
 // whose intermediate tensor has no other reader (the expand -> project pair of an
 // inverted-residual bottleneck).  HBM-bound: x is read once and y written once,

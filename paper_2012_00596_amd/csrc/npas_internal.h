@@ -72,13 +72,25 @@ struct DeviceFormat {
 // Filters in blocks of 128, channels in chunks of 64, taps kh*KW + kw; every (block,
 // chunk, tap) present: the kernels walk them in that order, one ring stage each
 // (rg_ptr / rg_chunk record the chunk order for inspection).  Per (block, chunk, tap) wimg
-// holds 16 A-operand images of 1 KB: image step*8 + tile, lane 16*q + r, value i =
-// W[128 fb + 16 tile + r][64 chunk + 32 step + 8 q + i][tap] (zero where pruned or past F).
+// holds 16 MFMA operand images of 1 KB: image step*8 + tile, lane 16*q + r, value i =
+// W[128 fb + 64 (tile / 4) + 4 r + tile % 4][64 chunk + 32 step + 8 q + i][tap] (zero where pruned
+// or past F): used as the column operand, the four tiles of a 64-filter half give every result
+// column four consecutive filters.
 struct RingFormat {
     bool present = false;
     int nfb = 0, taps = 1;
     std::vector<int32_t> rg_ptr;
     std::vector<uint32_t> rg_chunk;
+    std::vector<uint16_t> wimg;
+};
+
+// ---- small-channel format: k x k layers with fewer than 8 input channels (an image stem), at
+// most 64 filters and C*KH*KW <= 160.  The whole reduction, k = (kh*KW + kw)*C + c, is padded to
+// nsteps * 32; wimg holds per step four column-operand images of 1 KB: image step*4 + j, lane
+// 16*q + r, value i = W[4 r + j][k = 32 step + 8 q + i] (zero where pruned, past F or past K).
+struct SmallCFormat {
+    bool present = false;
+    int nsteps = 0;
     std::vector<uint16_t> wimg;
 };
 
@@ -95,6 +107,7 @@ struct DeviceCopy {
     const int32_t *rg_ptr = nullptr;
     const uint32_t *rg_chunk = nullptr;
     const void *wimg = nullptr;
+    const void *scimg = nullptr; // small-channel images
     const void *zeros = nullptr; // 256 bytes of zeros
 };
 
@@ -113,6 +126,7 @@ struct npas_packed {
     // execution format
     npas::DeviceFormat fmt;
     npas::RingFormat ring;
+    npas::SmallCFormat smallc;
     npas::DeviceCopy dev;
     // launch plans already computed for this layer, by geometry (filled by the run calls)
     mutable std::mutex plan_mu;
@@ -162,6 +176,21 @@ struct ConvValuArgs {
     const float *vw;
     int nvg, VB;
     int N, H, W, C, F, Ho, Wo, KH, KW, stride, pad, act;
+};
+
+struct SmallCArgs {
+    const void *x;
+    void *y;
+    const void *residual;
+    const float *bias;
+    const void *wimg;
+    int N, H, W, C, F, Ho, Wo, KH, KW, stride, pad, act;
+    int K, nsteps;                  // reduction length C*KH*KW and its 32-deep steps
+    int TH, TW, tilesY, tilesX;     // output tile (TH*TW == 256) and tiles per image
+    int PH, PW, pitch;              // LDS patch: rows, pixels per row, bytes per row
+    int row2;                       // 4-byte words staged per patch row when rows are fetched as words
+    uint32_t nitems;                // N * tilesY * tilesX
+    uint32_t div_tw, div_kwc, div_rowlen, div_row2, div_tiles, div_tx; // fastdiv magics
 };
 
 struct RingArgs {
@@ -219,6 +248,7 @@ const char *route_name(const npas_packed *p, int N, int H, int W, int stride, in
 // Tile plan of the k x k streaming kernel (geometry fields of *a); false: use another kernel.
 bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a);
 int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream);
+int launch_conv_smallc(int dtype, const SmallCArgs &a, void *stream);
 bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
                                 int act1, int act2, uint32_t use0, uint32_t use1, void *stream);

@@ -295,6 +295,28 @@ static void build_ring(npas_packed *p, const uint8_t *m, const uint8_t *w)
     r.rg_ptr[r.nfb] = (int32_t)r.rg_chunk.size();
 }
 
+// Small-channel format (see npas_internal.h): the stem of an image network has 3 input channels,
+// too few for 8-channel slabs; its whole reduction fits a handful of MFMA steps instead.
+static void build_smallc(npas_packed *p, const uint8_t *m, const uint8_t *w)
+{
+    SmallCFormat &sc = p->smallc;
+    const int F = p->F, C = p->C, T = p->KH * p->KW, K = C * T;
+    sc.present = true;
+    sc.nsteps = (K + 31) / 32;
+    sc.wimg.assign((size_t)sc.nsteps * 4 * 512, 0);
+    const uint16_t *w16 = reinterpret_cast<const uint16_t *>(w);
+    for (int step = 0; step < sc.nsteps; ++step)
+        for (int j = 0; j < 4; ++j)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int i = 0; i < 8; ++i) {
+                    const int r = lane & 15, q = lane >> 4, f = 4 * r + j, k = 32 * step + 8 * q + i;
+                    if (f >= F || k >= K) continue;
+                    const int tap = k / C, c = k % C;
+                    const size_t wi = ((size_t)f * C + c) * T + tap;
+                    if (m[wi]) sc.wimg[((size_t)(step * 4 + j) * 64 + lane) * 8 + i] = w16[wi];
+                }
+}
+
 static void build_valu_f32(npas_packed *p, const uint8_t *m, const uint8_t *w)
 {
     (void)m;
@@ -341,7 +363,7 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         // times the operand-fetch cost per kept position of the slab path; it pays once
         // fewer than a quarter of a tile's positions survive, and it is the only path for
         // channel counts that are not a multiple of 8 or filter counts that are not a multiple of 4.
-        const char *force = getenv("NPAS_FORCE_VARIANT"); // "gather" | "slab" | "noring": testing aid
+        const char *force = getenv("NPAS_FORCE_VARIANT"); // "gather" | "slab" | "noring" | "nosmallc": testing aid
         const bool slab_ok = p->C % 8 == 0 && p->F % 4 == 0;
         p->fmt.density = union_density(p, mask_full.data());
         bool gather = !slab_ok || p->fmt.density < 0.25;
@@ -354,6 +376,9 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         if (p->C % 64 == 0 && p->F % 4 == 0 && (double)((p->F + 127) / 128) * p->C * p->KH * p->KW * 256.0 < 256e6 &&
             !(force && strcmp(force, "noring") == 0))
             build_ring(p, mask_full.data(), (const uint8_t *)w_host);
+        if (p->C < 8 && p->F <= 64 && p->F % 4 == 0 && p->C * p->KH * p->KW <= 160 && p->KH * p->KW > 1 &&
+            !(force && strcmp(force, "nosmallc") == 0))
+            build_smallc(p, mask_full.data(), (const uint8_t *)w_host);
     }
     return NPAS_OK;
 }
@@ -383,6 +408,7 @@ int upload(npas_packed *p)
     size_t o_vp = place(blob, d.vg_ptr), o_vf = place(blob, d.vg_f0), o_vk = place(blob, d.vkent),
            o_vw = place(blob, d.vw);
     size_t o_rp = place(blob, p->ring.rg_ptr), o_rc = place(blob, p->ring.rg_chunk), o_ri = place(blob, p->ring.wimg);
+    size_t o_sc = place(blob, p->smallc.wimg);
     blob.resize((blob.size() + 255) / 256 * 256 + 256);
     void *ptr = nullptr;
     hipError_t e = hipMalloc(&ptr, blob.size());
@@ -410,6 +436,7 @@ int upload(npas_packed *p)
     p->dev.rg_ptr = (const int32_t *)(b + o_rp);
     p->dev.rg_chunk = (const uint32_t *)(b + o_rc);
     p->dev.wimg = b + o_ri;
+    p->dev.scimg = b + o_sc;
     p->dev.zeros = b + blob.size() - 256; // the blob ends with 256 zero bytes
     return NPAS_OK;
 }

@@ -255,6 +255,22 @@ def test_fc_with_rows_and_columns_pruned_inside_blocks(npas, torch):
     assert err <= 1e-2
 
 
+# Fewer than 8 input channels (an image stem): the whole-reduction kernel.  Ragged tiles, stride 2 with
+# padding 3, one to five reduction steps, filter counts below 64, more tiles than workgroups.
+SMALLC = [
+    ("stem_7x7_s2", 2, 37, 41, 3, 64, 7, 7, 2, 3, 8, 3, 3, dtypes.BF16, 1, False, True),
+    ("c1_3x3_f16", 3, 19, 23, 1, 16, 3, 3, 1, 1, 4, 1, 2, dtypes.F16, 1, True, True),
+    ("c4_5x5_f36", 2, 20, 18, 4, 36, 5, 5, 1, 2, 4, 4, 2, dtypes.BF16, 2, True, False),
+    ("c3_3x3_s2_f8", 1, 9, 9, 3, 8, 3, 3, 2, 1, 8, 3, 2, dtypes.BF16, 0, False, False),
+    ("c3_3x3_many_tiles", 13, 128, 128, 3, 8, 3, 3, 1, 1, 8, 3, 2, dtypes.BF16, 1, False, True),
+]
+
+
+@pytest.mark.parametrize("case", SMALLC, ids=[c[0] for c in SMALLC])
+def test_small_channel_kernel(npas, torch, case):
+    _run_edge_case(npas, torch, case, expect_kernel="conv_smallc_mfma")
+
+
 def test_block_punched_5x5(npas, torch):
     _run_edge_case(npas, torch, ("kernel_5x5", 2, 17, 19, 16, 24, 5, 5, 1, 2, 8, 4, 3, dtypes.BF16, 1, False, True))
     _run_edge_case(npas, torch, ("kernel_5x5_wide", 2, 12, 12, 64, 72, 5, 5, 1, 2, 8, 4, 2, dtypes.BF16, 0, True, False))
