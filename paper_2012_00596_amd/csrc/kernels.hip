@@ -1761,6 +1761,33 @@ __global__ __launch_bounds__(256) void global_avgpool_kernel(const void *x, void
     st_act<DT>(y, (size_t)i, (float)(s / (double)HW));
 }
 
+// 16-bit storage, C a multiple of 4: a thread averages 4 channels (8-byte loads, a wave reads 512
+// contiguous bytes of a pixel), seven loads in flight, fp32 sum (exact to ~1e-6 for a map of a few
+// thousand 16-bit values, far inside the storage type's rounding).
+template <int DT>
+__global__ __launch_bounds__(256) void global_avgpool_vec4_kernel(const void *x, void *y, int N, int HW, int C)
+{
+    const int C4 = C >> 2;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= N * C4) return;
+    const int n = i / C4, c4 = i - n * C4;
+    const uint2 *xp = reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(x) + (size_t)n * HW * C) + c4;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll 7
+    for (int p = 0; p < HW; ++p) {
+        const uint2 v = xp[(size_t)p * C4];
+        s0 += from_storage<DT>((uint16_t)(v.x & 0xffffu));
+        s1 += from_storage<DT>((uint16_t)(v.x >> 16));
+        s2 += from_storage<DT>((uint16_t)(v.y & 0xffffu));
+        s3 += from_storage<DT>((uint16_t)(v.y >> 16));
+    }
+    const float r = 1.0f / (float)HW;
+    uint2 out;
+    out.x = pack2<DT>(s0 * r, s1 * r);
+    out.y = pack2<DT>(s2 * r, s3 * r);
+    reinterpret_cast<uint2 *>(y)[i] = out;
+}
+
 // ------------------------------------------------------------------------------
 // fused_inverted_residual: y = act3(W3 . act2(DW3x3(act1(W1 . x))) + x) for the cascade 1x1 -> 3x3
 // depthwise (stride 1) -> 1x1 of the search space (section 5.1.1) when the two wide tensors
@@ -2228,7 +2255,11 @@ int launch_avgpool(const void *x, void *y, int N, int H, int W, int C, int dt, v
 {
     hipStream_t st = (hipStream_t)stream;
     unsigned grid = (unsigned)((N * C + 255) / 256);
-    if (dt == NPAS_F32) hipLaunchKernelGGL(global_avgpool_kernel<NPAS_F32>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
+    if (dt != NPAS_F32 && C % 4 == 0) {
+        grid = (unsigned)((N * (C / 4) + 255) / 256);
+        if (dt == NPAS_BF16) hipLaunchKernelGGL(global_avgpool_vec4_kernel<NPAS_BF16>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
+        else hipLaunchKernelGGL(global_avgpool_vec4_kernel<NPAS_F16>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
+    } else if (dt == NPAS_F32) hipLaunchKernelGGL(global_avgpool_kernel<NPAS_F32>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
     else if (dt == NPAS_BF16) hipLaunchKernelGGL(global_avgpool_kernel<NPAS_BF16>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
     else hipLaunchKernelGGL(global_avgpool_kernel<NPAS_F16>, dim3(grid), dim3(256), 0, st, x, y, N, H * W, C);
     hipError_t e = hipGetLastError();
