@@ -31,6 +31,17 @@ __device__ __forceinline__ uint32_t fastdiv(uint32_t n, uint32_t magic)
     return magic ? __umulhi(n, magic) : n; // magic = ceil(2^32 / d), 0 for d == 1
 }
 
+// Streaming (non-temporal) 8-byte accesses for tensors that are written or read once per launch and
+// are far larger than the L2: they leave the cache to the operands that are reused.
+__device__ __forceinline__ void store_stream8(void *p, uint2 v)
+{
+    __builtin_nontemporal_store(__builtin_bit_cast(unsigned long long, v), reinterpret_cast<unsigned long long *>(p));
+}
+__device__ __forceinline__ uint2 load_stream8(const void *p)
+{
+    return __builtin_bit_cast(uint2, __builtin_nontemporal_load(reinterpret_cast<const unsigned long long *>(p)));
+}
+
 __device__ __forceinline__ float act_apply(float v, int act)
 {
     if (act == NPAS_ACT_RELU) return fmaxf(v, 0.0f);
@@ -796,7 +807,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
         for (int t = 0; t < nst; ++t) {
             __builtin_amdgcn_s_barrier(); // this stage has landed; everyone is done with the stage before
             asm volatile("" ::: "memory");
-            if (rb && t == nst - 1) { // residual: asked for before the last multiply, used after it
+            if (rb && t == 0) { // residual: asked for at the item's first stage, used after its last
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
                     uint32_t ob = obase;
@@ -804,7 +815,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const bool ok = (uint32_t)(16 * s + i) < rows_left;
-                        res[s][i] = *reinterpret_cast<const uint2 *>(rb + (ok ? ob + (uint32_t)(16 * s + i) * (uint32_t)a.F * 2u : 0u));
+                        res[s][i] = load_stream8(rb + (ok ? ob + (uint32_t)(16 * s + i) * (uint32_t)a.F * 2u : 0u));
                     }
                 }
             }
@@ -843,7 +854,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
                 uint2 out;
                 out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
                 out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                *reinterpret_cast<uint2 *>(yb + obase + (uint32_t)(16 * s + i) * (uint32_t)a.F * 2u) = out;
+                store_stream8(yb + obase + (uint32_t)(16 * s + i) * (uint32_t)a.F * 2u, out);
             }
         if (c_item + nwg >= nitems) break;
         c_item += nwg;
