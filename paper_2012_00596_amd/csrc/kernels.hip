@@ -41,6 +41,11 @@ __device__ __forceinline__ uint2 load_stream8(const void *p)
 {
     return __builtin_bit_cast(uint2, __builtin_nontemporal_load(reinterpret_cast<const unsigned long long *>(p)));
 }
+__device__ __forceinline__ uint4 load_stream16(const void *p)
+{
+    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+    return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)));
+}
 
 __device__ __forceinline__ float act_apply(float v, int act)
 {
@@ -1523,7 +1528,7 @@ __device__ __forceinline__ void fpp_body(const FppArgs &a, int b0, int n16, int 
 #pragma unroll
     for (int k = 0; k < CNT; ++k) {
         const int pix = min((b0 + k) * 16 + n16, a.M - 1);
-        xin[k] = *reinterpret_cast<const uint4 *>(x16 + (size_t)pix * a.C1 + cq);
+        xin[k] = load_stream16(x16 + (size_t)pix * a.C1 + cq);
     }
     __builtin_amdgcn_sched_barrier(0); // keep every load above the first use (memory-level parallelism)
     // A layer-2 tile that keeps nothing in a chunk has an all-zero image there; it is multiplied
@@ -1555,7 +1560,7 @@ __device__ __forceinline__ void fpp_body(const FppArgs &a, int b0, int n16, int 
             uint2 o;
             o.x = pack2<DT>(clampf(d2[u][0], c2), clampf(d2[u][1], c2));
             o.y = pack2<DT>(clampf(d2[u][2], c2), clampf(d2[u][3], c2));
-            *reinterpret_cast<uint2 *>(y16 + (size_t)pix * a.F2 + fst[u]) = o;
+            store_stream8(y16 + (size_t)pix * a.F2 + fst[u], o); // written once, read by nobody in this launch
         }
     }
 }
