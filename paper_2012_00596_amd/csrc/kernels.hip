@@ -41,6 +41,11 @@ __device__ __forceinline__ uint2 load_stream8(const void *p)
 {
     return __builtin_bit_cast(uint2, __builtin_nontemporal_load(reinterpret_cast<const unsigned long long *>(p)));
 }
+__device__ __forceinline__ void store_stream16(void *p, uint4 v)
+{
+    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+    __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4 *>(p));
+}
 __device__ __forceinline__ uint4 load_stream16(const void *p)
 {
     typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
@@ -1964,7 +1969,7 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
             uint2 o;
             o.x = pack2<DT>(clampf(v[0], cl3), clampf(v[1], cl3));
             o.y = pack2<DT>(clampf(v[2], cl3), clampf(v[3], cl3));
-            *reinterpret_cast<uint2 *>(y16 + pix * a.F3 + f) = o;
+            store_stream8(y16 + pix * a.F3 + f, o);
         }
     }
 }
@@ -2190,7 +2195,7 @@ __global__ __launch_bounds__(256, 3) void depthwise3x3_rows_kernel(DwArgs a)
         out.y = pack2<DT>(clampf(acc[j][2], cl), clampf(acc[j][3], cl));
         out.z = pack2<DT>(clampf(acc[j][4], cl), clampf(acc[j][5], cl));
         out.w = pack2<DT>(clampf(acc[j][6], cl), clampf(acc[j][7], cl));
-        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(a.y) + yo) = out;
+        store_stream16(reinterpret_cast<uint16_t *>(a.y) + yo, out);
     }
 }
 
