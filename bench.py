@@ -39,6 +39,7 @@ def main():
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--stack", type=int, default=0, metavar="CFG",
                     help="time npas_run_stack end to end on config CFG (2, 5, or 6 = inverted-residual block) at --batch")
+    ap.add_argument("--graph", action="store_true", help="with --stack: capture the call into a HIP graph and time replays")
     ap.add_argument("--sweep", type=str, default="", choices=["", "rate", "block"],
                     help="rate: 3x3 conv 56x56x256->256 over pruning schemes and rates; block: residual stack over block sizes at 6x")
     ap.add_argument("--only", type=str, default="", help="with --per-layer: comma-separated layer indices to run")
@@ -200,8 +201,10 @@ def main():
     print(json.dumps(out))
 
 
-def time_stack(w, reps, torch, npas, helpers, fuse=True):
-    """(us per npas_run_stack call, launches, workspace bytes) for workload w."""
+def time_stack(w, reps, torch, npas, helpers, fuse=True, graph=False):
+    """(us per npas_run_stack call, launches, workspace bytes) for workload w.  graph: the call is
+    captured once into a HIP graph (the library allocates nothing and sets nothing during a run) and
+    the replays are timed: what a serving loop at small batch would do about the launch gaps."""
     N, H, W, C = w.x_shape
     packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
     st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W,
@@ -218,10 +221,22 @@ def time_stack(w, reps, torch, npas, helpers, fuse=True):
     for _ in range(5):
         st.run(x, y, N, ws, wsb, stream)
     torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        st.run(x, y, N, ws, wsb, stream)
-    e1.record()
+    if graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            st.run(x, y, N, ws, wsb, torch.cuda.current_stream().cuda_stream)
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+    else:
+        e0.record()
+        for _ in range(reps):
+            st.run(x, y, N, ws, wsb, stream)
+        e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) * 1e3 / reps, st.num_launches(), wsb
 
@@ -232,10 +247,11 @@ def stack_mode(args, torch, npas, helpers, configs):
     from workloads import sweeps
     w = {2: lambda: configs.config2(batch=args.batch), 5: lambda: configs.config5(batch=args.batch),
          6: lambda: sweeps.inverted_residual_block(batch=args.batch)}[cfg]()
-    us, launches, wsb = time_stack(w, args.reps, torch, npas, helpers, fuse=not args.no_fuse)
+    us, launches, wsb = time_stack(w, args.reps, torch, npas, helpers, fuse=not args.no_fuse, graph=args.graph)
     flop = 2.0 * w.dense_macs()
-    print("# config %d %s batch %d: npas_run_stack %.1f us per call, %d launches, workspace %.1f MB, %.1f TFLOP/s dense-equivalent, %.1f images/s"
-          % (cfg, w.name, w.x_shape[0], us, launches, wsb / 2**20, flop / us / 1e6, w.x_shape[0] / us * 1e6))
+    print("# config %d %s batch %d: npas_run_stack%s %.1f us per call, %d launches, workspace %.1f MB, %.1f TFLOP/s dense-equivalent, %.1f images/s"
+          % (cfg, w.name, w.x_shape[0], " (HIP graph replay)" if args.graph else "", us, launches, wsb / 2**20, flop / us / 1e6,
+             w.x_shape[0] / us * 1e6))
 
 
 def sweep_mode(args, torch, npas, helpers):
@@ -306,7 +322,10 @@ def per_layer(args, torch, npas, helpers, configs):
         wbytes = packed.info()["device_bytes"] if packed else 0
         if L.kind == "dwconv":
             wbytes = L.C * 9 * 2
-        abytes = (nin + nout + (nout if L.res >= 0 else 0)) * esz + wbytes
+        nin_alg = nin
+        if L.kind == "conv" and L.KH == 1 and L.KW == 1 and L.stride > 1:
+            nin_alg = nout // L.F * L.C  # a strided 1x1 layer needs only the input pixels it samples
+        abytes = (nin_alg + nout + (nout if L.res >= 0 else 0)) * esz + wbytes
         nsets = max(1, min(8, -(-600 * 2**20 // max(1, (nin + nout) * esz))))
         td = torch.float32 if w.dtype == 0 else torch.int16
         xs = [torch.randint(-3, 3, (nin,), device="cuda").to(td) if w.dtype else torch.randn(nin, device="cuda")

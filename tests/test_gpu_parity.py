@@ -225,6 +225,37 @@ def test_inverted_residual_block_layerwise_and_stack(npas, torch, stride):
         assert err <= 2e-2          # three roundings of bf16 activations compound
 
 
+def test_run_stack_in_a_hip_graph_replays_like_the_eager_call(npas, torch):
+    """npas_run_stack allocates nothing and clears nothing during a run, so a caller may capture it.
+    Several replays, with eager work and synchronisations in between, each against the eager result."""
+    print("run_stack captured in a HIP graph", flush=True)
+    w = configs.config5(batch=2, HW=32, width=16, blocks=(1, 1, 1, 1))
+    packed = [pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
+    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), w.x_shape[1], w.x_shape[2],
+                    npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL)
+    N = w.x_shape[0]
+    shapes = {0: w.x_shape}
+    for i, L in enumerate(w.layers):
+        shapes[i + 1] = helpers.out_shape(L, shapes[L.src])
+    wsb = st.workspace_bytes(N)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    x = to_dev(w.x_store, torch)
+    y_eager = new_dev(shapes[len(w.layers)], w.dtype, torch, fill=0x7FC1)
+    st.run(x, y_eager, N, ws, wsb)           # also the first call: one-time kernel attributes are set here
+    torch.cuda.synchronize()
+    y_graph = new_dev(shapes[len(w.layers)], w.dtype, torch, fill=0x7FC1)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        st.run(x, y_graph, N, ws, wsb, torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        y_graph.fill_(0x7FC1)                # eager work between the replays
+        ws.random_(0, 255)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), f"replay {rep} differs from the eager call"
+
+
 def test_depthwise_handle_is_rejected_by_the_convolution_call(npas, torch):
     ws, _ = dtypes.quantize(prng.normal(18, 1, 16 * 9).reshape(16, 3, 3), dtypes.BF16)
     p = npas.pack_depthwise3x3(ws, dtypes.BF16)
