@@ -357,6 +357,15 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
             a.small = 1;
             a.nptiles = (a.M + 63) / 64;
             a.nfb = (p->F + 63) / 64;
+        } else {
+            // 128 x 128 items (a little more than half the time of a 256 x 128 one: the weights are fetched
+            // per 128 pixels) when they divide over the 256 workgroups with fewer idle slots
+            const long big = (long)a.nptiles * a.nfb, med = (long)((a.M + 127) / 128) * a.nfb;
+            const double t_big = (double)((big + 255) / 256), t_med = 0.56 * (double)((med + 255) / 256);
+            if (t_med < 0.75 * t_big) {
+                a.small = 2;
+                a.nptiles = (a.M + 127) / 128;
+            }
         }
         a.act = act;
         a.flat = stride == 1;

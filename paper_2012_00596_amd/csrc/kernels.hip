@@ -625,6 +625,7 @@ template <int PW_, int FW_, int XW_, int WW_, int D_> struct PointwiseCfg {
 };
 using PointwiseBig = PointwiseCfg<4, 2, 3, 1, 3>;
 using PointwiseSmall = PointwiseCfg<1, 1, 2, 2, 8>;
+using PointwiseMedium = PointwiseCfg<2, 2, 2, 1, 4>; // 128 x 128 tiles, 4-stage ring: half-size items for layers whose 256 x 128 items divide badly over the CUs
 
 __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
 {
@@ -1197,15 +1198,17 @@ template <int DT, typename Cfg> static void launch_pointwise_cfg(const RingArgs 
     hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::kThreads), Cfg::kLdsBytes, st, a);
 }
 
-// a.small selects the 64 x 64 configuration; a.nptiles / a.nfb count that configuration's tiles.
+// a.small: 0 = 256 x 128 tiles, 1 = 64 x 64, 2 = 128 x 128; a.nptiles / a.nfb count that configuration's tiles.
 int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     if (dtype == NPAS_BF16) {
-        if (a.small) launch_pointwise_cfg<NPAS_BF16, PointwiseSmall>(a, st);
+        if (a.small == 1) launch_pointwise_cfg<NPAS_BF16, PointwiseSmall>(a, st);
+        else if (a.small == 2) launch_pointwise_cfg<NPAS_BF16, PointwiseMedium>(a, st);
         else launch_pointwise_cfg<NPAS_BF16, PointwiseBig>(a, st);
     } else if (dtype == NPAS_F16) {
-        if (a.small) launch_pointwise_cfg<NPAS_F16, PointwiseSmall>(a, st);
+        if (a.small == 1) launch_pointwise_cfg<NPAS_F16, PointwiseSmall>(a, st);
+        else if (a.small == 2) launch_pointwise_cfg<NPAS_F16, PointwiseMedium>(a, st);
         else launch_pointwise_cfg<NPAS_F16, PointwiseBig>(a, st);
     } else {
         set_error("pointwise_ring needs a 16-bit storage type");

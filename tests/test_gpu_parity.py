@@ -92,6 +92,8 @@ EDGE = [
     ("fp32_wide_group", 1, 5, 5, 8, 24, 1, 1, 1, 0, 24, 8, 2, dtypes.F32, 0, False, False),
     ("large_C_many_chunks", 1, 7, 7, 600, 130, 1, 1, 1, 0, 8, 4, 2, dtypes.BF16, 1, True, False),
     ("kernel_5x3", 1, 30, 30, 8, 16, 5, 3, 1, 2, 4, 4, 2, dtypes.BF16, 0, False, False),
+    # 100 items of 256 x 128 but 196 of 128 x 128: the pointwise ring's half-size tiles, ragged last tile
+    ("pointwise_half_size_tiles", 127, 7, 7, 128, 512, 1, 1, 1, 0, 8, 4, 3, dtypes.BF16, 1, True, True),
 ]
 
 
