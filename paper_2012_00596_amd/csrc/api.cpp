@@ -180,7 +180,7 @@ static int check_run(const npas_packed *p, const void *x, void *y, int N, int H,
 // plan with the best ratio of useful to computed columns, then the smaller halo.  Returns
 // false when no plan exists or the launch would leave most of the chip idle (the slab
 // kernel's smaller tiles serve those cases better).
-static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, bool force, SpatialRingArgs *a);
+static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, bool force, int maxpix, SpatialRingArgs *a);
 
 // The search is a few thousand candidates; its result depends only on the shapes, so it is
 // kept per shape (launches of a stack repeat the same few shapes).
@@ -197,14 +197,17 @@ bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRin
     if (it == cache.end()) {
         SpatialRingArgs g;
         std::memset(&g, 0, sizeof g);
-        const bool ok = plan_spatial_search(p, N, H, W, pad, force != 0, &g);
+        // 256-pixel tiles; if those would leave most of the chip idle, 128-pixel tiles (half the multiplying waves)
+        bool ok = plan_spatial_search(p, N, H, W, pad, false, 256, &g);
+        if (!ok) ok = plan_spatial_search(p, N, H, W, pad, false, 128, &g);
+        if (!ok && force) ok = plan_spatial_search(p, N, H, W, pad, true, 256, &g);
         it = cache.emplace(key, std::make_pair(ok, g)).first;
     }
     *a = it->second.second;
     return it->second.first;
 }
 
-static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, bool force, SpatialRingArgs *a)
+static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, bool force, int maxpix, SpatialRingArgs *a)
 {
     const int KH = p->KH, KW = p->KW, T = KH * KW;
     const int Ho = H + 2 * pad - KH + 1, Wo = W + 2 * pad - KW + 1;
@@ -214,16 +217,16 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     double best = -1.0;
     int bNI = 0, bTH = 0, bTW = 0;
     for (int TH = 1; TH <= std::min(Ho, 255); ++TH)
-        for (int TW = 1; TW <= std::min(Wo, 255) && TH * TW <= 256; ++TW) {
+        for (int TW = 1; TW <= std::min(Wo, 255) && TH * TW <= maxpix; ++TW) {
             const int PH = TH + KH - 1, PW = TW + KW - 1;
             const long ty = (Ho + TH - 1) / TH, tx = (Wo + TW - 1) / TW;
-            const int maxNI = std::min(N, 256 / (TH * TW));
+            const int maxNI = std::min(N, maxpix / (TH * TW));
             for (int NI = 1; NI <= maxNI; ++NI) {
                 const int npb = (NI * PH * PW + 7) / 8;
                 if (npb > max_npb) break;
                 const long tn = (N + NI - 1) / NI;
                 const int depth = std::min(6, (lds_total - 2048 * npb) / wstage);
-                const double eff = (double)N * Ho * Wo / ((double)tn * ty * tx * 256.0);
+                const double eff = (double)N * Ho * Wo / ((double)tn * ty * tx * (double)maxpix);
                 const double halo = (double)(NI * PH * PW) / (double)(NI * TH * TW);
                 const double score = eff - 0.02 * halo + 0.02 * (depth - 3);
                 if (score > best) {
@@ -235,6 +238,7 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     if (best < 0) return false;
     a->N = N; a->H = H; a->W = W; a->C = p->C; a->F = p->F; a->Ho = Ho; a->Wo = Wo;
     a->KH = KH; a->KW = KW; a->pad = pad;
+    a->pg = maxpix / 64;
     a->NI = bNI; a->TH = bTH; a->TW = bTW; a->PH = bTH + KH - 1; a->PW = bTW + KW - 1;
     a->tilesN = (N + bNI - 1) / bNI; a->tilesY = (Ho + bTH - 1) / bTH; a->tilesX = (Wo + bTW - 1) / bTW;
     a->nfb = p->ring.nfb;
@@ -243,7 +247,7 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     a->div_tw = magic_div((uint32_t)bTW); a->div_pw = magic_div((uint32_t)a->PW);
     a->div_thtw = magic_div((uint32_t)(bTH * bTW)); a->div_phpw = magic_div((uint32_t)(a->PH * a->PW));
     const long items = (long)a->tilesN * a->tilesY * a->tilesX * a->nfb;
-    const double eff = (double)N * Ho * Wo / ((double)a->tilesN * a->tilesY * a->tilesX * 256.0);
+    const double eff = (double)N * Ho * Wo / ((double)a->tilesN * a->tilesY * a->tilesX * (double)maxpix);
     // worth it when the launch fills most of the chip and neither the 256 pixel columns nor the
     // 128 filter rows of a workgroup are mostly padding (measured against the slab kernel)
     const double fill = (double)p->F / (128.0 * a->nfb);

@@ -896,7 +896,9 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
 // of the stage about to be multiplied; after the barrier the slot (or patch buffer) of the
 // stage before is free to be refilled.
 constexpr uint32_t kSpatialWStage = 16384;
-constexpr int kSpatialThreads = 16 * 64;
+// PG pixel groups of 64 x 2 filter groups of 64 multiply: 8 waves on a 256-pixel tile, or 4 on a 128-pixel
+// tile (launches whose 256-pixel tiles would leave most CUs without one).
+constexpr int spatial_threads(int pg) { return (2 * pg + 8) * 64; }
 constexpr int kSpatialFetchWaves = 4; // of each kind
 
 struct SpatialItem {
@@ -917,9 +919,11 @@ __device__ __forceinline__ SpatialItem spatial_item(const SpatialRingArgs &a, ui
     return it;
 }
 
-template <int DT>
-__global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRingArgs a)
+template <int DT, int PG>
+__global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(SpatialRingArgs a)
 {
+    constexpr int NCW = 2 * PG; // multiplying waves
+    constexpr int kSpatialThreads = spatial_threads(PG);
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lbase = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -944,9 +948,9 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
     }
     __syncthreads();
 
-    if (wave >= 8 + kSpatialFetchWaves) {
+    if (wave >= NCW + kSpatialFetchWaves) {
         // ---- patch fetch ------------------------------------------------------------------
-        const int wl = wave - 8 - kSpatialFetchWaves;
+        const int wl = wave - NCW - kSpatialFetchWaves;
         const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
         const uint8_t *zb = reinterpret_cast<const uint8_t *>(a.zeros) + (uint32_t)(lane & 7) * 16u;
         const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u;
@@ -998,9 +1002,9 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
         return;
     }
 
-    if (wave >= 8) {
+    if (wave >= NCW) {
         // ---- weight stage fetch: images wl*4 .. wl*4+3 of every stage ------------------------
-        const int wl = wave - 8;
+        const int wl = wave - NCW;
         constexpr int kImgs = 16 / kSpatialFetchWaves;
         const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)(wl * kImgs) * 1024u + (uint32_t)lane * 16u;
         uint32_t p_item = c_item, p_slot = 0;
@@ -1149,31 +1153,34 @@ __global__ __launch_bounds__(kSpatialThreads) void spatial_ring_kernel(SpatialRi
     }
 }
 
+template <int DT, int PG> static void launch_spatial_inst(const SpatialRingArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
+{
+    auto kern = spatial_ring_kernel<DT, PG>;
+    static bool attr_done = false; // one flag per instantiation
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(spatial_threads(PG)), lds_bytes, st, a);
+}
+
 int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     const size_t lds_bytes = (size_t)2 * a.npb * 1024 + (size_t)a.depth * kSpatialWStage + 2048 + (size_t)a.npb * 32;
     const long items = (long)a.tilesN * a.tilesY * a.tilesX * a.nfb;
     const unsigned grid = (unsigned)std::min<long>(items, 256);
-    static bool attr_done[2] = {false, false};
-    if (lds_bytes > 160 * 1024 || a.depth < 3 || a.depth > 6 || a.NI * a.TH * a.TW > 256 || a.TH > 255 || a.TW > 255 || a.PH > 1023 || a.PW > 1023) {
+    if (lds_bytes > 160 * 1024 || a.depth < 3 || a.depth > 6 || (a.pg != 4 && a.pg != 2) || a.NI * a.TH * a.TW > 64 * a.pg ||
+        a.TH > 255 || a.TW > 255 || a.PH > 1023 || a.PW > 1023) {
         set_error("spatial_ring: tile plan does not fit the kernel");
         return NPAS_E_SHAPE;
     }
     if (dtype == NPAS_BF16) {
-        auto kern = spatial_ring_kernel<NPAS_BF16>;
-        if (!attr_done[0]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            attr_done[0] = true;
-        }
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kSpatialThreads), lds_bytes, st, a);
+        if (a.pg == 4) launch_spatial_inst<NPAS_BF16, 4>(a, grid, lds_bytes, st);
+        else launch_spatial_inst<NPAS_BF16, 2>(a, grid, lds_bytes, st);
     } else if (dtype == NPAS_F16) {
-        auto kern = spatial_ring_kernel<NPAS_F16>;
-        if (!attr_done[1]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            attr_done[1] = true;
-        }
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kSpatialThreads), lds_bytes, st, a);
+        if (a.pg == 4) launch_spatial_inst<NPAS_F16, 4>(a, grid, lds_bytes, st);
+        else launch_spatial_inst<NPAS_F16, 2>(a, grid, lds_bytes, st);
     } else {
         set_error("spatial_ring needs a 16-bit storage type");
         return NPAS_E_DTYPE;

@@ -220,7 +220,8 @@ struct SpatialRingArgs {
     const void *zeros;          // >= 16 bytes of zeros on the device (source of padding pixels)
     int N, H, W, C, F, Ho, Wo;
     int KH, KW, pad;            // stride 1
-    int NI, TH, TW;             // tile: NI images x TH x TW output pixels (<= 256)
+    int pg;                     // pixel groups of 64 a workgroup multiplies: 4 (256-pixel tiles) or 2 (128)
+    int NI, TH, TW;             // tile: NI images x TH x TW output pixels (<= 64 pg)
     int PH, PW;                 // patch of one image of the tile
     int tilesN, tilesY, tilesX, nfb;
     int npb;                    // 1 KB blocks (8 pixels) of one patch chunk

@@ -151,6 +151,13 @@ def test_spatial_streaming_kernel(npas, torch, case, monkeypatch):
     _run_edge_case(npas, torch, case, expect_kernel="spatial_ring")
 
 
+def test_spatial_streaming_kernel_half_size_tiles(npas, torch):
+    """104 tiles of 256 pixels would leave most CUs idle; 256 tiles of 128 pixels (two 7x7 images each) do not:
+    the streaming kernel with half the multiplying waves, chosen by the library itself."""
+    _run_edge_case(npas, torch, ("sp_7x7_half_tiles", 128, 7, 7, 64, 512, 3, 3, 1, 1, 8, 4, 3, dtypes.BF16, 1, True, True),
+                   expect_kernel="spatial_ring")
+
+
 def test_config4_pattern_small_streaming_kernel(npas, torch, monkeypatch):
     monkeypatch.setenv("NPAS_FORCE_VARIANT", "spatial")
     print("config4 small, streaming kernel", flush=True)
