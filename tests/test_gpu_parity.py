@@ -372,6 +372,28 @@ def test_config2_run_stack_end_to_end(npas, torch, flags):
     assert err <= 1e-2
 
 
+def test_fp16_storage_through_the_fused_kernels_and_the_pointwise_ring(npas, torch):
+    """Every 16-bit kernel is instantiated for fp16 as well as bf16: the fused pair, the fused inverted-residual
+    block and the streaming 1x1 kernel on fp16 tensors (tolerance of R9 for one layer, doubled for fused layers)."""
+    from workloads import sweeps
+    print("fp16: fused pair", flush=True)
+    w = configs.config2(batch=2, HW=23, dtype=dtypes.F16)
+    got, st = _run_stack_gpu(npas, torch, w, 1)
+    rounded, _ = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+    err = rel_err(got, rounded[-1])
+    print(f"  launches={st.num_launches()} err={err:.3e}", flush=True)
+    assert st.num_launches() == 1 and err <= 2 * TOL[dtypes.F16]
+    print("fp16: fused inverted-residual block", flush=True)
+    w = sweeps.inverted_residual_block(batch=2, HW=13, dtype=dtypes.F16)
+    got, st = _run_stack_gpu(npas, torch, w, 3)
+    rounded, _ = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+    err = rel_err(got, rounded[-1])
+    print(f"  launches={st.num_launches()} err={err:.3e}", flush=True)
+    assert st.num_launches() == 1 and err <= 3 * TOL[dtypes.F16]
+    _run_edge_case(npas, torch, ("fp16_pointwise_ring", 3, 9, 11, 128, 136, 1, 1, 1, 0, 8, 4, 3, dtypes.F16, 2, True, True),
+                   expect_kernel="pointwise_ring")
+
+
 def test_config5_run_stack_end_to_end(npas, torch):
     print("config5 reduced run_stack", flush=True)
     w = configs.config5(batch=2, HW=64, width=16)
