@@ -438,6 +438,43 @@ def test_full_size_config4_sampled_images(npas, torch):
         assert err <= 1e-2
 
 
+def test_config5_batch128_sampled_images(npas, torch):
+    """The 50-layer stack's layers in the launch configuration the per-layer report times (batch 128: big tiles,
+    both tile sizes of the streaming kernels, the stem kernel), each on a seeded input of its real shape, checked
+    on three of the 128 images (a layer's output for one image depends on that image only)."""
+    w = configs.config5(batch=128)
+    shapes = {0: w.x_shape}
+    for i, L in enumerate(w.layers):
+        shapes[i + 1] = helpers.out_shape(L, shapes[L.src])
+    want = {"stem7x7": "conv_smallc_mfma", "s0b0_c3": "pointwise_ring", "s1b0_sc": "pointwise_ring", "s1b1_c2": "spatial_ring",
+            "s2b1_c3": "pointwise_ring", "s2b0_c2": "conv_slab_mfma", "s3b1_c1": "pointwise_ring", "s3b1_c2": "spatial_ring"}
+    seen = set()
+    for i, L in enumerate(w.layers):
+        if L.name not in want:
+            continue
+        seen.add(L.name)
+        in_shape, oshape = shapes[L.src], shapes[i + 1]
+        N, H, W, C = in_shape
+        print(f"config5 batch 128 layer {i} {L.name} in={in_shape}", flush=True)
+        xs, xe = dtypes.quantize(prng.normal(500 + i, 1, int(np.prod(in_shape))).reshape(in_shape), w.dtype)
+        rs = re = None
+        if L.res >= 0:
+            rs, re = dtypes.quantize(prng.normal(500 + i, 2, int(np.prod(oshape))).reshape(oshape), w.dtype)
+        p = pack_layer(npas, L, w.dtype)
+        assert npas.conv2d_kernel_name(p, N, H, W, L.stride, L.pad) == want[L.name]
+        y = run_layer_gpu(npas, torch, L, p, to_dev(xs, torch), in_shape, w.dtype, None if rs is None else to_dev(rs, torch))
+        got = from_dev(y, w.dtype).reshape(oshape)
+        for n in (0, 77, 127):
+            ref = oracle.round_to(oracle.conv2d_masked(xe[n:n + 1], L.w_exact, L.mask, L.stride, L.pad, None,
+                                                       None if re is None else re[n:n + 1], L.act), w.dtype)
+            err = rel_err(got[n:n + 1], ref)
+            print(f"  image {n} err={err:.3e}", flush=True)
+            assert err <= TOL[w.dtype]
+        del xs, xe, rs, re, y, got
+        torch.cuda.empty_cache()
+    assert seen == set(want)
+
+
 def test_pools(npas, torch):
     # C = 24 takes the 8-channel vector path for 16-bit storage, C = 5 the scalar one
     for dtype, C in ((dtypes.BF16, 24), (dtypes.F16, 24), (dtypes.BF16, 5), (dtypes.F32, 24)):
