@@ -598,7 +598,7 @@ template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid
 // Tile (PW * 64) pixels x (FW * 64) filters.  Stage = 64 channels: 128 B per pixel of
 // activations + FW * 8 weight images of 1 KB.  A load writes 64 lanes x 16 B lane-linearly
 // into one 1 KB LDS block.  Activations are stored unpadded with an XOR swizzle: 16-byte
-// vector cv of pixel p sits at p*128 + (cv ^ (p & 7))*16, so that the MFMA B-operand reads
+// vector cv of pixel p sits at p*128 + (cv ^ (p & 7))*16, so that the MFMA operand reads
 // (16 consecutive pixels, same cv) spread over the banks.
 //
 // Waves 0 .. PW*FW-1 multiply (PW pixel groups x FW filter groups, 64 x 64 outputs each), the
@@ -609,10 +609,11 @@ template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid
 // The multiplying waves issue no such loads; their residual / bias loads and their stores are
 // ordinary code the compiler waits for exactly.  One s_barrier per stage, executed by all.
 //
-// Two configurations: 256 x 128 tiles with a 3-stage ring (throughput: most bytes in flight
-// per CU, most reuse of the weights), and 64 x 64 tiles with an 8-stage ring for launches
-// that would leave most CUs without a tile (small batches): more, smaller items, and a whole
-// layer's channel loop in flight at once instead of one load latency per stage.
+// Three configurations: 256 x 128 tiles with a 3-stage ring (throughput: most bytes in flight
+// per CU, most reuse of the weights); 64 x 64 tiles with an 8-stage ring for launches that
+// would leave most CUs without a tile (small batches): more, smaller items, and a whole
+// layer's channel loop in flight at once instead of one load latency per stage; 128 x 128
+// tiles with a 4-stage ring in between, when the 256 x 128 items divide badly over the CUs.
 template <int PW_, int FW_, int XW_, int WW_, int D_> struct PointwiseCfg {
     static constexpr int PW = PW_, FW = FW_, XW = XW_, WW = WW_, D = D_;
     static constexpr int kComputeWaves = PW * FW;
