@@ -1663,7 +1663,27 @@ __global__ __launch_bounds__(256) void conv_valu_f32_kernel(ConvValuArgs a)
     const int k0 = a.vg_ptr[vg], k1 = a.vg_ptr[vg + 1];
     const int by = (int)oy * a.stride - a.pad, bx = (int)ox * a.stride - a.pad;
     const float *xn = a.x + (size_t)n * a.H * a.W * a.C;
-    for (int k = k0; k < k1; ++k) {
+    // eight positions at a time: their entries and activations are all asked for before the first
+    // multiply-add (one at a time, every position cost one load latency); the sums keep their order
+    constexpr int U = 8;
+    int k = k0;
+    for (; k + U <= k1; k += U) {
+        float xv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t ent = a.vkent[k + u];
+            const int iy = by + (int)(ent >> 24), ix = bx + (int)((ent >> 16) & 255u);
+            xv[u] = 0.0f;
+            if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) xv[u] = xn[(size_t)(iy * a.W + ix) * a.C + (ent & 0xffffu)];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float *w = a.vw + (size_t)(k + u) * VB;
+#pragma unroll
+            for (int j = 0; j < VB; ++j) acc[j] = fma((double)w[j], (double)xv[u], acc[j]);
+        }
+    }
+    for (; k < k1; ++k) {
         const uint32_t ent = a.vkent[k];
         const int iy = by + (int)(ent >> 24), ix = bx + (int)((ent >> 16) & 255u);
         float xv = 0.0f;
