@@ -633,7 +633,7 @@ __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                  :
                  : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr)
-                 : "memory");
+                 : "memory"); // m0 is reserved: the compiler keeps nothing in it across statements
 }
 
 // "At most n vector-memory operations of this wave outstanding" for a wave-uniform n < 64
@@ -1430,8 +1430,21 @@ __global__ __launch_bounds__(256) void conv_smallc_mfma_kernel(SmallCArgs a)
 // a free slot would start its share of the tiles when the others are done with theirs).
 template <typename K> static void launch_smallc_inst(K kern, const SmallCArgs &a, size_t lds_bytes, hipStream_t st)
 {
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds_bytes) != hipSuccess || per_cu < 1) per_cu = 1;
+    // the occupancy query is kept per instantiation and LDS size (a stack repeats the same launch)
+    static std::mutex mu;
+    static size_t known_lds = (size_t)-1;
+    static int known_per_cu = 1;
+    int per_cu;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (known_lds != lds_bytes) {
+            int v = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, kern, 256, lds_bytes) != hipSuccess || v < 1) v = 1;
+            known_lds = lds_bytes;
+            known_per_cu = v;
+        }
+        per_cu = known_per_cu;
+    }
     const unsigned grid = (unsigned)std::min<uint32_t>(a.nitems, 256u * (unsigned)std::min(per_cu, 4));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds_bytes, st, a);
 }
