@@ -625,7 +625,7 @@ template <int PW_, int FW_, int XW_, int WW_, int D_> struct PointwiseCfg {
     static_assert(D >= 3 && kXLoads * (D - 1) <= 63 && kWLoads * (D - 1) <= 63, "a wave can have 63 loads in flight");
 };
 using PointwiseBig = PointwiseCfg<4, 2, 3, 1, 3>;
-using PointwiseSmall = PointwiseCfg<1, 1, 2, 2, 8>;
+using PointwiseSmall = PointwiseCfg<1, 1, 4, 4, 8>;
 using PointwiseMedium = PointwiseCfg<2, 2, 2, 1, 4>; // 128 x 128 tiles, 4-stage ring: half-size items for layers whose 256 x 128 items divide badly over the CUs
 
 __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
