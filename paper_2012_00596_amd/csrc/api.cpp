@@ -255,7 +255,7 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
 }
 
 // Which kernel a run call launches for this layer and geometry.
-enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SMALLC, R_SLAB, R_GATHER };
+enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SMALLC, R_SMALLM, R_SLAB, R_GATHER };
 
 // Tile and patch of a small-channel launch: TH x TW = 256 output pixels with the fewest computed-but-
 // unused ones, the patch within 48 KB of LDS.  False when no tile shape fits.
@@ -304,6 +304,14 @@ static Route choose_route(const npas_packed *p, int N, int H, int W, int stride,
     const bool ring_ok = p->ring.present && (!gather || p->fmt.density >= 0.125);
     if (ring_ok && p->KH == 1 && p->KW == 1 && pad == 0) return R_POINTWISE_RING;
     if (ring_ok && stride == 1 && (p->KH > 1 || p->KW > 1) && plan_spatial(p, N, H, W, pad, sp)) return R_SPATIAL_RING;
+    // few output pixels (small batch, late stages): the tiled kernels would run a handful of workgroups, each
+    // walking the whole reduction alone; split the reduction over the waves of many small workgroups instead
+    if (ring_ok && (p->KH > 1 || p->KW > 1)) {
+        const long Ho = (H + 2 * pad - p->KH) / stride + 1, Wo = (W + 2 * pad - p->KW) / stride + 1;
+        const char *fv = std::getenv("NPAS_FORCE_VARIANT");
+        const long limit = fv && std::strcmp(fv, "smallm") == 0 ? (1L << 30) : 1024;
+        if (Ho > 0 && Wo > 0 && (long)N * Ho * Wo <= limit) return R_SMALLM;
+    }
     return gather ? R_GATHER : R_SLAB;
 }
 
@@ -315,6 +323,7 @@ const char *route_name(const npas_packed *p, int N, int H, int W, int stride, in
     case R_POINTWISE_RING: return "pointwise_ring";
     case R_SPATIAL_RING: return "spatial_ring";
     case R_SMALLC: return "conv_smallc_mfma";
+    case R_SMALLM: return "conv_smallm_mfma";
     case R_SLAB: return "conv_slab_mfma";
     default: return "conv_gather_mfma";
     }
@@ -335,6 +344,19 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         sc.wimg = p->dev.scimg;
         sc.act = act;
         return launch_conv_smallc(p->dtype, sc, stream);
+    }
+    if (route == R_SMALLM) {
+        SmallMArgs a;
+        a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias; a.wimg = p->dev.wimg;
+        a.N = N; a.H = H; a.W = W; a.C = p->C; a.F = p->F;
+        a.Ho = (H + 2 * pad - p->KH) / stride + 1; a.Wo = (W + 2 * pad - p->KW) / stride + 1;
+        a.KH = p->KH; a.KW = p->KW; a.stride = stride; a.pad = pad; a.act = act;
+        a.M = N * a.Ho * a.Wo;
+        a.nptiles = (a.M + 63) / 64;
+        a.nimg = p->ring.nfb * 8;
+        a.div_howo = magic_div((uint32_t)(a.Ho * a.Wo)); a.div_wo = magic_div((uint32_t)a.Wo);
+        a.div_kw = magic_div((uint32_t)p->KW); a.div_T2 = magic_div((uint32_t)(2 * p->KH * p->KW));
+        return launch_conv_smallm(p->dtype, a, stream);
     }
     if (route == R_VALU) {
         ConvValuArgs a;

@@ -1491,6 +1491,143 @@ int launch_conv_smallc(int dtype, const SmallCArgs &a, void *stream)
 }
 
 // ------------------------------------------------------------------------------
+// conv_smallm_mfma: k x k layers (C a multiple of 64, ring-format weights) on few output pixels:
+// batch 1, the late stages of a network.  The tiled kernels then run a handful of workgroups that
+// each walk the whole reduction (C*KH*KW / 32 MFMA steps) alone, one load latency after the
+// other.  Here a workgroup owns 64 output pixels x 16 filters (one weight image per step) and its
+// sixteen waves split the reduction: a wave takes a contiguous run of steps, fetches each step's
+// weight image (1 KB, coalesced) and its four activation fragments (lane = pixel n16 of a block,
+// 8 channels = 16 bytes at the tap's input pixel; zero padding by predicate) straight from
+// memory, three steps in flight, and accumulates 4 MFMA tiles.  The sixteen partial sums meet in
+// LDS; waves 0-3 add them up (always in the same order), add bias / residual, clamp, round and
+// store.  Stride and kernel size are free (every address is formed per lane).
+struct SmallMPix {
+    int n, iy0, ix0; // image and input coordinates of tap (0, 0); n < 0: no such pixel
+};
+
+template <int DT>
+__global__ __launch_bounds__(1024) void conv_smallm_mfma_kernel(SmallMArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
+    const uint32_t ptile = blockIdx.x % (uint32_t)a.nptiles, img = blockIdx.x / (uint32_t)a.nptiles;
+    const uint32_t fb = img >> 3, tile8 = img & 7u;
+    if ((int)(fb * 128u + (tile8 >> 2) * 64u) >= a.F) return; // an image of padding filters only (whole workgroup)
+    const int T = a.KH * a.KW, nch = a.C >> 6, S = nch * T * 2;
+    const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
+    const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (size_t)fb * nch * T * 16384u + tile8 * 1024u + (uint32_t)lane * 16u;
+
+    SmallMPix px[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const uint32_t m = ptile * 64u + (uint32_t)(s * 16 + n16);
+        const uint32_t n = fastdiv(m, a.div_howo), r = m - n * (uint32_t)(a.Ho * a.Wo);
+        const uint32_t oy = fastdiv(r, a.div_wo), ox = r - oy * (uint32_t)a.Wo;
+        px[s].n = m < (uint32_t)a.M ? (int)n : -1;
+        px[s].iy0 = (int)oy * a.stride - a.pad;
+        px[s].ix0 = (int)ox * a.stride - a.pad;
+    }
+    f32x4 acc[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int st0 = wave * S / 16, st1 = (wave + 1) * S / 16; // this wave's steps
+    constexpr int NB = 3;                                      // steps in flight
+    for (int sb = st0; sb < st1; sb += NB) {
+        uint4 wf[NB], xf[NB][4];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int st = sb + u;
+            if (st < st1) { // wave-uniform
+                // step st = (chunk * T + tap) * 2 + half
+                const uint32_t ct = (uint32_t)st >> 1, hs = (uint32_t)st & 1u;
+                const uint32_t cc = fastdiv(ct * 2u, a.div_T2), tap = ct - cc * (uint32_t)T;
+                const uint32_t kh = fastdiv(tap, a.div_kw), kw = tap - kh * (uint32_t)a.KW;
+                wf[u] = *reinterpret_cast<const uint4 *>(wb + (size_t)ct * 16384u + hs * 8192u);
+                const uint32_t coff = cc * 64u + hs * 32u + 8u * (uint32_t)q;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int iy = px[s].iy0 + (int)kh, ix = px[s].ix0 + (int)kw;
+                    const bool ok = px[s].n >= 0 && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
+                    xf[u][s] = uint4{0u, 0u, 0u, 0u};
+                    if (ok) xf[u][s] = *reinterpret_cast<const uint4 *>(x16 + ((size_t)(px[s].n * a.H + iy) * a.W + ix) * a.C + coff);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            if (sb + u < st1) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) acc[s] = mfma16<DT>(wf[u], xf[u][s], acc[s]);
+            }
+        }
+    }
+    // ---- the sixteen partial sums meet in LDS: [wave][block][lane] ----------------------------------
+    f32x4 *red = reinterpret_cast<f32x4 *>(lds);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) red[(wave * 4 + s) * 64 + lane] = acc[s];
+    __syncthreads();
+    if (wave >= 4) return;
+    f32x4 sum = red[wave * 64 + lane]; // block s = wave
+    for (int w = 1; w < 16; ++w) {
+        const f32x4 t = red[(w * 4 + wave) * 64 + lane];
+        sum[0] += t[0]; sum[1] += t[1]; sum[2] += t[2]; sum[3] += t[3];
+    }
+    // row 4q + i of the image is filter 128 fb + 64 (tile8 / 4) + 4 (4q + i) + tile8 % 4; column n16 is pixel 16 wave + n16
+    const uint32_t m = ptile * 64u + (uint32_t)(wave * 16 + n16);
+    if (m >= (uint32_t)a.M) return;
+    const Clamp cl = clamp_of(a.act);
+    uint16_t *y16 = reinterpret_cast<uint16_t *>(a.y);
+    const uint16_t *r16 = reinterpret_cast<const uint16_t *>(a.residual);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int f = (int)(fb * 128u + (tile8 >> 2) * 64u + 4u * (uint32_t)(4 * q + i) + (tile8 & 3u));
+        if (f >= a.F) continue;
+        float v = sum[i];
+        if (a.bias) v += a.bias[f];
+        const size_t o = (size_t)m * a.F + (size_t)f;
+        if (r16) v += from_storage<DT>(r16[o]);
+        y16[o] = to_storage<DT>(clampf(v, cl));
+    }
+}
+
+int launch_conv_smallm(int dtype, const SmallMArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds_bytes = 16 * 4 * 64 * 16;
+    const long grid = (long)a.nptiles * a.nimg;
+    if (a.C % 64 != 0 || a.M <= 0 || grid > 0x7fffffffL || (double)a.N * a.H * a.W * a.C >= 2147483648.0) {
+        set_error("conv_smallm_mfma: unsupported shape");
+        return NPAS_E_SHAPE;
+    }
+    static bool attr_done[2] = {false, false};
+    if (dtype == NPAS_BF16) {
+        auto kern = conv_smallm_mfma_kernel<NPAS_BF16>;
+        if (!attr_done[0]) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            attr_done[0] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1024), lds_bytes, st, a);
+    } else if (dtype == NPAS_F16) {
+        auto kern = conv_smallm_mfma_kernel<NPAS_F16>;
+        if (!attr_done[1]) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            attr_done[1] = true;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1024), lds_bytes, st, a);
+    } else {
+        set_error("conv_smallm_mfma needs a 16-bit storage type");
+        return NPAS_E_DTYPE;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("conv_smallm_mfma launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+// ------------------------------------------------------------------------------
 // Fused pointwise pair: y = act2(W2 * act1(W1 * x + b1) + b2) for two 1x1 layers
 // whose intermediate tensor has no other reader (the expand -> project pair of an
 // inverted-residual bottleneck).  HBM-bound: x is read once and y written once,

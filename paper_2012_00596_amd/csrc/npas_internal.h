@@ -193,6 +193,20 @@ struct SmallCArgs {
     uint32_t div_tw, div_kwc, div_rowlen, div_row2, div_tiles, div_tx; // fastdiv magics
 };
 
+// k x k layer on few output pixels (small batch, small maps): see conv_smallm_mfma_kernel
+struct SmallMArgs {
+    const void *x;
+    void *y;
+    const void *residual;
+    const float *bias;
+    const void *wimg;               // ring-format images
+    int N, H, W, C, F, Ho, Wo, KH, KW, stride, pad, act;
+    int M;                          // output pixels N*Ho*Wo
+    int nptiles;                    // 64-pixel tiles
+    int nimg;                       // 16-filter images: 8 per 128-filter block
+    uint32_t div_howo, div_wo, div_kw, div_T2; // fastdiv magics (Ho*Wo, Wo, KW, 2*KH*KW)
+};
+
 struct RingArgs {
     const void *x;
     void *y;
@@ -250,6 +264,7 @@ const char *route_name(const npas_packed *p, int N, int H, int W, int stride, in
 bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a);
 int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream);
 int launch_conv_smallc(int dtype, const SmallCArgs &a, void *stream);
+int launch_conv_smallm(int dtype, const SmallMArgs &a, void *stream);
 bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
                                 int act1, int act2, uint32_t use0, uint32_t use1, void *stream);

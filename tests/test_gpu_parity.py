@@ -311,6 +311,22 @@ def test_small_channel_kernel(npas, torch, case):
     _run_edge_case(npas, torch, case, expect_kernel="conv_smallc_mfma")
 
 
+# Few output pixels (batch 1, late stages): the kernel that splits the reduction over the waves of a workgroup.
+# Stride 2, non-square kernels, filter counts off the 16- and 128-filter grids, ragged pixel tiles, fp16.
+SMALLM = [
+    ("sm_7x7_512", 1, 7, 7, 512, 512, 3, 3, 1, 1, 8, 4, 3, dtypes.BF16, 1, False, True),
+    ("sm_stride2_ragged", 3, 15, 14, 128, 72, 3, 3, 2, 1, 8, 4, 3, dtypes.BF16, 0, True, True),
+    ("sm_5x3_fp16", 2, 12, 17, 64, 200, 5, 3, 1, 2, 4, 4, 2, dtypes.F16, 2, True, False),
+    ("sm_one_step_per_wave", 1, 9, 9, 64, 64, 3, 3, 1, 1, 8, 4, 2, dtypes.BF16, 1, False, False),
+    ("sm_more_waves_than_steps", 1, 5, 5, 64, 40, 2, 2, 1, 0, 8, 4, 2, dtypes.BF16, 0, False, False),
+]
+
+
+@pytest.mark.parametrize("case", SMALLM, ids=[c[0] for c in SMALLM])
+def test_small_pixel_count_kernel(npas, torch, case):
+    _run_edge_case(npas, torch, case, expect_kernel="conv_smallm_mfma")
+
+
 def test_block_punched_5x5(npas, torch):
     _run_edge_case(npas, torch, ("kernel_5x5", 2, 17, 19, 16, 24, 5, 5, 1, 2, 8, 4, 3, dtypes.BF16, 1, False, True))
     _run_edge_case(npas, torch, ("kernel_5x5_wide", 2, 12, 12, 64, 72, 5, 5, 1, 2, 8, 4, 2, dtypes.BF16, 0, True, False))
