@@ -302,7 +302,13 @@ static Route choose_route(const npas_packed *p, int N, int H, int W, int stride,
     // 16 x 32-block FC layer): those above 1/8 density.
     const bool gather = p->fmt.variant == V_MFMA_GATHER;
     const bool ring_ok = p->ring.present && (!gather || p->fmt.density >= 0.125);
-    if (ring_ok && p->KH == 1 && p->KW == 1 && pad == 0) return R_POINTWISE_RING;
+    if (ring_ok && p->KH == 1 && p->KW == 1 && pad == 0) {
+        // up to 256 output pixels (batch 1 from the 14 x 14 stage on, FC layers) the kernel that splits the
+        // reduction over a workgroup's waves is faster than the ring's smallest tiles (measured layer by layer)
+        const long Ho1 = (H - 1) / stride + 1, Wo1 = (W - 1) / stride + 1;
+        if ((long)N * Ho1 * Wo1 <= 256) return R_SMALLM;
+        return R_POINTWISE_RING;
+    }
     if (ring_ok && stride == 1 && (p->KH > 1 || p->KW > 1) && plan_spatial(p, N, H, W, pad, sp)) return R_SPATIAL_RING;
     // few output pixels (small batch, late stages): the tiled kernels would run a handful of workgroups, each
     // walking the whole reduction alone; split the reduction over the waves of many small workgroups instead
