@@ -251,7 +251,10 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     // worth it when the launch fills most of the chip and neither the 256 pixel columns nor the
     // 128 filter rows of a workgroup are mostly padding (measured against the slab kernel)
     const double fill = (double)p->F / (128.0 * a->nfb);
-    return force || (items >= 192 && eff >= 0.6 && fill >= 0.75);
+    // with 128-pixel tiles a long reduction (many stages per item) pays from fewer items on: the slab kernel's
+    // workgroups would walk it with one step of lookahead (512 -> 512 at 7 x 7, batch 32: 64 items, 64 -> 47 us)
+    const bool enough = items >= 192 || (maxpix == 128 && items >= 48 && items * (p->C / 64) * T >= 3000);
+    return force || (enough && eff >= 0.6 && fill >= 0.75);
 }
 
 // Which kernel a run call launches for this layer and geometry.
