@@ -318,8 +318,10 @@ static Route choose_route(const npas_packed *p, int N, int H, int W, int stride,
     if (ring_ok && (p->KH > 1 || p->KW > 1)) {
         const long Ho = (H + 2 * pad - p->KH) / stride + 1, Wo = (W + 2 * pad - p->KW) / stride + 1;
         const char *fv = std::getenv("NPAS_FORCE_VARIANT");
-        const long limit = fv && std::strcmp(fv, "smallm") == 0 ? (1L << 30) : 1024;
-        if (Ho > 0 && Wo > 0 && (long)N * Ho * Wo <= limit) return R_SMALLM;
+        const bool force = fv && std::strcmp(fv, "smallm") == 0;
+        // ... or little work altogether (a 56 x 56 x 64 -> 64 layer at batch 1: 5.8 against 8.8 us)
+        const double macs = (double)N * Ho * Wo * p->F * p->C * p->KH * p->KW;
+        if (Ho > 0 && Wo > 0 && (force || (long)N * Ho * Wo <= 1024 || macs <= 200e6)) return R_SMALLM;
     }
     return gather ? R_GATHER : R_SLAB;
 }

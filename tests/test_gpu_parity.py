@@ -319,6 +319,7 @@ SMALLM = [
     ("sm_5x3_fp16", 2, 12, 17, 64, 200, 5, 3, 1, 2, 4, 4, 2, dtypes.F16, 2, True, False),
     ("sm_one_step_per_wave", 1, 9, 9, 64, 64, 3, 3, 1, 1, 8, 4, 2, dtypes.BF16, 1, False, False),
     ("sm_more_waves_than_steps", 1, 5, 5, 64, 40, 2, 2, 1, 0, 8, 4, 2, dtypes.BF16, 0, False, False),
+    ("sm_many_pixels_little_work", 1, 41, 39, 64, 64, 3, 3, 1, 1, 8, 4, 3, dtypes.BF16, 1, True, True),
 ]
 
 
