@@ -404,6 +404,20 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
                 a.nptiles = (a.M + 127) / 128;
             }
         }
+        // Items of equal size in whole rounds: with the number of rounds the full tiles need, as many pixel
+        // tiles as fill those rounds, each of P <= tile height pixels (784 items of 256 pixels on 256
+        // workgroups are 4 rounds, the last all but empty; 1008 items of 200 pixels are 4 rounds of 200).
+        const int th = a.small == 1 ? 64 : a.small == 2 ? 128 : 256;
+        a.P = th;
+        if (a.small != 1 && !std::getenv("NPAS_NO_BALANCE")) {
+            const long rounds = ((long)a.nptiles * a.nfb + 255) / 256;
+            const long want = rounds * 256 / a.nfb; // pixel tiles that fill the rounds
+            if (want > a.nptiles) {
+                const int pp = (int)((a.M + want - 1) / want);
+                a.P = std::max(th / 2, std::min(th, (pp + 7) / 8 * 8));
+                a.nptiles = (a.M + a.P - 1) / a.P;
+            }
+        }
         a.act = act;
         a.flat = stride == 1;
         a.div_howo = magic_div((uint32_t)(a.Ho * a.Wo));

@@ -683,7 +683,8 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
     if (wave >= NC + WW) {
         // ---- activation fetch: blocks wl, wl + XW, wl + 2 XW, ... (8 pixels each) of every stage ----
         const int wl = wave - NC - WW;
-        const int nld = (Cfg::kXBlocks - wl + XW - 1) / XW; // this wave's loads per stage
+        const int nblocks = (a.P + 7) >> 3;                 // 8-pixel blocks of a tile that hold pixels of it
+        const int nld = max(0, (nblocks - wl + XW - 1) / XW); // this wave's loads per stage
         const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
         const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u; // which 16-byte vector of its pixel this lane fetches
         auto in_byte = [&](uint32_t m) __attribute__((always_inline)) -> uint32_t { // byte offset in x of output pixel m's input pixel
@@ -700,7 +701,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
             const PointwiseItem pi = pointwise_item(nfb, p_item);
             p_t = 0;
 #pragma unroll
-            for (int i = 0; i < Cfg::kXLoads; ++i) ppix[i] = in_byte(pi.ptile * (uint32_t)(PW * 64) + (uint32_t)((wl + XW * i) * 8 + (lane >> 3))) + pcv;
+            for (int i = 0; i < Cfg::kXLoads; ++i) ppix[i] = in_byte(pi.ptile * (uint32_t)a.P + (uint32_t)((wl + XW * i) * 8 + (lane >> 3))) + pcv;
         };
         producer_item();
         auto produce = [&]() __attribute__((always_inline)) { // always issues its nld loads; past the end it repeats the last stage
@@ -807,9 +808,10 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
         // is pixel 16s + 4q + i, filter 4 n16 + j.  A lane therefore owns 4 consecutive filters
         // of a pixel, and the 16 lanes of a quarter wave one whole 128-byte run of its row.
         const int fcol = (int)it.fb * (FW * 64) + wf * 64 + 4 * n16;
-        const uint32_t m0 = it.ptile * (uint32_t)(PW * 64) + (uint32_t)(wp * 64 + 4 * q);
+        const uint32_t ml = (uint32_t)(wp * 64 + 4 * q), m0 = it.ptile * (uint32_t)a.P + ml; // first pixel: in the tile, of all
         const uint32_t obase = (m0 * (uint32_t)a.F + (uint32_t)fcol) * 2u; // byte offset of (pixel m0, filter fcol)
-        const uint32_t rows_left = fcol < a.F && m0 < (uint32_t)a.M ? (uint32_t)a.M - m0 : 0u; // valid pixels from m0 on
+        // valid pixels from m0 on: to the end of the tile's P pixels (rows past them hold other tiles' pixels or stale data) and of the map
+        const uint32_t rows_left = fcol < a.F && m0 < (uint32_t)a.M && ml < (uint32_t)a.P ? min((uint32_t)a.M - m0, (uint32_t)a.P - ml) : 0u;
         f32x4 acc[4][4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)

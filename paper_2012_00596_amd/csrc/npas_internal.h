@@ -219,6 +219,7 @@ struct RingArgs {
     int C, F;
     int H, W, Ho, Wo, stride;   // input / output geometry (stride > 1: subsampled input pixels)
     int nptiles, nfb;           // pixel tiles and filter blocks of the chosen configuration
+    int P;                      // pixels per tile actually used (<= the configuration's tile height): evens out the items over the workgroups
     int small;                  // 0: 256 x 128 tiles, 3-stage ring; 1: 64 x 64 tiles, 8-stage ring
     int act;
     int flat;                   // 1: stride 1, input pixel index == output pixel index

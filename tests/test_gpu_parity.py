@@ -94,6 +94,10 @@ EDGE = [
     ("kernel_5x3", 1, 30, 30, 8, 16, 5, 3, 1, 2, 4, 4, 2, dtypes.BF16, 0, False, False),
     # 100 items of 256 x 128 but 196 of 128 x 128: the pointwise ring's half-size tiles, ragged last tile
     ("pointwise_half_size_tiles", 127, 7, 7, 128, 512, 1, 1, 1, 0, 8, 4, 3, dtypes.BF16, 1, True, True),
+    # pixel tiles evened out over the workgroups: 196 items of 256 pixels become 252 of 200 (the fourth
+    # pixel group of a tile holds 8 pixels), and 100 of 256 become 200 of 128 (two pixel groups empty)
+    ("pointwise_tiles_of_200_pixels", 1, 112, 112, 64, 512, 1, 1, 1, 0, 8, 4, 3, dtypes.BF16, 1, True, True),
+    ("pointwise_tiles_of_128_pixels", 2, 80, 80, 64, 256, 1, 1, 1, 0, 8, 4, 2, dtypes.BF16, 2, True, False),
 ]
 
 
