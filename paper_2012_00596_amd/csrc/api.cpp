@@ -257,8 +257,74 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     return force || (enough && eff >= 0.6 && fill >= 0.75);
 }
 
+// Tile plan of the resident-weights k x k kernel (at most 64 filters, all weight stages in LDS): the
+// spatial ring's search with the LDS that the weights leave, scored by useful columns times how evenly the
+// items fill rounds of 256 workgroups.  False when the weights do not fit or the launch is too small.
+bool plan_resident(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a)
+{
+    static std::mutex mu;
+    static std::map<std::array<int, 8>, std::pair<bool, SpatialRingArgs>> cache;
+    const std::array<int, 8> key = {p->KH, p->KW, p->C, p->F, N, H, W, pad};
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(key);
+    if (it != cache.end()) {
+        *a = it->second.second;
+        return it->second.first;
+    }
+    SpatialRingArgs g;
+    std::memset(&g, 0, sizeof g);
+    const int KH = p->KH, KW = p->KW, T = KH * KW;
+    const int Ho = H + 2 * pad - KH + 1, Wo = W + 2 * pad - KW + 1;
+    bool ok = T >= 2 && p->C % 64 == 0 && p->F <= 64 && p->ring.present && Ho > 0 && Wo > 0;
+    const int nst = ok ? (p->C / 64) * T : 0;
+    double best = -1e30;
+    int bNI = 0, bTH = 0, bTW = 0;
+    if (ok && spatial_resident_lds_bytes(8, nst) <= 160 * 1024) {
+        for (int TH = 1; TH <= std::min(Ho, 255); ++TH)
+            for (int TW = 1; TW <= std::min(Wo, 255) && TH * TW <= 256; ++TW) {
+                const int PH = TH + KH - 1, PW = TW + KW - 1;
+                const long ty = (Ho + TH - 1) / TH, tx = (Wo + TW - 1) / TW;
+                const int maxNI = std::min(N, 256 / (TH * TW));
+                for (int NI = 1; NI <= maxNI; ++NI) {
+                    const int npb = (NI * PH * PW + 7) / 8;
+                    if (spatial_resident_lds_bytes(npb, nst) > 160 * 1024) break;
+                    const long items = (long)((N + NI - 1) / NI) * ty * tx;
+                    const double eff = (double)N * Ho * Wo / ((double)items * 256.0);
+                    const double rounds = (double)items / (double)((items + 255) / 256 * 256);
+                    const double halo = (double)(PH * PW) / (double)(TH * TW);
+                    const double score = eff * rounds - 0.02 * halo;
+                    if (score > best) {
+                        best = score;
+                        bNI = NI; bTH = TH; bTW = TW;
+                    }
+                }
+            }
+    }
+    ok = ok && bNI > 0;
+    if (ok) {
+        g.N = N; g.H = H; g.W = W; g.C = p->C; g.F = p->F; g.Ho = Ho; g.Wo = Wo;
+        g.KH = KH; g.KW = KW; g.pad = pad;
+        g.pg = 4;
+        g.NI = bNI; g.TH = bTH; g.TW = bTW; g.PH = bTH + KH - 1; g.PW = bTW + KW - 1;
+        g.tilesN = (N + bNI - 1) / bNI; g.tilesY = (Ho + bTH - 1) / bTH; g.tilesX = (Wo + bTW - 1) / bTW;
+        g.nfb = 1;
+        g.npb = (bNI * g.PH * g.PW + 7) / 8;
+        g.depth = nst;
+        g.div_tw = magic_div((uint32_t)bTW); g.div_pw = magic_div((uint32_t)g.PW);
+        g.div_thtw = magic_div((uint32_t)(bTH * bTW)); g.div_phpw = magic_div((uint32_t)(g.PH * g.PW));
+        const long items = (long)g.tilesN * g.tilesY * g.tilesX;
+        const double eff = (double)N * Ho * Wo / ((double)items * 256.0);
+        const char *fv = std::getenv("NPAS_FORCE_VARIANT");
+        const bool force = fv && std::strcmp(fv, "resident") == 0;
+        ok = force || (items >= 192 && eff >= 0.6);
+    }
+    cache.emplace(key, std::make_pair(ok, g));
+    *a = g;
+    return ok;
+}
+
 // Which kernel a run call launches for this layer and geometry.
-enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SMALLC, R_SMALLM, R_SLAB, R_GATHER };
+enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SPATIAL_RESIDENT, R_SMALLC, R_SMALLM, R_SLAB, R_GATHER };
 
 // Tile and patch of a small-channel launch: TH x TW = 256 output pixels with the fewest computed-but-
 // unused ones, the patch within 48 KB of LDS.  False when no tile shape fits.
@@ -312,6 +378,12 @@ static Route choose_route(const npas_packed *p, int N, int H, int W, int stride,
         if ((long)N * Ho1 * Wo1 <= 256) return R_SMALLM;
         return R_POINTWISE_RING;
     }
+    {
+        const char *fv = std::getenv("NPAS_FORCE_VARIANT");
+        if (ring_ok && stride == 1 && (p->KH > 1 || p->KW > 1) && p->F <= 64 && !(fv && std::strcmp(fv, "noresident") == 0) &&
+            plan_resident(p, N, H, W, pad, sp))
+            return R_SPATIAL_RESIDENT;
+    }
     if (ring_ok && stride == 1 && (p->KH > 1 || p->KW > 1) && plan_spatial(p, N, H, W, pad, sp)) return R_SPATIAL_RING;
     // few output pixels (small batch, late stages): the tiled kernels would run a handful of workgroups, each
     // walking the whole reduction alone; split the reduction over the waves of many small workgroups instead
@@ -333,6 +405,7 @@ const char *route_name(const npas_packed *p, int N, int H, int W, int stride, in
     case R_VALU: return "conv_valu_f32";
     case R_POINTWISE_RING: return "pointwise_ring";
     case R_SPATIAL_RING: return "spatial_ring";
+    case R_SPATIAL_RESIDENT: return "spatial_resident";
     case R_SMALLC: return "conv_smallc_mfma";
     case R_SMALLM: return "conv_smallm_mfma";
     case R_SLAB: return "conv_slab_mfma";
@@ -423,6 +496,13 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.div_howo = magic_div((uint32_t)(a.Ho * a.Wo));
         a.div_wo = magic_div((uint32_t)a.Wo);
         return launch_pointwise_ring(p->dtype, a, stream);
+    }
+    if (route == R_SPATIAL_RESIDENT) { // k x k, at most 64 filters: all weights stay in LDS
+        SpatialRingArgs &a = sp;
+        a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
+        a.wimg = p->dev.wimg; a.zeros = p->dev.zeros;
+        a.act = act;
+        return launch_spatial_resident(p->dtype, a, stream);
     }
     if (route == R_SPATIAL_RING) { // k x k streaming path, when a tile plan fills the chip
         SpatialRingArgs &a = sp;

@@ -1196,6 +1196,215 @@ int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
     return NPAS_OK;
 }
 
+// ------------------------------------------------------------------------------
+// spatial_resident: k x k layers at stride 1 with C a multiple of 64 and at most 64 filters, whose
+// weight images (first filter half of every stage, 8 KB each) all fit in LDS next to two patch
+// buffers: a 3 x 3 layer on 64 channels is 72 KB.  The workgroup fetches them once and then only
+// streams patches: no weight traffic and no per-stage barrier, one barrier per (item, chunk).
+//   waves 0-7   multiply: 32 pixels x 64 filters each (two waves per SIMD: one's operand reads
+//               hide behind the other's MFMAs)
+//   waves 8-11  fetch the next patch while the current one is multiplied
+// Tile, patch layout, pixel table and epilogue are the spatial ring's.
+constexpr int kResidentThreads = 12 * 64;
+constexpr uint32_t kResidentWStage = 8192;
+
+template <int DT>
+__global__ __launch_bounds__(kResidentThreads) void spatial_resident_kernel(SpatialRingArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const uint32_t lbase = (uint32_t)(uintptr_t)lds;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
+    const uint32_t nwg = gridDim.x;
+    const uint32_t nitems = (uint32_t)(a.tilesN * a.tilesY * a.tilesX);
+    const int T = a.KH * a.KW, nch = a.C >> 6, nst = nch * T;
+    const uint32_t ppb = (uint32_t)a.npb * 1024u;                 // bytes of one patch buffer
+    const uint32_t lw = 2u * ppb;                                 // the weights: nst stages of 8 KB
+    const uint32_t lbias = lw + (uint32_t)nst * kResidentWStage;  // 64 floats (1 KB block)
+    const uint32_t ltab = lbias + 1024u;                          // patch pixel -> (image, row, column), 4 B each
+    uint32_t c_item = xcd_remap(blockIdx.x, nwg);
+    if (c_item >= nitems) return;
+    SpatialItem it = spatial_item(a, c_item);
+    const int phpw = a.PH * a.PW;
+
+    for (int pp = tid; pp < a.npb * 8; pp += kResidentThreads) {
+        const uint32_t img = fastdiv((uint32_t)pp, a.div_phpw), r = (uint32_t)pp - img * (uint32_t)phpw;
+        const uint32_t py = fastdiv(r, a.div_pw), px = r - py * (uint32_t)a.PW;
+        reinterpret_cast<uint32_t *>(lds + ltab)[pp] = (int)img < a.NI ? (img << 20 | py << 10 | px) : 0xffffffffu;
+    }
+    // weights: image i = stage * 8 + step * 4 + row tile, from [stage][step][8 tiles] in the packed format
+    {
+        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)lane * 16u;
+        for (int i = wave; i < nst * 8; i += kResidentThreads / 64)
+            lds_dma16(wb + (size_t)(i >> 3) * 16384u + (size_t)((i >> 2) & 1) * 8192u + (size_t)(i & 3) * 1024u, lbase + lw + (uint32_t)i * 1024u);
+        if (wave == 0 && a.bias) { // lanes past the filters fetch a copy that nobody reads
+            const int f = (lane & 15) * 4;
+            lds_dma16(a.bias + (f < a.F ? f : 0), lbase + lbias);
+        }
+    }
+    __syncthreads(); // the table
+
+    if (wave >= 8) {
+        // ---- patch fetch ------------------------------------------------------------------
+        const int wl = wave - 8;
+        const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
+        const uint8_t *zb = reinterpret_cast<const uint8_t *>(a.zeros) + (uint32_t)(lane & 7) * 16u;
+        const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u;
+        auto patch = [&](const SpatialItem &pi, int cc, uint32_t buf) __attribute__((always_inline)) {
+            for (int blk = wl; blk < a.npb; blk += 4) {
+                const uint32_t e = reinterpret_cast<const uint32_t *>(lds + ltab)[blk * 8 + (lane >> 3)];
+                const int n = pi.n0 + (int)(e >> 20), iy = pi.ty0 - a.pad + (int)((e >> 10) & 1023u), ix = pi.tx0 - a.pad + (int)(e & 1023u);
+                const bool inb = e != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
+                const uint8_t *src = inb ? xb + ((uint32_t)((n * a.H + iy) * a.W + ix) * (uint32_t)a.C + (uint32_t)cc * 64u) * 2u + pcv : zb;
+                lds_dma16(src, lbase + buf * ppb + (uint32_t)blk * 1024u);
+            }
+        };
+        patch(it, 0, 0);
+        uint32_t pbuf = 0;
+        for (;;) {
+            const bool more_items = c_item + nwg < nitems;
+            SpatialItem nit = it;
+            if (more_items) nit = spatial_item(a, c_item + nwg);
+            for (int cc = 0; cc < nch; ++cc) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this chunk's patch (and, the first time, the weights) have landed
+                __builtin_amdgcn_s_barrier();                    // ... and the other buffer has been multiplied
+                if (cc + 1 < nch) patch(it, cc + 1, pbuf ^ 1u);
+                else if (more_items) patch(nit, 0, pbuf ^ 1u);
+                pbuf ^= 1u;
+            }
+            if (!more_items) break;
+            c_item += nwg;
+            it = nit;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+
+    // ---- multiply ------------------------------------------------------------------------
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this wave's share of the weights
+    const int wp = wave;
+    const Clamp cl = clamp_of(a.act);
+    const int thtw = a.TH * a.TW;
+    uint32_t pb0[2]; // where this lane's operand rows (tile pixels 32 wp + 16 s + n16) sit in the patch
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const uint32_t m = (uint32_t)(wp * 32 + s * 16 + n16);
+        const uint32_t img = fastdiv(m, a.div_thtw), r = m - img * (uint32_t)thtw;
+        const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
+        pb0[s] = (int)m < a.NI * thtw ? img * (uint32_t)phpw + ty * (uint32_t)a.PW + tx : 0u;
+    }
+    uint32_t pbuf = 0;
+    const uint32_t arow = (uint32_t)lane * 16u;
+
+    for (;;) { // one item per iteration
+        f32x4 acc[4][2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const bool more_items = c_item + nwg < nitems;
+
+        for (int cc = 0; cc < nch; ++cc) {
+            __builtin_amdgcn_s_barrier(); // the chunk's patch is in LDS
+            asm volatile("" ::: "memory");
+            const uint8_t *pbp = lds + pbuf * ppb;
+            const uint8_t *wsp = lds + lw + (uint32_t)(cc * T) * kResidentWStage + arow;
+            uint32_t kh = 0, kw = 0;
+            for (int tap = 0; tap < T; ++tap) {
+                const uint32_t toff = kh * (uint32_t)a.PW + kw;
+                if (++kw == (uint32_t)a.KW) { kw = 0; ++kh; }
+#pragma unroll
+                for (int step = 0; step < 2; ++step) {
+                    uint4 A[4], B[2];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) A[j] = *reinterpret_cast<const uint4 *>(wsp + (uint32_t)(step * 4 + j) * 1024u);
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const uint32_t pp = pb0[s] + toff;
+                        B[s] = *reinterpret_cast<const uint4 *>(pbp + pp * 128u + ((((uint32_t)(step * 4 + q)) ^ (pp & 7u)) << 4));
+                    }
+#pragma unroll
+                    for (int s = 0; s < 2; ++s)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[j][s] = mfma16<DT>(B[s], A[j], acc[j][s]);
+                }
+                wsp += kResidentWStage;
+            }
+            pbuf ^= 1u;
+        }
+        // ---- bias (from LDS), residual, clamp (activation), round, store: result register i of (j, s) is tile
+        // pixel 32 wp + 16 s + 4q + i, filter 4 n16 + j; the 16 lanes of a quarter wave write one 128-byte run
+        const int fcol = 4 * n16;
+        float4 b4 = float4{0.f, 0.f, 0.f, 0.f};
+        if (a.bias) b4 = *reinterpret_cast<const float4 *>(lds + lbias + (uint32_t)(4 * n16) * 4u);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t m = (uint32_t)(wp * 32 + s * 16 + 4 * q + i);
+                asm volatile("" : "+v"(m)); // or the pixel decodes are done (and held) ahead of the item loop
+                const uint32_t img = fastdiv(m, a.div_thtw), r = m - img * (uint32_t)thtw;
+                const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
+                const int n = it.n0 + (int)img, oy = it.ty0 + (int)ty, ox = it.tx0 + (int)tx;
+                if ((int)m >= a.NI * thtw || n >= a.N || oy >= a.Ho || ox >= a.Wo || fcol >= a.F) continue;
+                const size_t o = (size_t)((n * a.Ho + oy) * a.Wo + ox) * (size_t)a.F + (size_t)fcol;
+                float v[4] = {acc[0][s][i] + b4.x, acc[1][s][i] + b4.y, acc[2][s][i] + b4.z, acc[3][s][i] + b4.w};
+                if (a.residual) {
+                    const uint2 r2 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.residual) + o);
+                    v[0] += from_storage<DT>((uint16_t)(r2.x & 0xffffu));
+                    v[1] += from_storage<DT>((uint16_t)(r2.x >> 16));
+                    v[2] += from_storage<DT>((uint16_t)(r2.y & 0xffffu));
+                    v[3] += from_storage<DT>((uint16_t)(r2.y >> 16));
+                }
+                uint2 out;
+                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
+                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o) = out;
+            }
+        if (!more_items) break;
+        c_item += nwg;
+        it = spatial_item(a, c_item);
+    }
+}
+
+template <int DT> static void launch_resident_inst(const SpatialRingArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
+{
+    auto kern = spatial_resident_kernel<DT>;
+    static bool attr_done = false; // one flag per instantiation
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kResidentThreads), lds_bytes, st, a);
+}
+
+size_t spatial_resident_lds_bytes(int npb, int nst) { return (size_t)2 * npb * 1024 + (size_t)nst * kResidentWStage + 1024 + (size_t)npb * 32; }
+
+int launch_spatial_resident(int dtype, const SpatialRingArgs &a, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const int nst = (a.C / 64) * a.KH * a.KW;
+    const size_t lds_bytes = spatial_resident_lds_bytes(a.npb, nst);
+    const long items = (long)a.tilesN * a.tilesY * a.tilesX;
+    const unsigned grid = (unsigned)std::min<long>(items, 256);
+    if (lds_bytes > 160 * 1024 || a.F > 64 || a.C % 64 != 0 || a.nfb != 1 || a.NI * a.TH * a.TW > 256 || a.npb > 4 * 60 ||
+        a.TH > 255 || a.TW > 255 || a.PH > 1023 || a.PW > 1023) {
+        set_error("spatial_resident: tile plan does not fit the kernel");
+        return NPAS_E_SHAPE;
+    }
+    if (dtype == NPAS_BF16) launch_resident_inst<NPAS_BF16>(a, grid, lds_bytes, st);
+    else if (dtype == NPAS_F16) launch_resident_inst<NPAS_F16>(a, grid, lds_bytes, st);
+    else {
+        set_error("spatial_resident needs a 16-bit storage type");
+        return NPAS_E_DTYPE;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("spatial_resident launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
 template <int DT, typename Cfg> static void launch_pointwise_cfg(const RingArgs &a, hipStream_t st)
 {
     static bool attr_done = false;

@@ -264,6 +264,8 @@ const char *route_name(const npas_packed *p, int N, int H, int W, int stride, in
 // Tile plan of the k x k streaming kernel (geometry fields of *a); false: use another kernel.
 bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a);
 int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream);
+int launch_spatial_resident(int dtype, const SpatialRingArgs &a, void *stream);
+size_t spatial_resident_lds_bytes(int npb, int nst); // LDS of a launch with npb patch blocks and nst weight stages
 int launch_conv_smallc(int dtype, const SmallCArgs &a, void *stream);
 int launch_conv_smallm(int dtype, const SmallMArgs &a, void *stream);
 bool fpp_supported(int nt1, int nt2);

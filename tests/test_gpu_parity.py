@@ -155,6 +155,27 @@ def test_spatial_streaming_kernel(npas, torch, case, monkeypatch):
     _run_edge_case(npas, torch, case, expect_kernel="spatial_ring")
 
 
+RESIDENT = [
+    ("res_3x3_64", 3, 20, 23, 64, 64, 3, 3, 1, 1, 8, 4, 3, dtypes.BF16, 1, True, True),
+    ("res_ragged_filters_fp16", 2, 13, 11, 64, 40, 3, 3, 1, 1, 8, 4, 2, dtypes.F16, 2, False, True),
+    ("res_two_chunks_2x2_pad0", 5, 9, 9, 128, 32, 2, 2, 1, 0, 4, 4, 2, dtypes.BF16, 0, True, False),
+    ("res_several_images_per_tile", 37, 7, 7, 64, 64, 3, 3, 1, 1, 8, 4, 5, dtypes.BF16, 1, False, False),
+    ("res_more_items_than_workgroups", 20, 56, 56, 64, 16, 3, 3, 1, 1, 8, 4, 3, dtypes.BF16, 1, False, True),
+]
+
+
+@pytest.mark.parametrize("case", RESIDENT, ids=[c[0] for c in RESIDENT])
+def test_spatial_resident_weights_kernel(npas, torch, case, monkeypatch):
+    monkeypatch.setenv("NPAS_FORCE_VARIANT", "resident")
+    _run_edge_case(npas, torch, case, expect_kernel="spatial_resident")
+
+
+def test_spatial_resident_weights_kernel_chosen_for_a_full_launch(npas, torch):
+    """56 x 56, 64 -> 64 at batch 16: 224 tiles of 8 x 28 pixels, chosen by the library itself."""
+    _run_edge_case(npas, torch, ("res_full_launch", 16, 56, 56, 64, 64, 3, 3, 1, 1, 8, 4, 3, dtypes.BF16, 1, False, True),
+                   expect_kernel="spatial_resident")
+
+
 def test_spatial_streaming_kernel_half_size_tiles(npas, torch):
     """104 tiles of 256 pixels would leave most CUs idle; 256 tiles of 128 pixels (two 7x7 images each) do not:
     the streaming kernel with half the multiplying waves, chosen by the library itself."""
