@@ -1202,7 +1202,9 @@ int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
 // buffers: a 3 x 3 layer on 64 channels is 72 KB.  The workgroup fetches them once and then only
 // streams patches: no weight traffic and no per-stage barrier, one barrier per (item, chunk).
 //   waves 0-7   multiply: 32 pixels x 64 filters each (two waves per SIMD: one's operand reads
-//               hide behind the other's MFMAs)
+//               hide behind the other's MFMAs; four waves of 64 x 64, one per SIMD, with the next
+//               step's operands read ahead by hand, read a third less from LDS and were slower:
+//               54 against 42 us on 56 x 56 x 64 -> 64 at batch 128)
 //   waves 8-11  fetch the next patch while the current one is multiplied
 // Tile, patch layout, pixel table and epilogue are the spatial ring's.
 constexpr int kResidentThreads = 12 * 64;
