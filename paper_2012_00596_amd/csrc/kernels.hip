@@ -899,9 +899,11 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
 // of the stage about to be multiplied; after the barrier the slot (or patch buffer) of the
 // stage before is free to be refilled.
 constexpr uint32_t kSpatialWStage = 16384;
-// PG pixel groups of 64 x 2 filter groups of 64 multiply: 8 waves on a 256-pixel tile, or 4 on a 128-pixel
-// tile (launches whose 256-pixel tiles would leave most CUs without one).
-constexpr int spatial_threads(int pg) { return (2 * pg + 8) * 64; }
+// Tiles of 64 PG pixels x 128 filters.  PG == 4: eight multiplying waves, 4 pixel groups of 64 x 2 filter groups
+// of 64.  PG == 2 (launches whose 256-pixel tiles would leave most CUs without one): also eight, 4 pixel
+// groups of 32 x 2 filter groups of 64.
+constexpr int spatial_waves(int pg) { return pg == 2 ? 8 : 2 * pg; } // multiplying waves
+constexpr int spatial_threads(int pg) { return (spatial_waves(pg) + 8) * 64; }
 constexpr int kSpatialFetchWaves = 4; // of each kind
 
 struct SpatialItem {
@@ -925,7 +927,9 @@ __device__ __forceinline__ SpatialItem spatial_item(const SpatialRingArgs &a, ui
 template <int DT, int PG>
 __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(SpatialRingArgs a)
 {
-    constexpr int NCW = 2 * PG; // multiplying waves
+    // PG == 4: 8 waves of 64 pixels x 64 filters.  PG == 2: 8 waves of 32 x 64 (two per SIMD; four waves of
+    // 64 x 64, one per SIMD, left the operand latency of every step exposed)
+    constexpr int NCW = spatial_waves(PG), S = PG == 2 ? 2 : 4, NB = 2 * S;
     constexpr int kSpatialThreads = spatial_threads(PG);
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lbase = (uint32_t)(uintptr_t)lds;
@@ -1061,10 +1065,10 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     const Clamp cl = clamp_of(a.act);
     const int thtw = a.TH * a.TW;
     // where this lane's operand rows (tile pixels 64 wp + 16 s + n16) sit in the patch (the same for every item)
-    uint32_t pb0[4];
+    uint32_t pb0[S];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const uint32_t m = (uint32_t)(wp * 64 + s * 16 + n16);
+    for (int s = 0; s < S; ++s) {
+        const uint32_t m = (uint32_t)(wp * (16 * S) + s * 16 + n16);
         const uint32_t img = fastdiv(m, a.div_thtw), r = m - img * (uint32_t)thtw;
         const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
         const bool valid = (int)m < a.NI * thtw;
@@ -1074,11 +1078,11 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     const uint32_t arow = (uint32_t)(wf * 4) * 1024u + (uint32_t)lane * 16u;
 
     for (;;) { // one item per iteration
-        f32x4 acc[4][4];
+        f32x4 acc[4][S];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int s = 0; s < S; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
         const bool more_items = c_item + nwg < nitems;
 
         for (int cc = 0; cc < nch; ++cc) {
@@ -1090,29 +1094,29 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
                 if (++c_slot == D) c_slot = 0;
                 const uint32_t kh = (uint32_t)tap / (uint32_t)a.KW, kw = (uint32_t)tap - kh * (uint32_t)a.KW;
                 const uint32_t toff = kh * (uint32_t)a.PW + kw;
-                // the 8 B fragments of the stage (2 steps x 4 pixel blocks) in use order, fetched
+                // the NB B fragments of the stage (2 steps x S pixel blocks) in use order, fetched
                 // three ahead of their use; A fragments one step ahead
-                uint32_t baddr[8];
+                uint32_t baddr[NB];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
+                for (int s = 0; s < S; ++s) {
                     const uint32_t pp = pb0[s] + toff;
                     baddr[s] = pp * 128u + ((((uint32_t)q) ^ (pp & 7u)) << 4);
-                    baddr[4 + s] = pp * 128u + ((((uint32_t)(4 + q)) ^ (pp & 7u)) << 4);
+                    baddr[S + s] = pp * 128u + ((((uint32_t)(4 + q)) ^ (pp & 7u)) << 4);
                 }
-                uint4 A[2][4], B[8];
+                uint4 A[2][4], B[NB];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) A[0][j] = *reinterpret_cast<const uint4 *>(wsp + j * 1024);
 #pragma unroll
                 for (int i = 0; i < 3; ++i) B[i] = *reinterpret_cast<const uint4 *>(pbp + baddr[i]);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    if (i + 3 < 8) B[i + 3] = *reinterpret_cast<const uint4 *>(pbp + baddr[i + 3]);
-                    if (i == 1) {
+                for (int i = 0; i < NB; ++i) {
+                    if (i + 3 < NB) B[i + 3] = *reinterpret_cast<const uint4 *>(pbp + baddr[i + 3]);
+                    if (i == (S == 4 ? 1 : 0)) {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) A[1][j] = *reinterpret_cast<const uint4 *>(wsp + 8192 + j * 1024);
                     }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[j][i & 3] = mfma16<DT>(B[i], A[i >> 2][j], acc[j][i & 3]);
+                    for (int j = 0; j < 4; ++j) acc[j][i % S] = mfma16<DT>(B[i], A[i / S][j], acc[j][i % S]);
                 }
             }
             pbuf ^= 1u;
@@ -1120,16 +1124,16 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
         // ---- bias (from LDS), residual, clamp (activation), round, store ---------------------
         // The patch is the MFMA's row operand and the weight images its column operand, and row r
         // of weight tile j is filter 4r + j of the wave's 64: result register i of (j, s) is tile
-        // pixel 64 wp + 16 s + 4q + i, filter 4 n16 + j.  A lane writes 4 consecutive filters of a
+        // pixel 16 S wp + 16 s + 4q + i, filter 4 n16 + j.  A lane writes 4 consecutive filters of a
         // pixel, the 16 lanes of a quarter wave one whole 128-byte run of its row.
         const int fcol = it.fb * 128 + wf * 64 + 4 * n16;
         float4 b4 = float4{0.f, 0.f, 0.f, 0.f};
         if (a.bias) b4 = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 4 * n16) * 4u);
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < S; ++s)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                uint32_t m = (uint32_t)(wp * 64 + s * 16 + 4 * q + i);
+                uint32_t m = (uint32_t)(wp * (16 * S) + s * 16 + 4 * q + i);
                 asm volatile("" : "+v"(m)); // or the 16 pixel decodes are done (and held) ahead of the item loop
                 const uint32_t img = fastdiv(m, a.div_thtw), r = m - img * (uint32_t)thtw;
                 const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
