@@ -180,52 +180,56 @@ static int check_run(const npas_packed *p, const void *x, void *y, int N, int H,
 // plan with the best ratio of useful to computed columns, then the smaller halo.  Returns
 // false when no plan exists or the launch would leave most of the chip idle (the slab
 // kernel's smaller tiles serve those cases better).
-static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, bool force, int maxpix, SpatialRingArgs *a);
+static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, int stride, bool force, int maxpix, SpatialRingArgs *a);
 
 // The search is a few thousand candidates; its result depends only on the shapes, so it is
 // kept per shape (launches of a stack repeat the same few shapes).
-bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a)
+bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, int stride, SpatialRingArgs *a)
 {
     static std::mutex mu;
-    static std::map<std::array<int, 10>, std::pair<bool, SpatialRingArgs>> cache;
+    static std::map<std::array<int, 11>, std::pair<bool, SpatialRingArgs>> cache;
     // NPAS_FORCE_VARIANT=spatial (tests): take this kernel whenever a plan exists
     const char *fv = std::getenv("NPAS_FORCE_VARIANT");
     const int force = fv && std::strcmp(fv, "spatial") == 0;
-    const std::array<int, 10> key = {p->KH, p->KW, p->C, p->F, p->ring.nfb, N, H, W, pad, force};
+    const std::array<int, 11> key = {p->KH, p->KW, p->C, p->F, p->ring.nfb, N, H, W, pad, force, stride};
     std::lock_guard<std::mutex> lock(mu);
     auto it = cache.find(key);
     if (it == cache.end()) {
         SpatialRingArgs g;
         std::memset(&g, 0, sizeof g);
         // 256-pixel tiles; if those would leave most of the chip idle, 128-pixel tiles (half the multiplying waves)
-        bool ok = plan_spatial_search(p, N, H, W, pad, false, 256, &g);
-        if (!ok) ok = plan_spatial_search(p, N, H, W, pad, false, 128, &g);
-        if (!ok && force) ok = plan_spatial_search(p, N, H, W, pad, true, 256, &g);
+        // (stride 2: 128-pixel tiles only, the four phase planes of a 256-pixel tile do not fit)
+        bool ok = stride == 1 && plan_spatial_search(p, N, H, W, pad, stride, false, 256, &g);
+        if (!ok) ok = plan_spatial_search(p, N, H, W, pad, stride, false, 128, &g);
+        if (!ok && force) ok = plan_spatial_search(p, N, H, W, pad, stride, true, stride == 1 ? 256 : 128, &g);
         it = cache.emplace(key, std::make_pair(ok, g)).first;
     }
     *a = it->second.second;
     return it->second.first;
 }
 
-static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, bool force, int maxpix, SpatialRingArgs *a)
+static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int pad, int stride, bool force, int maxpix, SpatialRingArgs *a)
 {
     const int KH = p->KH, KW = p->KW, T = KH * KW;
-    const int Ho = H + 2 * pad - KH + 1, Wo = W + 2 * pad - KW + 1;
-    const int lds_total = 160 * 1024 - 2048 /* bias buffers */ - 2048 /* pixel table */, wstage = 16384;
-    const int max_npb = (lds_total - 3 * wstage) / 2048;
-    if (T < 2 || p->C % 64 != 0) return false;
+    const bool s2 = stride == 2; // 3 x 3, pad 1: four phase planes of (TH + 1) x (TW + 1) pixels, one copy
+    if (stride != 1 && !(s2 && KH == 3 && KW == 3 && pad == 1)) return false;
+    const int Ho = (H + 2 * pad - KH) / stride + 1, Wo = (W + 2 * pad - KW) / stride + 1;
+    const int lds_total = 160 * 1024 - 2048 /* bias buffers */ - (s2 ? 4096 : 2048) /* pixel table */, wstage = 16384;
+    const int nbuf = s2 ? 4 : 2; // patch buffers (planes) of npb KB each
+    const int max_npb = std::min(s2 ? 124 : 1 << 20, (lds_total - 3 * wstage) / (1024 * nbuf));
+    if (T < 2 || p->C % 64 != 0 || Ho <= 0 || Wo <= 0) return false;
     double best = -1.0;
     int bNI = 0, bTH = 0, bTW = 0;
     for (int TH = 1; TH <= std::min(Ho, 255); ++TH)
         for (int TW = 1; TW <= std::min(Wo, 255) && TH * TW <= maxpix; ++TW) {
-            const int PH = TH + KH - 1, PW = TW + KW - 1;
+            const int PH = s2 ? TH + 1 : TH + KH - 1, PW = s2 ? TW + 1 : TW + KW - 1;
             const long ty = (Ho + TH - 1) / TH, tx = (Wo + TW - 1) / TW;
             const int maxNI = std::min(N, maxpix / (TH * TW));
             for (int NI = 1; NI <= maxNI; ++NI) {
                 const int npb = (NI * PH * PW + 7) / 8;
                 if (npb > max_npb) break;
                 const long tn = (N + NI - 1) / NI;
-                const int depth = std::min(6, (lds_total - 2048 * npb) / wstage);
+                const int depth = std::min(6, (lds_total - 1024 * nbuf * npb) / wstage);
                 const double eff = (double)N * Ho * Wo / ((double)tn * ty * tx * (double)maxpix);
                 const double halo = (double)(NI * PH * PW) / (double)(NI * TH * TW);
                 const double score = eff - 0.02 * halo + 0.02 * (depth - 3);
@@ -237,13 +241,13 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
         }
     if (best < 0) return false;
     a->N = N; a->H = H; a->W = W; a->C = p->C; a->F = p->F; a->Ho = Ho; a->Wo = Wo;
-    a->KH = KH; a->KW = KW; a->pad = pad;
+    a->KH = KH; a->KW = KW; a->pad = pad; a->stride = stride;
     a->pg = maxpix / 64;
-    a->NI = bNI; a->TH = bTH; a->TW = bTW; a->PH = bTH + KH - 1; a->PW = bTW + KW - 1;
+    a->NI = bNI; a->TH = bTH; a->TW = bTW; a->PH = s2 ? bTH + 1 : bTH + KH - 1; a->PW = s2 ? bTW + 1 : bTW + KW - 1;
     a->tilesN = (N + bNI - 1) / bNI; a->tilesY = (Ho + bTH - 1) / bTH; a->tilesX = (Wo + bTW - 1) / bTW;
     a->nfb = p->ring.nfb;
     a->npb = (bNI * a->PH * a->PW + 7) / 8;
-    a->depth = std::min(6, (lds_total - 2048 * a->npb) / wstage);
+    a->depth = std::min(6, (lds_total - 1024 * nbuf * a->npb) / wstage);
     a->div_tw = magic_div((uint32_t)bTW); a->div_pw = magic_div((uint32_t)a->PW);
     a->div_thtw = magic_div((uint32_t)(bTH * bTW)); a->div_phpw = magic_div((uint32_t)(a->PH * a->PW));
     const long items = (long)a->tilesN * a->tilesY * a->tilesX * a->nfb;
@@ -253,7 +257,8 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     const double fill = (double)p->F / (128.0 * a->nfb);
     // with 128-pixel tiles a long reduction (many stages per item) pays from fewer items on: the slab kernel's
     // workgroups would walk it with one step of lookahead (512 -> 512 at 7 x 7, batch 32: 64 items, 64 -> 47 us)
-    const bool enough = items >= 192 || (maxpix == 128 && items >= 48 && items * (p->C / 64) * T >= 3000);
+    // (at stride 2 only from 64 stages per item on: 256 -> 256 onto 14 x 14 at batch 32, 100 items of 36 stages, 32 against 27 us)
+    const bool enough = items >= 192 || (maxpix == 128 && items >= 48 && items * (p->C / 64) * T >= 3000 && (!s2 || (p->C / 64) * T >= 64));
     return force || (enough && eff >= 0.6 && fill >= 0.75);
 }
 
@@ -304,7 +309,7 @@ bool plan_resident(const npas_packed *p, int N, int H, int W, int pad, SpatialRi
     if (ok) {
         g.N = N; g.H = H; g.W = W; g.C = p->C; g.F = p->F; g.Ho = Ho; g.Wo = Wo;
         g.KH = KH; g.KW = KW; g.pad = pad;
-        g.pg = 4;
+        g.pg = 4; g.stride = 1;
         g.NI = bNI; g.TH = bTH; g.TW = bTW; g.PH = bTH + KH - 1; g.PW = bTW + KW - 1;
         g.tilesN = (N + bNI - 1) / bNI; g.tilesY = (Ho + bTH - 1) / bTH; g.tilesX = (Wo + bTW - 1) / bTW;
         g.nfb = 1;
@@ -384,7 +389,12 @@ static Route choose_route(const npas_packed *p, int N, int H, int W, int stride,
             plan_resident(p, N, H, W, pad, sp))
             return R_SPATIAL_RESIDENT;
     }
-    if (ring_ok && stride == 1 && (p->KH > 1 || p->KW > 1) && plan_spatial(p, N, H, W, pad, sp)) return R_SPATIAL_RING;
+    {
+        const char *fv = std::getenv("NPAS_FORCE_VARIANT");
+        const bool s2_off = stride == 2 && fv && std::strcmp(fv, "nospatial2") == 0;
+        if (ring_ok && (stride == 1 || stride == 2) && !s2_off && (p->KH > 1 || p->KW > 1) && plan_spatial(p, N, H, W, pad, stride, sp))
+            return R_SPATIAL_RING;
+    }
     // few output pixels (small batch, late stages): the tiled kernels would run a handful of workgroups, each
     // walking the whole reduction alone; split the reduction over the waves of many small workgroups instead
     if (ring_ok && (p->KH > 1 || p->KW > 1)) {

@@ -924,7 +924,12 @@ __device__ __forceinline__ SpatialItem spatial_item(const SpatialRingArgs &a, ui
     return it;
 }
 
-template <int DT, int PG>
+// S2: stride 2, 3 x 3, pad 1.  The patch is kept as four phase planes (input rows and columns of one parity
+// each), every plane a dense (TH + 1) x (TW + 1) grid, so that a tap reads one plane at an offset of 0 or 1
+// rows / columns exactly as at stride 1.  The taps are walked plane by plane (4 + 2 + 2 + 1 stages); a plane's
+// buffer is refilled with the next chunk's pixels as soon as its last tap is done, which leaves every refill
+// at least five stages: one copy of the patch in LDS instead of two.
+template <int DT, int PG, bool S2>
 __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(SpatialRingArgs a)
 {
     // PG == 4: 8 waves of 64 pixels x 64 filters.  PG == 2: 8 waves of 32 x 64 (two per SIMD; four waves of
@@ -938,7 +943,7 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     const uint32_t nitems = (uint32_t)(a.tilesN * a.tilesY * a.tilesX * a.nfb);
     const int T = a.KH * a.KW, nch = a.C >> 6;
     const uint32_t ppb = (uint32_t)a.npb * 1024u;      // bytes of one patch buffer
-    const uint32_t wring = 2u * ppb;                   // LDS offset of the weight ring
+    const uint32_t wring = (S2 ? 4u : 2u) * ppb;       // LDS offset of the weight ring (after two patch buffers, or four planes)
     const uint32_t D = (uint32_t)a.depth;              // weight stages in the ring
     const uint32_t lbias = wring + D * kSpatialWStage; // two 1 KB bias buffers (item parity)
     const uint32_t ltab = lbias + 2048u;               // patch pixel -> (image, row, column), 4 B each
@@ -948,10 +953,19 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     const int phpw = a.PH * a.PW;
 
     // patch pixel table (the same for every item): img << 20 | row << 10 | column, ~0 past the end
-    for (int pp = tid; pp < a.npb * 8; pp += kSpatialThreads) {
+    // (at stride 2: per plane; rows 2 py - ph + 1 and columns 2 px - pw + 1 of the tile's input window, where
+    // planes 0, 1 hold the odd rows (ph = 1: taps kh = 0, 2) and planes 0, 2 the odd columns (pw = 1: kw = 0, 2))
+    for (int idx = tid; idx < a.npb * 8 * (S2 ? 4 : 1); idx += kSpatialThreads) {
+        const int plane = S2 ? idx / (a.npb * 8) : 0, pp = idx - plane * (a.npb * 8);
         const uint32_t img = fastdiv((uint32_t)pp, a.div_phpw), r = (uint32_t)pp - img * (uint32_t)phpw;
         const uint32_t py = fastdiv(r, a.div_pw), px = r - py * (uint32_t)a.PW;
-        reinterpret_cast<uint32_t *>(lds + ltab)[pp] = (int)img < a.NI ? (img << 20 | py << 10 | px) : 0xffffffffu;
+        uint32_t e = (int)img < a.NI ? (img << 20 | py << 10 | px) : 0xffffffffu;
+        if (S2 && (int)img < a.NI) {
+            const uint32_t ph = plane < 2 ? 1u : 0u, pw = (plane & 1) ? 0u : 1u;
+            const bool used = (ph == 1u || (int)py < a.TH) && (pw == 1u || (int)px < a.TW);
+            e = used ? (img << 20 | (2u * py - ph + 1u) << 10 | (2u * px - pw + 1u)) : 0xffffffffu;
+        }
+        reinterpret_cast<uint32_t *>(lds + ltab)[idx] = e;
     }
     __syncthreads();
 
@@ -974,12 +988,60 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
                 lds_dma16(src, lbase + buf * ppb + (uint32_t)blk * 1024u);
             }
         };
+        // stride 2: this wave's blocks of one plane of (item pi, chunk cc)
+        auto plane_fetch = [&](const SpatialItem &pi, int cc, int plane) __attribute__((always_inline)) {
+            for (int k = 0; k < nblk; ++k) {
+                const int blk = plane * a.npb + wl + kSpatialFetchWaves * k;
+                const uint32_t e = reinterpret_cast<const uint32_t *>(lds + ltab)[blk * 8 + (lane >> 3)];
+                const int n = pi.n0 + (int)(e >> 20), iy = 2 * pi.ty0 - a.pad + (int)((e >> 10) & 1023u), ix = 2 * pi.tx0 - a.pad + (int)(e & 1023u);
+                const bool inb = e != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
+                const uint8_t *src = inb ? xb + ((uint32_t)((n * a.H + iy) * a.W + ix) * (uint32_t)a.C + (uint32_t)cc * 64u) * 2u + pcv : zb;
+                lds_dma16(src, lbase + (uint32_t)blk * 1024u);
+            }
+        };
         // bias of an item's 128 filters (512 B; lanes 32-63 fetch a copy that nobody reads)
         auto bias_block = [&](const SpatialItem &pi, uint32_t buf) __attribute__((always_inline)) {
             if (!a.bias || wl != 0) return;
             const int f = pi.fb * 128 + (lane & 31) * 4;
             lds_dma16(a.bias + (f < a.F ? f : 0), lbase + lbias + buf * 1024u);
         };
+        if (S2) {
+            // Stages 0-3 read plane 0, 4-5 plane 1, 6-7 plane 2, 8 plane 3.  Issue order, one burst of nblk loads
+            // each: ... plane 3 of this chunk after barrier 0, then planes 0, 1, 2 of the next chunk after
+            // barriers 4, 6, 8.  A plane is awaited at its first stage; two bursts were issued after it by then
+            // (fewer at the very end), and a wave's loads complete in order.
+            plane_fetch(it, 0, 0);
+            plane_fetch(it, 0, 1);
+            plane_fetch(it, 0, 2);
+            bias_block(it, 0);
+            uint32_t bbuf = 0;
+            for (;;) {
+                const bool more_items = c_item + nwg < nitems;
+                SpatialItem nit = it;
+                if (more_items) nit = spatial_item(a, c_item + nwg);
+                for (int cc = 0; cc < nch; ++cc) {
+                    const bool within = cc + 1 < nch, have_next = within || more_items;
+                    const SpatialItem &ni = within ? it : nit;
+                    const int ncc = within ? cc + 1 : 0;
+                    for (int st = 0; st < 9; ++st) {
+                        if (st == 0 || st == 4) wait_vmcnt((uint32_t)(2 * nblk));
+                        else if (st == 6) wait_vmcnt((uint32_t)(have_next ? 2 * nblk : nblk));
+                        else if (st == 8) wait_vmcnt((uint32_t)(have_next ? 2 * nblk : 0));
+                        __builtin_amdgcn_s_barrier();
+                        if (st == 0) {
+                            plane_fetch(it, cc, 3);
+                            if (!within && more_items) bias_block(nit, bbuf ^ 1u);
+                        } else if (have_next && (st == 4 || st == 6 || st == 8)) plane_fetch(ni, ncc, (st - 4) >> 1);
+                    }
+                }
+                if (!more_items) break;
+                c_item += nwg;
+                it = nit;
+                bbuf ^= 1u;
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            return;
+        }
         patch(it, 0, 0, 0, nblk);
         bias_block(it, 0);
         uint32_t pbuf = 0, bbuf = 0;
@@ -1018,7 +1080,9 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
         int p_fb = it.fb, p_cc = 0, p_tap = 0;
         bool p_done = false;
         auto produce_w = [&]() __attribute__((always_inline)) { // always issues its 4 loads; past the end it repeats the last stage
-            const uint8_t *wsrc = wb + (size_t)((p_fb * nch + p_cc) * T + p_tap) * kSpatialWStage;
+            // stride 2: the taps in plane order (kh, kw both even; kw = 1; kh = 1; the centre)
+            const int tapi = S2 ? (int)((0x453718620ull >> (4 * p_tap)) & 15ull) : p_tap;
+            const uint8_t *wsrc = wb + (size_t)((p_fb * nch + p_cc) * T + tapi) * kSpatialWStage;
             const uint32_t dst = lbase + wring + p_slot * kSpatialWStage + (uint32_t)(wl * kImgs) * 1024u;
 #pragma unroll
             for (int i = 0; i < kImgs; ++i) lds_dma16(wsrc + i * 1024, dst + (uint32_t)i * 1024u);
@@ -1086,14 +1150,21 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
         const bool more_items = c_item + nwg < nitems;
 
         for (int cc = 0; cc < nch; ++cc) {
-            const uint8_t *pbp = lds + pbuf * ppb;
+            const uint8_t *pbp = lds + (S2 ? 0u : pbuf * ppb);
             for (int tap = 0; tap < T; ++tap) {
                 __builtin_amdgcn_s_barrier(); // this stage's weights (and, at tap 0, the chunk's patch) are in LDS
                 asm volatile("" ::: "memory");
                 const uint8_t *wsp = lds + wring + c_slot * kSpatialWStage + arow;
                 if (++c_slot == D) c_slot = 0;
                 const uint32_t kh = (uint32_t)tap / (uint32_t)a.KW, kw = (uint32_t)tap - kh * (uint32_t)a.KW;
-                const uint32_t toff = kh * (uint32_t)a.PW + kw;
+                uint32_t toff = kh * (uint32_t)a.PW + kw;
+                if (S2) { // stage `tap` of the plane order: which plane, and 0 or 1 rows / columns into it
+                    const uint32_t pl = (uint32_t)a.npb * 8u, st = (uint32_t)tap;
+                    toff = st < 4u ? (st >> 1) * (uint32_t)a.PW + (st & 1u)
+                         : st < 6u ? pl + (st - 4u) * (uint32_t)a.PW
+                         : st < 8u ? 2u * pl + (st - 6u)
+                                   : 3u * pl;
+                }
                 // the NB B fragments of the stage (2 steps x S pixel blocks) in use order, fetched
                 // three ahead of their use; A fragments one step ahead
                 uint32_t baddr[NB];
@@ -1160,9 +1231,9 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     }
 }
 
-template <int DT, int PG> static void launch_spatial_inst(const SpatialRingArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
+template <int DT, int PG, bool S2 = false> static void launch_spatial_inst(const SpatialRingArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
-    auto kern = spatial_ring_kernel<DT, PG>;
+    auto kern = spatial_ring_kernel<DT, PG, S2>;
     static bool attr_done = false; // one flag per instantiation
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -1174,19 +1245,23 @@ template <int DT, int PG> static void launch_spatial_inst(const SpatialRingArgs 
 int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds_bytes = (size_t)2 * a.npb * 1024 + (size_t)a.depth * kSpatialWStage + 2048 + (size_t)a.npb * 32;
+    const bool s2 = a.stride == 2;
+    const size_t lds_bytes = (size_t)(s2 ? 4 : 2) * a.npb * (1024 + (s2 ? 32 : 16)) + (size_t)a.depth * kSpatialWStage + 2048;
     const long items = (long)a.tilesN * a.tilesY * a.tilesX * a.nfb;
     const unsigned grid = (unsigned)std::min<long>(items, 256);
     if (lds_bytes > 160 * 1024 || a.depth < 3 || a.depth > 6 || (a.pg != 4 && a.pg != 2) || a.NI * a.TH * a.TW > 64 * a.pg ||
-        a.TH > 255 || a.TW > 255 || a.PH > 1023 || a.PW > 1023) {
+        a.TH > 255 || a.TW > 255 || a.PH > 1023 || a.PW > 1023 || (a.stride != 1 && a.stride != 2) ||
+        (s2 && (a.pg != 2 || a.KH != 3 || a.KW != 3 || a.pad != 1 || a.PH != a.TH + 1 || a.PW != a.TW + 1 || a.npb > 4 * 31))) {
         set_error("spatial_ring: tile plan does not fit the kernel");
         return NPAS_E_SHAPE;
     }
     if (dtype == NPAS_BF16) {
-        if (a.pg == 4) launch_spatial_inst<NPAS_BF16, 4>(a, grid, lds_bytes, st);
+        if (s2) launch_spatial_inst<NPAS_BF16, 2, true>(a, grid, lds_bytes, st);
+        else if (a.pg == 4) launch_spatial_inst<NPAS_BF16, 4>(a, grid, lds_bytes, st);
         else launch_spatial_inst<NPAS_BF16, 2>(a, grid, lds_bytes, st);
     } else if (dtype == NPAS_F16) {
-        if (a.pg == 4) launch_spatial_inst<NPAS_F16, 4>(a, grid, lds_bytes, st);
+        if (s2) launch_spatial_inst<NPAS_F16, 2, true>(a, grid, lds_bytes, st);
+        else if (a.pg == 4) launch_spatial_inst<NPAS_F16, 4>(a, grid, lds_bytes, st);
         else launch_spatial_inst<NPAS_F16, 2>(a, grid, lds_bytes, st);
     } else {
         set_error("spatial_ring needs a 16-bit storage type");

@@ -234,7 +234,8 @@ struct SpatialRingArgs {
     const void *wimg;
     const void *zeros;          // >= 16 bytes of zeros on the device (source of padding pixels)
     int N, H, W, C, F, Ho, Wo;
-    int KH, KW, pad;            // stride 1
+    int KH, KW, pad;
+    int stride;                 // 1, or 2 (3 x 3, pad 1: the patch as four phase planes, PH = TH + 1, PW = TW + 1, npb per plane)
     int pg;                     // pixel groups of 64 a workgroup multiplies: 4 (256-pixel tiles) or 2 (128)
     int NI, TH, TW;             // tile: NI images x TH x TW output pixels (<= 64 pg)
     int PH, PW;                 // patch of one image of the tile
@@ -262,7 +263,7 @@ int launch_conv_valu(const ConvValuArgs &a, void *stream);
 int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream);
 const char *route_name(const npas_packed *p, int N, int H, int W, int stride, int pad);
 // Tile plan of the k x k streaming kernel (geometry fields of *a); false: use another kernel.
-bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a);
+bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, int stride, SpatialRingArgs *a);
 int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream);
 int launch_spatial_resident(int dtype, const SpatialRingArgs &a, void *stream);
 size_t spatial_resident_lds_bytes(int npb, int nst); // LDS of a launch with npb patch blocks and nst weight stages

@@ -176,6 +176,21 @@ def test_spatial_resident_weights_kernel_chosen_for_a_full_launch(npas, torch):
                    expect_kernel="spatial_resident")
 
 
+SPATIAL_STRIDE2 = [
+    ("sp2_ragged", 3, 17, 19, 64, 128, 3, 3, 2, 1, 8, 4, 3, dtypes.BF16, 1, True, True),
+    ("sp2_two_chunks_fp16", 2, 24, 24, 128, 72, 3, 3, 2, 1, 8, 4, 2, dtypes.F16, 2, False, True),
+    ("sp2_several_images_per_tile", 21, 14, 14, 64, 64, 3, 3, 2, 1, 8, 4, 5, dtypes.BF16, 0, True, False),
+    ("sp2_even_input_one_row_tiles", 2, 6, 40, 64, 32, 3, 3, 2, 1, 4, 4, 2, dtypes.BF16, 1, False, False),
+    ("sp2_more_items_than_workgroups", 70, 32, 32, 64, 512, 3, 3, 2, 1, 8, 4, 4, dtypes.BF16, 1, False, True),
+]
+
+
+@pytest.mark.parametrize("case", SPATIAL_STRIDE2, ids=[c[0] for c in SPATIAL_STRIDE2])
+def test_spatial_streaming_kernel_stride2(npas, torch, case, monkeypatch):
+    monkeypatch.setenv("NPAS_FORCE_VARIANT", "spatial")
+    _run_edge_case(npas, torch, case, expect_kernel="spatial_ring")
+
+
 def test_spatial_streaming_kernel_half_size_tiles(npas, torch):
     """104 tiles of 256 pixels would leave most CUs idle; 256 tiles of 128 pixels (two 7x7 images each) do not:
     the streaming kernel with half the multiplying waves, chosen by the library itself."""
@@ -482,14 +497,15 @@ def test_full_size_config4_sampled_images(npas, torch):
 
 def test_config5_batch128_sampled_images(npas, torch):
     """The 50-layer stack's layers in the launch configuration the per-layer report times (batch 128: big tiles,
-    both tile sizes of the streaming kernels, the stem kernel), each on a seeded input of its real shape, checked
+    both tile sizes of the streaming kernels, their stride-2 mode, the resident-weights kernel, the stem kernel), each on a seeded input of its real shape, checked
     on three of the 128 images (a layer's output for one image depends on that image only)."""
     w = configs.config5(batch=128)
     shapes = {0: w.x_shape}
     for i, L in enumerate(w.layers):
         shapes[i + 1] = helpers.out_shape(L, shapes[L.src])
     want = {"stem7x7": "conv_smallc_mfma", "s0b0_c3": "pointwise_ring", "s1b0_sc": "pointwise_ring", "s1b1_c2": "spatial_ring",
-            "s2b1_c3": "pointwise_ring", "s2b0_c2": "conv_slab_mfma", "s3b1_c1": "pointwise_ring", "s3b1_c2": "spatial_ring"}
+            "s2b1_c3": "pointwise_ring", "s2b0_c2": "spatial_ring", "s3b1_c1": "pointwise_ring", "s3b1_c2": "spatial_ring",
+            "s0b1_c2": "spatial_resident"}
     seen = set()
     for i, L in enumerate(w.layers):
         if L.name not in want:
