@@ -877,7 +877,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
 }
 
 // ------------------------------------------------------------------------------
-// spatial_ring: k x k layers at stride 1 with C a multiple of 64.  A stage is one tap of one
+// spatial_ring: k x k layers at stride 1 (3 x 3 at stride 2: see S2 at the kernel) with C a multiple of 64.  A stage is one tap of one
 // 64-channel chunk (two MFMA steps); its 16 weight images (16 KB) go through a ring of `depth`
 // LDS slots.  The activations of a chunk are the halo patch of the output tile
 // ([patch pixel][64 channels], 128 B per pixel, XOR-swizzled by the patch pixel index),
