@@ -146,3 +146,31 @@ def test_stack_wiring_checks_and_workspace():
     with pytest.raises(npas.NpasError):
         npas.Stack(bad, 32, 32)
     assert npas.lib().npas_run_stack(st.handle, 256, 256, 1, None, 0, None) == npas.E_WORKSPACE
+
+
+def _bp_layer(C, F, k, seed, rate=3):
+    m = masks.block_punched_mask(F, C, k, k, 8, 4 if C % 4 == 0 else C, rate, seed)
+    store, _ = dtypes.quantize(prng.normal(seed, 1, F * C * k * k, 0.1).reshape(F, C, k, k), dtypes.BF16)
+    return npas.pack_block_punched(store, m, 8, 4 if C % 4 == 0 else C, dtypes.BF16)
+
+
+def test_kernel_choice_follows_layer_and_launch_shape():
+    """Host logic only: which kernel a layer gets depends on its shape and on how many tiles the launch has."""
+    name = npas.conv2d_kernel_name
+    p = _bp_layer(64, 64, 3, 41)                       # 3x3 on 64 channels, 64 filters: all weight stages fit in LDS
+    assert name(p, 128, 56, 56, 1, 1) == "spatial_resident"
+    assert name(p, 8, 56, 56, 1, 1) == "conv_slab_mfma"          # 112 tiles: too few for the persistent kernels
+    assert name(p, 1, 56, 56, 1, 1) == "conv_smallm_mfma"        # little work in all: reduction split over the waves
+    p = _bp_layer(128, 128, 3, 42)
+    assert name(p, 128, 28, 28, 1, 1) == "spatial_ring"
+    assert name(p, 128, 56, 56, 2, 1) == "spatial_ring"          # stride 2: phase planes
+    assert name(p, 128, 56, 56, 2, 0) == "conv_slab_mfma"        # ... for pad 1 only
+    assert name(p, 1, 28, 28, 1, 1) == "conv_smallm_mfma"
+    p = _bp_layer(64, 256, 1, 43)
+    assert name(p, 128, 56, 56, 1, 0) == "pointwise_ring"
+    assert name(p, 1, 14, 14, 1, 0) == "conv_smallm_mfma"        # up to 256 output pixels
+    assert name(p, 1, 56, 56, 1, 0) == "pointwise_ring"
+    p = _bp_layer(3, 64, 7, 44)
+    assert name(p, 2, 224, 224, 2, 3) == "conv_smallc_mfma"      # fewer than 8 input channels
+    p = _bp_layer(24, 144, 1, 45, rate=4)
+    assert name(p, 64, 56, 56, 1, 0) == "conv_slab_mfma"         # channels not a multiple of 64
