@@ -903,8 +903,13 @@ constexpr uint32_t kSpatialWStage = 16384;
 // of 64.  PG == 2 (launches whose 256-pixel tiles would leave most CUs without one): also eight, 4 pixel
 // groups of 32 x 2 filter groups of 64.
 constexpr int spatial_waves(int pg) { return pg == 2 ? 8 : 2 * pg; } // multiplying waves
-constexpr int spatial_threads(int pg) { return (spatial_waves(pg) + 8) * 64; }
-constexpr int kSpatialFetchWaves = 4; // of each kind
+// Fetching waves of each kind.  (Two of each on 256-pixel tiles, which leaves every wave 170 registers instead of
+// 128: 44 -> 49 us on 28 x 28 x 128 -> 128 at batch 128, the loads of a stage are issued too slowly.  With the
+// registers of sixteen waves the compiler keeps one pixel fragment per wave in flight (read, wait, four MFMAs);
+// pinning a three-fragment read-ahead with sched_group_barrier was slower as well, 15.4 -> 16.5 us on the
+// pattern layer: two waves per SIMD already cover each other's waits.)
+constexpr int spatial_fetch_waves(int) { return 4; }
+constexpr int spatial_threads(int pg) { return (spatial_waves(pg) + 2 * spatial_fetch_waves(pg)) * 64; }
 
 struct SpatialItem {
     int n0, ty0, tx0, fb;
@@ -935,7 +940,7 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     // PG == 4: 8 waves of 64 pixels x 64 filters.  PG == 2: 8 waves of 32 x 64 (two per SIMD; four waves of
     // 64 x 64, one per SIMD, left the operand latency of every step exposed)
     constexpr int NCW = spatial_waves(PG), S = PG == 2 ? 2 : 4, NB = 2 * S;
-    constexpr int kSpatialThreads = spatial_threads(PG);
+    constexpr int kSpatialThreads = spatial_threads(PG), kSpatialFetchWaves = spatial_fetch_waves(PG);
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lbase = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -1109,11 +1114,8 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
             const bool more_items = c_item + nwg < nitems;
             for (int st = 0; st < nch * T; ++st) {
                 // at most the D-2 stages issued after the one about to be multiplied stay in flight
-                static_assert(kImgs == 4, "the waits below count 4 loads per stage");
-                if (D == 3) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                else if (D == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-                else if (D == 5) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+                static_assert(kImgs * 4 <= 63, "a wave can have 63 loads in flight");
+                wait_vmcnt((uint32_t)kImgs * (D - 2u));
                 __builtin_amdgcn_s_barrier();
                 produce_w(); // the stage D-1 ahead, into the slot the barrier freed
             }
