@@ -98,6 +98,8 @@ EDGE = [
     # pixel group of a tile holds 8 pixels), and 100 of 256 become 200 of 128 (two pixel groups empty)
     ("pointwise_tiles_of_200_pixels", 1, 112, 112, 64, 512, 1, 1, 1, 0, 8, 4, 3, dtypes.BF16, 1, True, True),
     ("pointwise_tiles_of_128_pixels", 2, 80, 80, 64, 256, 1, 1, 1, 0, 8, 4, 2, dtypes.BF16, 2, True, False),
+    # 50 items of 256 x 128: too few; 392 of 64 x 64 would take two rounds, 98 of 128 x 128 take one
+    ("pointwise_medium_tiles_instead_of_small", 32, 14, 14, 256, 256, 1, 1, 1, 0, 8, 4, 3, dtypes.BF16, 1, False, True),
 ]
 
 
