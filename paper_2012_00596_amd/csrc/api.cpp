@@ -380,7 +380,10 @@ static Route choose_route(const npas_packed *p, int N, int H, int W, int stride,
         // up to 256 output pixels (batch 1 from the 14 x 14 stage on, FC layers) the kernel that splits the
         // reduction over a workgroup's waves is faster than the ring's smallest tiles (measured layer by layer)
         const long Ho1 = (H - 1) / stride + 1, Wo1 = (W - 1) / stride + 1;
-        if ((long)N * Ho1 * Wo1 <= 256) return R_SMALLM;
+        // (beyond that while its workgroups, 64 pixels x 16 filters each, still fit one round: 2048 -> 512 at 7 x 7,
+        // batch 8: 18.4 -> 11.6 us; with more workgroups than that it loses, 512 -> 2048 at the same size: 9.3 -> 21 us)
+        const long M1 = (long)N * Ho1 * Wo1;
+        if (M1 <= 256 || (p->C >= 1024 && ((M1 + 63) / 64) * ((p->F + 15) / 16) <= 256)) return R_SMALLM; // (and the reduction long)
         return R_POINTWISE_RING;
     }
     {
