@@ -170,6 +170,9 @@ def test_kernel_choice_follows_layer_and_launch_shape():
     assert name(p, 128, 56, 56, 1, 0) == "pointwise_ring"
     assert name(p, 1, 14, 14, 1, 0) == "conv_smallm_mfma"        # up to 256 output pixels
     assert name(p, 1, 56, 56, 1, 0) == "pointwise_ring"
+    p = _bp_layer(1024, 256, 1, 46)
+    assert name(p, 8, 7, 7, 1, 0) == "conv_smallm_mfma"          # long reduction, 7 x 16 workgroups: one round
+    assert name(p, 32, 14, 14, 1, 0) == "pointwise_ring"
     p = _bp_layer(3, 64, 7, 44)
     assert name(p, 2, 224, 224, 2, 3) == "conv_smallc_mfma"      # fewer than 8 input channels
     p = _bp_layer(24, 144, 1, 45, rate=4)
