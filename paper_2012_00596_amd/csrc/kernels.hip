@@ -612,11 +612,14 @@ template <int DT> static int launch_slab_dt(const ConvMfmaArgs &a, unsigned grid
 // Three configurations: 256 x 128 tiles with a 3-stage ring (throughput: most bytes in flight
 // per CU, most reuse of the weights); 64 x 64 tiles with an 8-stage ring for launches that
 // would leave most CUs without a tile (small batches): more, smaller items, and a whole
-// layer's channel loop in flight at once instead of one load latency per stage; 128 x 128
+// layer's channel loop in flight at once instead of one load latency per stage (its tile is
+// multiplied by four waves of 16 pixels x 64 filters, one per SIMD: such a launch is a chain of
+// stage latencies, and four short chains of 8 MFMAs beat one of 32); 128 x 128
 // tiles with a 4-stage ring in between, when the 256 x 128 items divide badly over the CUs.
-template <int PW_, int FW_, int XW_, int WW_, int D_> struct PointwiseCfg {
-    static constexpr int PW = PW_, FW = FW_, XW = XW_, WW = WW_, D = D_;
-    static constexpr int kComputeWaves = PW * FW;
+// S: 16-pixel blocks of a multiplying wave (4: 64 pixels x 64 filters; fewer: more, narrower waves per tile)
+template <int PW_, int FW_, int XW_, int WW_, int D_, int S_ = 4> struct PointwiseCfg {
+    static constexpr int PW = PW_, FW = FW_, XW = XW_, WW = WW_, D = D_, S = S_;
+    static constexpr int kComputeWaves = PW * FW * (4 / S);
     static constexpr int kThreads = (kComputeWaves + XW + WW) * 64;
     static constexpr uint32_t kXBytes = PW * 8192, kWBytes = FW * 8192, kStageBytes = kXBytes + kWBytes;
     static constexpr int kXBlocks = PW * 8, kWImages = FW * 8;             // 1 KB loads per stage
@@ -625,7 +628,7 @@ template <int PW_, int FW_, int XW_, int WW_, int D_> struct PointwiseCfg {
     static_assert(D >= 3 && kXLoads * (D - 1) <= 63 && kWLoads * (D - 1) <= 63, "a wave can have 63 loads in flight");
 };
 using PointwiseBig = PointwiseCfg<4, 2, 3, 1, 3>;
-using PointwiseSmall = PointwiseCfg<1, 1, 4, 4, 8>;
+using PointwiseSmall = PointwiseCfg<1, 1, 4, 4, 8, 1>;
 using PointwiseMedium = PointwiseCfg<2, 2, 2, 1, 4>; // 128 x 128 tiles, 4-stage ring: half-size items for layers whose 256 x 128 items divide badly over the CUs
 
 __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
@@ -669,7 +672,7 @@ __device__ __forceinline__ PointwiseItem pointwise_item(uint32_t nfb, uint32_t i
 template <int DT, typename Cfg>
 __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs a)
 {
-    constexpr int PW = Cfg::PW, FW = Cfg::FW, XW = Cfg::XW, WW = Cfg::WW, D = Cfg::D, NC = Cfg::kComputeWaves;
+    constexpr int PW = Cfg::PW, FW = Cfg::FW, XW = Cfg::XW, WW = Cfg::WW, D = Cfg::D, NC = Cfg::kComputeWaves, S = Cfg::S;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lbase = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -799,7 +802,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
     uint8_t *yb = reinterpret_cast<uint8_t *>(a.y);
     const uint8_t *rb = reinterpret_cast<const uint8_t *>(a.residual);
     const Clamp cl = clamp_of(a.act);
-    const uint32_t brow = (uint32_t)((wp * 64 + n16) * 128), arow = (uint32_t)(wf * 4) * 1024u + (uint32_t)lane * 16u;
+    const uint32_t brow = (uint32_t)((wp * (16 * S) + n16) * 128), arow = (uint32_t)(wf * 4) * 1024u + (uint32_t)lane * 16u;
     uint32_t c_slot = 0, bbuf = 0;
     for (;;) { // one item per iteration
         const PointwiseItem it = pointwise_item(nfb, c_item);
@@ -808,22 +811,22 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
         // is pixel 16s + 4q + i, filter 4 n16 + j.  A lane therefore owns 4 consecutive filters
         // of a pixel, and the 16 lanes of a quarter wave one whole 128-byte run of its row.
         const int fcol = (int)it.fb * (FW * 64) + wf * 64 + 4 * n16;
-        const uint32_t ml = (uint32_t)(wp * 64 + 4 * q), m0 = it.ptile * (uint32_t)a.P + ml; // first pixel: in the tile, of all
+        const uint32_t ml = (uint32_t)(wp * (16 * S) + 4 * q), m0 = it.ptile * (uint32_t)a.P + ml; // first pixel: in the tile, of all
         const uint32_t obase = (m0 * (uint32_t)a.F + (uint32_t)fcol) * 2u; // byte offset of (pixel m0, filter fcol)
         // valid pixels from m0 on: to the end of the tile's P pixels (rows past them hold other tiles' pixels or stale data) and of the map
         const uint32_t rows_left = fcol < a.F && m0 < (uint32_t)a.M && ml < (uint32_t)a.P ? min((uint32_t)a.M - m0, (uint32_t)a.P - ml) : 0u;
-        f32x4 acc[4][4];
+        f32x4 acc[4][S];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
-        uint2 res[4][4]; // [s][i]
+            for (int s = 0; s < S; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        uint2 res[S][4]; // [s][i]
         for (int t = 0; t < nst; ++t) {
             __builtin_amdgcn_s_barrier(); // this stage has landed; everyone is done with the stage before
             asm volatile("" ::: "memory");
             if (rb && t == 0) { // residual: asked for at the item's first stage, used after its last
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
+                for (int s = 0; s < S; ++s) {
                     uint32_t ob = obase;
                     asm volatile("" : "+v"(ob)); // keeps the 16 addresses from being formed (and held) outside the loop
 #pragma unroll
@@ -837,15 +840,15 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
             if (++c_slot == (uint32_t)D) c_slot = 0;
 #pragma unroll
             for (int step = 0; step < 2; ++step) {
-                uint4 A[4], B[4];
+                uint4 A[4], B[S];
                 const uint8_t *ap = sb + Cfg::kXBytes + (uint32_t)(step * FW * 4) * 1024u + arow;
                 const uint8_t *bp = sb + brow + (uint32_t)(((step * 4 + q) ^ (n16 & 7)) * 16);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) A[j] = *reinterpret_cast<const uint4 *>(ap + j * 1024);
 #pragma unroll
-                for (int s = 0; s < 4; ++s) B[s] = *reinterpret_cast<const uint4 *>(bp + s * 2048);
+                for (int s = 0; s < S; ++s) B[s] = *reinterpret_cast<const uint4 *>(bp + s * 2048);
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
+                for (int s = 0; s < S; ++s)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) acc[j][s] = mfma16<DT>(B[s], A[j], acc[j][s]);
             }
@@ -854,7 +857,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
         float4 bv = float4{0.f, 0.f, 0.f, 0.f};
         if (a.bias) bv = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 4 * n16) * 4u);
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < S; ++s)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if ((uint32_t)(16 * s + i) >= rows_left) continue;
