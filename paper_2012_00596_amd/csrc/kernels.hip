@@ -629,7 +629,7 @@ template <int PW_, int FW_, int XW_, int WW_, int D_, int S_ = 4> struct Pointwi
 };
 using PointwiseBig = PointwiseCfg<4, 2, 3, 1, 3>;
 using PointwiseSmall = PointwiseCfg<1, 1, 4, 4, 8, 1>;
-using PointwiseMedium = PointwiseCfg<2, 2, 2, 1, 4>; // 128 x 128 tiles, 4-stage ring: half-size items for layers whose 256 x 128 items divide badly over the CUs
+using PointwiseMedium = PointwiseCfg<2, 2, 2, 1, 4, 2>; // 128 x 128 tiles, 4-stage ring: half-size items for layers whose 256 x 128 items divide badly over the CUs
 
 __device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
 {
