@@ -208,7 +208,7 @@ def time_stack(w, reps, torch, npas, helpers, fuse=True, graph=False):
     N, H, W, C = w.x_shape
     packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
     st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W,
-                    npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL if fuse else 0)
+                    npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL | npas.STACK_FUSE_CONV_MAXPOOL if fuse else 0)
     wsb = st.workspace_bytes(N)
     x = helpers.to_dev(w.x_store, torch)
     shapes = {0: w.x_shape}

@@ -18,6 +18,7 @@ SCHEME_BLOCK_PUNCHED, SCHEME_FC_BLOCK, SCHEME_PATTERN, SCHEME_DEPTHWISE = 0, 1, 
 LAYER_CONV, LAYER_FC, LAYER_MAXPOOL3X3S2, LAYER_GLOBAL_AVGPOOL, LAYER_DEPTHWISE3X3 = 0, 1, 2, 3, 4
 STACK_FUSE_POINTWISE = 1
 STACK_FUSE_INVERTED_RESIDUAL = 2
+STACK_FUSE_CONV_MAXPOOL = 4
 OK, E_NULL, E_SHAPE, E_MASK_NOT_BLOCK_UNIFORM, E_MASK_NOT_IN_LIBRARY, E_DTYPE, E_WORKSPACE, E_HIP, E_MASK_VALUE = \
     0, -1, -2, -3, -4, -5, -6, -7, -8
 

@@ -351,6 +351,7 @@ static bool plan_smallc(const npas_packed *p, int N, int H, int W, int stride, i
         }
     }
     if (best < 0) return false;
+    a->pool = 0; a->PTH = a->PTW = a->PHo = a->PWo = 0; a->div_ptw = 0;
     a->N = N; a->H = H; a->W = W; a->C = p->C; a->F = p->F; a->Ho = Ho; a->Wo = Wo;
     a->KH = p->KH; a->KW = p->KW; a->stride = stride; a->pad = pad;
     a->K = p->C * p->KH * p->KW; a->nsteps = p->smallc.nsteps;
@@ -363,6 +364,51 @@ static bool plan_smallc(const npas_packed *p, int N, int H, int W, int stride, i
     a->div_tiles = magic_div((uint32_t)(a->tilesY * a->tilesX));
     a->div_tx = magic_div((uint32_t)a->tilesX);
     return true;
+}
+
+// The same kernel with the 3 x 3 / stride 2 / pad 1 max pool that follows done inside it: tiles of 8 x 7 pooled
+// pixels = 17 x 15 conv pixels (255 of the kernel's 256 operand rows; neighbouring tiles share one conv row and
+// column, 14 % more multiplies for a conv output that never reaches memory).
+static bool plan_smallc_pool(const npas_packed *p, int N, int H, int W, int stride, int pad, SmallCArgs *a)
+{
+    const int Ho = (H + 2 * pad - p->KH) / stride + 1, Wo = (W + 2 * pad - p->KW) / stride + 1;
+    if (!p->smallc.present || Ho <= 0 || Wo <= 0) return false;
+    std::memset(a, 0, sizeof *a);
+    a->pool = 1; a->PTH = 8; a->PTW = 7;
+    a->PHo = (Ho - 1) / 2 + 1; a->PWo = (Wo - 1) / 2 + 1;
+    a->TH = 2 * a->PTH + 1; a->TW = 2 * a->PTW + 1;
+    a->tilesY = (a->PHo + a->PTH - 1) / a->PTH; a->tilesX = (a->PWo + a->PTW - 1) / a->PTW;
+    a->PH = (a->TH - 1) * stride + p->KH; a->PW = (a->TW - 1) * stride + p->KW;
+    a->pitch = (a->PW * p->C * 2 + 3) / 4 * 4 + 4;
+    if ((long)a->PH * a->pitch > 48 * 1024 || (long)a->PH * a->PW * p->C > 256 * 24) return false;
+    a->N = N; a->H = H; a->W = W; a->C = p->C; a->F = p->F; a->Ho = Ho; a->Wo = Wo;
+    a->KH = p->KH; a->KW = p->KW; a->stride = stride; a->pad = pad;
+    a->K = p->C * p->KH * p->KW; a->nsteps = p->smallc.nsteps;
+    a->nitems = (uint32_t)N * (uint32_t)(a->tilesY * a->tilesX);
+    a->div_tw = magic_div((uint32_t)a->TW);
+    a->div_ptw = magic_div((uint32_t)a->PTW);
+    a->div_kwc = magic_div((uint32_t)(p->KW * p->C));
+    a->div_rowlen = magic_div((uint32_t)(a->PW * p->C));
+    a->row2 = (a->PW * p->C + 2) / 2;
+    a->div_row2 = magic_div((uint32_t)a->row2);
+    a->div_tiles = magic_div((uint32_t)(a->tilesY * a->tilesX));
+    a->div_tx = magic_div((uint32_t)a->tilesX);
+    return true;
+}
+
+// conv (small-channel kernel) + max pool 3 x 3 / 2 as one launch; y is the pooled tensor
+int run_conv_maxpool(const npas_packed *p, const void *x, void *y, int N, int H, int W, int stride, int pad, const void *bias,
+                     int act, void *stream)
+{
+    SmallCArgs sc;
+    if (!plan_smallc_pool(p, N, H, W, stride, pad, &sc)) {
+        set_error("conv + max pool: the layer does not fit the small-channel kernel");
+        return NPAS_E_SHAPE;
+    }
+    sc.x = x; sc.y = y; sc.residual = nullptr; sc.bias = (const float *)bias;
+    sc.wimg = p->dev.scimg;
+    sc.act = act;
+    return launch_conv_smallc(p->dtype, sc, stream);
 }
 
 static Route choose_route(const npas_packed *p, int N, int H, int W, int stride, int pad, SpatialRingArgs *sp,
@@ -570,6 +616,7 @@ struct npas_stack {
         int fpp_nt1 = 0;                  // live intermediate tiles of that pair
         uint32_t fpp_use[2] = {0, 0};     // chunk masks of that pair
         bool fused_away = false;          // second layer of a fused pair: runs inside the first
+        bool pool_fused = false;          // conv whose max pool (the next layer) is done in the same kernel
         // first layer of a fused 1x1 -> depthwise 3x3 -> 1x1 block: device images and tile
         const void *ir_w1 = nullptr, *ir_w3 = nullptr;
         const uint32_t *ir_wdw = nullptr;
@@ -608,7 +655,7 @@ static size_t place_tensors(const npas_stack *s, int N, std::vector<size_t> *off
     size_t total = 0;
     const int esz = dtype_size(s->dtype);
     for (int t = 1; t < nt - 1; ++t) { // tensor t is written by layer t-1
-        if (s->nodes[t - 1].fused_blob || s->nodes[t - 1].ir_w1) continue; // intermediate of a fused pair / block never reaches memory
+        if (s->nodes[t - 1].fused_blob || s->nodes[t - 1].ir_w1 || s->nodes[t - 1].pool_fused) continue; // intermediate of a fused pair / block never reaches memory
         if (t >= 2 && s->nodes[t - 2].ir_w1) continue;                      // nor does the second one of a fused block
         sz[t] = (tensor_elems_per_image(s, t) * N * esz + 255) / 256 * 256;
         // drop tensors whose last reader ran before layer t-1
@@ -1030,6 +1077,19 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             c.fused_away = true;
         }
     }
+    if (flags & NPAS_STACK_FUSE_CONV_MAXPOOL) {
+        for (int i = 0; i + 1 < n_layers; ++i) {
+            npas_stack::Node &a = s->nodes[i], &b = s->nodes[i + 1];
+            if (a.fused_away || a.d.kind != NPAS_LAYER_CONV || b.d.kind != NPAS_LAYER_MAXPOOL3X3S2 || b.d.src != i + 1 || a.d.res >= 0) continue;
+            bool other_reader = false;
+            for (int j = i + 1; j < n_layers; ++j)
+                if ((j != i + 1 && s->nodes[j].d.src == i + 1) || s->nodes[j].d.res == i + 1) other_reader = true;
+            SmallCArgs sc;
+            if (other_reader || !plan_smallc_pool(a.d.packed, 1, a.H, a.W, a.d.stride, a.d.pad, &sc)) continue;
+            a.pool_fused = true;
+            b.fused_away = true;
+        }
+    }
     if (flags & NPAS_STACK_FUSE_POINTWISE) {
         int ndev = 0;
         bool have_dev = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
@@ -1127,6 +1187,12 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
                 rc = launch_fused_inverted_residual(p1->dtype, x, tensor(i + 3), n.ir_w1, n.ir_w3, n.ir_wdw, N, n.H, n.W, p1->C,
                                                     p3->F, n.ir_nslots, n.ir_TH, n.ir_TW, n.d.act, s->nodes[i + 1].d.act,
                                                     s->nodes[i + 2].d.act, n.ir_residual, hip_stream);
+            if (rc) return rc;
+            continue;
+        }
+        if (n.pool_fused) { // this layer and the max pool after it as one kernel; the conv output is never stored
+            rc = check_run(n.d.packed, x, tensor(i + 2), N, n.H, n.W, n.d.stride, n.d.pad);
+            if (!rc) rc = run_conv_maxpool(n.d.packed, x, tensor(i + 2), N, n.H, n.W, n.d.stride, n.d.pad, n.d.bias_dev, n.d.act, hip_stream);
             if (rc) return rc;
             continue;
         }

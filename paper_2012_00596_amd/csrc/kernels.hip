@@ -1586,13 +1586,17 @@ int launch_conv_mfma(int dtype, int variant, const ConvMfmaArgs &a, unsigned gri
 // otherwise value by value.
 constexpr int kSmallCLoads = 24;
 
-template <int DT, int NS, bool WIDE>
-__global__ __launch_bounds__(256) void conv_smallc_mfma_kernel(SmallCArgs a)
+// POOL: the layer is followed by a 3 x 3 / stride 2 / pad 1 max pool.  The tile's conv outputs (after bias,
+// activation and rounding; positions outside the conv output as -inf) go to LDS instead of memory, and the
+// workgroup then writes the pooled pixels that lie wholly inside the tile: the conv output never reaches HBM.
+template <int DT, int NS, bool WIDE, bool POOL>
+__global__ __launch_bounds__(256, POOL ? 2 : 1) void conv_smallc_mfma_kernel(SmallCArgs a) // (two waves per SIMD: 256 registers; left alone the pooled variant takes 264 and one workgroup per CU)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
     const uint16_t *x16 = reinterpret_cast<const uint16_t *>(a.x);
     uint16_t *lds16 = reinterpret_cast<uint16_t *>(lds);
+    uint8_t *ctile = lds + (((uint32_t)(a.PH * a.pitch) + 15u) & ~15u); // POOL: the tile's conv outputs, 256 x 128 B
     const Clamp cl = clamp_of(a.act);
 
     uint4 wreg[NS][4];
@@ -1630,7 +1634,8 @@ __global__ __launch_bounds__(256) void conv_smallc_mfma_kernel(SmallCArgs a)
     auto fetch_patch = [&](uint32_t item) __attribute__((always_inline)) {
         const uint32_t n = fastdiv(item, a.div_tiles), trem = item - n * tiles_img;
         const uint32_t tyi = fastdiv(trem, a.div_tx), txi = trem - tyi * (uint32_t)a.tilesX;
-        const int iy0 = (int)tyi * a.TH * a.stride - a.pad, ixe0 = ((int)txi * a.TW * a.stride - a.pad) * a.C; // first row, first value of a row
+        const int fy0 = POOL ? 2 * (int)tyi * a.PTH - 1 : (int)tyi * a.TH, fx0 = POOL ? 2 * (int)txi * a.PTW - 1 : (int)txi * a.TW; // the tile's first conv pixel
+        const int iy0 = fy0 * a.stride - a.pad, ixe0 = (fx0 * a.stride - a.pad) * a.C; // first row, first value of a row
         const uint16_t *xn = x16 + (size_t)n * a.H * (size_t)(a.W * a.C);
 #pragma unroll
         for (int i = 0; i < NPV; ++i) {
@@ -1653,7 +1658,7 @@ __global__ __launch_bounds__(256) void conv_smallc_mfma_kernel(SmallCArgs a)
     while (item < a.nitems) {
         const uint32_t n = fastdiv(item, a.div_tiles), trem = item - n * tiles_img;
         const uint32_t tyi = fastdiv(trem, a.div_tx), txi = trem - tyi * (uint32_t)a.tilesX;
-        const int ty0 = (int)tyi * a.TH, tx0 = (int)txi * a.TW;
+        const int ty0 = POOL ? 2 * (int)tyi * a.PTH - 1 : (int)tyi * a.TH, tx0 = POOL ? 2 * (int)txi * a.PTW - 1 : (int)txi * a.TW;
         __syncthreads(); // the tile before has been read
 #pragma unroll
         for (int i = 0; i < NPV; ++i) {
@@ -1668,7 +1673,7 @@ __global__ __launch_bounds__(256) void conv_smallc_mfma_kernel(SmallCArgs a)
         }
         __syncthreads();
         // WIDE: the tile's first value sits one value into its LDS rows when it is an odd one
-        const uint32_t phase2 = WIDE ? (uint32_t)((((int)txi * a.TW * a.stride - a.pad) * a.C) & 1) * 2u : 0u;
+        const uint32_t phase2 = WIDE ? (uint32_t)(((tx0 * a.stride - a.pad) * a.C) & 1) * 2u : 0u;
         const uint32_t next = item + gridDim.x;
         if (next < a.nitems) fetch_patch(next); // lands while this tile is multiplied
 #pragma unroll 1
@@ -1703,6 +1708,17 @@ __global__ __launch_bounds__(256) void conv_smallc_mfma_kernel(SmallCArgs a)
                     ++oty;
                 }
                 const int oy = ty0 + (int)oty, ox = tx0 + (int)otx;
+                if (POOL) { // to the tile in LDS: [tile pixel][64 filters]
+                    const bool valid = (int)oty < a.TH && (uint32_t)oy < (uint32_t)a.Ho && (uint32_t)ox < (uint32_t)a.Wo && fcol < a.F;
+                    const uint32_t ninf = DT == NPAS_BF16 ? 0xff80ff80u : 0xfc00fc00u; // -inf, -inf
+                    uint2 out{ninf, ninf};
+                    if (valid) {
+                        out.x = pack2<DT>(clampf(acc[0][i], cl), clampf(acc[1][i], cl));
+                        out.y = pack2<DT>(clampf(acc[2][i], cl), clampf(acc[3][i], cl));
+                    }
+                    *reinterpret_cast<uint2 *>(ctile + (m0 + (uint32_t)i) * 128u + (uint32_t)n16 * 8u) = out;
+                    continue;
+                }
                 if (oy >= a.Ho || ox >= a.Wo || fcol >= a.F) continue;
                 const size_t o = (((size_t)n * a.Ho + (size_t)oy) * a.Wo + (size_t)ox) * (size_t)a.F + (size_t)fcol;
                 float v[4] = {acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
@@ -1717,6 +1733,41 @@ __global__ __launch_bounds__(256) void conv_smallc_mfma_kernel(SmallCArgs a)
                 out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
                 out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
                 *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o) = out;
+            }
+        }
+        if (POOL) {
+            __syncthreads(); // the tile's conv outputs are in LDS
+            // thread = (pooled pixel of the tile, 16 filters): the maximum over its 3 x 3 window of conv pixels
+            const uint32_t pp = (uint32_t)tid >> 2, f0 = (uint32_t)(tid & 3) * 16u;
+            const uint32_t pty = fastdiv(pp, a.div_ptw), ptx = pp - pty * (uint32_t)a.PTW;
+            const int py = (int)tyi * a.PTH + (int)pty, px = (int)txi * a.PTW + (int)ptx;
+            if ((int)pty < a.PTH && py < a.PHo && px < a.PWo) {
+                uint16_t *dst = reinterpret_cast<uint16_t *>(a.y) + (((size_t)n * a.PHo + (size_t)py) * a.PWo + (size_t)px) * (size_t)a.F + f0;
+#pragma unroll 1
+                for (uint32_t hf = 0; hf < 2; ++hf) { // 8 filters at a time: the main loop's registers stay live across this
+                    if ((int)(f0 + 8u * hf) >= a.F) break;
+                    float mx[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) mx[e] = -INFINITY;
+#pragma unroll
+                    for (int d = 0; d < 9; ++d) {
+                        const uint32_t cm = (2u * pty + (uint32_t)(d / 3)) * (uint32_t)a.TW + 2u * ptx + (uint32_t)(d % 3);
+                        const uint4 v = *reinterpret_cast<const uint4 *>(ctile + cm * 128u + f0 * 2u + hf * 16u);
+                        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            mx[2 * e] = fmaxf(mx[2 * e], from_storage<DT>((uint16_t)(w[e] & 0xffffu)));
+                            mx[2 * e + 1] = fmaxf(mx[2 * e + 1], from_storage<DT>((uint16_t)(w[e] >> 16)));
+                        }
+                    }
+                    uint2 o0, o1; // F is a multiple of 4: the second 4 filters may lie past it
+                    o0.x = pack2<DT>(mx[0], mx[1]);
+                    o0.y = pack2<DT>(mx[2], mx[3]);
+                    o1.x = pack2<DT>(mx[4], mx[5]);
+                    o1.y = pack2<DT>(mx[6], mx[7]);
+                    *reinterpret_cast<uint2 *>(dst + 8 * hf) = o0;
+                    if ((int)(f0 + 8u * hf + 4u) < a.F) *reinterpret_cast<uint2 *>(dst + 8 * hf + 4) = o1;
+                }
             }
         }
         item = next;
@@ -1751,8 +1802,11 @@ template <int DT> static int launch_smallc_dt(const SmallCArgs &a, size_t lds_by
     const bool wide = (a.W * a.C) % 2 == 0;
 #define NPAS_SC(N_)                                                                        \
     case N_:                                                                               \
-        if (wide) launch_smallc_inst(conv_smallc_mfma_kernel<DT, N_, true>, a, lds_bytes, st); \
-        else launch_smallc_inst(conv_smallc_mfma_kernel<DT, N_, false>, a, lds_bytes, st);     \
+        if (a.pool) {                                                                      \
+            if (wide) launch_smallc_inst(conv_smallc_mfma_kernel<DT, N_, true, true>, a, lds_bytes, st); \
+            else launch_smallc_inst(conv_smallc_mfma_kernel<DT, N_, false, true>, a, lds_bytes, st);     \
+        } else if (wide) launch_smallc_inst(conv_smallc_mfma_kernel<DT, N_, true, false>, a, lds_bytes, st); \
+        else launch_smallc_inst(conv_smallc_mfma_kernel<DT, N_, false, false>, a, lds_bytes, st);     \
         break;
     switch (a.nsteps) {
         NPAS_SC(1) NPAS_SC(2) NPAS_SC(3) NPAS_SC(4) NPAS_SC(5)
@@ -1765,8 +1819,11 @@ template <int DT> static int launch_smallc_dt(const SmallCArgs &a, size_t lds_by
 int launch_conv_smallc(int dtype, const SmallCArgs &a, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds_bytes = (size_t)a.PH * a.pitch;
-    if (a.TH * a.TW != 256 || lds_bytes > 48 * 1024 || a.PH * a.PW * a.C > 256 * kSmallCLoads ||
+    const size_t patch_bytes = (size_t)a.PH * a.pitch;
+    const size_t lds_bytes = a.pool ? ((patch_bytes + 15) & ~(size_t)15) + 256 * 128 : patch_bytes;
+    const bool pool_ok = !a.pool || (a.TH == 2 * a.PTH + 1 && a.TW == 2 * a.PTW + 1 && a.TH * a.TW <= 256 && a.PTH * a.PTW <= 64 &&
+                                    !a.residual && a.PHo > 0 && a.PWo > 0);
+    if ((a.pool ? !pool_ok : a.TH * a.TW != 256) || patch_bytes > 48 * 1024 || a.PH * a.PW * a.C > 256 * kSmallCLoads ||
         a.PH * a.row2 > 128 * kSmallCLoads || a.row2 * 4 > a.pitch || a.F > 64 || a.F % 4 != 0 || a.K > 32 * a.nsteps || a.K < 1) {
         set_error("conv_smallc_mfma: plan does not fit the kernel");
         return NPAS_E_SHAPE;

@@ -191,6 +191,11 @@ struct SmallCArgs {
     int row2;                       // 4-byte words staged per patch row when rows are fetched as words
     uint32_t nitems;                // N * tilesY * tilesX
     uint32_t div_tw, div_kwc, div_rowlen, div_row2, div_tiles, div_tx; // fastdiv magics
+    // pool != 0: a 3 x 3 / stride 2 / pad 1 max pool follows and is done in the same kernel; y is the pooled
+    // tensor (N x PHo x PWo x F).  A tile is then PTH x PTW pooled pixels = (2 PTH + 1) x (2 PTW + 1) conv pixels
+    // (TH x TW, at most 256) starting one conv row / column before 2 x the pooled origin.
+    int pool, PTH, PTW, PHo, PWo;
+    uint32_t div_ptw;
 };
 
 // k x k layer on few output pixels (small batch, small maps): see conv_smallm_mfma_kernel

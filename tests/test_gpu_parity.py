@@ -283,7 +283,7 @@ def test_run_stack_in_a_hip_graph_replays_like_the_eager_call(npas, torch):
     w = configs.config5(batch=2, HW=32, width=16, blocks=(1, 1, 1, 1))
     packed = [pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
     st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), w.x_shape[1], w.x_shape[2],
-                    npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL)
+                    npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL | npas.STACK_FUSE_CONV_MAXPOOL)
     N = w.x_shape[0]
     shapes = {0: w.x_shape}
     for i, L in enumerate(w.layers):
@@ -456,7 +456,7 @@ def test_fp16_storage_through_the_fused_kernels_and_the_pointwise_ring(npas, tor
 def test_config5_run_stack_end_to_end(npas, torch):
     print("config5 reduced run_stack", flush=True)
     w = configs.config5(batch=2, HW=64, width=16)
-    got, st = _run_stack_gpu(npas, torch, w)
+    got, st = _run_stack_gpu(npas, torch, w, npas.STACK_FUSE_CONV_MAXPOOL)
     rounded, _ = oracle.run_stack(w.x_exact, w.layers, w.dtype)
     ref = rounded[-1]
     norm_err = np.abs(got - ref).max() / np.abs(ref).max()
@@ -464,6 +464,37 @@ def test_config5_run_stack_end_to_end(npas, torch):
     # 50+ bf16 layers: element-wise 1e-2 cannot hold end to end (roundings compound), the norm-wise bound must
     assert norm_err <= 1e-2 * np.sqrt(len(w.layers))
     assert (got.argmax(1) == ref.argmax(1)).all()
+
+
+STEM_POOL = [
+    # name, N, H, W, C, F, k, stride, pad, block channels, act, dtype
+    ("stem7x7_ragged", 3, 37, 41, 3, 64, 7, 2, 3, 3, configs.ACT_RELU, dtypes.BF16),
+    ("stem7x7_no_activation_fp16", 2, 64, 64, 3, 40, 7, 2, 3, 3, configs.ACT_NONE, dtypes.F16),
+    ("conv3x3_stride1_4_channels", 2, 30, 33, 4, 32, 3, 1, 1, 4, configs.ACT_RELU6, dtypes.BF16),
+    ("more_tiles_than_workgroups", 9, 224, 224, 3, 64, 7, 2, 3, 3, configs.ACT_RELU, dtypes.BF16),
+]
+
+
+@pytest.mark.parametrize("case", STEM_POOL, ids=[c[0] for c in STEM_POOL])
+def test_conv_and_maxpool_as_one_kernel(npas, torch, case):
+    """A small-channel conv and the 3x3 / stride 2 max pool after it, one launch (NPAS_STACK_FUSE_CONV_MAXPOOL): the
+    pooled tensor against the oracle's conv -> round -> max pool, and against the two-launch stack bit for bit."""
+    name, N, H, W, C, F, k, stride, pad, Bc, act, dtype = case
+    print(f"conv+maxpool {name}", flush=True)
+    xs, xe = configs._tensor(77, 1, (N, H, W, C), 1.0, dtype)
+    layers = [configs._bp_conv(77, 0, C, F, k, stride, pad, 8, Bc, 2, 0.2, dtype, act, 0, -1, "stem"),
+              configs.Layer("maxpool", src=1, C=F, F=F, KH=3, KW=3, stride=2, pad=1, name="maxpool")]
+    w = configs.Workload("stem_pool", dtype, (N, H, W, C), xs, xe, layers)
+    fused, st = _run_stack_gpu(npas, torch, w, npas.STACK_FUSE_CONV_MAXPOOL)
+    plain, st0 = _run_stack_gpu(npas, torch, w, 0)
+    assert st.num_launches() == 1 and st0.num_launches() == 2
+    assert st.workspace_bytes(N) == 0
+    np.testing.assert_array_equal(fused, plain)
+    if N * H * W <= 64 * 64 * 4:
+        rounded, _ = oracle.run_stack(xe, layers, dtype)
+        err = rel_err(fused, rounded[-1])
+        print(f"  err={err:.3e}", flush=True)
+        assert err <= TOL[dtype]
 
 
 def test_full_size_config2_sampled(npas, torch):
