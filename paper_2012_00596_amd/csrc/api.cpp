@@ -342,7 +342,7 @@ static bool plan_smallc(const npas_packed *p, int N, int H, int W, int stride, i
         const int tw = 256 / th;
         const int ph = (th - 1) * stride + p->KH, pw = (tw - 1) * stride + p->KW;
         const int pitch = (pw * p->C * 2 + 3) / 4 * 4 + 4;
-        if ((long)ph * pitch > 48 * 1024 || (long)ph * pw * p->C > 256 * 24) continue; // LDS, and 24 staged values per thread
+        if ((long)ph * pitch > 48 * 1024 || (long)ph * pw * p->C > 256 * 24 || (long)ph * ((pw * p->C + 2) / 2) > 128 * 24) continue; // LDS, and 24 staged values (12 words) per thread
         const int ty = (Ho + th - 1) / th, tx = (Wo + tw - 1) / tw;
         const long cost = (long)ty * tx * 4096 + std::abs(th - tw); // tiles first, then the squarer shape (smaller patch)
         if (best < 0 || cost < best) {
@@ -380,7 +380,7 @@ static bool plan_smallc_pool(const npas_packed *p, int N, int H, int W, int stri
     a->tilesY = (a->PHo + a->PTH - 1) / a->PTH; a->tilesX = (a->PWo + a->PTW - 1) / a->PTW;
     a->PH = (a->TH - 1) * stride + p->KH; a->PW = (a->TW - 1) * stride + p->KW;
     a->pitch = (a->PW * p->C * 2 + 3) / 4 * 4 + 4;
-    if ((long)a->PH * a->pitch > 48 * 1024 || (long)a->PH * a->PW * p->C > 256 * 24) return false;
+    if ((long)a->PH * a->pitch > 48 * 1024 || (long)a->PH * a->PW * p->C > 256 * 24 || (long)a->PH * ((a->PW * p->C + 2) / 2) > 128 * 24) return false;
     a->N = N; a->H = H; a->W = W; a->C = p->C; a->F = p->F; a->Ho = Ho; a->Wo = Wo;
     a->KH = p->KH; a->KW = p->KW; a->stride = stride; a->pad = pad;
     a->K = p->C * p->KH * p->KW; a->nsteps = p->smallc.nsteps;
