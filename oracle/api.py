@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "npas_oracle.c")
 _LIB = os.path.join(_HERE, "libnpas_oracle.so")
 
-ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
+ACT_NONE, ACT_RELU, ACT_RELU6, ACT_HARDSWISH = 0, 1, 2, 3
 F32, BF16, F16 = 0, 1, 2
 
 

@@ -32,12 +32,19 @@
 #endif
 
 enum { ORACLE_OK = 0, ORACLE_E_ARG = -1, ORACLE_E_MASK = -2 };
-enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2 };
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_HARDSWISH = 3 };
 
+/* Activations of the paper's networks: ReLU / ReLU6, and hard-swish, which Phase 1 of the
+ * framework puts in place of swish (section 5.1):  hswish(v) = v * min(max(v + 3, 0), 6) / 6. */
 static double activate(double v, int act)
 {
     if (act == ACT_RELU)  return v > 0.0 ? v : 0.0;
     if (act == ACT_RELU6) return v < 0.0 ? 0.0 : (v > 6.0 ? 6.0 : v);
+    if (act == ACT_HARDSWISH) {
+        double t = v + 3.0;
+        t = t < 0.0 ? 0.0 : (t > 6.0 ? 6.0 : t);
+        return v * t / 6.0;
+    }
     return v;
 }
 

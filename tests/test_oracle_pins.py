@@ -304,3 +304,91 @@ def test_generator_hits_the_requested_rates():
     lib = masks.pattern_library(8, 3)
     mp, ids = masks.pattern_mask(128, 128, lib, 0.3, 4)
     assert (ids == 255).sum() == 4915 and mp.sum() == 4 * (128 * 128 - 4915)
+
+
+def test_hard_swish_matches_its_formula():
+    """hard-swish (paper section 5.1, Phase 1): v * clip(v + 3, 0, 6) / 6, here through every layer kind that
+    takes an activation, with the residual added before it."""
+    X = rnd(71, (1, 6, 5, 4), 2.0)
+    Wt = rnd(72, (6, 4, 3, 3), 0.8)
+    m = masks.block_punched_mask(6, 4, 3, 3, 2, 2, 2, 9)
+    R = rnd(73, (1, 6, 5, 6), 3.0)
+    base = oracle.conv2d_masked(X, Wt, m, 1, 1) + R
+    hs = base * np.clip(base + 3.0, 0.0, 6.0) / 6.0
+    np.testing.assert_allclose(oracle.conv2d_masked(X, Wt, m, 1, 1, None, R, oracle.ACT_HARDSWISH), hs, rtol=1e-13, atol=1e-13)
+    assert (base < -3).any() and (base > 3).any() and ((base > -3) & (base < 3)).any()     # all three branches
+    assert (hs[base <= -3] == 0).all() and np.allclose(hs[base >= 3], base[base >= 3], rtol=1e-15)
+    Xf, Wf = rnd(74, (3, 12), 2.0), rnd(75, (10, 12))
+    mf = masks.fc_block_mask(10, 12, 4, 4, 2, 3)
+    v = Xf @ (Wf * mf).T
+    np.testing.assert_allclose(oracle.fc_masked(Xf, Wf, mf, None, oracle.ACT_HARDSWISH), v * np.clip(v + 3, 0, 6) / 6,
+                               rtol=1e-13, atol=1e-13)
+    Wd = rnd(76, (4, 3, 3))
+    d = oracle.dwconv3x3(X, Wd, 1)
+    np.testing.assert_allclose(oracle.dwconv3x3(X, Wd, 1, None, None, oracle.ACT_HARDSWISH), d * np.clip(d + 3, 0, 6) / 6,
+                               rtol=1e-13, atol=1e-13)
+
+
+def _bf16(a):
+    """float64 -> nearest bfloat16 (ties to even) -> float64, through PyTorch's cast (not the oracle's rounding)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def _assert_same_rounded(got, want, what=""):
+    """Bit equality, except that a value the two float64 summation orders put on opposite sides of a rounding
+    boundary may differ by one bfloat16 step (at most one element in a thousand; none for the seeds used here on
+    the machine this was written on)."""
+    got, want = np.asarray(got), np.asarray(want)
+    assert got.shape == want.shape, what
+    bad = got != want
+    if bad.any():
+        assert bad.mean() <= 1e-3, f"{what}: {bad.sum()} of {bad.size} elements differ"
+        assert (np.abs(got - want)[bad] <= np.abs(want)[bad] * 2.0 ** -7 + 1e-30).all(), what
+
+
+def test_run_stack_wiring_and_rounding_against_plain_numpy():
+    """The stack walker (which tensor a layer reads, which it adds, where activations are rounded) against the
+    same networks written out by hand with NumPy matrix products, float64 library convolutions and PyTorch's
+    bfloat16 cast.  The rounded tensors must agree bit for bit: a wrong src / res index, a residual added after
+    the activation or a missed rounding between layers changes them."""
+    from workloads import configs
+    # (a) the 1x1 -> ReLU6 -> 1x1 pair: round_bf16(clip(x W1m^T, 0, 6)) W2m^T
+    w = configs.config2(batch=1, HW=5)
+    L1, L2 = w.layers
+    rounded, raw = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+    x = w.x_exact.reshape(-1, L1.C)
+    W1m = (L1.w_exact * L1.mask).reshape(L1.F, L1.C)
+    W2m = (L2.w_exact * L2.mask).reshape(L2.F, L2.C)
+    mid = _bf16(np.clip(x @ W1m.T, 0.0, 6.0))
+    out = mid @ W2m.T
+    _assert_same_rounded(rounded[1].reshape(-1, L1.F), mid, "pair intermediate")
+    np.testing.assert_allclose(raw[2].reshape(-1, L2.F), out, rtol=0, atol=1e-12)
+    _assert_same_rounded(rounded[2].reshape(-1, L2.F), _bf16(out), "pair output")
+    # (b) one bottleneck with a projection shortcut, the residual added before the ReLU, after a stem + max pool
+    w = configs.config5(batch=1, HW=20, width=8, blocks=(1,), classes=10)
+    names = [L.name for L in w.layers]
+    assert names == ["stem7x7", "maxpool", "s0b0_c1", "s0b0_c2", "s0b0_sc", "s0b0_c3", "avgpool", "fc"]
+    rounded, raw = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+    Ls = dict(zip(names, w.layers))
+
+    def conv(x, L, res=None):
+        y = torch_conv(x, L.w_exact * L.mask, L.stride, L.pad)
+        if res is not None:
+            y = y + res
+        return _bf16(np.maximum(y, 0.0) if L.act == configs.ACT_RELU else y)
+
+    t1 = conv(w.x_exact, Ls["stem7x7"])
+    t2 = torch.nn.functional.max_pool2d(torch.from_numpy(t1.transpose(0, 3, 1, 2)), 3, 2, 1).numpy().transpose(0, 2, 3, 1)
+    t3 = conv(t2, Ls["s0b0_c1"])
+    t4 = conv(t3, Ls["s0b0_c2"])
+    t5 = conv(t2, Ls["s0b0_sc"])                       # the shortcut reads the block input, no activation
+    assert Ls["s0b0_sc"].act == configs.ACT_NONE and Ls["s0b0_c3"].res == 5 and Ls["s0b0_c3"].src == 4
+    t6 = conv(t4, Ls["s0b0_c3"], res=t5)               # residual before the ReLU
+    t7 = _bf16(t6.mean(axis=(1, 2)))
+    Lf = Ls["fc"]
+    t8 = t7 @ (Lf.w_exact * Lf.mask).reshape(Lf.F, Lf.C).T
+    for i, t in enumerate((t1, t2, t3, t4, t5, t6, t7), start=1):
+        _assert_same_rounded(rounded[i].reshape(t.shape), t, f"tensor {i} ({names[i - 1]})")
+    np.testing.assert_allclose(raw[8], t8, rtol=0, atol=1e-12)
+    _assert_same_rounded(rounded[8], _bf16(t8), "logits")
+    assert np.abs(t6).max() > 0 and (t6 == 0).any()

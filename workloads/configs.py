@@ -20,7 +20,7 @@ import numpy as np
 from . import dtypes, masks, prng
 
 BASE_SEED = 20201200
-ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
+ACT_NONE, ACT_RELU, ACT_RELU6, ACT_HARDSWISH = 0, 1, 2, 3
 
 
 @dataclass
