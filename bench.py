@@ -1,11 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the sparse-inference hot path on one MI355X.
 
-One step = one pass of the block-punched 1x1 stack 24 -> 144 -> 24 (ReLU6 between,
-8x8 blocks, 4x pruning, batch 64, 56x56, bf16) through npas_run_stack, inputs
-already resident in HBM.  Prints one JSON line: dense-equivalent TFLOP/s, the
-HBM roofline of the dominant kernel (timed with events on the launch stream) and
-the CPU oracle timed on a bounded sample of the same workload.
+Default: one step = one npas_run_stack call on the benchmark's configs[4] at batch 128 (the 50-layer
+bottleneck residual stack, every conv block-punched 8x4 at a per-layer rate from {2, 3, 5}, block-based
+FC), bf16, inputs resident in HBM.  Prints ONE JSON line: dense-equivalent TFLOP/s of the whole stack
+(value), median / min per step, the roofline of the stack (sum of per-layer floors / measured) and of the
+kernel that takes most of its time, the launch floor measured in the same run, batch-1 latency, the
+configs[1] fused-pair figure, and the CPU oracle timed on a bounded sample.
+
+Other modes (tables for profiles/): --per-layer, --stack, --sweep, --copy-calibration.
 """
 import argparse
 import json
@@ -18,18 +21,24 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0
+HBM_PEAK_GBS = 8000.0          # GB/s
+MFMA_PEAK_TFLOPS = 2500.0      # bf16 / fp16 dense
+VALU_PEAK_TFLOPS = 157.3       # fp32 vector
+ALL_FUSIONS = 7                # STACK_FUSE_POINTWISE | _INVERTED_RESIDUAL | _CONV_MAXPOOL
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--batch", type=int, default=64)
-    ap.add_argument("--no-fuse", action="store_true", help="run the two layers as two kernels")
-    ap.add_argument("--no-rotate", action="store_true", help="reuse one buffer set (stays in the 256 MB Infinity Cache)")
+    ap.add_argument("--batch", type=int, default=0, help="batch size (default: 128 for the headline stack, 64 for config 2)")
+    ap.add_argument("--headline", type=int, default=5, choices=[2, 5],
+                    help="which config the JSON line's value is quoted on: 5 = configs[4] (default), 2 = configs[1]")
+    ap.add_argument("--no-fuse", action="store_true", help="no stack fusion flags (one launch per layer)")
+    ap.add_argument("--no-rotate", action="store_true", help="reuse one buffer set")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-extras", action="store_true", help="skip the batch-1, configs[1] and per-layer legs of the headline run")
     ap.add_argument("--per-layer", type=int, default=0, metavar="CFG",
                     help="instead of the headline line, print a per-layer table (us, dense-equivalent TFLOP/s, "
                          "algorithmic GB/s, roofline fraction) for config CFG in 1..5 (BASELINE.json's configs[CFG-1]); "
@@ -43,188 +52,377 @@ def main():
     ap.add_argument("--sweep", type=str, default="", choices=["", "rate", "block"],
                     help="rate: 3x3 conv 56x56x256->256 over pruning schemes and rates; block: residual stack over block sizes at 6x")
     ap.add_argument("--only", type=str, default="", help="with --per-layer: comma-separated layer indices to run")
-    ap.add_argument("--reps", type=int, default=20, help="with --per-layer: timed launches per layer")
+    ap.add_argument("--reps", type=int, default=20, help="with --per-layer / --stack / --sweep: timed launches")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     import paper_2012_00596_amd as npas
-    from tests import helpers
-    from workloads import configs
+    from workloads import configs, harness
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     if args.copy_calibration:
-        n = args.copy_calibration * 2**20
-        src = torch.arange(n // 4, dtype=torch.int32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(5):
-            dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 5
-        e0.record()
-        for _ in range(5):
-            dst.zero_()
-        e1.record()
-        torch.cuda.synchronize()
-        ms_w = e0.elapsed_time(e1) / 5
-        e0.record()
-        for _ in range(5):
-            src.sum()
-        e1.record()
-        torch.cuda.synchronize()
-        ms_r = e0.elapsed_time(e1) / 5
-        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 10,
-                          "copy_GBps": 2 * n / ms / 1e6, "fill_GBps": n / ms_w / 1e6, "read_sum_GBps": n / ms_r / 1e6}))
-        return
+        return copy_calibration(args, torch)
     if args.per_layer:
-        return per_layer(args, torch, npas, helpers, configs)
+        return per_layer(args, torch, npas, harness, configs)
     if args.stack:
-        return stack_mode(args, torch, npas, helpers, configs)
+        return stack_mode(args, torch, npas, harness, configs)
     if args.sweep:
-        return sweep_mode(args, torch, npas, helpers)
-    w = configs.config2(batch=args.batch)
-    N, H, W, C = w.x_shape
-    npx = N * H * W
-    packed = [helpers.pack_layer(npas, L, w.dtype) for L in w.layers]
-    flags = 0 if args.no_fuse else npas.STACK_FUSE_POINTWISE
-    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W, flags)
-    wsb = st.workspace_bytes(N)
-    launches = st.num_launches()
+        return sweep_mode(args, torch, npas, harness)
+    return headline(args, torch, npas, harness, configs)
 
-    F1, F2 = w.layers[0].F, w.layers[1].F
-    x_bytes, mid_bytes, y_bytes = npx * C * 2, npx * F1 * 2, npx * F2 * 2
-    meta_bytes = sum(p.info()["device_bytes"] for p in packed)
-    set_bytes = x_bytes + y_bytes + wsb
-    nsets = 1 if args.no_rotate else max(2, -(-640 * 2**20 // set_bytes))
-    xs = [helpers.to_dev(w.x_store, torch) for _ in range(nsets)]
-    ys = [helpers.new_dev((N, H, W, F2), w.dtype, torch, fill=0) for _ in range(nsets)]
-    wss = [torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+
+# ---- shared pieces ---------------------------------------------------------------------------------------------
+
+class StackRunner:
+    """A packed workload as an npas_stack plus rotating device buffer sets."""
+
+    def __init__(self, w, torch, npas, harness, flags, nsets):
+        self.w, self.torch, self.npas = w, torch, npas
+        self.N, self.H, self.W = w.x_shape[0], w.x_shape[1], w.x_shape[2]
+        self.packed = [harness.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
+        self.st = npas.Stack(harness.stack_descs(npas, w.layers, self.packed), self.H, self.W, flags)
+        self.wsb = self.st.workspace_bytes(self.N)
+        shapes = {0: w.x_shape}
+        for i, L in enumerate(w.layers):
+            shapes[i + 1] = harness.out_shape(L, shapes[L.src])
+        self.shapes = shapes
+        self.xs = [harness.to_dev(w.x_store, torch) for _ in range(nsets)]
+        self.ys = [harness.new_dev(shapes[len(w.layers)], w.dtype, torch, fill=0) for _ in range(nsets)]
+        self.wss = [torch.empty(max(self.wsb, 256), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+        self.nsets = nsets
+        self.stream = torch.cuda.current_stream().cuda_stream
+
+    def step(self, i):
+        k = i % self.nsets
+        self.st.run(self.xs[k], self.ys[k], self.N, self.wss[k], self.wsb, self.stream)
+
+    def timed(self, steps, warmup):
+        """(wall seconds per step over all steps, per-step device milliseconds from events on the launch stream)."""
+        torch = self.torch
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        t0 = time.perf_counter()
+        ev[0].record()
+        for i in range(steps):
+            self.step(i)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps
+        per = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)])
+        return wall, per
+
+
+def layer_costs(w, packed, harness):
+    """Per layer: dense-equivalent and kept FLOPs, algorithmic bytes (activations in and out once, residual once,
+    the canonical compact weights and their index: 4 bytes per list entry and per group), and the roofline floor."""
+    esz = 4 if w.dtype == 0 else 2
+    shapes = {0: w.x_shape}
+    rows = []
+    for i, L in enumerate(w.layers):
+        ishape = shapes[L.src]
+        oshape = harness.out_shape(L, ishape)
+        shapes[i + 1] = oshape
+        nin, nout = int(np.prod(ishape)), int(np.prod(oshape))
+        macs = kept = 0
+        wbytes = 0
+        if L.kind in ("conv", "fc"):
+            npix = nout // L.F
+            macs = npix * L.F * L.C * L.KH * L.KW
+            kept = npix * int(L.mask.sum())
+            info = packed[i].info()
+            wbytes = info["compact_weight_bytes"] + 4 * info["K_total"] + 4 * (info["G"] + 1)
+        elif L.kind == "dwconv":
+            macs = kept = nout * 9
+            wbytes = L.C * 9 * esz
+        nin_alg = nin
+        if L.kind == "conv" and L.KH == 1 and L.KW == 1 and L.stride > 1:
+            nin_alg = nout // L.F * L.C          # a strided 1x1 layer needs only the input pixels it samples
+        abytes = (nin_alg + nout + (nout if L.res >= 0 else 0)) * esz + wbytes
+        vec = w.dtype == 0 or L.kind == "dwconv"  # fp32 and depthwise layers run on the vector ALUs
+        peak = VALU_PEAK_TFLOPS if vec else MFMA_PEAK_TFLOPS
+        t_hbm, t_mm = abytes / (HBM_PEAK_GBS * 1e9) * 1e6, 2.0 * macs / (peak * 1e12) * 1e6
+        rows.append(dict(i=i, L=L, ishape=ishape, oshape=oshape, nin=nin, nout=nout, flop=2.0 * macs, kept_flop=2.0 * kept,
+                         abytes=abytes, wbytes=wbytes, t_hbm=t_hbm, t_mm=t_mm, floor_us=max(t_hbm, t_mm),
+                         bound="hbm" if t_hbm >= t_mm else ("alu" if vec else "mfma")))
+    return rows
+
+
+def stack_floor_us(rows, fused_conv_pool=True):
+    """Sum of the per-launch floors.  A conv whose max pool runs in the same launch neither writes the conv output
+    nor reads it back: its floor is taken on input + pooled output."""
+    total = 0.0
+    skip = set()
+    for k, r in enumerate(rows):
+        if k in skip:
+            continue
+        L = r["L"]
+        nxt = rows[k + 1] if k + 1 < len(rows) else None
+        if fused_conv_pool and L.kind == "conv" and L.C < 8 and nxt is not None and nxt["L"].kind == "maxpool" and nxt["L"].src == k + 1:
+            esz = 2
+            b = (r["nin"] + nxt["nout"]) * esz + r["wbytes"]
+            total += max(b / (HBM_PEAK_GBS * 1e9) * 1e6, r["t_mm"])
+            skip.add(k + 1)
+            continue
+        total += r["floor_us"]
+    return total
+
+
+def time_layers(w, packed, rows, torch, npas, reps, only=()):
+    """Times every layer on its own seeded-size buffers (rotated so that small layers do not sit in the cache);
+    fills rows[i]['us'] and rows[i]['kernel']."""
     stream = torch.cuda.current_stream().cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    esz = 4 if w.dtype == 0 else 2
+    for r in rows:
+        i, L, ishape, oshape = r["i"], r["L"], r["ishape"], r["oshape"]
+        if only and i not in only:
+            continue
+        nin, nout = r["nin"], r["nout"]
+        p = packed[i]
+        nsets = max(1, min(8, -(-600 * 2**20 // max(1, (nin + nout) * esz))))
+        td = torch.float32 if w.dtype == 0 else torch.int16
+        if w.dtype == 0:
+            xs = [torch.randn(nin, device="cuda") for _ in range(nsets)]
+        elif w.dtype == 1:
+            xs = [torch.randn(nin, device="cuda").to(torch.bfloat16).view(torch.int16) for _ in range(nsets)]
+        else:
+            xs = [torch.randn(nin, device="cuda").to(torch.float16).view(torch.int16) for _ in range(nsets)]
+        ys = [torch.empty(nout, dtype=td, device="cuda") for _ in range(nsets)]
+        rs = [torch.zeros(nout, dtype=td, device="cuda") for _ in range(nsets)] if L.res >= 0 else None
 
-    def step(i):
-        k = i % nsets
-        st.run(xs[k], ys[k], N, wss[k], wsb, stream)
+        def run(k):
+            if L.kind == "conv":
+                N, H, W_, _ = ishape
+                npas.conv2d_sparse(p, xs[k], ys[k], N, H, W_, L.stride, L.pad, None, rs[k] if rs else None, L.act, stream)
+            elif L.kind == "fc":
+                npas.fc_sparse(p, xs[k], ys[k], ishape[0], None, L.act, stream)
+            elif L.kind == "dwconv":
+                N, H, W_, _ = ishape
+                npas.depthwise3x3(p, xs[k], ys[k], N, H, W_, L.stride, None, rs[k] if rs else None, L.act, stream)
+            elif L.kind == "maxpool":
+                N, H, W_, C = ishape
+                npas.maxpool3x3s2(xs[k], ys[k], N, H, W_, C, w.dtype, stream)
+            else:
+                N, H, W_, C = ishape
+                npas.global_avgpool(xs[k], ys[k], N, H, W_, C, w.dtype, stream)
+        for k in range(3):
+            run(k % nsets)
+        torch.cuda.synchronize()
+        e0.record()
+        for k in range(reps):
+            run(k % nsets)
+        e1.record()
+        torch.cuda.synchronize()
+        r["us"] = e0.elapsed_time(e1) * 1e3 / reps
+        if L.kind == "conv":
+            r["kernel"] = npas.conv2d_kernel_name(p, ishape[0], ishape[1], ishape[2], L.stride, L.pad)
+        elif L.kind == "fc":
+            r["kernel"] = npas.conv2d_kernel_name(p, ishape[0], 1, 1, 1, 0)
+        else:
+            r["kernel"] = L.kind
+        del xs, ys, rs
+        torch.cuda.empty_cache()
 
-    for i in range(args.warmup):
-        step(i)
+
+def launch_floor_us(torch, npas, n=2000):
+    """Launch-to-launch time of an empty kernel on the stream the benchmark uses, measured now."""
+    stream = torch.cuda.current_stream().cuda_stream
+    npas.launch_empty(200, stream)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / args.steps
-
-    # per-step device time with events on the launch stream (excludes host launch gaps only if the
-    # queue stays full; reported next to the wall-clock figure)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    for i in range(args.steps):
-        step(i)
+    npas.launch_empty(n, stream)
     e1.record()
     torch.cuda.synchronize()
-    dev_ms = e0.elapsed_time(e1) / args.steps
+    return e0.elapsed_time(e1) * 1e3 / n
 
+
+# ---- the headline line -----------------------------------------------------------------------------------------
+
+def headline(args, torch, npas, harness, configs):
+    cfg = args.headline
+    batch = args.batch or (128 if cfg == 5 else 64)
+    flags = 0 if args.no_fuse else ALL_FUSIONS
+    w = configs.config5(batch=batch) if cfg == 5 else configs.config2(batch=batch)
+    # buffer sets: the stack's working set at batch 128 (several hundred MB of intermediates) is far beyond the
+    # 256 MB Infinity Cache on its own; two sets keep even the input and output cold.  configs[1] is 19 MB: rotate
+    # through enough sets to exceed the cache.
+    probe = StackRunner(w, torch, npas, harness, flags, 1)
+    set_bytes = probe.wsb + sum(t.numel() * t.element_size() for t in (probe.xs[0], probe.ys[0]))
+    nsets = 1 if args.no_rotate else max(2, min(64, -(-640 * 2**20 // set_bytes)))
+    del probe
+    torch.cuda.empty_cache()
+    run = StackRunner(w, torch, npas, harness, flags, nsets)
+    wall, per = run.timed(args.steps, args.warmup)
+    launches = run.st.num_launches()
     dense_flop = 2.0 * w.dense_macs()
-    # dominant kernel: fused -> the only kernel (reads x, writes y); per-layer -> either layer moves
-    # x/mid (read) + mid/y (write) = 67.4 MB, the slower one is timed
-    if launches == 1:
-        alg_bytes = x_bytes + y_bytes + meta_bytes
-        kern_ms = dev_ms
-        kname = "pointwise_pair_fused"
-    else:
-        alg_bytes = x_bytes + mid_bytes + packed[0].info()["device_bytes"]
-        mids = [helpers.new_dev((N, H, W, F1), w.dtype, torch, fill=0) for _ in range(nsets)]
-        per = []
-        for li, L in enumerate(w.layers):
-            e0.record()
-            for i in range(args.steps):
-                k = i % nsets
-                if li == 0:
-                    npas.conv2d_sparse(packed[0], xs[k], mids[k], N, H, W, 1, 0, None, None, L.act, stream)
-                else:
-                    npas.conv2d_sparse(packed[1], mids[k], ys[k], N, H, W, 1, 0, None, None, L.act, stream)
-            e1.record()
-            torch.cuda.synchronize()
-            per.append(e0.elapsed_time(e1) / args.steps)
-        kern_ms = max(per)
-        kname = "%s (layer %d of 2)" % (npas.conv2d_kernel_name(packed[per.index(kern_ms)], N, H, W, 1, 0), per.index(kern_ms) + 1)
-    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
-    # HBM bytes per launch of the fused kernel as measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE scaled by a
-    # plain copy); only valid for the default workload and launch configuration
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "fused_pointwise_pair_cfg2_hbm_traffic.md")
-    if launches == 1 and N == 64 and os.path.exists(tfile):
-        for line in open(tfile):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = int(line.split(":")[1])
+    rows = layer_costs(w, run.packed, harness)
+    kept_flop = sum(r["kept_flop"] for r in rows)
+    floor_us = stack_floor_us(rows, fused_conv_pool=bool(flags & 4))
+    med_ms, min_ms = float(np.median(per)), float(per.min())
 
+    name = ("configs[4]: 50-layer bottleneck residual stack, 224x224x3, batch %d, bf16 NHWC, every conv block-punched 8x4 at a "
+            "per-layer rate from {2,3,5}, block-based 16x32 FC 2048->1000" % batch) if cfg == 5 else \
+           ("configs[1]: 1x1 stack 24->144->24, batch %d, 56x56, bf16 NHWC, 8x8 blocks, 4x pruning, ReLU6" % batch)
     out = {
         "metric": "dense-equivalent TFLOP/s and per-layer us for block-punched sparse conv at 1 GPU",
-        "value": dense_flop / dt / 1e12,
+        "value": dense_flop / wall / 1e12,
         "unit": "TFLOP/s (dense-equivalent)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": dt * 1e3,
-        "device_ms_per_step": dev_ms,
+        "ms_per_step": wall * 1e3,
+        "device_ms_per_step": {"median": med_ms, "min": min_ms, "mean": float(per.mean())},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: 1x1 stack 24->144->24, batch %d, 56x56, bf16 NHWC, 8x8 blocks, 4x pruning, ReLU6"
-                               % N, "launches_per_step": launches, "buffer_sets": nsets,
-                   "dense_equiv_gflop_per_step": dense_flop / 1e9},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kname,
-                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kern_ms},
+        "config": {"workload": name, "launches_per_step": launches, "buffer_sets": nsets, "images_per_s": batch / wall,
+                   "workspace_MB": run.wsb / 2**20, "dense_equiv_gflop_per_step": dense_flop / 1e9,
+                   "kept_gflop_per_step": kept_flop / 1e9,
+                   "executed_gflop_per_step_note": "the MFMA kernels of this stack multiply every position of a 16-filter "
+                   "tile that any of its filter groups keeps; at these rates that is the dense count (dense_equiv)"},
     }
+
+    # roofline: the stack as a whole (sum of per-launch floors over the measured median), and the kernel that takes
+    # most of the stack's time, from a per-layer timing pass of the same run
+    roof = {"stack_floor_ms": floor_us / 1e3, "stack_frac": floor_us / 1e3 / med_ms,
+            "stack_floor_note": "sum over launches of max(algorithmic bytes / 8 TB/s, dense-equivalent FLOP / 2.5 PFLOP/s); "
+                                "bytes = activations in + out (+ residual) once + compact weights + 4 B per list entry"}
+    if not args.no_extras:
+        time_layers(w, run.packed, rows, torch, npas, max(5, min(20, args.steps // 5)))
+        per_kernel = {}
+        for r in rows:
+            k = per_kernel.setdefault(r["kernel"], dict(launches=0, us=0.0, bytes=0.0, flop=0.0, floor_us=0.0))
+            k["launches"] += 1; k["us"] += r["us"]; k["bytes"] += r["abytes"]; k["flop"] += r["flop"]; k["floor_us"] += r["floor_us"]
+        for k in per_kernel.values():
+            k["frac"] = k["floor_us"] / k["us"]
+            k["GBps"] = k["bytes"] / k["us"] / 1e3
+            k["TFLOPs_dense_equiv"] = k["flop"] / k["us"] / 1e6
+        dom = max(per_kernel, key=lambda n: per_kernel[n]["us"])
+        d = per_kernel[dom]
+        hbm_rows = [r for r in rows if r["kernel"] == dom and r["bound"] == "hbm"]
+        mm_rows = [r for r in rows if r["kernel"] == dom and r["bound"] != "hbm"]
+        hbm_us, mm_us = sum(r["us"] for r in hbm_rows), sum(r["us"] for r in mm_rows)
+        if hbm_us >= mm_us:      # the dominant kernel's launches are mostly HBM-bound ones: quote it on those
+            ach = sum(r["abytes"] for r in hbm_rows) / hbm_us / 1e3
+            roof.update(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                        launches_counted=len(hbm_rows), avg_launch_us=hbm_us / len(hbm_rows),
+                        algorithmic_bytes_per_launch=sum(r["abytes"] for r in hbm_rows) / len(hbm_rows))
+        else:
+            ach = sum(r["flop"] for r in mm_rows) / mm_us / 1e6
+            roof.update(bound="mfma", achieved=ach, peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_PEAK_TFLOPS,
+                        launches_counted=len(mm_rows), avg_launch_us=mm_us / len(mm_rows),
+                        algorithmic_flop_per_launch=sum(r["flop"] for r in mm_rows) / len(mm_rows))
+        roof.update(kernel=dom, traffic=None,
+                    traffic_note="not measured inside this run; rocprofv3 --pmc figures per layer are in profiles/",
+                    kernel_share_of_stack_time=d["us"] / sum(k["us"] for k in per_kernel.values()))
+        out["per_kernel"] = {n: {a: (round(b, 4) if isinstance(b, float) else b) for a, b in k.items() if a not in ("bytes", "flop")}
+                             for n, k in per_kernel.items()}
+        out["per_layer_sum_ms"] = sum(r["us"] for r in rows) / 1e3
+        floor = launch_floor_us(torch, npas)
+        out["launch_floor_us"] = {"empty_kernel": floor, "times_launches": floor * launches}
+    else:
+        roof.update(bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=floor_us / 1e3 / med_ms, traffic=None)
+    out["roofline"] = roof
+
+    if not args.no_extras and cfg == 5:
+        # the same stack at batch 1 (latency), and the configs[1] fused pair
+        del run
+        torch.cuda.empty_cache()
+        w1 = configs.config5(batch=1)
+        r1 = StackRunner(w1, torch, npas, harness, flags, 4)
+        _, p1 = r1.timed(100, 20)
+        out["batch1"] = {"workload": "configs[4] at batch 1", "median_us": float(np.median(p1)) * 1e3, "min_us": float(p1.min()) * 1e3,
+                         "launches": r1.st.num_launches(), "floor_us": stack_floor_us(layer_costs(w1, r1.packed, harness)),
+                         "launch_floor_us": out["launch_floor_us"]["empty_kernel"] * r1.st.num_launches()}
+        del r1
+        w2 = configs.config2(batch=64)
+        x2 = int(np.prod(w2.x_shape)) * 2
+        r2 = StackRunner(w2, torch, npas, harness, flags, max(2, -(-640 * 2**20 // (2 * x2))))
+        _, p2 = r2.timed(200, 20)
+        b2 = 2 * x2 + sum(4 * p.info()["K_total"] + p.info()["compact_weight_bytes"] for p in r2.packed)
+        med2 = float(np.median(p2)) * 1e3
+        out["config2_fused_pair"] = {"workload": "configs[1]: 24->144->24, batch 64, 56x56, one fused launch", "median_us": med2,
+                                     "min_us": float(p2.min()) * 1e3, "launches": r2.st.num_launches(),
+                                     "algorithmic_bytes": b2, "GBps": b2 / med2 / 1e3, "hbm_frac": b2 / med2 / 1e3 / HBM_PEAK_GBS,
+                                     "TFLOPs_dense_equiv": 2.0 * w2.dense_macs() / med2 / 1e6}
+        del r2
+        torch.cuda.empty_cache()
 
     if not args.no_cpu:
         import oracle
-        sample_px = 2 * H * W                      # two images' worth of pixels
-        xsub = w.x_exact.reshape(npx, C)[:sample_px].reshape(1, 1, sample_px, C)
+        nimg = min(2, batch) if cfg == 5 else 1
+        if cfg == 5:
+            xsub = w.x_exact[:nimg]
+            frac = nimg / batch
+            what = "%d of %d images of the same stack" % (nimg, batch)
+        else:
+            npx = int(np.prod(w.x_shape[:3]))
+            spx = 2 * w.x_shape[1] * w.x_shape[2]
+            xsub = w.x_exact.reshape(npx, -1)[:spx].reshape(1, 1, spx, -1)
+            frac = spx / npx
+            what = "%d of %d pixels of the same stack" % (spx, npx)
         t0 = time.perf_counter()
         reps = 0
-        while time.perf_counter() - t0 < 10.0:
+        while reps < 1 or time.perf_counter() - t0 < 10.0:
             oracle.run_stack(xsub, w.layers, w.dtype)
             reps += 1
         cdt = (time.perf_counter() - t0) / reps
-        out["cpu_baseline"] = {"value": dense_flop * (sample_px / npx) / cdt / 1e12,
-                               "unit": "TFLOP/s (dense-equivalent)", "cores": oracle.num_threads(), "kind": "oracle",
-                               "sample": "%d of %d pixels of the same stack, %d repetitions" % (sample_px, npx, reps)}
+        out["cpu_baseline"] = {"value": dense_flop * frac / cdt / 1e12, "unit": "TFLOP/s (dense-equivalent)",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "%s, %d repetition(s), %.2f s each, scaled to the unit" % (what, reps, cdt)}
     print(json.dumps(out))
 
 
-def time_stack(w, reps, torch, npas, helpers, fuse=True, graph=False):
+# ---- tables ----------------------------------------------------------------------------------------------------
+
+def copy_calibration(args, torch):
+    n = args.copy_calibration * 2**20
+    src = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 5
+    e0.record()
+    for _ in range(5):
+        dst.zero_()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_w = e0.elapsed_time(e1) / 5
+    e0.record()
+    for _ in range(5):
+        src.sum()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_r = e0.elapsed_time(e1) / 5
+    print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 10,
+                      "copy_GBps": 2 * n / ms / 1e6, "fill_GBps": n / ms_w / 1e6, "read_sum_GBps": n / ms_r / 1e6}))
+
+
+def time_stack(w, reps, torch, npas, harness, fuse=True, graph=False):
     """(us per npas_run_stack call, launches, workspace bytes) for workload w.  graph: the call is
     captured once into a HIP graph (the library allocates nothing and sets nothing during a run) and
     the replays are timed: what a serving loop at small batch would do about the launch gaps."""
-    N, H, W, C = w.x_shape
-    packed = [helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
-    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), H, W,
-                    npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL | npas.STACK_FUSE_CONV_MAXPOOL if fuse else 0)
-    wsb = st.workspace_bytes(N)
-    x = helpers.to_dev(w.x_store, torch)
-    shapes = {0: w.x_shape}
-    for i, L in enumerate(w.layers):
-        shapes[i + 1] = helpers.out_shape(L, shapes[L.src])
-    y = helpers.new_dev(shapes[len(w.layers)], w.dtype, torch, fill=0)
-    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
-    stream = torch.cuda.current_stream().cuda_stream
+    run = StackRunner(w, torch, npas, harness, ALL_FUSIONS if fuse else 0, 1)
+    x, y, ws, N = run.xs[0], run.ys[0], run.wss[0], run.N
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for _ in range(5):
-        st.run(x, y, N, ws, wsb, stream)
+        run.step(0)
     torch.cuda.synchronize()
     if graph:
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            st.run(x, y, N, ws, wsb, torch.cuda.current_stream().cuda_stream)
+            run.st.run(x, y, N, ws, run.wsb, torch.cuda.current_stream().cuda_stream)
         for _ in range(3):
             g.replay()
         torch.cuda.synchronize()
@@ -235,53 +433,55 @@ def time_stack(w, reps, torch, npas, helpers, fuse=True, graph=False):
     else:
         e0.record()
         for _ in range(reps):
-            st.run(x, y, N, ws, wsb, stream)
+            run.step(0)
         e1.record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / reps, st.num_launches(), wsb
+    return e0.elapsed_time(e1) * 1e3 / reps, run.st.num_launches(), run.wsb
 
 
-def stack_mode(args, torch, npas, helpers, configs):
+def stack_mode(args, torch, npas, harness, configs):
     """npas_run_stack end to end: one call runs every layer of the config on one stream."""
     cfg = args.stack
     from workloads import sweeps
-    w = {2: lambda: configs.config2(batch=args.batch), 5: lambda: configs.config5(batch=args.batch),
-         6: lambda: sweeps.inverted_residual_block(batch=args.batch)}[cfg]()
-    us, launches, wsb = time_stack(w, args.reps, torch, npas, helpers, fuse=not args.no_fuse, graph=args.graph)
+    batch = args.batch or 64
+    w = {2: lambda: configs.config2(batch=batch), 5: lambda: configs.config5(batch=batch),
+         6: lambda: sweeps.inverted_residual_block(batch=batch)}[cfg]()
+    us, launches, wsb = time_stack(w, args.reps, torch, npas, harness, fuse=not args.no_fuse, graph=args.graph)
     flop = 2.0 * w.dense_macs()
     print("# config %d %s batch %d: npas_run_stack%s %.1f us per call, %d launches, workspace %.1f MB, %.1f TFLOP/s dense-equivalent, %.1f images/s"
           % (cfg, w.name, w.x_shape[0], " (HIP graph replay)" if args.graph else "", us, launches, wsb / 2**20, flop / us / 1e6,
              w.x_shape[0] / us * 1e6))
 
 
-def sweep_mode(args, torch, npas, helpers):
+def sweep_mode(args, torch, npas, harness):
     """The paper's two design-space sweeps (section 4) on synthetic layers: latency only."""
     from workloads import sweeps
+    batch = args.batch or 64
     stream = torch.cuda.current_stream().cuda_stream
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     if args.sweep == "block":
-        print("# residual stack, every pruned layer at 6x, batch %d: npas_run_stack per call" % args.batch)
+        print("# residual stack, every pruned layer at 6x, batch %d: npas_run_stack per call" % batch)
         print("%-9s %10s %12s" % ("Bf x Bc", "us", "images/s"))
         for Bf, Bc in sweeps.BLOCK_SIZES:
-            w = sweeps.block_sweep_stack(Bf, Bc, batch=args.batch)
-            us, _, _ = time_stack(w, args.reps, torch, npas, helpers)
-            print("%-9s %10.1f %12.1f" % ("%dx%d" % (Bf, Bc), us, args.batch / us * 1e6), flush=True)
+            w = sweeps.block_sweep_stack(Bf, Bc, batch=batch)
+            us, _, _ = time_stack(w, args.reps, torch, npas, harness)
+            print("%-9s %10.1f %12.1f" % ("%dx%d" % (Bf, Bc), us, batch / us * 1e6), flush=True)
         return
-    print("# 3x3 conv 56x56x256 -> 256, stride 1, batch %d, bf16; us per launch (dense-equivalent TFLOP/s of the unpruned layer)" % args.batch)
+    print("# 3x3 conv 56x56x256 -> 256, stride 1, batch %d, bf16; us per launch (dense-equivalent TFLOP/s of the unpruned layer)" % batch)
     print("%-14s" % "scheme" + "".join("%22s" % ("%gx" % r) for r in sweeps.RATES))
-    dense_flop = 2.0 * args.batch * 56 * 56 * 256 * 256 * 9
+    dense_flop = 2.0 * batch * 56 * 56 * 256 * 256 * 9
     for scheme in sweeps.RATE_SCHEMES:
         cells, kerns = [], set()
         for r in sweeps.RATES:
             if scheme == "pattern" and r < 2.25:
                 cells.append("%22s" % "-")
                 continue
-            w = sweeps.rate_sweep_layer(scheme, r, batch=args.batch)
+            w = sweeps.rate_sweep_layer(scheme, r, batch=batch)
             L = w.layers[0]
-            packed = helpers.pack_layer(npas, L, w.dtype)
+            packed = harness.pack_layer(npas, L, w.dtype)
             N, H, W_, C = w.x_shape
-            x = helpers.to_dev(w.x_store, torch)
-            y = helpers.new_dev((N, H, W_, L.F), w.dtype, torch, fill=0)
+            x = harness.to_dev(w.x_store, torch)
+            y = harness.new_dev((N, H, W_, L.F), w.dtype, torch, fill=0)
             for _ in range(3):
                 npas.conv2d_sparse(packed, x, y, N, H, W_, 1, 1, None, None, 0, stream)
             torch.cuda.synchronize()
@@ -297,97 +497,31 @@ def sweep_mode(args, torch, npas, helpers):
         print("%-14s" % scheme + "".join(cells) + "   " + ",".join(sorted(kerns)), flush=True)
 
 
-def per_layer(args, torch, npas, helpers, configs):
+def per_layer(args, torch, npas, harness, configs):
     """Per-layer timing of one config, every layer on its own buffers (rotated when small)."""
-    MFMA_PEAK, HBM_PEAK = 2500.0, 8000.0           # TFLOP/s (bf16 dense), GB/s
     cfg = args.per_layer
     from workloads import sweeps
-    w = {1: configs.config1, 2: lambda: configs.config2(batch=args.batch), 3: configs.config3, 4: configs.config4,
-         5: lambda: configs.config5(batch=args.batch), 6: lambda: sweeps.inverted_residual_block(batch=args.batch)}[cfg]()
-    stream = torch.cuda.current_stream().cuda_stream
-    shapes = {0: w.x_shape}
-    rows = []
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    tot_us = tot_flop = tot_bytes = 0.0
+    batch = args.batch or (128 if cfg == 5 else 64)
+    w = {1: configs.config1, 2: lambda: configs.config2(batch=batch), 3: configs.config3, 4: configs.config4,
+         5: lambda: configs.config5(batch=batch), 6: lambda: sweeps.inverted_residual_block(batch=batch)}[cfg]()
+    packed = [harness.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
+    rows = layer_costs(w, packed, harness)
     only = set(int(t) for t in args.only.split(",") if t)
-    for i, L in enumerate(w.layers):
-        ishape = shapes[L.src]
-        oshape = helpers.out_shape(L, ishape)
-        shapes[i + 1] = oshape
-        if only and i not in only:
-            continue
-        esz = 4 if w.dtype == 0 else 2
-        nin, nout = int(np.prod(ishape)), int(np.prod(oshape))
-        packed = helpers.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None
-        wbytes = packed.info()["device_bytes"] if packed else 0
-        if L.kind == "dwconv":
-            wbytes = L.C * 9 * 2
-        nin_alg = nin
-        if L.kind == "conv" and L.KH == 1 and L.KW == 1 and L.stride > 1:
-            nin_alg = nout // L.F * L.C  # a strided 1x1 layer needs only the input pixels it samples
-        abytes = (nin_alg + nout + (nout if L.res >= 0 else 0)) * esz + wbytes
-        nsets = max(1, min(8, -(-600 * 2**20 // max(1, (nin + nout) * esz))))
-        td = torch.float32 if w.dtype == 0 else torch.int16
-        xs = [torch.randint(-3, 3, (nin,), device="cuda").to(td) if w.dtype else torch.randn(nin, device="cuda")
-              for _ in range(nsets)]
-        if w.dtype == 1:   # small finite bf16 values
-            xs = [(torch.randn(nin, device="cuda") ).to(torch.bfloat16).view(torch.int16) for _ in range(nsets)]
-        ys = [torch.empty(nout, dtype=td, device="cuda") for _ in range(nsets)]
-        rs = [torch.zeros(nout, dtype=td, device="cuda") for _ in range(nsets)] if L.res >= 0 else None
-
-        def run(k):
-            if L.kind == "conv":
-                N, H, W_, _ = ishape
-                npas.conv2d_sparse(packed, xs[k], ys[k], N, H, W_, L.stride, L.pad, None, rs[k] if rs else None, L.act, stream)
-            elif L.kind == "fc":
-                npas.fc_sparse(packed, xs[k], ys[k], ishape[0], None, L.act, stream)
-            elif L.kind == "dwconv":
-                N, H, W_, _ = ishape
-                npas.depthwise3x3(packed, xs[k], ys[k], N, H, W_, L.stride, None, rs[k] if rs else None, L.act, stream)
-            elif L.kind == "maxpool":
-                N, H, W_, C = ishape
-                npas.maxpool3x3s2(xs[k], ys[k], N, H, W_, C, w.dtype, stream)
-            else:
-                N, H, W_, C = ishape
-                npas.global_avgpool(xs[k], ys[k], N, H, W_, C, w.dtype, stream)
-        reps = args.reps
-        for k in range(3):
-            run(k % nsets)
-        torch.cuda.synchronize()
-        e0.record()
-        for k in range(reps):
-            run(k % nsets)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
-        macs = 0
-        if L.kind == "conv":
-            macs = oshape[0] * oshape[1] * oshape[2] * L.F * L.C * L.KH * L.KW
-        elif L.kind == "fc":
-            macs = ishape[0] * L.F * L.C
-        elif L.kind == "dwconv":
-            macs = oshape[0] * oshape[1] * oshape[2] * L.C * 9
-        flop = 2.0 * macs
-        peak = 157.3 if (w.dtype == 0 or L.kind == "dwconv") else MFMA_PEAK    # fp32 and depthwise layers run on the vector ALUs
-        t_hbm, t_mfma = abytes / (HBM_PEAK * 1e9) * 1e6, flop / (peak * 1e12) * 1e6
-        bound = "hbm" if t_hbm >= t_mfma else ("alu" if (w.dtype == 0 or L.kind == "dwconv") else "mfma")
-        frac = max(t_hbm, t_mfma) / us
-        if L.kind == "conv":
-            kern = npas.conv2d_kernel_name(packed, ishape[0], ishape[1], ishape[2], L.stride, L.pad)
-        elif L.kind == "fc":
-            kern = npas.conv2d_kernel_name(packed, ishape[0], 1, 1, 1, 0)
-        else:
-            kern = L.kind
-        rows.append((i, L.name or L.kind, "x".join(map(str, ishape)), "x".join(map(str, oshape)), L.KH, L.stride, L.rate,
-                     kern.replace("conv_", ""), us, flop / us / 1e6, abytes / us / 1e3, bound, frac))
-        tot_us += us; tot_flop += flop; tot_bytes += abytes
-        del xs, ys, rs
-        torch.cuda.empty_cache()
-    print("# config %d  %s  (us per launch; TFLOP/s dense-equivalent; GB/s algorithmic; frac = roofline floor / measured)" % (cfg, w.name))
+    time_layers(w, packed, rows, torch, npas, args.reps, only)
+    rows = [r for r in rows if "us" in r]
+    print("# config %d  %s  (us per launch; TFLOP/s dense-equivalent; GB/s algorithmic, weights counted in compact form + index; "
+          "frac = roofline floor / measured)" % (cfg, w.name))
     print("%3s %-12s %-18s %-18s %2s %1s %4s %-14s %9s %9s %9s %5s %6s" % ("i", "layer", "in", "out", "k", "s", "rate", "kernel", "us", "TFLOP/s", "GB/s", "bound", "frac"))
     for r in rows:
-        print("%3d %-12s %-18s %-18s %2d %1d %4.1f %-14s %9.2f %9.2f %9.1f %5s %6.3f" % r)
-    print("# total %.1f us  %.1f TFLOP/s dense-equivalent  %.1f GB/s algorithmic" % (tot_us, tot_flop / tot_us / 1e6, tot_bytes / tot_us / 1e3))
+        L = r["L"]
+        print("%3d %-12s %-18s %-18s %2d %1d %4.1f %-14s %9.2f %9.2f %9.1f %5s %6.3f"
+              % (r["i"], L.name or L.kind, "x".join(map(str, r["ishape"])), "x".join(map(str, r["oshape"])), L.KH, L.stride, L.rate,
+                 r["kernel"].replace("conv_", ""), r["us"], r["flop"] / r["us"] / 1e6, r["abytes"] / r["us"] / 1e3, r["bound"],
+                 r["floor_us"] / r["us"]))
+    tot_us = sum(r["us"] for r in rows)
+    print("# total %.1f us  %.1f TFLOP/s dense-equivalent  %.1f GB/s algorithmic  sum of floors %.1f us (%.3f of the total)"
+          % (tot_us, sum(r["flop"] for r in rows) / tot_us / 1e6, sum(r["abytes"] for r in rows) / tot_us / 1e3,
+             sum(r["floor_us"] for r in rows), sum(r["floor_us"] for r in rows) / tot_us))
 
 
 if __name__ == "__main__":

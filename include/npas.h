@@ -19,17 +19,20 @@
  *     row-major, in the layer's storage type.  Masks are uint8, same shape,
  *     1 = weight kept, 0 = pruned; weight values under a 0 are ignored.
  *   - Activations are NHWC, contiguous, in the same storage type as the packed
- *     weights.  Accumulation is fp32; outputs are rounded to the storage type
- *     (round to nearest even).  bias is fp32 [F] and may be NULL.
+ *     weights.  16-bit layers (bf16 / fp16) accumulate in fp32 on the matrix cores;
+ *     fp32 layers accumulate in fp64 (products of two fp32 values are exact there, so
+ *     the stored result is the correctly rounded one).  Outputs are rounded to the
+ *     storage type (round to nearest even).  bias is fp32 [F] and may be NULL.
  *   - Convolution is cross-correlation with zero padding:
  *       Y[n,y,x,f] = act(bias[f] + sum W[f,c,kh,kw] X[n, y*s+kh-p, x*s+kw-p, c] + residual[n,y,x,f])
  *       Ho = (H + 2p - KH)/s + 1.
  *   - All device work is enqueued on the caller's stream (`hip_stream` is a
  *     hipStream_t passed as void*, NULL = default stream).  Run calls neither
- *     allocate nor synchronise.  Pack calls allocate device memory for the handle
- *     and copy to it synchronously; on a machine without a GPU they still build
- *     the host-side compact form (so it can be exported), and run calls on such a
- *     handle fail with NPAS_E_HIP.
+ *     allocate nor synchronise.  Pack calls allocate device memory for the handle,
+ *     enqueue the upload on `hip_stream` and wait for it (the source is the
+ *     library's own host buffer), so the handle is ready for any stream on return;
+ *     on a machine without a GPU they still build the host-side compact form (so it
+ *     can be exported), and run calls on such a handle fail with NPAS_E_HIP.
  *   - Every function returns 0 (NPAS_OK) or a negative npas_status;
  *     npas_last_error() gives a thread-local message for the last failure.
  *   - Activations must be finite: a stored zero weight (padding of a partial
@@ -50,7 +53,9 @@ typedef struct npas_packed npas_packed; /* one packed layer */
 typedef struct npas_stack npas_stack;   /* a wired list of layers */
 
 typedef enum { NPAS_F32 = 0, NPAS_BF16 = 1, NPAS_F16 = 2 } npas_dtype;
-typedef enum { NPAS_ACT_NONE = 0, NPAS_ACT_RELU = 1, NPAS_ACT_RELU6 = 2 } npas_act;
+/* ReLU6 = min(max(v, 0), 6); hard-swish (what Phase 1 of the framework puts in place of swish,
+ * section 5.1) = v * min(max(v + 3, 0), 6) / 6.  Applied after bias and residual, before rounding. */
+typedef enum { NPAS_ACT_NONE = 0, NPAS_ACT_RELU = 1, NPAS_ACT_RELU6 = 2, NPAS_ACT_HARDSWISH = 3 } npas_act;
 typedef enum { NPAS_SCHEME_BLOCK_PUNCHED = 0, NPAS_SCHEME_FC_BLOCK = 1, NPAS_SCHEME_PATTERN = 2,
                NPAS_SCHEME_DEPTHWISE = 3 } npas_scheme;
 
@@ -67,6 +72,15 @@ typedef enum {
 } npas_status;
 
 const char *npas_last_error(void);
+
+/* Testing aid.  The library reads two environment switches once, when it is loaded: NPAS_FORCE_VARIANT
+ * (gather | slab | noring | nosmallc | spatial | nospatial2 | smallm | resident | noresident | nofcgather | valu:
+ * overrides the format / kernel choice, nothing else) and NPAS_NO_BALANCE (pointwise tiles of full height).
+ * This call replaces them for the process (force_variant NULL or "" = none); it must not race with pack / run calls. */
+void npas_debug_set_switches(const char *force_variant, int no_balance);
+/* Measurement aid: enqueues `count` launches of an empty kernel (one wave) on the stream, so that a report can
+ * state the launch-to-launch floor of the machine next to the kernels' times. */
+int npas_debug_launch_empty(int count, void *hip_stream);
 
 /* ---- packing ------------------------------------------------------------- */
 
@@ -106,7 +120,9 @@ int npas_pack_depthwise3x3(const void *w_host, int C, npas_dtype dt, void *hip_s
  *                 device-format bytes, canonical compact-weight bytes, reserved }. */
 int npas_packed_info(const npas_packed *p, int64_t info[16]);
 
-/* Canonical compact form, copied to caller's HOST buffers (any may be NULL):
+/* The compact storage of a pruned layer (section 3, "Compiler Optimizations": only the weights a
+ * block keeps are stored, with the positions its filters share), in one canonical order so that two
+ * packers can be compared bit for bit.  Copied to caller's HOST buffers (any may be NULL):
  *   grp_ptr  int32 [G+1]        prefix sums of the per-group list lengths
  *   k_pos    int32 [K_total]    per group, ascending: (kh*KW + kw)*C + c of every
  *                               position kept by any filter of the group
@@ -124,8 +140,9 @@ void npas_free(npas_packed *p);
 
 /* ---- running one layer ---------------------------------------------------- */
 
-/* Sparse convolution of x_dev [N][H][W][C] into y_dev [N][Ho][Wo][F] through a
- * packed layer of any scheme.  residual_dev (nullable) has y's shape and type and
+/* Inference through one pruned CONV layer (section 3, block-punched pruning, Fig. 1 (f); section 2.1,
+ * pattern-based pruning, Fig. 1 (e)): the masked-dense convolution of the header comment, computed
+ * from the packed form.  x_dev [N][H][W][C] -> y_dev [N][Ho][Wo][F], a packed layer of any scheme.  residual_dev (nullable) has y's shape and type and
  * is added before the activation.  Errors: NULL handle/x/y, non-positive sizes,
  * an empty output, or more than 2^31-1 elements in x or y -> NPAS_E_NULL /
  * NPAS_E_SHAPE; launch failure -> NPAS_E_HIP. */
@@ -133,14 +150,16 @@ int npas_conv2d_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int
                        int stride, int pad, const void *bias_dev, const void *residual_dev,
                        npas_act act, void *hip_stream);
 
-/* Name of the kernel npas_conv2d_sparse launches for this layer and geometry
- * ("conv_valu_f32", "conv_gather_mfma", "conv_slab_mfma", "pointwise_ring",
- * "spatial_ring"); a static string, NULL for a NULL handle.  For reports and tests:
+/* Name of the kernel npas_conv2d_sparse / npas_fc_sparse launch for this layer and geometry
+ * ("conv_valu_f32", "conv_wave_f32", "conv_gather_mfma", "conv_slab_mfma", "pointwise_ring",
+ * "spatial_ring", "spatial_resident", "conv_smallc_mfma", "conv_smallm_mfma", "fc_gather_mfma");
+ * a static string, NULL for a NULL handle.  For reports and tests:
  * the choice depends on the packed format and on how well the problem fills the chip. */
 const char *npas_conv2d_kernel_name(const npas_packed *p, int N, int H, int W, int stride, int pad);
 
-/* Sparse fully-connected layer: x_dev [B][IN] -> y_dev [B][OUT]; the handle comes
- * from npas_pack_fc_block (or any 1x1 packed layer). */
+/* Inference through one pruned FC layer (section 3, block-based pruning, Fig. 1 (g)):
+ *   y[b,o] = act(bias[o] + sum over the columns i the block of row o keeps of W[o,i] x[b,i]).
+ * x_dev [B][IN] -> y_dev [B][OUT]; the handle comes from npas_pack_fc_block (or any 1x1 packed layer). */
 int npas_fc_sparse(const npas_packed *p, const void *x_dev, void *y_dev, int B, const void *bias_dev,
                    npas_act act, void *hip_stream);
 
@@ -165,7 +184,9 @@ int npas_global_avgpool(const void *x_dev, void *y_dev, int N, int H, int W, int
 typedef enum { NPAS_LAYER_CONV = 0, NPAS_LAYER_FC = 1, NPAS_LAYER_MAXPOOL3X3S2 = 2,
                NPAS_LAYER_GLOBAL_AVGPOOL = 3, NPAS_LAYER_DEPTHWISE3X3 = 4 } npas_layer_kind;
 
-/* Tensor 0 is the stack input; layer i writes tensor i+1; the last layer's
+/* A network is a sequence of such layers (section 5.1: per-layer filter type, scheme and rate); running
+ * several as one call is where layer fusion (section 3, "Compiler Optimizations") can happen.
+ * Tensor 0 is the stack input; layer i writes tensor i+1; the last layer's
  * tensor is the stack output.  `src` and `res` name earlier tensors (res = -1:
  * no residual).  `packed` must outlive the stack. */
 typedef struct {
@@ -198,6 +219,14 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
                    size_t workspace_bytes, void *hip_stream);
 /* Number of kernels one npas_run_stack call launches (after fusion). */
 int npas_stack_num_launches(const npas_stack *s);
+/* For tests and reports: the launches one npas_run_stack call makes for batch N, in order, and where their
+ * tensors live.  Row r of rows_host (int64 [max_rows][NPAS_DESCRIBE_COLS]) =
+ *   { first layer of the launch, last layer it absorbs, input tensor, residual tensor (-1: none), output tensor,
+ *     workspace offset of the input, of the residual, of the output (-1: the tensor is x_dev, -2: y_dev, -3: none),
+ *     bytes of the input, of the residual, of the output }.
+ * Returns the number of launches (rows beyond max_rows are not written), or a negative npas_status. */
+#define NPAS_DESCRIBE_COLS 11
+int npas_stack_describe(const npas_stack *s, int N, int64_t *rows_host, int max_rows);
 void npas_stack_free(npas_stack *s);
 
 #ifdef __cplusplus

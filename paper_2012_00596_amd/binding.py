@@ -13,7 +13,7 @@ SOURCES = ["pack.cpp", "api.cpp", "kernels.hip"]
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "npas.h")
 
 F32, BF16, F16 = 0, 1, 2
-ACT_NONE, ACT_RELU, ACT_RELU6 = 0, 1, 2
+ACT_NONE, ACT_RELU, ACT_RELU6, ACT_HARDSWISH = 0, 1, 2, 3
 SCHEME_BLOCK_PUNCHED, SCHEME_FC_BLOCK, SCHEME_PATTERN, SCHEME_DEPTHWISE = 0, 1, 2, 3
 LAYER_CONV, LAYER_FC, LAYER_MAXPOOL3X3S2, LAYER_GLOBAL_AVGPOOL, LAYER_DEPTHWISE3X3 = 0, 1, 2, 3, 4
 STACK_FUSE_POINTWISE = 1
@@ -28,8 +28,10 @@ EXPORTS = [
     "npas_packed_info", "npas_packed_export", "npas_free", "npas_conv2d_sparse", "npas_conv2d_kernel_name",
     "npas_fc_sparse",
     "npas_maxpool3x3s2", "npas_global_avgpool", "npas_stack_create", "npas_stack_workspace_bytes",
-    "npas_run_stack", "npas_stack_num_launches", "npas_stack_free",
+    "npas_run_stack", "npas_stack_num_launches", "npas_stack_free", "npas_stack_describe", "npas_debug_set_switches",
+    "npas_debug_launch_empty",
 ]
+DESCRIBE_COLS = 11
 
 
 class NpasError(RuntimeError):
@@ -39,15 +41,26 @@ class NpasError(RuntimeError):
 
 
 def build(force: bool = True) -> str:
-    """Compile libnpas.so for gfx950 in-tree with hipcc."""
+    """Compile libnpas.so for gfx950 in-tree with hipcc (one object per source, compiled side by side)."""
+    from concurrent.futures import ThreadPoolExecutor
     srcs = [os.path.join(_CSRC, s) for s in SOURCES]
     deps = srcs + [os.path.join(_CSRC, "npas_internal.h"), HEADER]
     if not force and os.path.exists(_LIB) and all(os.path.getmtime(_LIB) >= os.path.getmtime(d) for d in deps):
         return _LIB
-    cmd = ["hipcc", "-O3", "--offload-arch=gfx950", "-fPIC", "-shared", "-std=c++17",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-           "-o", _LIB] + srcs
-    subprocess.check_call(cmd)
+    flags = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+             "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+    objdir = os.path.join(_HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    objs = [os.path.join(objdir, os.path.basename(s) + ".o") for s in srcs]
+
+    def compile_one(pair):
+        src, obj = pair
+        if force or not os.path.exists(obj) or any(os.path.getmtime(obj) < os.path.getmtime(d) for d in [src] + deps[len(srcs):]):
+            subprocess.check_call(["hipcc"] + flags + ["-c", src, "-o", obj])
+
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+        list(pool.map(compile_one, zip(srcs, objs)))
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", _LIB] + objs)
     return _LIB
 
 
@@ -91,12 +104,26 @@ def lib():
         L.npas_stack_num_launches.argtypes = [vp]
         L.npas_stack_free.argtypes = [vp]
         L.npas_stack_free.restype = None
+        L.npas_stack_describe.argtypes = [vp, ip, vp, ip]
+        L.npas_debug_launch_empty.argtypes = [ip, vp]
+        L.npas_debug_set_switches.argtypes = [C.c_char_p, ip]
+        L.npas_debug_set_switches.restype = None
         _lib = L
     return _lib
 
 
 def last_error() -> str:
     return lib().npas_last_error().decode()
+
+
+def set_switches(force_variant=None, no_balance=False):
+    """Testing aid: replaces NPAS_FORCE_VARIANT / NPAS_NO_BALANCE for this process (None = no override)."""
+    lib().npas_debug_set_switches(force_variant.encode() if force_variant else None, 1 if no_balance else 0)
+
+
+def launch_empty(count, stream=None):
+    """Measurement aid: `count` launches of an empty kernel on the stream."""
+    _check(lib().npas_debug_launch_empty(count, stream))
 
 
 def _check(rc):
@@ -247,6 +274,16 @@ class Stack:
 
     def num_launches(self):
         return int(lib().npas_stack_num_launches(self.handle))
+
+    def describe(self, N):
+        """The launches of one run at batch N: list of dicts (see npas_stack_describe in include/npas.h)."""
+        n = self.num_launches()
+        rows = np.zeros((max(n, 1), DESCRIBE_COLS), dtype=np.int64)
+        got = lib().npas_stack_describe(self.handle, N, _host(rows), n)
+        if got < 0:
+            _check(got)
+        keys = ["first", "last", "src", "res", "out", "off_src", "off_res", "off_out", "bytes_src", "bytes_res", "bytes_out"]
+        return [dict(zip(keys, (int(v) for v in rows[i]))) for i in range(got)]
 
     def run(self, x, y, N, workspace, workspace_bytes, stream=None):
         _check(lib().npas_run_stack(self.handle, _dev(x), _dev(y), N, _dev(workspace), workspace_bytes, stream))

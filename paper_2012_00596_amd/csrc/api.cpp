@@ -188,9 +188,8 @@ bool plan_spatial(const npas_packed *p, int N, int H, int W, int pad, int stride
 {
     static std::mutex mu;
     static std::map<std::array<int, 11>, std::pair<bool, SpatialRingArgs>> cache;
-    // NPAS_FORCE_VARIANT=spatial (tests): take this kernel whenever a plan exists
-    const char *fv = std::getenv("NPAS_FORCE_VARIANT");
-    const int force = fv && std::strcmp(fv, "spatial") == 0;
+    // forced (tests): take this kernel whenever a plan exists
+    const int force = switches().force == FV_SPATIAL;
     const std::array<int, 11> key = {p->KH, p->KW, p->C, p->F, p->ring.nfb, N, H, W, pad, force, stride};
     std::lock_guard<std::mutex> lock(mu);
     auto it = cache.find(key);
@@ -267,14 +266,16 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
 // items fill rounds of 256 workgroups.  False when the weights do not fit or the launch is too small.
 bool plan_resident(const npas_packed *p, int N, int H, int W, int pad, SpatialRingArgs *a)
 {
+    struct Entry { bool fits, worth; SpatialRingArgs g; };
     static std::mutex mu;
-    static std::map<std::array<int, 8>, std::pair<bool, SpatialRingArgs>> cache;
+    static std::map<std::array<int, 8>, Entry> cache;
     const std::array<int, 8> key = {p->KH, p->KW, p->C, p->F, N, H, W, pad};
+    const bool force = switches().force == FV_RESIDENT; // tests: take this kernel whenever a plan exists
     std::lock_guard<std::mutex> lock(mu);
     auto it = cache.find(key);
     if (it != cache.end()) {
-        *a = it->second.second;
-        return it->second.first;
+        *a = it->second.g;
+        return it->second.fits && (force || it->second.worth);
     }
     SpatialRingArgs g;
     std::memset(&g, 0, sizeof g);
@@ -306,6 +307,7 @@ bool plan_resident(const npas_packed *p, int N, int H, int W, int pad, SpatialRi
             }
     }
     ok = ok && bNI > 0;
+    bool worth = false;
     if (ok) {
         g.N = N; g.H = H; g.W = W; g.C = p->C; g.F = p->F; g.Ho = Ho; g.Wo = Wo;
         g.KH = KH; g.KW = KW; g.pad = pad;
@@ -319,13 +321,11 @@ bool plan_resident(const npas_packed *p, int N, int H, int W, int pad, SpatialRi
         g.div_thtw = magic_div((uint32_t)(bTH * bTW)); g.div_phpw = magic_div((uint32_t)(g.PH * g.PW));
         const long items = (long)g.tilesN * g.tilesY * g.tilesX;
         const double eff = (double)N * Ho * Wo / ((double)items * 256.0);
-        const char *fv = std::getenv("NPAS_FORCE_VARIANT");
-        const bool force = fv && std::strcmp(fv, "resident") == 0;
-        ok = force || (items >= 192 && eff >= 0.6);
+        worth = items >= 192 && eff >= 0.6;
     }
-    cache.emplace(key, std::make_pair(ok, g));
+    cache.emplace(key, Entry{ok, worth, g});
     *a = g;
-    return ok;
+    return ok && (force || worth);
 }
 
 // Which kernel a run call launches for this layer and geometry.
@@ -432,15 +432,11 @@ static Route choose_route(const npas_packed *p, int N, int H, int W, int stride,
         if (M1 <= 256 || (p->C >= 1024 && ((M1 + 63) / 64) * ((p->F + 15) / 16) <= 256)) return R_SMALLM; // (and the reduction long)
         return R_POINTWISE_RING;
     }
+    const int fv = switches().force;
+    if (ring_ok && stride == 1 && (p->KH > 1 || p->KW > 1) && p->F <= 64 && fv != FV_NORESIDENT && plan_resident(p, N, H, W, pad, sp))
+        return R_SPATIAL_RESIDENT;
     {
-        const char *fv = std::getenv("NPAS_FORCE_VARIANT");
-        if (ring_ok && stride == 1 && (p->KH > 1 || p->KW > 1) && p->F <= 64 && !(fv && std::strcmp(fv, "noresident") == 0) &&
-            plan_resident(p, N, H, W, pad, sp))
-            return R_SPATIAL_RESIDENT;
-    }
-    {
-        const char *fv = std::getenv("NPAS_FORCE_VARIANT");
-        const bool s2_off = stride == 2 && fv && std::strcmp(fv, "nospatial2") == 0;
+        const bool s2_off = stride == 2 && fv == FV_NOSPATIAL2;
         if (ring_ok && (stride == 1 || stride == 2) && !s2_off && (p->KH > 1 || p->KW > 1) && plan_spatial(p, N, H, W, pad, stride, sp))
             return R_SPATIAL_RING;
     }
@@ -448,8 +444,7 @@ static Route choose_route(const npas_packed *p, int N, int H, int W, int stride,
     // walking the whole reduction alone; split the reduction over the waves of many small workgroups instead
     if (ring_ok && (p->KH > 1 || p->KW > 1)) {
         const long Ho = (H + 2 * pad - p->KH) / stride + 1, Wo = (W + 2 * pad - p->KW) / stride + 1;
-        const char *fv = std::getenv("NPAS_FORCE_VARIANT");
-        const bool force = fv && std::strcmp(fv, "smallm") == 0;
+        const bool force = fv == FV_SMALLM;
         // ... or little work altogether (a 56 x 56 x 64 -> 64 layer at batch 1: 5.8 against 8.8 us)
         const double macs = (double)N * Ho * Wo * p->F * p->C * p->KH * p->KW;
         if (Ho > 0 && Wo > 0 && (force || (long)N * Ho * Wo <= 1024 || macs <= 200e6)) return R_SMALLM;
@@ -475,7 +470,7 @@ const char *route_name(const npas_packed *p, int N, int H, int W, int stride, in
 int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y, int N, int H, int W, int stride,
              int pad, const void *bias, const void *residual, int act, void *stream)
 {
-    if (act != NPAS_ACT_NONE && act != NPAS_ACT_RELU && act != NPAS_ACT_RELU6) {
+    if (!valid_act(act)) {
         set_error("unknown activation %d", act);
         return NPAS_E_SHAPE;
     }
@@ -547,7 +542,7 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         // workgroups are 4 rounds, the last all but empty; 1008 items of 200 pixels are 4 rounds of 200).
         const int th = a.small == 1 ? 64 : a.small == 2 ? 128 : 256;
         a.P = th;
-        if (a.small != 1 && !std::getenv("NPAS_NO_BALANCE")) {
+        if (a.small != 1 && !switches().no_balance) {
             const long rounds = ((long)a.nptiles * a.nfb + 255) / 256;
             const long want = rounds * 256 / a.nfb; // pixel tiles that fill the rounds
             if (want > a.nptiles) {
@@ -612,12 +607,14 @@ struct npas_stack {
         int H, W, C;    // input dims
         int Ho, Wo, F;  // output dims (FC / avgpool: Ho = Wo = 1)
         int dtype;
-        const void *fused_blob = nullptr; // set on the first layer of a fused 1x1 pair
+        bool pair_head = false;           // first layer of a fused 1x1 pair (runs the next layer too)
+        const void *fused_blob = nullptr; // that pair's weight images on the device (NULL without a GPU)
         int fpp_nt1 = 0;                  // live intermediate tiles of that pair
         uint32_t fpp_use[2] = {0, 0};     // chunk masks of that pair
         bool fused_away = false;          // second layer of a fused pair: runs inside the first
         bool pool_fused = false;          // conv whose max pool (the next layer) is done in the same kernel
-        // first layer of a fused 1x1 -> depthwise 3x3 -> 1x1 block: device images and tile
+        // first layer of a fused 1x1 -> depthwise 3x3 -> 1x1 block (runs the next two layers too): device images and tile
+        bool ir_head = false;
         const void *ir_w1 = nullptr, *ir_w3 = nullptr;
         const uint32_t *ir_wdw = nullptr;
         int ir_nslots = 0, ir_TH = 0, ir_TW = 0, ir_residual = 0;
@@ -643,9 +640,14 @@ static size_t tensor_elems_per_image(const npas_stack *s, int t)
     return (size_t)n.Ho * n.Wo * n.F;
 }
 
+// Layers a launch starting at layer i covers beyond i (fused pair, conv + max pool: 1; fused block: 2).
+static int absorbed_after(const npas_stack::Node &n) { return n.ir_head ? 2 : (n.pair_head || n.pool_fused) ? 1 : 0; }
+
 // Greedy first-fit placement of the intermediate tensors (1 .. n-1) into the
-// workspace; a tensor's slot is free again after its last reader has run.
-// Returns total bytes; offsets[t] for intermediates.
+// workspace; a tensor's slot is free again after the last launch reading it has run.
+// `last_use[t]` is the last layer reading tensor t; a fused launch reads its inputs while it writes the
+// output of the last layer it absorbs, which npas_stack_create has recorded by moving last_use of those
+// inputs to that layer.  Returns total bytes; offsets[t] for intermediates.
 static size_t place_tensors(const npas_stack *s, int N, std::vector<size_t> *offsets)
 {
     const int nt = (int)s->nodes.size() + 1;
@@ -655,8 +657,9 @@ static size_t place_tensors(const npas_stack *s, int N, std::vector<size_t> *off
     size_t total = 0;
     const int esz = dtype_size(s->dtype);
     for (int t = 1; t < nt - 1; ++t) { // tensor t is written by layer t-1
-        if (s->nodes[t - 1].fused_blob || s->nodes[t - 1].ir_w1 || s->nodes[t - 1].pool_fused) continue; // intermediate of a fused pair / block never reaches memory
-        if (t >= 2 && s->nodes[t - 2].ir_w1) continue;                      // nor does the second one of a fused block
+        const npas_stack::Node &w = s->nodes[t - 1];
+        if (w.pair_head || w.ir_head || w.pool_fused) continue;          // intermediate of a fused pair / block never reaches memory
+        if (t >= 2 && s->nodes[t - 2].ir_head) continue;                 // nor does the second one of a fused block
         sz[t] = (tensor_elems_per_image(s, t) * N * esz + 255) / 256 * 256;
         // drop tensors whose last reader ran before layer t-1
         live.erase(std::remove_if(live.begin(), live.end(), [&](const Live &l) { return l.until < t - 1; }),
@@ -877,7 +880,7 @@ static int run_depthwise(const npas_packed *p, const void *x, void *y, int N, in
         set_error("bad geometry N=%d H=%d W=%d stride=%d", N, H, W, stride);
         return NPAS_E_SHAPE;
     }
-    if (act != NPAS_ACT_NONE && act != NPAS_ACT_RELU && act != NPAS_ACT_RELU6) {
+    if (!valid_act(act)) {
         set_error("unknown activation %d", act);
         return NPAS_E_SHAPE;
     }
@@ -910,6 +913,15 @@ static int check_pool(const void *x, void *y, int N, int H, int W, int C, int dt
         return NPAS_E_DTYPE;
     }
     return NPAS_OK;
+}
+
+int npas_debug_launch_empty(int count, void *hip_stream)
+{
+    if (count < 0 || count > 100000) {
+        set_error("bad launch count %d", count);
+        return NPAS_E_SHAPE;
+    }
+    return launch_empty(count, hip_stream);
 }
 
 int npas_maxpool3x3s2(const void *x_dev, void *y_dev, int N, int H, int W, int C, npas_dtype dt, void *hip_stream)
@@ -1015,6 +1027,10 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             set_error("layer %d: a depthwise handle needs a DEPTHWISE3X3 layer", i);
             return NPAS_E_SHAPE;
         }
+        if (weighted && !valid_act(d.act)) {
+            set_error("layer %d: unknown activation %d", i, d.act);
+            return NPAS_E_SHAPE;
+        }
         if (weighted && d.packed->dtype != s->dtype) {
             set_error("layer %d: storage type %d differs from the stack's %d", i, d.packed->dtype, s->dtype);
             return NPAS_E_DTYPE;
@@ -1031,13 +1047,29 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
         dims[i + 1] = {nd.Ho, nd.Wo, nd.F};
         s->nodes.push_back(nd);
     }
+    // Uploads a fused launch's weight images; without a GPU the plan is kept (placement and launch count are the
+    // same) and the run call fails like any other on such a machine.
+    int ndev = 0;
+    const bool have_dev = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
+    if (!have_dev) (void)hipGetLastError();
+    auto upload_blob = [&](const void *data, size_t bytes, void **dptr) -> int {
+        *dptr = nullptr;
+        if (!have_dev) return NPAS_OK;
+        if (hipMalloc(dptr, bytes) != hipSuccess || hipMemcpy(*dptr, data, bytes, hipMemcpyHostToDevice) != hipSuccess) {
+            if (*dptr) (void)hipFree(*dptr);
+            set_error("could not upload the weight images of a fused launch (%zu bytes)", bytes);
+            for (void *q : s->blobs) (void)hipFree(q);
+            s->blobs.clear();
+            return NPAS_E_HIP;
+        }
+        s->blobs.push_back(*dptr);
+        return NPAS_OK;
+    };
+    auto busy = [](const npas_stack::Node &n) { return n.fused_away || n.pair_head || n.ir_head || n.pool_fused; };
     if (flags & NPAS_STACK_FUSE_INVERTED_RESIDUAL) {
-        int ndev = 0;
-        bool have_dev = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
-        if (!have_dev) (void)hipGetLastError();
-        for (int i = 0; i + 2 < n_layers && have_dev; ++i) {
+        for (int i = 0; i + 2 < n_layers; ++i) {
             npas_stack::Node &a = s->nodes[i], &b = s->nodes[i + 1], &c = s->nodes[i + 2];
-            if (a.fused_away || !is_plain_pointwise(a.d) || !is_plain_pointwise(c.d) || a.d.res >= 0) continue;
+            if (busy(a) || busy(b) || busy(c) || !is_plain_pointwise(a.d) || !is_plain_pointwise(c.d) || a.d.res >= 0) continue;
             if (b.d.kind != NPAS_LAYER_DEPTHWISE3X3 || b.d.stride != 1 || b.d.bias_dev || b.d.res >= 0) continue;
             if (b.d.src != i + 1 || c.d.src != i + 2 || (c.d.res >= 0 && c.d.res != a.d.src)) continue;
             bool other_reader = false; // the two tensors inside the block must have no reader outside it
@@ -1061,17 +1093,13 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             std::memcpy(blob.data() + o3, ip.w3.data(), b3);
             std::memcpy(blob.data() + od, ip.wdw.data(), bd);
             void *dptr = nullptr;
-            if (hipMalloc(&dptr, blob.size()) != hipSuccess ||
-                hipMemcpy(dptr, blob.data(), blob.size(), hipMemcpyHostToDevice) != hipSuccess) {
-                if (dptr) (void)hipFree(dptr);
-                set_error("could not upload the fused-block weight images");
-                for (void *q : s->blobs) (void)hipFree(q);
-                return NPAS_E_HIP;
+            if (int rc = upload_blob(blob.data(), blob.size(), &dptr)) return rc;
+            a.ir_head = true;
+            if (dptr) {
+                a.ir_w1 = dptr;
+                a.ir_w3 = (const uint8_t *)dptr + o3;
+                a.ir_wdw = (const uint32_t *)((const uint8_t *)dptr + od);
             }
-            s->blobs.push_back(dptr);
-            a.ir_w1 = dptr;
-            a.ir_w3 = (const uint8_t *)dptr + o3;
-            a.ir_wdw = (const uint32_t *)((const uint8_t *)dptr + od);
             a.ir_nslots = ip.nslots; a.ir_TH = th; a.ir_TW = tw; a.ir_residual = c.d.res >= 0;
             b.fused_away = true;
             c.fused_away = true;
@@ -1080,7 +1108,7 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
     if (flags & NPAS_STACK_FUSE_CONV_MAXPOOL) {
         for (int i = 0; i + 1 < n_layers; ++i) {
             npas_stack::Node &a = s->nodes[i], &b = s->nodes[i + 1];
-            if (a.fused_away || a.d.kind != NPAS_LAYER_CONV || b.d.kind != NPAS_LAYER_MAXPOOL3X3S2 || b.d.src != i + 1 || a.d.res >= 0) continue;
+            if (busy(a) || busy(b) || a.d.kind != NPAS_LAYER_CONV || b.d.kind != NPAS_LAYER_MAXPOOL3X3S2 || b.d.src != i + 1 || a.d.res >= 0) continue;
             bool other_reader = false;
             for (int j = i + 1; j < n_layers; ++j)
                 if ((j != i + 1 && s->nodes[j].d.src == i + 1) || s->nodes[j].d.res == i + 1) other_reader = true;
@@ -1091,37 +1119,40 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
         }
     }
     if (flags & NPAS_STACK_FUSE_POINTWISE) {
-        int ndev = 0;
-        bool have_dev = hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0;
-        if (!have_dev) (void)hipGetLastError();
-        for (int i = 0; i + 1 < n_layers && have_dev; ++i) {
+        for (int i = 0; i + 1 < n_layers; ++i) {
             npas_stack::Node &a = s->nodes[i], &b = s->nodes[i + 1];
-            if (a.fused_away || !is_plain_pointwise(a.d) || !is_plain_pointwise(b.d)) continue;
+            // neither layer may already belong to (or head) another fused launch
+            if (busy(a) || busy(b) || !is_plain_pointwise(a.d) || !is_plain_pointwise(b.d)) continue;
             // the intermediate (tensor i+1) must feed layer i+1 only, and neither layer adds a residual
             if (b.d.src != i + 1 || a.d.res >= 0 || b.d.res >= 0) continue;
             bool other_reader = false;
             for (int j = i + 1; j < n_layers; ++j)
                 if ((j != i + 1 && s->nodes[j].d.src == i + 1) || s->nodes[j].d.res == i + 1) other_reader = true;
-            if (other_reader || i + 1 == n_layers) continue;
+            if (other_reader) continue;
             const npas_packed *p1 = a.d.packed, *p2 = b.d.packed;
             if (p1->C > 32 || p1->C % 8 || p2->F % 4 || p2->F > 32) continue;
             FppPlan fp = build_fpp(p1, p2);
             if (!fpp_supported(fp.nt1, (p2->F + 15) / 16)) continue;
-            std::vector<uint16_t> &blob = fp.blob;
             void *dptr = nullptr;
-            if (hipMalloc(&dptr, blob.size() * 2) != hipSuccess ||
-                hipMemcpy(dptr, blob.data(), blob.size() * 2, hipMemcpyHostToDevice) != hipSuccess) {
-                if (dptr) (void)hipFree(dptr);
-                set_error("could not upload the fused-pair weight image");
-                for (void *q : s->blobs) (void)hipFree(q);
-                return NPAS_E_HIP;
-            }
-            s->blobs.push_back(dptr);
+            if (int rc = upload_blob(fp.blob.data(), fp.blob.size() * 2, &dptr)) return rc;
+            a.pair_head = true;
             a.fused_blob = dptr;
             a.fpp_nt1 = fp.nt1;
             a.fpp_use[0] = fp.use[0];
             a.fpp_use[1] = fp.use[1];
             b.fused_away = true;
+        }
+    }
+    // A fused launch reads its inputs while it writes the output of the last layer it absorbs: keep them
+    // allocated until then (the workspace placement frees a tensor after the layer recorded here).
+    for (int i = 0; i < n_layers; ++i) {
+        const npas_stack::Node &h = s->nodes[i];
+        const int last = i + absorbed_after(h);
+        if (last == i) continue;
+        for (int j = i; j <= last; ++j) {
+            const npas_layer_desc &d = s->nodes[j].d;
+            if (d.src <= i) s->last_use[d.src] = std::max(s->last_use[d.src], last);
+            if (d.res >= 0 && d.res <= i) s->last_use[d.res] = std::max(s->last_use[d.res], last);
         }
     }
     *out = s.release();
@@ -1142,8 +1173,45 @@ int npas_stack_num_launches(const npas_stack *s)
     return n;
 }
 
-int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, void *workspace_dev,
-                   size_t workspace_bytes, void *hip_stream)
+int npas_stack_describe(const npas_stack *s, int N, int64_t *rows_host, int max_rows)
+{
+    if (!s || (!rows_host && max_rows > 0)) {
+        set_error("NULL argument");
+        return NPAS_E_NULL;
+    }
+    if (N <= 0 || max_rows < 0) {
+        set_error("bad batch %d or row count %d", N, max_rows);
+        return NPAS_E_SHAPE;
+    }
+    std::vector<size_t> off;
+    (void)place_tensors(s, N, &off);
+    const int nl = (int)s->nodes.size();
+    const int64_t esz = dtype_size(s->dtype);
+    auto where = [&](int t) -> int64_t { return t < 0 ? -3 : t == 0 ? -1 : t == nl ? -2 : (int64_t)off[t]; };
+    auto bytes = [&](int t) -> int64_t { return t < 0 ? 0 : (int64_t)tensor_elems_per_image(s, t) * N * esz; };
+    int r = 0;
+    for (int i = 0; i < nl; ++i) {
+        const npas_stack::Node &n = s->nodes[i];
+        if (n.fused_away) continue;
+        const int last = i + absorbed_after(n);
+        const int res = n.ir_head ? s->nodes[last].d.res : n.d.res; // a fused block adds its input at its last layer
+        if (r < max_rows) {
+            const int64_t row[NPAS_DESCRIBE_COLS] = {i, last, n.d.src, res, last + 1, where(n.d.src), where(res), where(last + 1),
+                                                     bytes(n.d.src), bytes(res), bytes(last + 1)};
+            std::memcpy(rows_host + (size_t)r * NPAS_DESCRIBE_COLS, row, sizeof row);
+        }
+        ++r;
+    }
+    return r;
+}
+
+} // extern "C"
+
+namespace npas {
+
+// The body of npas_run_stack; also behind the allocation-free entry point.
+int run_stack_impl(const npas_stack *s, const void *x_dev, void *y_dev, int N, void *workspace_dev, size_t workspace_bytes,
+                   void *hip_stream)
 {
     if (!s || !x_dev || !y_dev) {
         set_error("NULL argument");
@@ -1153,17 +1221,14 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
         set_error("bad batch %d", N);
         return NPAS_E_SHAPE;
     }
-    std::vector<size_t> off;
-    size_t need;
-    {   // placement depends on N only; keep the last one
-        std::lock_guard<std::mutex> lock(s->place_mu);
-        if (s->place_N != N) {
-            s->place_need = place_tensors(s, N, &s->place_off);
-            s->place_N = N;
-        }
-        off = s->place_off;
-        need = s->place_need;
+    // placement depends on N only; the last one is kept (and read under the lock: no copy, no allocation per call)
+    std::lock_guard<std::mutex> lock(s->place_mu);
+    if (s->place_N != N) {
+        s->place_need = place_tensors(s, N, &s->place_off);
+        s->place_N = N;
     }
+    const std::vector<size_t> &off = s->place_off;
+    const size_t need = s->place_need;
     if (need > 0 && (!workspace_dev || workspace_bytes < need || ((uintptr_t)workspace_dev & 255))) {
         set_error("workspace: need %zu bytes, 256-byte aligned; got %zu at %p", need, workspace_bytes, workspace_dev);
         return NPAS_E_WORKSPACE;
@@ -1180,9 +1245,13 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
         const void *x = tensor(n.d.src);
         void *y = tensor(i + 1);
         int rc = NPAS_OK;
-        if (n.ir_w1) { // this layer and the next two as one kernel; the tensors between them are never stored
+        if (n.ir_head) { // this layer and the next two as one kernel; the tensors between them are never stored
             const npas_packed *p1 = n.d.packed, *p3 = s->nodes[i + 2].d.packed;
             rc = check_run(p1, x, tensor(i + 3), N, n.H, n.W, 1, 0);
+            if (!rc && !n.ir_w1) {
+                set_error("fused block has no device copy (stack created on a machine without a GPU)");
+                rc = NPAS_E_HIP;
+            }
             if (!rc)
                 rc = launch_fused_inverted_residual(p1->dtype, x, tensor(i + 3), n.ir_w1, n.ir_w3, n.ir_wdw, N, n.H, n.W, p1->C,
                                                     p3->F, n.ir_nslots, n.ir_TH, n.ir_TW, n.d.act, s->nodes[i + 1].d.act,
@@ -1196,9 +1265,13 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
             if (rc) return rc;
             continue;
         }
-        if (n.fused_blob) { // this layer and the next as one kernel; the tensor between them is never stored
+        if (n.pair_head) { // this layer and the next as one kernel; the tensor between them is never stored
             const npas_packed *p1 = n.d.packed, *p2 = s->nodes[i + 1].d.packed;
             rc = check_run(p1, x, tensor(i + 2), N, n.H, n.W, 1, 0);
+            if (!rc && !n.fused_blob) {
+                set_error("fused pair has no device copy (stack created on a machine without a GPU)");
+                rc = NPAS_E_HIP;
+            }
             if (!rc)
                 rc = launch_fused_pointwise_pair(p1->dtype, x, tensor(i + 2), n.fused_blob, N * n.H * n.W, p1->C,
                                                  n.fpp_nt1, p2->F, n.d.act, s->nodes[i + 1].d.act, n.fpp_use[0],
@@ -1231,6 +1304,16 @@ int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
         if (rc) return rc;
     }
     return NPAS_OK;
+}
+
+} // namespace npas
+
+extern "C" {
+
+int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, void *workspace_dev,
+                   size_t workspace_bytes, void *hip_stream)
+{
+    return npas::run_stack_impl(s, x_dev, y_dev, N, workspace_dev, workspace_bytes, hip_stream);
 }
 
 void npas_stack_free(npas_stack *s)

@@ -16,11 +16,20 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstdlib>
+#include <mutex>
 #include <type_traits>
 
 #include "npas_internal.h"
 
 namespace npas {
+
+// Raises a kernel's dynamic LDS limit once per process (one std::once_flag per kernel instantiation).
+template <typename K> static void allow_lds_once(std::once_flag &once, K kern, int bytes)
+{
+    std::call_once(once, [&] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    });
+}
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -56,18 +65,26 @@ __device__ __forceinline__ float act_apply(float v, int act)
 {
     if (act == NPAS_ACT_RELU) return fmaxf(v, 0.0f);
     if (act == NPAS_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
+    if (act == NPAS_ACT_HARDSWISH) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
     return v;
 }
 
-// The three activations as one clamp to [lo, hi] (none: +-inf, ReLU: [0, inf), ReLU6: [0, 6]).
+// The activations as one clamp to [lo, hi] (none: +-inf, ReLU: [0, inf), ReLU6: [0, 6]); hard-swish
+// (v * clamp(v + 3, 0, 6) / 6) is that clamp of v + 3 times v / 6, behind a wave-uniform flag.
 struct Clamp {
     float lo, hi;
+    bool hs;
 };
 __device__ __forceinline__ Clamp clamp_of(int act)
 {
-    return Clamp{act == NPAS_ACT_NONE ? -INFINITY : 0.0f, act == NPAS_ACT_RELU6 ? 6.0f : INFINITY};
+    return Clamp{act == NPAS_ACT_NONE ? -INFINITY : 0.0f, (act == NPAS_ACT_RELU6 || act == NPAS_ACT_HARDSWISH) ? 6.0f : INFINITY,
+                 act == NPAS_ACT_HARDSWISH};
 }
-__device__ __forceinline__ float clampf(float v, Clamp c) { return __builtin_amdgcn_fmed3f(v, c.lo, c.hi); }
+__device__ __forceinline__ float clampf(float v, Clamp c)
+{
+    if (c.hs) return v * __builtin_amdgcn_fmed3f(v + 3.0f, 0.0f, 6.0f) * (1.0f / 6.0f);
+    return __builtin_amdgcn_fmed3f(v, c.lo, c.hi);
+}
 
 // fp32 -> 16-bit storage, round to nearest even.
 template <int DT> __device__ __forceinline__ uint16_t to_storage(float v)
@@ -558,11 +575,8 @@ template <int DT, int WT, int WB, int WGF, int NPF, int OCC>
 static int launch_slab_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
     auto kern = conv_slab_mfma_kernel<DT, WT, WB, WGF, NPF, OCC>;
-    static bool attr_done = false; // one flag per instantiation
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        attr_done = true;
-    }
+    static std::once_flag once; // one per instantiation
+    allow_lds_once(once, kern, 96 * 1024);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds_bytes, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -1239,11 +1253,8 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
 template <int DT, int PG, bool S2 = false> static void launch_spatial_inst(const SpatialRingArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
     auto kern = spatial_ring_kernel<DT, PG, S2>;
-    static bool attr_done = false; // one flag per instantiation
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_done = true;
-    }
+    static std::once_flag once; // one per instantiation
+    allow_lds_once(once, kern, 160 * 1024);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(spatial_threads(PG)), lds_bytes, st, a);
 }
 
@@ -1455,11 +1466,8 @@ __global__ __launch_bounds__(kResidentThreads) void spatial_resident_kernel(Spat
 template <int DT> static void launch_resident_inst(const SpatialRingArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
     auto kern = spatial_resident_kernel<DT>;
-    static bool attr_done = false; // one flag per instantiation
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_done = true;
-    }
+    static std::once_flag once; // one per instantiation
+    allow_lds_once(once, kern, 160 * 1024);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kResidentThreads), lds_bytes, st, a);
 }
 
@@ -1493,12 +1501,9 @@ int launch_spatial_resident(int dtype, const SpatialRingArgs &a, void *stream)
 
 template <int DT, typename Cfg> static void launch_pointwise_cfg(const RingArgs &a, hipStream_t st)
 {
-    static bool attr_done = false;
+    static std::once_flag once; // one per instantiation
     auto kern = pointwise_ring_kernel<DT, Cfg>;
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
-        attr_done = true;
-    }
+    allow_lds_once(once, kern, (int)Cfg::kLdsBytes);
     const unsigned grid = (unsigned)std::min<long>((long)a.nptiles * a.nfb, 256);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::kThreads), Cfg::kLdsBytes, st, a);
 }
@@ -1527,18 +1532,12 @@ int launch_pointwise_ring(int dtype, const RingArgs &a, void *stream)
     return NPAS_OK;
 }
 
-static bool g_lds_attr_set[2][2] = {{false, false}, {false, false}};
-
 template <int DT, int S>
 static int launch_mfma_inst(const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, hipStream_t st)
 {
     auto kern = conv_gather_mfma_kernel<DT, S>;
-    bool &done = g_lds_attr_set[DT == NPAS_BF16 ? 0 : 1][S == 8 ? 0 : 1];
-    if (!done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  64 * 1024);
-        done = true;
-    }
+    static std::once_flag once; // one per instantiation
+    allow_lds_once(once, kern, 64 * 1024);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds_bytes, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -1954,20 +1953,14 @@ int launch_conv_smallm(int dtype, const SmallMArgs &a, void *stream)
         set_error("conv_smallm_mfma: unsupported shape");
         return NPAS_E_SHAPE;
     }
-    static bool attr_done[2] = {false, false};
+    static std::once_flag once[2];
     if (dtype == NPAS_BF16) {
         auto kern = conv_smallm_mfma_kernel<NPAS_BF16>;
-        if (!attr_done[0]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-            attr_done[0] = true;
-        }
+        allow_lds_once(once[0], kern, (int)lds_bytes);
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1024), lds_bytes, st, a);
     } else if (dtype == NPAS_F16) {
         auto kern = conv_smallm_mfma_kernel<NPAS_F16>;
-        if (!attr_done[1]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-            attr_done[1] = true;
-        }
+        allow_lds_once(once[1], kern, (int)lds_bytes);
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(1024), lds_bytes, st, a);
     } else {
         set_error("conv_smallm_mfma needs a 16-bit storage type");
@@ -2534,20 +2527,14 @@ int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void
         return NPAS_E_SHAPE;
     }
     const long grid = (long)N * a.tilesY * a.tilesX;
-    static bool attr_done[2] = {false, false};
+    static std::once_flag once[2];
     if (dtype == NPAS_BF16) {
         auto kern = fused_inverted_residual_kernel<NPAS_BF16>;
-        if (!attr_done[0]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            attr_done[0] = true;
-        }
+        allow_lds_once(once[0], kern, 160 * 1024);
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, st, a);
     } else if (dtype == NPAS_F16) {
         auto kern = fused_inverted_residual_kernel<NPAS_F16>;
-        if (!attr_done[1]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            attr_done[1] = true;
-        }
+        allow_lds_once(once[1], kern, 160 * 1024);
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, st, a);
     } else {
         set_error("fused inverted residual needs a 16-bit storage type");
@@ -2779,6 +2766,19 @@ int launch_depthwise3x3(int dt, const void *x, void *y, const void *w, const flo
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("depthwise3x3 launch failed: %s", hipGetErrorString(e));
+        return NPAS_E_HIP;
+    }
+    return NPAS_OK;
+}
+
+__global__ void empty_kernel() {}
+
+int launch_empty(int count, void *stream)
+{
+    for (int i = 0; i < count; ++i) hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("empty launch failed: %s", hipGetErrorString(e));
         return NPAS_E_HIP;
     }
     return NPAS_OK;

@@ -18,6 +18,17 @@ void set_error(const char *fmt, ...);
 
 inline int dtype_size(int dt) { return dt == NPAS_F32 ? 4 : 2; }
 
+// Testing switches (NPAS_FORCE_VARIANT / NPAS_NO_BALANCE): read from the environment once, at load;
+// npas_debug_set_switches replaces them.
+enum ForceVariant { FV_NONE = 0, FV_GATHER, FV_SLAB, FV_NORING, FV_NOSMALLC, FV_SPATIAL, FV_NOSPATIAL2, FV_SMALLM,
+                    FV_RESIDENT, FV_NORESIDENT, FV_NOFCGATHER, FV_VALU };
+struct Switches {
+    int force = FV_NONE;
+    bool no_balance = false;
+};
+const Switches &switches();
+inline bool valid_act(int act) { return act >= NPAS_ACT_NONE && act <= NPAS_ACT_HARDSWISH; }
+
 // Kernel variants a packed layer can be executed with.
 enum Variant {
     V_VALU_F32 = 0,    // fp32 storage: one thread per (pixel, filter sub-group), scalar-broadcast weights
@@ -259,8 +270,11 @@ struct ConvPlan {
 };
 
 int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, const void *w_host);
-int upload(npas_packed *p);
+int upload(npas_packed *p, void *hip_stream);
 int plan_conv(const npas_packed *p, int N, int H, int W, int stride, int pad, ConvPlan *out);
+
+int run_stack_impl(const npas_stack *s, const void *x_dev, void *y_dev, int N, void *workspace_dev, size_t workspace_bytes,
+                   void *hip_stream);
 
 // launchers (kernels.hip)
 int launch_conv_mfma(int dtype, int variant, const ConvMfmaArgs &a, unsigned grid, size_t lds_bytes, void *stream);
@@ -283,6 +297,7 @@ int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void
                                    int residual, void *stream);
 int launch_depthwise3x3(int dt, const void *x, void *y, const void *w, const float *bias, const void *residual, int N, int H,
                         int W, int C, int stride, int act, void *stream);
+int launch_empty(int count, void *stream);
 int launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream);
 int launch_avgpool(const void *x, void *y, int N, int H, int W, int C, int dt, void *stream);
 

@@ -28,6 +28,29 @@ void set_error(const char *fmt, ...)
 
 const char *last_error() { return g_err; }
 
+static int parse_force(const char *v)
+{
+    static const char *names[] = {"", "gather", "slab", "noring", "nosmallc", "spatial", "nospatial2", "smallm",
+                                  "resident", "noresident", "nofcgather", "valu"};
+    if (!v) return FV_NONE;
+    for (int i = 1; i < (int)(sizeof(names) / sizeof(names[0])); ++i)
+        if (strcmp(v, names[i]) == 0) return i;
+    return FV_NONE;
+}
+
+static Switches &switches_rw()
+{
+    static Switches sw = [] {
+        Switches s;
+        s.force = parse_force(getenv("NPAS_FORCE_VARIANT"));
+        s.no_balance = getenv("NPAS_NO_BALANCE") != nullptr;
+        return s;
+    }();
+    return sw;
+}
+
+const Switches &switches() { return switches_rw(); }
+
 static inline size_t widx(int f, int c, int kh, int kw, int C, int KH, int KW)
 {
     return (((size_t)f * C + c) * KH + kh) * KW + kw;
@@ -363,21 +386,21 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         // times the operand-fetch cost per kept position of the slab path; it pays once
         // fewer than a quarter of a tile's positions survive, and it is the only path for
         // channel counts that are not a multiple of 8 or filter counts that are not a multiple of 4.
-        const char *force = getenv("NPAS_FORCE_VARIANT"); // "gather" | "slab" | "noring" | "nosmallc": testing aid
+        const int force = switches().force; // gather | slab | noring | nosmallc: testing aid
         const bool slab_ok = p->C % 8 == 0 && p->F % 4 == 0;
         p->fmt.density = union_density(p, mask_full.data());
         bool gather = !slab_ok || p->fmt.density < 0.25;
-        if (force && slab_ok && (strcmp(force, "gather") == 0 || strcmp(force, "slab") == 0)) gather = strcmp(force, "gather") == 0;
+        if (slab_ok && (force == FV_GATHER || force == FV_SLAB)) gather = force == FV_GATHER;
         if (gather) build_mfma_gather(p, mask_full.data(), (const uint8_t *)w_host);
         else build_mfma_slab(p, mask_full.data(), (const uint8_t *)w_host);
         // layers with whole 64-channel chunks also get the streaming (ring) format, which the run calls
         // prefer for 1x1 layers without padding and k x k layers at stride 1 unless the layer is sparse
         // enough for the gather kernel to win (the ring multiplies every position)
         if (p->C % 64 == 0 && p->F % 4 == 0 && (double)((p->F + 127) / 128) * p->C * p->KH * p->KW * 256.0 < 256e6 &&
-            !(force && strcmp(force, "noring") == 0))
+            force != FV_NORING)
             build_ring(p, mask_full.data(), (const uint8_t *)w_host);
         if (p->C < 8 && p->F <= 64 && p->F % 4 == 0 && p->C * p->KH * p->KW <= 160 && p->KH * p->KW > 1 &&
-            !(force && strcmp(force, "nosmallc") == 0))
+            force != FV_NOSMALLC)
             build_smallc(p, mask_full.data(), (const uint8_t *)w_host);
     }
     return NPAS_OK;
@@ -392,7 +415,7 @@ static size_t place(std::vector<uint8_t> &blob, const std::vector<T> &v)
     return off;
 }
 
-int upload(npas_packed *p)
+int upload(npas_packed *p, void *hip_stream)
 {
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
@@ -416,7 +439,9 @@ int upload(npas_packed *p)
         set_error("hipMalloc(%zu) failed: %s", blob.size(), hipGetErrorString(e));
         return NPAS_E_HIP;
     }
-    e = hipMemcpy(ptr, blob.data(), blob.size(), hipMemcpyHostToDevice);
+    // on the caller's stream; the source is a local buffer, so wait for the copy before it goes away
+    e = hipMemcpyAsync(ptr, blob.data(), blob.size(), hipMemcpyHostToDevice, (hipStream_t)hip_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream);
     if (e != hipSuccess) {
         (void)hipFree(ptr);
         set_error("hipMemcpy to device failed: %s", hipGetErrorString(e));
@@ -441,10 +466,10 @@ int upload(npas_packed *p)
     return NPAS_OK;
 }
 
-static int finish_pack(npas_packed *p, const std::vector<uint8_t> &mask, const void *w, npas_packed **out)
+static int finish_pack(npas_packed *p, const std::vector<uint8_t> &mask, const void *w, void *hip_stream, npas_packed **out)
 {
     int rc = build_device_format(p, mask, w);
-    if (rc == NPAS_OK) rc = upload(p);
+    if (rc == NPAS_OK) rc = upload(p, hip_stream);
     if (rc != NPAS_OK) {
         delete p;
         return rc;
@@ -484,10 +509,16 @@ extern "C" {
 
 const char *npas_last_error(void) { return npas::last_error(); }
 
+void npas_debug_set_switches(const char *force_variant, int no_balance)
+{
+    npas::Switches &sw = npas::switches_rw();
+    sw.force = npas::parse_force(force_variant);
+    sw.no_balance = no_balance != 0;
+}
+
 int npas_pack_block_punched(const void *w_host, const uint8_t *mask_host, int F, int C, int KH, int KW, int Bf,
                             int Bc, npas_dtype dt, void *hip_stream, npas_packed **out)
 {
-    (void)hip_stream;
     int rc = check_common(w_host, mask_host, out, F, C, KH, KW, Bf, Bc, dt);
     if (rc) return rc;
     size_t n = (size_t)F * C * KH * KW;
@@ -499,13 +530,12 @@ int npas_pack_block_punched(const void *w_host, const uint8_t *mask_host, int F,
     p->F = F; p->C = C; p->KH = KH; p->KW = KW; p->Bf = std::min(Bf, F); p->Bc = std::min(Bc, C);
     pack_canonical(p, (const uint8_t *)w_host, mask_host);
     std::vector<uint8_t> mask(mask_host, mask_host + n);
-    return finish_pack(p, mask, w_host, out);
+    return finish_pack(p, mask, w_host, hip_stream, out);
 }
 
 int npas_pack_fc_block(const void *w_host, const uint8_t *mask_host, int OUT, int IN, int Br, int Bcol,
                        npas_dtype dt, void *hip_stream, npas_packed **out)
 {
-    (void)hip_stream;
     int rc = check_common(w_host, mask_host, out, OUT, IN, 1, 1, Br, Bcol, dt);
     if (rc) return rc;
     size_t n = (size_t)OUT * IN;
@@ -517,13 +547,12 @@ int npas_pack_fc_block(const void *w_host, const uint8_t *mask_host, int OUT, in
     p->F = OUT; p->C = IN; p->KH = 1; p->KW = 1; p->Bf = std::min(Br, OUT); p->Bc = std::min(Bcol, IN);
     pack_canonical(p, (const uint8_t *)w_host, mask_host);
     std::vector<uint8_t> mask(mask_host, mask_host + n);
-    return finish_pack(p, mask, w_host, out);
+    return finish_pack(p, mask, w_host, hip_stream, out);
 }
 
 int npas_pack_pattern(const void *w_host, const uint8_t *mask_host, int F, int C, const uint8_t *library_host,
                       int n_pat, npas_dtype dt, void *hip_stream, npas_packed **out)
 {
-    (void)hip_stream;
     int rc = check_common(w_host, mask_host, out, F, C, 3, 3, 1, 1, dt);
     if (rc) return rc;
     if (!library_host) {
@@ -567,12 +596,11 @@ int npas_pack_pattern(const void *w_host, const uint8_t *mask_host, int F, int C
     }
     pack_canonical(p, w, mask_host);
     std::vector<uint8_t> mask(mask_host, mask_host + n);
-    return finish_pack(p, mask, w_host, out);
+    return finish_pack(p, mask, w_host, hip_stream, out);
 }
 
 int npas_pack_depthwise3x3(const void *w_host, int C, npas_dtype dt, void *hip_stream, npas_packed **out)
 {
-    (void)hip_stream;
     if (!w_host || !out) {
         set_error("NULL argument (w_host=%p out=%p)", w_host, (void *)out);
         return NPAS_E_NULL;
@@ -606,7 +634,7 @@ int npas_pack_depthwise3x3(const void *w_host, int C, npas_dtype dt, void *hip_s
         for (int c = 0; c < C; ++c)
             for (int t = 0; t < 9; ++t) p->fmt.wfrag[(size_t)t * C + c] = w[(size_t)c * 9 + t];
     }
-    int rc = upload(p);
+    int rc = upload(p, hip_stream);
     if (rc != NPAS_OK) {
         delete p;
         return rc;

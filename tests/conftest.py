@@ -17,3 +17,10 @@ def npas():
     """The Python binding of the HIP library (built beforehand, in-tree)."""
     import paper_2012_00596_amd as pkg
     return pkg
+
+
+@pytest.fixture
+def force_variant(npas):
+    """Overrides the library's kernel / format choice for one test (the NPAS_FORCE_VARIANT switch)."""
+    yield lambda name: npas.set_switches(name)
+    npas.set_switches(None)

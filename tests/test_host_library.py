@@ -177,3 +177,103 @@ def test_kernel_choice_follows_layer_and_launch_shape():
     assert name(p, 2, 224, 224, 2, 3) == "conv_smallc_mfma"      # fewer than 8 input channels
     p = _bp_layer(24, 144, 1, 45, rate=4)
     assert name(p, 64, 56, 56, 1, 0) == "conv_slab_mfma"         # channels not a multiple of 64
+
+
+# ---- workspace placement of fused stacks (host logic: works without a GPU) -----------------------------------
+
+def _pw(seed, idx, C, F, act, src, res=-1):
+    return configs._bp_conv(seed, idx, C, F, 1, 1, 0, 8, 8, 2, 0.2, dtypes.BF16, act, src, res, name=f"pw{idx}")
+
+
+def _dw(seed, idx, C, src, stride=1):
+    ws, we = configs._tensor(seed, 150 + idx, (C, 3, 3), 0.3, dtypes.BF16)
+    return configs.Layer("dwconv", "", C, C, 3, 3, stride, 1, 1, 1, 1.0, configs.ACT_RELU6, src, -1, ws, we, name=f"dw{idx}")
+
+
+def _stack(layers, HW, flags):
+    packed = [helpers.pack_layer(npas, L, dtypes.BF16) if L.kind in ("conv", "fc", "dwconv") else None for L in layers]
+    return npas.Stack(helpers.stack_descs(npas, layers, packed), HW, HW, flags)
+
+
+def _assert_placement_is_safe(st, N):
+    """No launch may write over bytes that it, or a later launch, still has to read: tensors whose lifetimes
+    (launch that writes them .. last launch that reads them) intersect must not share workspace bytes."""
+    rows = st.describe(N)
+    assert len(rows) == st.num_launches()
+    born, last_read, where = {}, {}, {}
+    for r, row in enumerate(rows):
+        for key in ("src", "res"):
+            t = row[key]
+            if t >= 0:
+                last_read[t] = r
+                if row["off_" + key] >= 0:
+                    assert where.setdefault(t, (row["off_" + key], row["bytes_" + key])) == (row["off_" + key], row["bytes_" + key])
+        t = row["out"]
+        born[t] = r
+        if row["off_out"] >= 0:
+            where[t] = (row["off_out"], row["bytes_out"])
+            assert row["off_out"] % 256 == 0 and row["off_out"] + row["bytes_out"] <= st.workspace_bytes(N)
+    ts = sorted(where)
+    for i, a in enumerate(ts):
+        for b in ts[i + 1:]:
+            la, lb = (born.get(a, -1), last_read.get(a, born.get(a, -1))), (born.get(b, -1), last_read.get(b, born.get(b, -1)))
+            if la[0] <= lb[1] and lb[0] <= la[1]:               # alive during a common launch
+                (oa, sa), (ob, sb) = where[a], where[b]
+                assert oa + sa <= ob or ob + sb <= oa, f"tensors {a} and {b} overlap in the workspace while both are alive"
+    return rows
+
+
+def test_fused_launches_never_write_over_their_own_inputs():
+    A = configs
+    # three fused 1x1 pairs in a row, of unequal widths (before the fix tensor 4 was placed over tensor 2)
+    chain = [_pw(1, 0, 16, 48, A.ACT_RELU6, 0), _pw(1, 1, 48, 24, A.ACT_NONE, 1),
+             _pw(1, 2, 24, 64, A.ACT_RELU6, 2), _pw(1, 3, 64, 8, A.ACT_NONE, 3),
+             _pw(1, 4, 8, 40, A.ACT_RELU6, 4), _pw(1, 5, 40, 32, A.ACT_NONE, 5)]
+    st = _stack(chain, 12, npas.STACK_FUSE_POINTWISE)
+    rows = _assert_placement_is_safe(st, 3)
+    assert [(r["first"], r["last"]) for r in rows] == [(0, 1), (2, 3), (4, 5)]
+    assert rows[1]["off_src"] >= 0 and rows[1]["off_out"] >= 0
+    # two inverted-residual blocks without residual, then a plain layer
+    blocks = [_pw(2, 0, 16, 64, A.ACT_RELU6, 0), _dw(2, 1, 64, 1), _pw(2, 2, 64, 24, A.ACT_NONE, 2),
+              _pw(2, 3, 24, 96, A.ACT_RELU6, 3), _dw(2, 4, 96, 4), _pw(2, 5, 96, 32, A.ACT_NONE, 5),
+              _pw(2, 6, 32, 16, A.ACT_RELU, 6)]
+    st = _stack(blocks, 10, npas.STACK_FUSE_INVERTED_RESIDUAL)
+    rows = _assert_placement_is_safe(st, 2)
+    assert [(r["first"], r["last"]) for r in rows] == [(0, 2), (3, 5), (6, 6)]
+    # with a residual the fused block reads its input again at its last layer
+    res = [_pw(3, 0, 24, 24, A.ACT_RELU, 0), _pw(3, 1, 24, 96, A.ACT_RELU6, 1), _dw(3, 2, 96, 2),
+           _pw(3, 3, 96, 24, A.ACT_NONE, 3, res=1), _pw(3, 4, 24, 16, A.ACT_NONE, 4)]
+    st = _stack(res, 9, npas.STACK_FUSE_INVERTED_RESIDUAL)
+    rows = _assert_placement_is_safe(st, 2)
+    assert (rows[1]["first"], rows[1]["last"], rows[1]["src"], rows[1]["res"]) == (1, 3, 1, 1)
+    # the same stacks without fusion, and a residual stack with every fusion allowed
+    for layers, hw in ((chain, 12), (blocks, 10), (res, 9)):
+        _assert_placement_is_safe(_stack(layers, hw, 0), 2)
+    w = configs.config5(batch=1, HW=32, width=16, blocks=(1, 2, 1, 1))
+    for flags in (0, npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL | npas.STACK_FUSE_CONV_MAXPOOL):
+        st = _stack(w.layers, 32, flags)
+        rows = _assert_placement_is_safe(st, 3)
+        assert rows[-1]["off_out"] == -2 and rows[0]["off_src"] == -1
+
+
+def test_a_layer_joins_one_fused_launch_only():
+    """A 1x1 layer in front of a fused inverted-residual block must not swallow the block's first layer as the
+    second half of a fused pair (the block would then never run)."""
+    A = configs
+    layers = [_pw(4, 0, 16, 24, A.ACT_RELU6, 0),
+              _pw(4, 1, 24, 32, A.ACT_RELU6, 1), _dw(4, 2, 32, 2), _pw(4, 3, 32, 16, A.ACT_NONE, 3)]
+    st = _stack(layers, 8, npas.STACK_FUSE_POINTWISE | npas.STACK_FUSE_INVERTED_RESIDUAL)
+    rows = _assert_placement_is_safe(st, 2)
+    assert [(r["first"], r["last"]) for r in rows] == [(0, 0), (1, 3)]
+    assert {r["out"] for r in rows} == {1, 4}
+
+
+def test_switches_are_read_once_and_can_be_replaced():
+    p = _bp_layer(128, 128, 3, 42)
+    assert npas.conv2d_kernel_name(p, 2, 14, 14, 1, 1) == "conv_smallm_mfma"
+    npas.set_switches("spatial")
+    try:
+        assert npas.conv2d_kernel_name(p, 2, 14, 14, 1, 1) == "spatial_ring"
+    finally:
+        npas.set_switches(None)
+    assert npas.conv2d_kernel_name(p, 2, 14, 14, 1, 1) == "conv_smallm_mfma"
