@@ -9,7 +9,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 _LIB = os.path.join(_HERE, "libnpas.so")
-SOURCES = ["pack.cpp", "api.cpp", "kernels.hip"]
+SOURCES = ["pack.cpp", "api.cpp", "kernels.hip", "small_kernels.hip"]
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "npas.h")
 
 F32, BF16, F16 = 0, 1, 2
@@ -44,7 +44,7 @@ def build(force: bool = True) -> str:
     """Compile libnpas.so for gfx950 in-tree with hipcc (one object per source, compiled side by side)."""
     from concurrent.futures import ThreadPoolExecutor
     srcs = [os.path.join(_CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(_CSRC, "npas_internal.h"), HEADER]
+    deps = srcs + [os.path.join(_CSRC, "npas_internal.h"), os.path.join(_CSRC, "device_util.h"), HEADER]
     if not force and os.path.exists(_LIB) and all(os.path.getmtime(_LIB) >= os.path.getmtime(d) for d in deps):
         return _LIB
     flags = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",

@@ -329,7 +329,7 @@ bool plan_resident(const npas_packed *p, int N, int H, int W, int pad, SpatialRi
 }
 
 // Which kernel a run call launches for this layer and geometry.
-enum Route { R_VALU, R_POINTWISE_RING, R_SPATIAL_RING, R_SPATIAL_RESIDENT, R_SMALLC, R_SMALLM, R_SLAB, R_GATHER };
+enum Route { R_VALU, R_WAVE_F32, R_FC_GATHER, R_POINTWISE_RING, R_SPATIAL_RING, R_SPATIAL_RESIDENT, R_SMALLC, R_SMALLM, R_SLAB, R_GATHER };
 
 // Tile and patch of a small-channel launch: TH x TW = 256 output pixels with the fewest computed-but-
 // unused ones, the patch within 48 KB of LDS.  False when no tile shape fits.
@@ -414,7 +414,17 @@ int run_conv_maxpool(const npas_packed *p, const void *x, void *y, int N, int H,
 static Route choose_route(const npas_packed *p, int N, int H, int W, int stride, int pad, SpatialRingArgs *sp,
                           SmallCArgs *sc = nullptr)
 {
-    if (p->fmt.variant == V_VALU_F32) return R_VALU;
+    if (p->fmt.variant == V_VALU_F32) {
+        // few lanes in all (a small layer: the launch is a chain of load latencies): split every reduction over 8 lanes
+        const long Ho0 = (H + 2 * pad - p->KH) / stride + 1, Wo0 = (W + 2 * pad - p->KW) / stride + 1;
+        const bool small = (double)N * Ho0 * Wo0 * p->fmt.nvg * 8.0 <= 4.0 * 1024 * 1024;
+        return p->wavef.present && small && switches().force != FV_VALU ? R_WAVE_F32 : R_VALU;
+    }
+    // sparse 1x1 / FC layer on few pixels: the exact per-tile lists (nothing pruned is multiplied, compact weights)
+    if (p->fc.present && p->KH == 1 && p->KW == 1 && pad == 0 && switches().force != FV_NOFCGATHER) {
+        const long M0 = (long)N * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+        if (M0 <= 1024) return R_FC_GATHER;
+    }
     SmallCArgs sc_local;
     if (p->smallc.present && plan_smallc(p, N, H, W, stride, pad, sc ? sc : &sc_local)) return R_SMALLC;
     // A gather-format layer (few surviving positions) leaves the ring kernels, which multiply
@@ -457,6 +467,8 @@ const char *route_name(const npas_packed *p, int N, int H, int W, int stride, in
     SpatialRingArgs sp;
     switch (choose_route(p, N, H, W, stride, pad, &sp)) {
     case R_VALU: return "conv_valu_f32";
+    case R_WAVE_F32: return "conv_wave_f32";
+    case R_FC_GATHER: return "fc_gather_mfma";
     case R_POINTWISE_RING: return "pointwise_ring";
     case R_SPATIAL_RING: return "spatial_ring";
     case R_SPATIAL_RESIDENT: return "spatial_resident";
@@ -495,6 +507,37 @@ int run_conv(const npas_packed *p, const ConvPlan *plan, const void *x, void *y,
         a.div_howo = magic_div((uint32_t)(a.Ho * a.Wo)); a.div_wo = magic_div((uint32_t)a.Wo);
         a.div_kw = magic_div((uint32_t)p->KW); a.div_T2 = magic_div((uint32_t)(2 * p->KH * p->KW));
         return launch_conv_smallm(p->dtype, a, stream);
+    }
+    if (route == R_FC_GATHER) {
+        FcGatherArgs a;
+        a.x = x; a.y = y; a.residual = residual; a.bias = (const float *)bias;
+        a.tptr = p->dev.fc_tptr; a.koff = p->dev.fc_koff; a.wimg = p->dev.fc_wimg;
+        a.C = p->C; a.F = p->F; a.ntiles = p->fc.ntiles; a.act = act;
+        a.H = H; a.W = W; a.stride = stride;
+        a.Ho = (H - 1) / stride + 1; a.Wo = (W - 1) / stride + 1;
+        a.M = N * a.Ho * a.Wo;
+        a.pitch = 2 * p->C + 8;
+        a.div_howo = magic_div((uint32_t)(a.Ho * a.Wo)); a.div_wo = magic_div((uint32_t)a.Wo);
+        const long nptiles = (a.M + 15) / 16;
+        // eight waves per workgroup = tiles x runs of a tile's list: as few tiles (as many runs) as keeps the
+        // launch within about two workgroups per CU (each stages the 16 activation rows again)
+        a.tiles_per_wg = 8;
+        for (int tpw = 1; tpw < 8; tpw *= 2)
+            if (nptiles * ((a.ntiles + tpw - 1) / tpw) <= 512) {
+                a.tiles_per_wg = tpw;
+                break;
+            }
+        return launch_fc_gather(p->dtype, a, stream);
+    }
+    if (route == R_WAVE_F32) {
+        WaveF32Args a;
+        a.x = (const float *)x; a.y = (float *)y; a.residual = (const float *)residual; a.bias = (const float *)bias;
+        a.wg_ptr = p->dev.wv_ptr; a.vg_f0 = p->dev.vg_f0; a.kent = p->dev.wv_kent; a.w = p->dev.wv_w;
+        a.nvg = p->fmt.nvg; a.VB = p->fmt.VB;
+        a.N = N; a.H = H; a.W = W; a.C = p->C; a.F = p->F;
+        a.Ho = (H + 2 * pad - p->KH) / stride + 1; a.Wo = (W + 2 * pad - p->KW) / stride + 1;
+        a.KH = p->KH; a.KW = p->KW; a.stride = stride; a.pad = pad; a.act = act;
+        return launch_conv_wave_f32(a, stream);
     }
     if (route == R_VALU) {
         ConvValuArgs a;

@@ -20,120 +20,9 @@
 #include <type_traits>
 
 #include "npas_internal.h"
+#include "device_util.h"
 
 namespace npas {
-
-// Raises a kernel's dynamic LDS limit once per process (one std::once_flag per kernel instantiation).
-template <typename K> static void allow_lds_once(std::once_flag &once, K kern, int bytes)
-{
-    std::call_once(once, [&] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    });
-}
-
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-
-__device__ __forceinline__ uint32_t fastdiv(uint32_t n, uint32_t magic)
-{
-    return magic ? __umulhi(n, magic) : n; // magic = ceil(2^32 / d), 0 for d == 1
-}
-
-// Streaming (non-temporal) 8-byte accesses for tensors that are written or read once per launch and
-// are far larger than the L2: they leave the cache to the operands that are reused.
-__device__ __forceinline__ void store_stream8(void *p, uint2 v)
-{
-    __builtin_nontemporal_store(__builtin_bit_cast(unsigned long long, v), reinterpret_cast<unsigned long long *>(p));
-}
-__device__ __forceinline__ uint2 load_stream8(const void *p)
-{
-    return __builtin_bit_cast(uint2, __builtin_nontemporal_load(reinterpret_cast<const unsigned long long *>(p)));
-}
-__device__ __forceinline__ void store_stream16(void *p, uint4 v)
-{
-    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-    __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4 *>(p));
-}
-__device__ __forceinline__ uint4 load_stream16(const void *p)
-{
-    typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-    return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p)));
-}
-
-__device__ __forceinline__ float act_apply(float v, int act)
-{
-    if (act == NPAS_ACT_RELU) return fmaxf(v, 0.0f);
-    if (act == NPAS_ACT_RELU6) return fminf(fmaxf(v, 0.0f), 6.0f);
-    if (act == NPAS_ACT_HARDSWISH) return v * fminf(fmaxf(v + 3.0f, 0.0f), 6.0f) * (1.0f / 6.0f);
-    return v;
-}
-
-// The activations as one clamp to [lo, hi] (none: +-inf, ReLU: [0, inf), ReLU6: [0, 6]); hard-swish
-// (v * clamp(v + 3, 0, 6) / 6) is that clamp of v + 3 times v / 6, behind a wave-uniform flag.
-struct Clamp {
-    float lo, hi;
-    bool hs;
-};
-__device__ __forceinline__ Clamp clamp_of(int act)
-{
-    return Clamp{act == NPAS_ACT_NONE ? -INFINITY : 0.0f, (act == NPAS_ACT_RELU6 || act == NPAS_ACT_HARDSWISH) ? 6.0f : INFINITY,
-                 act == NPAS_ACT_HARDSWISH};
-}
-__device__ __forceinline__ float clampf(float v, Clamp c)
-{
-    if (c.hs) return v * __builtin_amdgcn_fmed3f(v + 3.0f, 0.0f, 6.0f) * (1.0f / 6.0f);
-    return __builtin_amdgcn_fmed3f(v, c.lo, c.hi);
-}
-
-// fp32 -> 16-bit storage, round to nearest even.
-template <int DT> __device__ __forceinline__ uint16_t to_storage(float v)
-{
-    if (DT == NPAS_BF16) {
-        uint32_t u = __float_as_uint(v);
-        if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40); // NaN stays NaN
-        u += 0x7fffu + ((u >> 16) & 1u);
-        return (uint16_t)(u >> 16);
-    } else {
-        _Float16 h = (_Float16)v;
-        return __builtin_bit_cast(uint16_t, h);
-    }
-}
-
-// two fp32 -> one dword of two 16-bit storage values (lo, hi), round to nearest even
-template <int DT> __device__ __forceinline__ uint32_t pack2(float lo, float hi)
-{
-    typedef __attribute__((ext_vector_type(2))) float f32x2;
-    if (DT == NPAS_BF16) {
-        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
-    } else {
-        typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, f16x2));
-    }
-}
-
-template <int DT> __device__ __forceinline__ float from_storage(uint16_t b)
-{
-    if (DT == NPAS_BF16) return __uint_as_float((uint32_t)b << 16);
-    return (float)__builtin_bit_cast(_Float16, b);
-}
-
-template <int DT> __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c)
-{
-    if (DT == NPAS_BF16)
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
-
-// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run
-// of logical ids so that workgroups sharing an activation patch share an L2.
-__device__ __forceinline__ uint32_t xcd_remap(uint32_t wg, uint32_t nwg)
-{
-    uint32_t xcd = wg & 7u, idx = wg >> 3, q = nwg >> 3, r = nwg & 7u;
-    return xcd * q + (xcd < r ? xcd : r) + idx;
-}
 
 // Copies the input patch of one output tile, channels [cc*CC, cc*CC + CC), into LDS as
 // [patch pixel][channel] with `pitch` bytes per pixel; out-of-image pixels become zeros.

@@ -105,6 +105,31 @@ struct SmallCFormat {
     std::vector<uint16_t> wimg;
 };
 
+// ---- exact-list format of sparse 1x1 / FC layers (fc_gather_mfma): per 16-filter tile the list of input channels
+// kept by ANY filter of the tile, over all of C, ascending, padded to a multiple of 32 with copies of channel 0 whose
+// weights are zero.  With 16-row blocks (the block-based FC scheme) a tile is one block row and the list is exactly
+// the block's kept columns: the shared positions become the K dimension of a dense 16 x K sub-GEMM.
+//   tptr[t] .. tptr[t+1]   the tile's 32-entry steps
+//   koff[step][32]         byte offset (2 * channel) of each entry in a staged activation row
+//   wimg[step][lane][8]    MFMA A-operand image: lane = 16 q + r holds W[16 t + r][entries 8 q .. 8 q + 7]
+struct FcFormat {
+    bool present = false;
+    int ntiles = 0, max_steps = 0;
+    std::vector<int32_t> tptr;
+    std::vector<uint16_t> koff;
+    std::vector<uint16_t> wimg;
+};
+
+// ---- lane-split format of fp32 layers (conv_wave_f32): the canonical group lists, each padded to a multiple of
+// 8 entries (entry coding as vkent, weight rows [entry][VB] as vw; padding entries carry zero weights and repeat the
+// group's first position, or position 0 of an empty group).  wg_ptr[v] .. wg_ptr[v+1] in entries.
+struct WaveF32Format {
+    bool present = false;
+    std::vector<int32_t> wg_ptr;
+    std::vector<uint32_t> kent;
+    std::vector<float> w;
+};
+
 struct DeviceCopy {
     int device = -1;
     void *blob = nullptr; // one allocation holding everything below
@@ -119,6 +144,12 @@ struct DeviceCopy {
     const uint32_t *rg_chunk = nullptr;
     const void *wimg = nullptr;
     const void *scimg = nullptr; // small-channel images
+    const int32_t *fc_tptr = nullptr; // exact-list format
+    const uint16_t *fc_koff = nullptr;
+    const void *fc_wimg = nullptr;
+    const int32_t *wv_ptr = nullptr;  // lane-split fp32 format
+    const uint32_t *wv_kent = nullptr;
+    const float *wv_w = nullptr;
     const void *zeros = nullptr; // 256 bytes of zeros
 };
 
@@ -138,6 +169,8 @@ struct npas_packed {
     npas::DeviceFormat fmt;
     npas::RingFormat ring;
     npas::SmallCFormat smallc;
+    npas::FcFormat fc;
+    npas::WaveF32Format wavef;
     npas::DeviceCopy dev;
     // launch plans already computed for this layer, by geometry (filled by the run calls)
     mutable std::mutex plan_mu;
@@ -262,6 +295,35 @@ struct SpatialRingArgs {
     uint32_t div_tw, div_pw, div_thtw, div_phpw; // magic reciprocals
 };
 
+// Sparse 1x1 / FC layer on few pixels through the exact per-tile lists: see fc_gather_mfma_kernel
+struct FcGatherArgs {
+    const void *x;
+    void *y;
+    const void *residual;
+    const float *bias;
+    const int32_t *tptr;
+    const uint16_t *koff;
+    const void *wimg;
+    int M, C, F, ntiles, act;
+    int tiles_per_wg;   // filter tiles one workgroup (8 waves) walks
+    int pitch;          // bytes of one staged activation row in LDS
+    int H, W, Ho, Wo, stride; // geometry of a strided 1x1 layer (stride 1: M pixels, flat)
+    uint32_t div_howo, div_wo;
+};
+
+// fp32 layer with the reduction of every output split over 8 lanes: see conv_wave_f32_kernel
+struct WaveF32Args {
+    const float *x;
+    float *y;
+    const float *residual;
+    const float *bias;
+    const int32_t *wg_ptr, *vg_f0;
+    const uint32_t *kent;
+    const float *w;
+    int nvg, VB;
+    int N, H, W, C, F, Ho, Wo, KH, KW, stride, pad, act;
+};
+
 // Host-side plan of one conv launch (tile shape, grid, LDS bytes).
 struct ConvPlan {
     ConvGeom g;
@@ -288,6 +350,8 @@ int launch_spatial_resident(int dtype, const SpatialRingArgs &a, void *stream);
 size_t spatial_resident_lds_bytes(int npb, int nst); // LDS of a launch with npb patch blocks and nst weight stages
 int launch_conv_smallc(int dtype, const SmallCArgs &a, void *stream);
 int launch_conv_smallm(int dtype, const SmallMArgs &a, void *stream);
+int launch_fc_gather(int dtype, const FcGatherArgs &a, void *stream);
+int launch_conv_wave_f32(const WaveF32Args &a, void *stream);
 bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
                                 int act1, int act2, uint32_t use0, uint32_t use1, void *stream);

@@ -340,6 +340,69 @@ static void build_smallc(npas_packed *p, const uint8_t *m, const uint8_t *w)
                 }
 }
 
+// Exact-list format (see npas_internal.h): built for 16-bit 1x1 / FC layers sparse enough for it to pay.
+static void build_fc(npas_packed *p, const uint8_t *m, const uint8_t *w)
+{
+    FcFormat &fc = p->fc;
+    const int F = p->F, C = p->C;
+    fc.present = true;
+    fc.ntiles = (F + 15) / 16;
+    fc.tptr.assign(fc.ntiles + 1, 0);
+    fc.koff.clear();
+    fc.wimg.clear();
+    fc.max_steps = 0;
+    const uint16_t *w16 = reinterpret_cast<const uint16_t *>(w);
+    std::vector<int> list;
+    for (int t = 0; t < fc.ntiles; ++t) {
+        const int f0 = 16 * t, nf = std::min(16, F - f0);
+        list.clear();
+        for (int c = 0; c < C; ++c) {
+            bool any = false;
+            for (int j = 0; j < nf && !any; ++j) any = m[(size_t)(f0 + j) * C + c] != 0;
+            if (any) list.push_back(c);
+        }
+        const int steps = ((int)list.size() + 31) / 32;
+        fc.tptr[t] = (int32_t)(fc.koff.size() / 32);
+        fc.max_steps = std::max(fc.max_steps, steps);
+        const size_t k0 = fc.koff.size(), w0 = fc.wimg.size();
+        fc.koff.resize(k0 + (size_t)steps * 32, 0);
+        fc.wimg.resize(w0 + (size_t)steps * 512, 0);
+        for (size_t e = 0; e < list.size(); ++e) {
+            fc.koff[k0 + e] = (uint16_t)(2 * list[e]);
+            const size_t step = e / 32, q = (e % 32) / 8, i = e % 8;
+            for (int r = 0; r < nf; ++r) {
+                const size_t wi = (size_t)(f0 + r) * C + list[e];
+                if (m[wi]) fc.wimg[w0 + step * 512 + (q * 16 + r) * 8 + i] = w16[wi];
+            }
+        }
+    }
+    fc.tptr[fc.ntiles] = (int32_t)(fc.koff.size() / 32);
+}
+
+// Lane-split fp32 format (see npas_internal.h): the sub-group lists of build_valu_f32, padded to multiples of 8.
+static void build_wave_f32(npas_packed *p)
+{
+    const DeviceFormat &d = p->fmt;
+    WaveF32Format &wf = p->wavef;
+    wf.present = true;
+    wf.wg_ptr.assign(1, 0);
+    wf.kent.clear();
+    wf.w.clear();
+    for (int v = 0; v < d.nvg; ++v) {
+        const int k0 = d.vg_ptr[v], k1 = d.vg_ptr[v + 1];
+        for (int k = k0; k < k1; ++k) {
+            wf.kent.push_back(d.vkent[k]);
+            for (int j = 0; j < d.VB; ++j) wf.w.push_back(d.vw[(size_t)k * d.VB + j]);
+        }
+        const uint32_t fill = k1 > k0 ? d.vkent[k0] : 0u;
+        while ((wf.kent.size() - (size_t)wf.wg_ptr[v]) % 8 != 0) {
+            wf.kent.push_back(fill);
+            for (int j = 0; j < d.VB; ++j) wf.w.push_back(0.0f);
+        }
+        wf.wg_ptr.push_back((int32_t)wf.kent.size());
+    }
+}
+
 static void build_valu_f32(npas_packed *p, const uint8_t *m, const uint8_t *w)
 {
     (void)m;
@@ -381,6 +444,7 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
     }
     if (p->dtype == NPAS_F32) {
         build_valu_f32(p, mask_full.data(), (const uint8_t *)w_host);
+        if (switches().force != FV_VALU) build_wave_f32(p);
     } else {
         // Element gather skips exactly what a 16-filter tile's groups punch, at about four
         // times the operand-fetch cost per kept position of the slab path; it pays once
@@ -399,6 +463,9 @@ int build_device_format(npas_packed *p, const std::vector<uint8_t> &mask_full, c
         if (p->C % 64 == 0 && p->F % 4 == 0 && (double)((p->F + 127) / 128) * p->C * p->KH * p->KW * 256.0 < 256e6 &&
             force != FV_NORING)
             build_ring(p, mask_full.data(), (const uint8_t *)w_host);
+        // sparse 1x1 / FC layers also get the exact per-tile lists (a staged activation row must fit in LDS sixteen times)
+        if (p->KH == 1 && p->KW == 1 && p->F % 4 == 0 && p->C % 8 == 0 && p->C <= 4096 && p->fmt.density <= 0.5 && force != FV_NOFCGATHER)
+            build_fc(p, mask_full.data(), (const uint8_t *)w_host);
         if (p->C < 8 && p->F <= 64 && p->F % 4 == 0 && p->C * p->KH * p->KW <= 160 && p->KH * p->KW > 1 &&
             force != FV_NOSMALLC)
             build_smallc(p, mask_full.data(), (const uint8_t *)w_host);
@@ -432,6 +499,8 @@ int upload(npas_packed *p, void *hip_stream)
            o_vw = place(blob, d.vw);
     size_t o_rp = place(blob, p->ring.rg_ptr), o_rc = place(blob, p->ring.rg_chunk), o_ri = place(blob, p->ring.wimg);
     size_t o_sc = place(blob, p->smallc.wimg);
+    size_t o_ft = place(blob, p->fc.tptr), o_fk = place(blob, p->fc.koff), o_fw = place(blob, p->fc.wimg);
+    size_t o_wp = place(blob, p->wavef.wg_ptr), o_wk = place(blob, p->wavef.kent), o_ww = place(blob, p->wavef.w);
     blob.resize((blob.size() + 255) / 256 * 256 + 256);
     void *ptr = nullptr;
     hipError_t e = hipMalloc(&ptr, blob.size());
@@ -462,6 +531,12 @@ int upload(npas_packed *p, void *hip_stream)
     p->dev.rg_chunk = (const uint32_t *)(b + o_rc);
     p->dev.wimg = b + o_ri;
     p->dev.scimg = b + o_sc;
+    p->dev.fc_tptr = (const int32_t *)(b + o_ft);
+    p->dev.fc_koff = (const uint16_t *)(b + o_fk);
+    p->dev.fc_wimg = b + o_fw;
+    p->dev.wv_ptr = (const int32_t *)(b + o_wp);
+    p->dev.wv_kent = (const uint32_t *)(b + o_wk);
+    p->dev.wv_w = (const float *)(b + o_ww);
     p->dev.zeros = b + blob.size() - 256; // the blob ends with 256 zero bytes
     return NPAS_OK;
 }

@@ -54,7 +54,32 @@ def layerwise(npas, torch, w, check_meta=True):
 
 def test_config1_conv3x3_fp32(npas, torch):
     print("config1 fp32 3x3", flush=True)
-    layerwise(npas, torch, configs.config1())
+    w = configs.config1()
+    p = pack_layer(npas, w.layers[0], w.dtype)
+    assert npas.conv2d_kernel_name(p, 1, 32, 32, 1, 1) == "conv_wave_f32"      # reductions split over lanes
+    layerwise(npas, torch, w)
+
+
+def test_config1_conv3x3_fp32_one_lane_per_output(npas, torch, force_variant):
+    force_variant("valu")
+    w = configs.config1()
+    p = pack_layer(npas, w.layers[0], w.dtype)
+    assert npas.conv2d_kernel_name(p, 1, 32, 32, 1, 1) == "conv_valu_f32"
+    layerwise(npas, torch, w)
+
+
+WAVE_F32 = [
+    ("wf_stride2_res_bias_hswish", 2, 9, 9, 8, 12, 3, 3, 2, 1, 4, 4, 2, dtypes.F32, 3, True, True),
+    ("wf_wide_group_1x1", 1, 5, 5, 8, 24, 1, 1, 1, 0, 24, 8, 2, dtypes.F32, 0, False, False),
+    ("wf_list_not_a_multiple_of_8", 3, 7, 6, 5, 6, 3, 3, 1, 1, 2, 5, 3, dtypes.F32, 1, False, True),
+    ("wf_single_filter_groups", 1, 6, 6, 4, 5, 3, 3, 1, 1, 1, 1, 2, dtypes.F32, 2, True, False),
+    ("wf_ragged_lanes", 1, 3, 5, 16, 8, 5, 5, 1, 2, 8, 4, 5, dtypes.F32, 0, False, True),
+]
+
+
+@pytest.mark.parametrize("case", WAVE_F32, ids=[c[0] for c in WAVE_F32])
+def test_fp32_lane_split_kernel(npas, torch, case):
+    _run_edge_case(npas, torch, case, expect_kernel="conv_wave_f32")
 
 
 def test_config2_pointwise_stack_small(npas, torch):
@@ -64,7 +89,37 @@ def test_config2_pointwise_stack_small(npas, torch):
 
 def test_config3_fc_block_full(npas, torch):
     print("config3 full", flush=True)
-    layerwise(npas, torch, configs.config3())
+    w = configs.config3()
+    p = pack_layer(npas, w.layers[0], w.dtype)
+    assert npas.conv2d_kernel_name(p, w.x_shape[0], 1, 1, 1, 0) == "fc_gather_mfma"    # the exact-list kernel
+    layerwise(npas, torch, w)
+
+
+def test_config3_fc_block_full_dense_format_route(npas, torch, force_variant):
+    """The same layer through the route that multiplies the dense weight images (what the exact-list kernel replaced)."""
+    force_variant("nofcgather")
+    w = configs.config3()
+    p = pack_layer(npas, w.layers[0], w.dtype)
+    assert npas.conv2d_kernel_name(p, w.x_shape[0], 1, 1, 1, 0) != "fc_gather_mfma"
+    layerwise(npas, torch, w)
+
+
+FC_GATHER = [
+    # name, B (as N x H x W), C, F, stride, Bf, Bc, rate, dtype, act, use_res, use_bias
+    ("fcg_ragged_rows_and_tiles", (37, 1, 1), 192, 88, 1, 16, 32, 5, dtypes.BF16, 1, False, True),
+    ("fcg_one_row", (1, 1, 1), 64, 16, 1, 16, 32, 4, dtypes.BF16, 0, False, False),
+    ("fcg_8x4_blocks_union_of_two_groups", (3, 9, 11), 256, 136, 1, 8, 4, 5, dtypes.BF16, 3, True, True),
+    ("fcg_fp16_long_list", (5, 1, 1), 2048, 40, 1, 16, 32, 2.5, dtypes.F16, 2, False, True),
+    ("fcg_strided_1x1", (3, 15, 14), 320, 72, 2, 8, 4, 5, dtypes.BF16, 2, True, False),
+    ("fcg_many_tiles_two_rows", (2, 1, 1), 96, 1000, 1, 16, 32, 5, dtypes.BF16, 0, False, True),
+]
+
+
+@pytest.mark.parametrize("case", FC_GATHER, ids=[c[0] for c in FC_GATHER])
+def test_fc_gather_kernel(npas, torch, case):
+    name, (N, H, W), C, F, stride, Bf, Bc, rate, dtype, act, use_res, use_bias = case
+    _run_edge_case(npas, torch, (name, N, H, W, C, F, 1, 1, stride, 0, Bf, Bc, rate, dtype, act, use_res, use_bias),
+                   expect_kernel="fc_gather_mfma")
 
 
 def test_config4_pattern_small(npas, torch):
