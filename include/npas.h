@@ -217,6 +217,15 @@ size_t npas_stack_workspace_bytes(const npas_stack *s, int N);
  * npas_stack_workspace_bytes(s, N) long (NPAS_E_WORKSPACE otherwise). */
 int npas_run_stack(const npas_stack *s, const void *x_dev, void *y_dev, int N, void *workspace_dev,
                    size_t workspace_bytes, void *hip_stream);
+/* npas_run_stack for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The intermediate tensors live in a device
+ * array inside the library (NPAS_STATIC_WORKSPACE_BYTES on every GPU the process uses, held until it ends);
+ * the call allocates nothing on host or device paths of HIP and launches the same kernels as npas_run_stack.
+ * A stack that needs more workspace at batch N (npas_stack_workspace_bytes) is refused with
+ * NPAS_E_WORKSPACE.  All calls on one GPU share the array: calls whose work overlaps in time on one GPU
+ * (different streams, or threads) race; calls on one stream are safe.  Nothing in the array needs clearing. */
+#define NPAS_STATIC_WORKSPACE_BYTES (32u << 20)
+int npas_run_stack_static(const npas_stack *s, const void *x_dev, void *y_dev, int N, void *hip_stream);
 /* Number of kernels one npas_run_stack call launches (after fusion). */
 int npas_stack_num_launches(const npas_stack *s);
 /* For tests and reports: the launches one npas_run_stack call makes for batch N, in order, and where their

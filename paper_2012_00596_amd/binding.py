@@ -9,7 +9,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 _LIB = os.path.join(_HERE, "libnpas.so")
-SOURCES = ["pack.cpp", "api.cpp", "kernels.hip", "small_kernels.hip"]
+SOURCES = ["pack.cpp", "api.cpp", "kernels.hip", "small_kernels.hip", "noalloc.hip"]
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "npas.h")
 
 F32, BF16, F16 = 0, 1, 2
@@ -29,8 +29,9 @@ EXPORTS = [
     "npas_fc_sparse",
     "npas_maxpool3x3s2", "npas_global_avgpool", "npas_stack_create", "npas_stack_workspace_bytes",
     "npas_run_stack", "npas_stack_num_launches", "npas_stack_free", "npas_stack_describe", "npas_debug_set_switches",
-    "npas_debug_launch_empty",
+    "npas_run_stack_static", "npas_debug_launch_empty",
 ]
+STATIC_WORKSPACE_BYTES = 32 << 20
 DESCRIBE_COLS = 11
 
 
@@ -105,6 +106,7 @@ def lib():
         L.npas_stack_free.argtypes = [vp]
         L.npas_stack_free.restype = None
         L.npas_stack_describe.argtypes = [vp, ip, vp, ip]
+        L.npas_run_stack_static.argtypes = [vp, vp, vp, ip, vp]
         L.npas_debug_launch_empty.argtypes = [ip, vp]
         L.npas_debug_set_switches.argtypes = [C.c_char_p, ip]
         L.npas_debug_set_switches.restype = None
@@ -274,6 +276,10 @@ class Stack:
 
     def num_launches(self):
         return int(lib().npas_stack_num_launches(self.handle))
+
+    def run_static(self, x, y, N, stream=None):
+        """npas_run_stack_static: the library's own static workspace, no allocation."""
+        _check(lib().npas_run_stack_static(self.handle, _dev(x), _dev(y), N, stream))
 
     def describe(self, N):
         """The launches of one run at batch N: list of dicts (see npas_stack_describe in include/npas.h)."""
