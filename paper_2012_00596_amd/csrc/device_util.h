@@ -122,4 +122,31 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t wg, uint32_t nwg)
     return xcd * q + (xcd < r ? xcd : r) + idx;
 }
 
+// Direct global -> LDS load: 64 lanes x 16 bytes land lane-linearly in the 1 KB block at lds_addr; nothing is held in registers.
+__device__ __forceinline__ void lds_dma16(const void *gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr)
+                 : "memory"); // m0 is reserved: the compiler keeps nothing in it across statements
+}
+
+// "At most n vector-memory operations of this wave outstanding" for a wave-uniform n < 64
+// (the instruction takes an immediate).
+__device__ __forceinline__ void wait_vmcnt(uint32_t n)
+{
+#define NPAS_W(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
+    switch (n) {
+        NPAS_W(0) NPAS_W(1) NPAS_W(2) NPAS_W(3) NPAS_W(4) NPAS_W(5) NPAS_W(6) NPAS_W(7) NPAS_W(8) NPAS_W(9) NPAS_W(10)
+        NPAS_W(11) NPAS_W(12) NPAS_W(13) NPAS_W(14) NPAS_W(15) NPAS_W(16) NPAS_W(17) NPAS_W(18) NPAS_W(19) NPAS_W(20)
+        NPAS_W(21) NPAS_W(22) NPAS_W(23) NPAS_W(24) NPAS_W(25) NPAS_W(26) NPAS_W(27) NPAS_W(28) NPAS_W(29) NPAS_W(30)
+        NPAS_W(31) NPAS_W(32) NPAS_W(33) NPAS_W(34) NPAS_W(35) NPAS_W(36) NPAS_W(37) NPAS_W(38) NPAS_W(39) NPAS_W(40)
+        NPAS_W(41) NPAS_W(42) NPAS_W(43) NPAS_W(44) NPAS_W(45) NPAS_W(46) NPAS_W(47) NPAS_W(48) NPAS_W(49) NPAS_W(50)
+        NPAS_W(51) NPAS_W(52) NPAS_W(53) NPAS_W(54) NPAS_W(55) NPAS_W(56) NPAS_W(57) NPAS_W(58) NPAS_W(59) NPAS_W(60)
+        NPAS_W(61) NPAS_W(62)
+    default: asm volatile("s_waitcnt vmcnt(63)" ::: "memory"); break;
+    }
+#undef NPAS_W
+}
+
 } // namespace npas
