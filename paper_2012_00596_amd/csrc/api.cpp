@@ -213,7 +213,7 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     const bool s2 = stride == 2; // 3 x 3, pad 1: four phase planes of (TH + 1) x (TW + 1) pixels, one copy
     if (stride != 1 && !(s2 && KH == 3 && KW == 3 && pad == 1)) return false;
     const int Ho = (H + 2 * pad - KH) / stride + 1, Wo = (W + 2 * pad - KW) / stride + 1;
-    const int lds_total = 160 * 1024 - 2048 /* bias buffers */ - (s2 ? 4096 : 2048) /* pixel table */, wstage = 16384;
+    const int lds_total = 160 * 1024 - 2048 /* bias buffers */ - (s2 ? 4096 : 2048) /* patch pixel table */ - 1024 /* tile pixel table */, wstage = 16384;
     const int nbuf = s2 ? 4 : 2; // patch buffers (planes) of npb KB each
     const int max_npb = std::min(s2 ? 124 : 1 << 20, (lds_total - 3 * wstage) / (1024 * nbuf));
     if (T < 2 || p->C % 64 != 0 || Ho <= 0 || Wo <= 0) return false;

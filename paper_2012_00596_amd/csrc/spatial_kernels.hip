@@ -64,6 +64,71 @@ __device__ __forceinline__ SpatialItem spatial_item(const SpatialRingArgs &a, ui
     return it;
 }
 
+// Output pixel table of a tile shape (the same for every item): entry m = image << 16 | row << 8 | column of tile
+// pixel m inside the tile, ~0 past the tile's pixels.  1 KB of LDS (256 entries).
+__device__ __forceinline__ void spatial_out_table(const SpatialRingArgs &a, uint32_t *tab, int npix, int tid, int nthreads)
+{
+    const int thtw = a.TH * a.TW;
+    for (int m = tid; m < npix; m += nthreads) {
+        const uint32_t img = fastdiv((uint32_t)m, a.div_thtw), r = (uint32_t)m - img * (uint32_t)thtw;
+        const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
+        tab[m] = m < a.NI * thtw ? (img << 16 | ty << 8 | tx) : 0xffffffffu;
+    }
+}
+
+// Epilogue of a multiplying wave: bias, residual, activation, round, store.  Result register i of acc[j][s] is tile
+// pixel m0 + 16 s + i (m0 = the wave's first pixel + 4 q), filter fcol + j: a lane writes 4 consecutive filters of a
+// pixel, the 16 lanes of a quarter wave one whole 128-byte run of its row.  `ot` points at the lane's entry m0 of
+// the output pixel table.  The activation kind and the residual are wave-uniform and compiled in (a branch per
+// value and a pixel decode by division per store made this epilogue as long as five stages of the main loop).
+template <int DT, int S, bool HS, bool RES>
+__device__ __forceinline__ void spatial_store_tile(const SpatialRingArgs &a, const SpatialItem &it, const uint8_t *ot,
+                                                   const f32x4 (&acc)[4][S], float4 b4, int fcol, Clamp cl)
+{
+    if (fcol >= a.F) return;
+    const uint16_t *rp = reinterpret_cast<const uint16_t *>(a.residual);
+    uint16_t *yp = reinterpret_cast<uint16_t *>(a.y);
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        const uint4 e4 = *reinterpret_cast<const uint4 *>(ot + s * 64);
+        const uint32_t ev[4] = {e4.x, e4.y, e4.z, e4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t e = ev[i];
+            const int n = it.n0 + (int)(e >> 16), oy = it.ty0 + (int)((e >> 8) & 255u), ox = it.tx0 + (int)(e & 255u);
+            if (e == 0xffffffffu || n >= a.N || oy >= a.Ho || ox >= a.Wo) continue;
+            const size_t o = (size_t)(uint32_t)((n * a.Ho + oy) * a.Wo + ox) * (size_t)(uint32_t)a.F + (size_t)(uint32_t)fcol;
+            float v[4] = {acc[0][s][i] + b4.x, acc[1][s][i] + b4.y, acc[2][s][i] + b4.z, acc[3][s][i] + b4.w};
+            if (RES) {
+                const uint2 r2 = *reinterpret_cast<const uint2 *>(rp + o);
+                v[0] += from_storage<DT>((uint16_t)(r2.x & 0xffffu));
+                v[1] += from_storage<DT>((uint16_t)(r2.x >> 16));
+                v[2] += from_storage<DT>((uint16_t)(r2.y & 0xffffu));
+                v[3] += from_storage<DT>((uint16_t)(r2.y >> 16));
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = HS ? v[j] * __builtin_amdgcn_fmed3f(v[j] + 3.0f, 0.0f, 6.0f) * (1.0f / 6.0f) : __builtin_amdgcn_fmed3f(v[j], cl.lo, cl.hi);
+            uint2 out;
+            out.x = pack2<DT>(v[0], v[1]);
+            out.y = pack2<DT>(v[2], v[3]);
+            *reinterpret_cast<uint2 *>(yp + o) = out;
+        }
+    }
+}
+template <int DT, int S>
+__device__ __forceinline__ void spatial_epilogue(const SpatialRingArgs &a, const SpatialItem &it, const uint8_t *ot,
+                                                 const f32x4 (&acc)[4][S], float4 b4, int fcol, Clamp cl)
+{
+    if (cl.hs) {
+        if (a.residual) spatial_store_tile<DT, S, true, true>(a, it, ot, acc, b4, fcol, cl);
+        else spatial_store_tile<DT, S, true, false>(a, it, ot, acc, b4, fcol, cl);
+    } else {
+        if (a.residual) spatial_store_tile<DT, S, false, true>(a, it, ot, acc, b4, fcol, cl);
+        else spatial_store_tile<DT, S, false, false>(a, it, ot, acc, b4, fcol, cl);
+    }
+}
+
 // S2: stride 2, 3 x 3, pad 1.  The patch is kept as four phase planes (input rows and columns of one parity
 // each), every plane a dense (TH + 1) x (TW + 1) grid, so that a tap reads one plane at an offset of 0 or 1
 // rows / columns exactly as at stride 1.  The taps are walked plane by plane (4 + 2 + 2 + 1 stages); a plane's
@@ -87,6 +152,7 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     const uint32_t D = (uint32_t)a.depth;              // weight stages in the ring
     const uint32_t lbias = wring + D * kSpatialWStage; // two 1 KB bias buffers (item parity)
     const uint32_t ltab = lbias + 2048u;               // patch pixel -> (image, row, column), 4 B each
+    const uint32_t lotab = ltab + (S2 ? 4u : 1u) * (uint32_t)a.npb * 32u; // tile pixel -> (image, row, column) inside the tile
     uint32_t c_item = xcd_remap(blockIdx.x, nwg);
     if (c_item >= nitems) return;
     SpatialItem it = spatial_item(a, c_item);
@@ -107,6 +173,7 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
         }
         reinterpret_cast<uint32_t *>(lds + ltab)[idx] = e;
     }
+    spatial_out_table(a, reinterpret_cast<uint32_t *>(lds + lotab), 64 * PG, tid, kSpatialThreads);
     __syncthreads();
 
     if (wave >= NCW + kSpatialFetchWaves) {
@@ -404,38 +471,15 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
                 pbuf ^= 1u;
             }
         }
-        // ---- bias (from LDS), residual, clamp (activation), round, store ---------------------
-        // The patch is the MFMA's row operand and the weight images its column operand, and row r
-        // of weight tile j is filter 4r + j of the wave's 64: result register i of (j, s) is tile
-        // pixel 16 S wp + 16 s + 4q + i, filter 4 n16 + j.  A lane writes 4 consecutive filters of a
-        // pixel, the 16 lanes of a quarter wave one whole 128-byte run of its row.
-        const int fcol = it.fb * 128 + wf * 64 + 4 * n16;
-        float4 b4 = float4{0.f, 0.f, 0.f, 0.f};
-        if (a.bias) b4 = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 4 * n16) * 4u);
-#pragma unroll
-        for (int s = 0; s < S; ++s)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint32_t m = (uint32_t)(wp * (16 * S) + s * 16 + 4 * q + i);
-                asm volatile("" : "+v"(m)); // or the 16 pixel decodes are done (and held) ahead of the item loop
-                const uint32_t img = fastdiv(m, a.div_thtw), r = m - img * (uint32_t)thtw;
-                const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
-                const int n = it.n0 + (int)img, oy = it.ty0 + (int)ty, ox = it.tx0 + (int)tx;
-                if ((int)m >= a.NI * thtw || n >= a.N || oy >= a.Ho || ox >= a.Wo || fcol >= a.F) continue;
-                const size_t o = (size_t)((n * a.Ho + oy) * a.Wo + ox) * (size_t)a.F + (size_t)fcol;
-                float v[4] = {acc[0][s][i] + b4.x, acc[1][s][i] + b4.y, acc[2][s][i] + b4.z, acc[3][s][i] + b4.w};
-                if (a.residual) {
-                    const uint2 r2 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.residual) + o);
-                    v[0] += from_storage<DT>((uint16_t)(r2.x & 0xffffu));
-                    v[1] += from_storage<DT>((uint16_t)(r2.x >> 16));
-                    v[2] += from_storage<DT>((uint16_t)(r2.y & 0xffffu));
-                    v[3] += from_storage<DT>((uint16_t)(r2.y >> 16));
-                }
-                uint2 out;
-                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o) = out;
-            }
+        // ---- bias (from LDS), residual, activation, round, store ------------------------------
+        // The patch is the MFMA's row operand and the weight images its column operand, and row r of weight tile j
+        // is filter 4r + j of the wave's 64: result register i of (j, s) is tile pixel 16 S wp + 16 s + 4q + i,
+        // filter 4 n16 + j.
+        {
+            float4 b4 = float4{0.f, 0.f, 0.f, 0.f};
+            if (a.bias) b4 = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 4 * n16) * 4u);
+            spatial_epilogue<DT, S>(a, it, lds + lotab + (uint32_t)(wp * (16 * S) + 4 * q) * 4u, acc, b4, it.fb * 128 + wf * 64 + 4 * n16, cl);
+        }
         if (!more_items) break;
         c_item += nwg;
         it = spatial_item(a, c_item);
@@ -455,7 +499,7 @@ int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     const bool s2 = a.stride == 2;
-    const size_t lds_bytes = (size_t)(s2 ? 4 : 2) * a.npb * (1024 + (s2 ? 32 : 16)) + (size_t)a.depth * kSpatialWStage + 2048;
+    const size_t lds_bytes = (size_t)(s2 ? 4 : 2) * a.npb * (1024 + (s2 ? 32 : 16)) + (size_t)a.depth * kSpatialWStage + 2048 + 1024;
     const long items = (long)a.tilesN * a.tilesY * a.tilesX * a.nfb;
     const unsigned grid = (unsigned)std::min<long>(items, 256);
     if (lds_bytes > 160 * 1024 || a.depth < 3 || a.depth > 6 || (a.pg != 4 && a.pg != 2) || a.NI * a.TH * a.TW > 64 * a.pg ||
@@ -511,6 +555,7 @@ __global__ __launch_bounds__(kResidentThreads) void spatial_resident_kernel(Spat
     const uint32_t lw = 2u * ppb;                                 // the weights: nst stages of 8 KB
     const uint32_t lbias = lw + (uint32_t)nst * kResidentWStage;  // 64 floats (1 KB block)
     const uint32_t ltab = lbias + 1024u;                          // patch pixel -> (image, row, column), 4 B each
+    const uint32_t lotab = ltab + (uint32_t)a.npb * 32u;          // tile pixel -> (image, row, column) inside the tile
     uint32_t c_item = xcd_remap(blockIdx.x, nwg);
     if (c_item >= nitems) return;
     SpatialItem it = spatial_item(a, c_item);
@@ -521,6 +566,7 @@ __global__ __launch_bounds__(kResidentThreads) void spatial_resident_kernel(Spat
         const uint32_t py = fastdiv(r, a.div_pw), px = r - py * (uint32_t)a.PW;
         reinterpret_cast<uint32_t *>(lds + ltab)[pp] = (int)img < a.NI ? (img << 20 | py << 10 | px) : 0xffffffffu;
     }
+    spatial_out_table(a, reinterpret_cast<uint32_t *>(lds + lotab), 256, tid, kResidentThreads);
     // weights: image i = stage * 8 + step * 4 + row tile, from [stage][step][8 tiles] in the packed format
     {
         const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)lane * 16u;
@@ -621,35 +667,13 @@ __global__ __launch_bounds__(kResidentThreads) void spatial_resident_kernel(Spat
             }
             pbuf ^= 1u;
         }
-        // ---- bias (from LDS), residual, clamp (activation), round, store: result register i of (j, s) is tile
-        // pixel 32 wp + 16 s + 4q + i, filter 4 n16 + j; the 16 lanes of a quarter wave write one 128-byte run
-        const int fcol = 4 * n16;
-        float4 b4 = float4{0.f, 0.f, 0.f, 0.f};
-        if (a.bias) b4 = *reinterpret_cast<const float4 *>(lds + lbias + (uint32_t)(4 * n16) * 4u);
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint32_t m = (uint32_t)(wp * 32 + s * 16 + 4 * q + i);
-                asm volatile("" : "+v"(m)); // or the pixel decodes are done (and held) ahead of the item loop
-                const uint32_t img = fastdiv(m, a.div_thtw), r = m - img * (uint32_t)thtw;
-                const uint32_t ty = fastdiv(r, a.div_tw), tx = r - ty * (uint32_t)a.TW;
-                const int n = it.n0 + (int)img, oy = it.ty0 + (int)ty, ox = it.tx0 + (int)tx;
-                if ((int)m >= a.NI * thtw || n >= a.N || oy >= a.Ho || ox >= a.Wo || fcol >= a.F) continue;
-                const size_t o = (size_t)((n * a.Ho + oy) * a.Wo + ox) * (size_t)a.F + (size_t)fcol;
-                float v[4] = {acc[0][s][i] + b4.x, acc[1][s][i] + b4.y, acc[2][s][i] + b4.z, acc[3][s][i] + b4.w};
-                if (a.residual) {
-                    const uint2 r2 = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(a.residual) + o);
-                    v[0] += from_storage<DT>((uint16_t)(r2.x & 0xffffu));
-                    v[1] += from_storage<DT>((uint16_t)(r2.x >> 16));
-                    v[2] += from_storage<DT>((uint16_t)(r2.y & 0xffffu));
-                    v[3] += from_storage<DT>((uint16_t)(r2.y >> 16));
-                }
-                uint2 out;
-                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o) = out;
-            }
+        // ---- bias (from LDS), residual, activation, round, store: result register i of (j, s) is tile
+        // pixel 32 wp + 16 s + 4q + i, filter 4 n16 + j
+        {
+            float4 b4 = float4{0.f, 0.f, 0.f, 0.f};
+            if (a.bias) b4 = *reinterpret_cast<const float4 *>(lds + lbias + (uint32_t)(4 * n16) * 4u);
+            spatial_epilogue<DT, 2>(a, it, lds + lotab + (uint32_t)(wp * 32 + 4 * q) * 4u, acc, b4, 4 * n16, cl);
+        }
         if (!more_items) break;
         c_item += nwg;
         it = spatial_item(a, c_item);
@@ -664,7 +688,7 @@ template <int DT> static void launch_resident_inst(const SpatialRingArgs &a, uns
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kResidentThreads), lds_bytes, st, a);
 }
 
-size_t spatial_resident_lds_bytes(int npb, int nst) { return (size_t)2 * npb * 1024 + (size_t)nst * kResidentWStage + 1024 + (size_t)npb * 32; }
+size_t spatial_resident_lds_bytes(int npb, int nst) { return (size_t)2 * npb * 1024 + (size_t)nst * kResidentWStage + 1024 + (size_t)npb * 32 + 1024; }
 
 int launch_spatial_resident(int dtype, const SpatialRingArgs &a, void *stream)
 {
