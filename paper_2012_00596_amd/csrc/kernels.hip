@@ -546,6 +546,56 @@ __device__ __forceinline__ PointwiseItem pointwise_item(uint32_t nfb, uint32_t i
     return it;
 }
 
+// Epilogue of a multiplying wave of the pointwise ring: bias, residual, activation, round, store.  Result register i
+// of acc[j][s] is the pixel 16 s + i rows after the lane's first one (row pitch `pitch` bytes, first row at yb0),
+// filter j of the lane's 4.  The activation kind, the residual and "every row of the wave is inside the map" are
+// wave-uniform and compiled in: with a branch per value and a mask per store this epilogue was longer than the
+// main loop of a 64-channel layer.
+template <int DT, int S, bool HS, bool RES, bool FULL>
+__device__ __forceinline__ void pointwise_store_tile(uint8_t *yb0, uint32_t pitch, uint32_t rows_left, const f32x4 (&acc)[4][S],
+                                                     const uint2 (&res)[S][4], float4 bv, Clamp cl)
+{
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (!FULL && (uint32_t)(16 * s + i) >= rows_left) continue;
+            float v[4] = {acc[0][s][i] + bv.x, acc[1][s][i] + bv.y, acc[2][s][i] + bv.z, acc[3][s][i] + bv.w};
+            if (RES) {
+                v[0] += from_storage<DT>((uint16_t)(res[s][i].x & 0xffffu));
+                v[1] += from_storage<DT>((uint16_t)(res[s][i].x >> 16));
+                v[2] += from_storage<DT>((uint16_t)(res[s][i].y & 0xffffu));
+                v[3] += from_storage<DT>((uint16_t)(res[s][i].y >> 16));
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                v[j] = HS ? v[j] * __builtin_amdgcn_fmed3f(v[j] + 3.0f, 0.0f, 6.0f) * (1.0f / 6.0f) : __builtin_amdgcn_fmed3f(v[j], cl.lo, cl.hi);
+            uint2 out;
+            out.x = pack2<DT>(v[0], v[1]);
+            out.y = pack2<DT>(v[2], v[3]);
+            store_stream8(yb0 + (uint32_t)(16 * s + i) * pitch, out);
+        }
+}
+template <int DT, int S, bool HS, bool RES>
+__device__ __forceinline__ void pointwise_store_rows(uint8_t *yb0, uint32_t pitch, uint32_t rows_left, const f32x4 (&acc)[4][S],
+                                                     const uint2 (&res)[S][4], float4 bv, Clamp cl)
+{
+    if (__all(rows_left >= (uint32_t)(16 * S))) pointwise_store_tile<DT, S, HS, RES, true>(yb0, pitch, rows_left, acc, res, bv, cl);
+    else pointwise_store_tile<DT, S, HS, RES, false>(yb0, pitch, rows_left, acc, res, bv, cl);
+}
+template <int DT, int S>
+__device__ __forceinline__ void pointwise_epilogue(uint8_t *yb0, uint32_t pitch, uint32_t rows_left, bool has_res, const f32x4 (&acc)[4][S],
+                                                   const uint2 (&res)[S][4], float4 bv, Clamp cl)
+{
+    if (cl.hs) {
+        if (has_res) pointwise_store_rows<DT, S, true, true>(yb0, pitch, rows_left, acc, res, bv, cl);
+        else pointwise_store_rows<DT, S, true, false>(yb0, pitch, rows_left, acc, res, bv, cl);
+    } else {
+        if (has_res) pointwise_store_rows<DT, S, false, true>(yb0, pitch, rows_left, acc, res, bv, cl);
+        else pointwise_store_rows<DT, S, false, false>(yb0, pitch, rows_left, acc, res, bv, cl);
+    }
+}
+
 template <int DT, typename Cfg>
 __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs a)
 {
@@ -730,26 +780,12 @@ __global__ __launch_bounds__(Cfg::kThreads) void pointwise_ring_kernel(RingArgs 
                     for (int j = 0; j < 4; ++j) acc[j][s] = mfma16<DT>(B[s], A[j], acc[j][s]);
             }
         }
-        // ---- bias, residual, clamp (activation), round, store -----------------------------
-        float4 bv = float4{0.f, 0.f, 0.f, 0.f};
-        if (a.bias) bv = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 4 * n16) * 4u);
-#pragma unroll
-        for (int s = 0; s < S; ++s)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if ((uint32_t)(16 * s + i) >= rows_left) continue;
-                float v[4] = {acc[0][s][i] + bv.x, acc[1][s][i] + bv.y, acc[2][s][i] + bv.z, acc[3][s][i] + bv.w};
-                if (rb) {
-                    v[0] += from_storage<DT>((uint16_t)(res[s][i].x & 0xffffu));
-                    v[1] += from_storage<DT>((uint16_t)(res[s][i].x >> 16));
-                    v[2] += from_storage<DT>((uint16_t)(res[s][i].y & 0xffffu));
-                    v[3] += from_storage<DT>((uint16_t)(res[s][i].y >> 16));
-                }
-                uint2 out;
-                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
-                store_stream8(yb + obase + (uint32_t)(16 * s + i) * (uint32_t)a.F * 2u, out);
-            }
+        // ---- bias, residual, activation, round, store --------------------------------------
+        {
+            float4 bv = float4{0.f, 0.f, 0.f, 0.f};
+            if (a.bias) bv = *reinterpret_cast<const float4 *>(lds + lbias + bbuf * 1024u + (uint32_t)(wf * 64 + 4 * n16) * 4u);
+            pointwise_epilogue<DT, S>(yb + obase, (uint32_t)a.F * 2u, rows_left, rb != nullptr, acc, res, bv, cl);
+        }
         if (c_item + nwg >= nitems) break;
         c_item += nwg;
         bbuf ^= 1u;
