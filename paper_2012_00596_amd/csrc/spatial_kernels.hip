@@ -178,36 +178,42 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
 
     if (wave >= NCW + kSpatialFetchWaves) {
         // ---- patch fetch ------------------------------------------------------------------
-        const int wl = wave - NCW - kSpatialFetchWaves;
+        const int wl = __builtin_amdgcn_readfirstlane(wave - NCW - kSpatialFetchWaves); // (the compiler cannot see that a wave index is uniform)
         const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
         const uint8_t *zb = reinterpret_cast<const uint8_t *>(a.zeros) + (uint32_t)(lane & 7) * 16u;
         const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u;
         const int nblk = (a.npb - wl + kSpatialFetchWaves - 1) / kSpatialFetchWaves; // this wave's blocks: wl, wl + 4, ...
         // blocks per stage, spread over all but the chunk's last two stages (the patch must have landed at the barrier
-        // of the last one): a patch load holds the issuing wave for some 600 cycles (timestamps around the barriers),
-        // and two of them per stage made these waves the last to arrive
+        // of the last one)
         const int per = (nblk + max(1, T - 2) - 1) / max(1, T - 2);
+        // Blocks first + 4 k, k in [k0, k1), of the pixel table go to LDS at dst + 4096 k; (y0, x0) is the tile origin in
+        // input coordinates.  Four at a time: the table entries are read first and the four address computations are
+        // independent, so they overlap (the loads themselves are ordered against the table reads); one at a time a
+        // load held the wave for some 500 cycles, measured around the barriers.  Keeping an item's offsets in
+        // registers instead (they only move by 128 bytes per chunk) compiled to copies and branches and was slower.
+        auto fetch_blocks = [&](const SpatialItem &pi, int y0, int x0, int cc, int first, uint32_t dst, int k0, int k1) __attribute__((always_inline)) {
+            const uint32_t *tab = reinterpret_cast<const uint32_t *>(lds + ltab) + first * 8 + (lane >> 3);
+            for (; k0 < k1; k0 += 4) {
+                uint32_t e[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) e[j] = tab[min(k0 + j, k1 - 1) * (kSpatialFetchWaves * 8)];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (k0 + j >= k1) break;
+                    const int n = pi.n0 + (int)(e[j] >> 20), iy = y0 + (int)((e[j] >> 10) & 1023u), ix = x0 + (int)(e[j] & 1023u);
+                    const bool inb = e[j] != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
+                    const uint8_t *src = inb ? xb + ((uint32_t)((n * a.H + iy) * a.W + ix) * (uint32_t)a.C + (uint32_t)cc * 64u) * 2u + pcv : zb;
+                    lds_dma16(src, dst + (uint32_t)(k0 + j) * (kSpatialFetchWaves * 1024u));
+                }
+            }
+        };
         // blocks [k0, k1) of this wave's share of the patch of (item pi, chunk cc)
         auto patch = [&](const SpatialItem &pi, int cc, uint32_t buf, int k0, int k1) __attribute__((always_inline)) {
-            for (int k = k0; k < min(k1, nblk); ++k) {
-                const int blk = wl + kSpatialFetchWaves * k;
-                const uint32_t e = reinterpret_cast<const uint32_t *>(lds + ltab)[blk * 8 + (lane >> 3)];
-                const int n = pi.n0 + (int)(e >> 20), iy = pi.ty0 - a.pad + (int)((e >> 10) & 1023u), ix = pi.tx0 - a.pad + (int)(e & 1023u);
-                const bool inb = e != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
-                const uint8_t *src = inb ? xb + ((uint32_t)((n * a.H + iy) * a.W + ix) * (uint32_t)a.C + (uint32_t)cc * 64u) * 2u + pcv : zb;
-                lds_dma16(src, lbase + buf * ppb + (uint32_t)blk * 1024u);
-            }
+            fetch_blocks(pi, pi.ty0 - a.pad, pi.tx0 - a.pad, cc, wl, lbase + buf * ppb + (uint32_t)wl * 1024u, k0, min(k1, nblk));
         };
         // stride 2: this wave's blocks of one plane of (item pi, chunk cc)
         auto plane_fetch = [&](const SpatialItem &pi, int cc, int plane) __attribute__((always_inline)) {
-            for (int k = 0; k < nblk; ++k) {
-                const int blk = plane * a.npb + wl + kSpatialFetchWaves * k;
-                const uint32_t e = reinterpret_cast<const uint32_t *>(lds + ltab)[blk * 8 + (lane >> 3)];
-                const int n = pi.n0 + (int)(e >> 20), iy = 2 * pi.ty0 - a.pad + (int)((e >> 10) & 1023u), ix = 2 * pi.tx0 - a.pad + (int)(e & 1023u);
-                const bool inb = e != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
-                const uint8_t *src = inb ? xb + ((uint32_t)((n * a.H + iy) * a.W + ix) * (uint32_t)a.C + (uint32_t)cc * 64u) * 2u + pcv : zb;
-                lds_dma16(src, lbase + (uint32_t)blk * 1024u);
-            }
+            fetch_blocks(pi, 2 * pi.ty0 - a.pad, 2 * pi.tx0 - a.pad, cc, plane * a.npb + wl, lbase + (uint32_t)(plane * a.npb + wl) * 1024u, 0, nblk);
         };
         // bias of an item's 128 filters (512 B; lanes 32-63 fetch a copy that nobody reads)
         auto bias_block = [&](const SpatialItem &pi, uint32_t buf) __attribute__((always_inline)) {
