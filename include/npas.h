@@ -201,7 +201,7 @@ typedef struct {
 
 enum {
     NPAS_STACK_FUSE_POINTWISE = 1,         /* allow a 1x1 -> act -> 1x1 pair to run as one kernel */
-    NPAS_STACK_FUSE_INVERTED_RESIDUAL = 2, /* allow 1x1 -> depthwise 3x3 (stride 1) -> 1x1 (+ block input) to run as one kernel */
+    NPAS_STACK_FUSE_INVERTED_RESIDUAL = 2, /* allow 1x1 -> depthwise 3x3 (stride 1 or 2) -> 1x1, each with or without bias, (+ block input at stride 1) to run as one kernel */
     NPAS_STACK_FUSE_CONV_MAXPOOL = 4       /* allow a conv on fewer than 8 channels (an image stem) and the max pool after it to run as one kernel */
 };
 

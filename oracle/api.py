@@ -188,14 +188,15 @@ def run_layer(L, tensors, dtype):
     """One layer of a stack on already-rounded inputs; returns the unrounded
     float64 output.  `L` is any object with the workload Layer fields."""
     x = tensors[L.src]
+    bias = getattr(L, "bias", None)  # per output channel, part of the layer like its weights
     if L.kind == "conv":
         res = tensors[L.res] if L.res >= 0 else None
-        return conv2d_masked(x, L.w_exact, L.mask, L.stride, L.pad, None, res, L.act)
+        return conv2d_masked(x, L.w_exact, L.mask, L.stride, L.pad, bias, res, L.act)
     if L.kind == "fc":
-        return fc_masked(x, L.w_exact, L.mask, None, L.act)
+        return fc_masked(x, L.w_exact, L.mask, bias, L.act)
     if L.kind == "dwconv":
         res = tensors[L.res] if L.res >= 0 else None
-        return dwconv3x3(x, L.w_exact, L.stride, None, res, L.act)
+        return dwconv3x3(x, L.w_exact, L.stride, bias, res, L.act)
     if L.kind == "maxpool":
         return maxpool3x3s2(x)
     if L.kind == "avgpool":

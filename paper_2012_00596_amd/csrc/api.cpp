@@ -659,6 +659,7 @@ struct npas_stack {
         // first layer of a fused 1x1 -> depthwise 3x3 -> 1x1 block (runs the next two layers too): device images and tile
         bool ir_head = false;
         const void *ir_w1 = nullptr, *ir_w3 = nullptr;
+        const int *ir_perm = nullptr;
         const uint32_t *ir_wdw = nullptr;
         int ir_nslots = 0, ir_TH = 0, ir_TW = 0, ir_residual = 0;
     };
@@ -813,6 +814,7 @@ struct IrPlan {
     int nslots = 0;                 // live intermediate channels, padded to a multiple of 32
     std::vector<uint16_t> w1, w3;   // A-operand images
     std::vector<uint32_t> wdw;      // [9][nslots]: the weight's storage bits in the low (even slot) or high (odd slot) half
+    std::vector<int> perm;          // [nslots]: intermediate channel of each slot, -1 = padding
 };
 
 static IrPlan build_ir(const npas_packed *p1, const npas_packed *pdw, const npas_packed *p3)
@@ -849,22 +851,24 @@ static IrPlan build_ir(const npas_packed *p1, const npas_packed *pdw, const npas
     for (int s = 0; s < plan.nslots; ++s)
         if (perm[s] >= 0)
             for (int t = 0; t < 9; ++t) plan.wdw[(size_t)t * plan.nslots + s] = (uint32_t)wd[(size_t)perm[s] * 9 + t] << (s & 1 ? 16 : 0);
+    plan.perm = perm;
     return plan;
 }
 
 // Output tile of the fused block for an H x W map: the shape that costs least, counting the
 // halo pixels expanded (cheap) and the 16-pixel blocks of depthwise work (about four times dearer),
 // among those whose LDS footprint leaves room for several workgroups per CU.
-static void plan_ir_tile(int H, int W, int nslots, int *TH, int *TW)
+static void plan_ir_tile(int Ho, int Wo, int nslots, int stride, int *TH, int *TW)
 {
     double best = 1e300;
     *TH = 1; *TW = 1;
     for (int th = 1; th <= 32; ++th)
         for (int tw = 1; tw <= 64; ++tw) {
-            if ((th + 2) * (tw + 2) > 256) continue; // four 16-pixel halo blocks per wave at most
-            if (fused_ir_lds_bytes(th, tw, nslots) > 64 * 1024) continue;
-            const double tiles = (double)((H + th - 1) / th) * ((W + tw - 1) / tw);
-            const double cost = tiles * (1.0 * (((th + 2) * (tw + 2) + 15) / 16) + 4.0 * ((th * tw + 15) / 16) + 2.0);
+            const int ph = (th - 1) * stride + 3, pw = (tw - 1) * stride + 3; // input pixels under the tile, with halo
+            if (ph * pw > 256) continue; // four 16-pixel halo blocks per wave at most
+            if (fused_ir_lds_bytes(th, tw, nslots, stride) > 64 * 1024) continue;
+            const double tiles = (double)((Ho + th - 1) / th) * ((Wo + tw - 1) / tw);
+            const double cost = tiles * (1.0 * ((ph * pw + 15) / 16) + 4.0 * ((th * tw + 15) / 16) + 2.0);
             if (cost < best) {
                 best = cost;
                 *TH = th; *TW = tw;
@@ -872,11 +876,13 @@ static void plan_ir_tile(int H, int W, int nslots, int *TH, int *TW)
         }
 }
 
-static bool is_plain_pointwise(const npas_layer_desc &d)
+// a 16-bit 1 x 1 layer at stride 1 without padding (the fused block takes a bias, the fused pair does not)
+static bool is_pointwise16(const npas_layer_desc &d)
 {
     return d.kind == NPAS_LAYER_CONV && d.packed && d.packed->KH == 1 && d.packed->KW == 1 && d.stride == 1 &&
-           d.pad == 0 && d.packed->dtype != NPAS_F32 && !d.bias_dev;
+           d.pad == 0 && d.packed->dtype != NPAS_F32;
 }
+static bool is_plain_pointwise(const npas_layer_desc &d) { return is_pointwise16(d) && !d.bias_dev; }
 
 } // namespace npas
 
@@ -1112,8 +1118,9 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
     if (flags & NPAS_STACK_FUSE_INVERTED_RESIDUAL) {
         for (int i = 0; i + 2 < n_layers; ++i) {
             npas_stack::Node &a = s->nodes[i], &b = s->nodes[i + 1], &c = s->nodes[i + 2];
-            if (busy(a) || busy(b) || busy(c) || !is_plain_pointwise(a.d) || !is_plain_pointwise(c.d) || a.d.res >= 0) continue;
-            if (b.d.kind != NPAS_LAYER_DEPTHWISE3X3 || b.d.stride != 1 || b.d.bias_dev || b.d.res >= 0) continue;
+            if (busy(a) || busy(b) || busy(c) || !is_pointwise16(a.d) || !is_pointwise16(c.d) || a.d.res >= 0) continue;
+            if (b.d.kind != NPAS_LAYER_DEPTHWISE3X3 || (b.d.stride != 1 && b.d.stride != 2) || b.d.res >= 0) continue;
+            if (b.d.stride == 2 && c.d.res >= 0) continue; // the block input has another shape than its output
             if (b.d.src != i + 1 || c.d.src != i + 2 || (c.d.res >= 0 && c.d.res != a.d.src)) continue;
             bool other_reader = false; // the two tensors inside the block must have no reader outside it
             for (int j = i + 1; j < n_layers; ++j) {
@@ -1127,14 +1134,16 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
             IrPlan ip = build_ir(p1, b.d.packed, p3);
             if (ip.nslots > 192) continue;
             int th, tw;
-            plan_ir_tile(a.H, a.W, ip.nslots, &th, &tw);
-            if (fused_ir_lds_bytes(th, tw, ip.nslots) > 64 * 1024) continue;
-            const size_t b1 = ip.w1.size() * 2, b3 = ip.w3.size() * 2, bd = ip.wdw.size() * 4;
-            const size_t o3 = (b1 + 255) / 256 * 256, od = o3 + (b3 + 255) / 256 * 256;
-            std::vector<uint8_t> blob(od + bd);
+            const int st2 = b.d.stride;
+            plan_ir_tile((a.H - 1) / st2 + 1, (a.W - 1) / st2 + 1, ip.nslots, st2, &th, &tw);
+            if (fused_ir_lds_bytes(th, tw, ip.nslots, st2) > 64 * 1024) continue;
+            const size_t b1 = ip.w1.size() * 2, b3 = ip.w3.size() * 2, bd = ip.wdw.size() * 4, bp = ip.perm.size() * 4;
+            const size_t o3 = (b1 + 255) / 256 * 256, od = o3 + (b3 + 255) / 256 * 256, op = od + (bd + 255) / 256 * 256;
+            std::vector<uint8_t> blob(op + bp);
             std::memcpy(blob.data(), ip.w1.data(), b1);
             std::memcpy(blob.data() + o3, ip.w3.data(), b3);
             std::memcpy(blob.data() + od, ip.wdw.data(), bd);
+            std::memcpy(blob.data() + op, ip.perm.data(), bp);
             void *dptr = nullptr;
             if (int rc = upload_blob(blob.data(), blob.size(), &dptr)) return rc;
             a.ir_head = true;
@@ -1142,6 +1151,7 @@ int npas_stack_create(const npas_layer_desc *layers, int n_layers, int H, int W,
                 a.ir_w1 = dptr;
                 a.ir_w3 = (const uint8_t *)dptr + o3;
                 a.ir_wdw = (const uint32_t *)((const uint8_t *)dptr + od);
+                a.ir_perm = (const int *)((const uint8_t *)dptr + op);
             }
             a.ir_nslots = ip.nslots; a.ir_TH = th; a.ir_TW = tw; a.ir_residual = c.d.res >= 0;
             b.fused_away = true;
@@ -1295,10 +1305,15 @@ int run_stack_impl(const npas_stack *s, const void *x_dev, void *y_dev, int N, v
                 set_error("fused block has no device copy (stack created on a machine without a GPU)");
                 rc = NPAS_E_HIP;
             }
-            if (!rc)
-                rc = launch_fused_inverted_residual(p1->dtype, x, tensor(i + 3), n.ir_w1, n.ir_w3, n.ir_wdw, N, n.H, n.W, p1->C,
-                                                    p3->F, n.ir_nslots, n.ir_TH, n.ir_TW, n.d.act, s->nodes[i + 1].d.act,
-                                                    s->nodes[i + 2].d.act, n.ir_residual, hip_stream);
+            if (!rc) {
+                const npas_layer_desc &d2 = s->nodes[i + 1].d, &d3 = s->nodes[i + 2].d;
+                IrLaunch l;
+                l.x = x; l.y = tensor(i + 3); l.w1 = n.ir_w1; l.w3 = n.ir_w3; l.wdw = n.ir_wdw; l.perm = n.ir_perm;
+                l.b1 = (const float *)n.d.bias_dev; l.b2 = (const float *)d2.bias_dev; l.b3 = (const float *)d3.bias_dev;
+                l.N = N; l.H = n.H; l.W = n.W; l.C1 = p1->C; l.F3 = p3->F; l.nslots = n.ir_nslots; l.TH = n.ir_TH; l.TW = n.ir_TW;
+                l.stride = d2.stride; l.act1 = n.d.act; l.act2 = d2.act; l.act3 = d3.act; l.residual = n.ir_residual;
+                rc = launch_fused_inverted_residual(p1->dtype, l, hip_stream);
+            }
             if (rc) return rc;
             continue;
         }

@@ -1631,15 +1631,17 @@ __global__ __launch_bounds__(256) void global_avgpool_vec4_kernel(const void *x,
 }
 
 // ------------------------------------------------------------------------------
-// fused_inverted_residual: y = act3(W3 . act2(DW3x3(act1(W1 . x))) + x) for the cascade 1x1 -> 3x3
-// depthwise (stride 1) -> 1x1 of the search space (section 5.1.1) when the two wide tensors
-// between the layers have no other reader.  They never leave the CU: HBM sees x once and y once.
+// fused_inverted_residual: y = act3(W3 . act2(DW3x3(act1(W1 . x + b1)) + b2) + b3 [+ x]) for the cascade
+// 1x1 -> 3x3 depthwise (stride 1 or 2) -> 1x1 of the search space (section 5.1.1) when the two wide
+// tensors between the layers have no other reader.  They never leave the CU: HBM sees x once and y once.
+// The block input is added at stride 1 only (at stride 2 the shapes differ); the biases are optional.
 //
 // A workgroup (4 waves) owns an output tile of TH x TW pixels.
-//   1. Expansion: for the tile plus a one-pixel halo, 16 pixels at a time, layer 1's MFMAs
-//      (K = C1 <= 32 in one step) produce 16 x 16 output tiles that are clamped, rounded and written
-//      to LDS as [halo pixel][slot] in the storage type.  Halo pixels outside the image read x as
-//      zero, which gives zero (the layers carry no bias here), as the padding of the depthwise
+//   1. Expansion: for the input pixels under the tile plus a one-pixel halo ((TH-1) stride + 3 rows),
+//      16 pixels at a time, layer 1's MFMAs
+//      (K = C1 <= 32 in one step) produce 16 x 16 output tiles that get their bias, are clamped, rounded and
+//      written to LDS as [halo pixel][slot] in the storage type.  Halo pixels outside the image are written
+//      as zero, as the padding of the depthwise
 //      layer must be.  A slot is an intermediate channel some filter of layer 3 keeps; channels
 //      nobody keeps are dead and are never computed (the pruning of layer 3 pays in layers 1 and 2).
 //   2. Depthwise + projection, 16 output pixels at a time: lane (q, n) forms the depthwise output
@@ -1670,11 +1672,14 @@ struct IrArgs {
     const void *w3;      // [nt3][nk][64 lanes][8] layer-3 A-operand images, K in slot order
     const uint32_t *wdw; // [9][nslots] depthwise weights in slot order, each alone in its half of a 16-bit pair
                          // (even slots low, odd slots high, the other half zero)
+    const int *perm;     // [nslots] intermediate channel of each slot, -1: padding slot
+    const float *b1, *b2, *b3; // biases of the three layers in channel order, or null
     int N, H, W, C1, F3;
+    int stride, Ho, Wo;  // of the depthwise layer; output map
     int nt1, nk, nt3;    // slots / 16, slots / 32, ceil(F3 / 16)
     int TH, TW, tilesY, tilesX;
     int act1, act2, act3;
-    int residual;        // 1: add the block input (needs F3 == C1)
+    int residual;        // 1: add the block input (needs F3 == C1 and stride 1)
     uint32_t div_tw, div_pw;
 };
 
@@ -1683,17 +1688,19 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
-    const int PH = a.TH + 2, PW = a.TW + 2, nslots = a.nt1 * 16;
+    const int PH = (a.TH - 1) * a.stride + 3, PW = (a.TW - 1) * a.stride + 3, nslots = a.nt1 * 16;
     const int nhb = (PH * PW + 15) >> 4, nob = (a.TH * a.TW + 15) >> 4; // 16-pixel blocks of the halo tile / the tile
     const uint32_t pitch = (uint32_t)nslots * 2u + kIrPad;               // bytes per halo pixel
     uint8_t *y1 = lds;
     uint32_t *dww = reinterpret_cast<uint32_t *>(lds + (size_t)nhb * 16 * pitch);
+    float *lb1 = reinterpret_cast<float *>(dww + 9 * nslots), *lb2 = lb1 + nslots; // biases of layers 1 and 2 in slot order
 
     uint32_t tile = blockIdx.x;
     const int txi = (int)(tile % (uint32_t)a.tilesX);
     tile /= (uint32_t)a.tilesX;
     const int tyi = (int)(tile % (uint32_t)a.tilesY), n = (int)(tile / (uint32_t)a.tilesY);
-    const int ty0 = tyi * a.TH, tx0 = txi * a.TW;
+    const int ty0 = tyi * a.TH, tx0 = txi * a.TW;             // in the output map
+    const int iy0 = ty0 * a.stride - 1, ix0 = tx0 * a.stride - 1; // input pixel of halo pixel (0, 0)
 
     for (int i = tid; i < 9 * nslots; i += 256) dww[i] = a.wdw[i];
 
@@ -1704,18 +1711,25 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
     // every load of this phase is issued before the first MFMA: the wave's activation vectors (up to four
     // 16-pixel blocks) and layer 1's images, so that one memory latency is paid instead of one per block and image
     uint4 xv[4], w1r[12];
+    bool inside[4]; // the lane's halo pixel of round r lies in the image
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int hb = wave + 4 * r;
         const uint32_t hp = (uint32_t)(hb * 16 + n16);
         const uint32_t py = fastdiv(hp, a.div_pw), px = hp - py * (uint32_t)PW;
-        const int iy = ty0 - 1 + (int)py, ix = tx0 - 1 + (int)px;
-        const bool inb = hb < nhb && (int)py < PH && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W && 8 * q < a.C1;
+        const int iy = iy0 + (int)py, ix = ix0 + (int)px;
+        inside[r] = hb < nhb && (int)py < PH && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
         xv[r] = uint4{0u, 0u, 0u, 0u};
-        if (inb) xv[r] = *reinterpret_cast<const uint4 *>(x16 + ((size_t)(n * a.H + iy) * a.W + ix) * a.C1 + 8 * q);
+        if (inside[r] && 8 * q < a.C1) xv[r] = *reinterpret_cast<const uint4 *>(x16 + ((size_t)(n * a.H + iy) * a.W + ix) * a.C1 + 8 * q);
     }
 #pragma unroll
     for (int t = 0; t < 12; ++t) w1r[t] = t < a.nt1 ? w1[t * 64] : uint4{0u, 0u, 0u, 0u};
+    for (int i = tid; i < nslots; i += 256) { // bias tables, asked for behind the loads above
+        const int c = a.b1 || a.b2 ? a.perm[i] : -1;
+        lb1[i] = a.b1 && c >= 0 ? a.b1[c] : 0.f;
+        lb2[i] = a.b2 && c >= 0 ? a.b2[c] : 0.f;
+    }
+    __syncthreads();
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int hb = wave + 4 * r;
@@ -1724,9 +1738,11 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
         for (int t = 0; t < 12; ++t) {
             if (hb < nhb && t < a.nt1) {
                 const f32x4 d = mfma16<DT>(w1r[t], xv[r], f32x4{0.f, 0.f, 0.f, 0.f});
+                const float4 bb = *reinterpret_cast<const float4 *>(lb1 + 16 * t + 4 * q); // result register i: slot 16 t + 4 q + i
                 uint2 o;
-                o.x = pack2<DT>(clampf(d[0], cl1), clampf(d[1], cl1));
-                o.y = pack2<DT>(clampf(d[2], cl1), clampf(d[3], cl1));
+                o.x = pack2<DT>(clampf(d[0] + bb.x, cl1), clampf(d[1] + bb.y, cl1));
+                o.y = pack2<DT>(clampf(d[2] + bb.z, cl1), clampf(d[3] + bb.w, cl1));
+                if (!inside[r]) o = uint2{0u, 0u}; // padding of the depthwise layer, whatever the bias
                 *reinterpret_cast<uint2 *>(dst + t * 32) = o;
             }
         }
@@ -1741,12 +1757,13 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
         const uint32_t m = (uint32_t)(ob * 16 + n16);
         const uint32_t ty = fastdiv(m, a.div_tw), tx = m - ty * (uint32_t)a.TW;
         const int oy = ty0 + (int)ty, ox = tx0 + (int)tx;
-        const bool valid = (int)ty < a.TH && oy < a.H && ox < a.W;
-        const uint8_t *base = y1 + (valid ? (size_t)(ty * (uint32_t)PW + tx) * pitch : 0) + (uint32_t)(8 * q) * 2u;
+        const bool valid = (int)ty < a.TH && oy < a.Ho && ox < a.Wo;
+        const uint8_t *base = y1 + (valid ? (size_t)((ty * (uint32_t)PW + tx) * (uint32_t)a.stride) * pitch : 0) + (uint32_t)(8 * q) * 2u;
         f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int k = 0; k < a.nk; ++k) {
             const uint4 w3a = w3[k * 64], w3b = a.nt3 == 2 ? w3[(a.nk + k) * 64] : uint4{0u, 0u, 0u, 0u}; // asked for before the taps
-            float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            const float4 ba = *reinterpret_cast<const float4 *>(lb2 + 32 * k + 8 * q), bb = *reinterpret_cast<const float4 *>(lb2 + 32 * k + 8 * q + 4);
+            float s[8] = {ba.x, ba.y, ba.z, ba.w, bb.x, bb.y, bb.z, bb.w};
             uint4 vt[9]; // all nine taps asked for before the first is used
 #pragma unroll
             for (int tap = 0; tap < 9; ++tap)
@@ -1774,12 +1791,16 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
             if (a.nt3 == 2) acc1 = mfma16<DT>(w3b, b, acc1);
         }
         if (!valid) continue;
-        const size_t pix = (size_t)(n * a.H + oy) * a.W + ox;
+        const size_t pix = (size_t)(n * a.Ho + oy) * a.Wo + ox;
         for (int u = 0; u < a.nt3; ++u) {
             const int f = 16 * u + 4 * q;
             if (f >= a.F3) continue;
             const f32x4 d = u == 0 ? acc0 : acc1;
             float v[4] = {d[0], d[1], d[2], d[3]};
+            if (a.b3) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] += a.b3[f + i];
+            }
             if (a.residual) {
                 const uint2 r = *reinterpret_cast<const uint2 *>(x16 + pix * a.C1 + f);
                 v[0] += from_storage<DT>((uint16_t)(r.x & 0xffffu));
@@ -1795,28 +1816,31 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
     }
 }
 
-size_t fused_ir_lds_bytes(int TH, int TW, int nslots)
+size_t fused_ir_lds_bytes(int TH, int TW, int nslots, int stride)
 {
-    const int nhb = ((TH + 2) * (TW + 2) + 15) / 16;
-    return (size_t)nhb * 16 * ((size_t)nslots * 2 + kIrPad) + (size_t)9 * nslots * 4;
+    const int nhb = (((TH - 1) * stride + 3) * ((TW - 1) * stride + 3) + 15) / 16;
+    return (size_t)nhb * 16 * ((size_t)nslots * 2 + kIrPad) + (size_t)9 * nslots * 4 + (size_t)2 * nslots * 4;
 }
 
-int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void *w1, const void *w3, const uint32_t *wdw, int N,
-                                   int H, int W, int C1, int F3, int nslots, int TH, int TW, int act1, int act2, int act3,
-                                   int residual, void *stream)
+int launch_fused_inverted_residual(int dtype, const IrLaunch &l, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
+    const int N = l.N, H = l.H, W = l.W, C1 = l.C1, F3 = l.F3, nslots = l.nslots, TH = l.TH, TW = l.TW, stride = l.stride;
     IrArgs a;
-    a.x = x; a.y = y; a.w1 = w1; a.w3 = w3; a.wdw = wdw;
+    a.x = l.x; a.y = l.y; a.w1 = l.w1; a.w3 = l.w3; a.wdw = l.wdw; a.perm = l.perm;
+    a.b1 = l.b1; a.b2 = l.b2; a.b3 = l.b3;
     a.N = N; a.H = H; a.W = W; a.C1 = C1; a.F3 = F3;
+    a.stride = stride; a.Ho = (H - 1) / stride + 1; a.Wo = (W - 1) / stride + 1; // 3 x 3, padding 1
     a.nt1 = nslots / 16; a.nk = nslots / 32; a.nt3 = (F3 + 15) / 16;
-    a.TH = TH; a.TW = TW; a.tilesY = (H + TH - 1) / TH; a.tilesX = (W + TW - 1) / TW;
-    a.act1 = act1; a.act2 = act2; a.act3 = act3; a.residual = residual;
+    a.TH = TH; a.TW = TW; a.tilesY = (a.Ho + TH - 1) / TH; a.tilesX = (a.Wo + TW - 1) / TW;
+    a.act1 = l.act1; a.act2 = l.act2; a.act3 = l.act3; a.residual = l.residual;
+    const int PH = (TH - 1) * stride + 3, PW = (TW - 1) * stride + 3;
     a.div_tw = TW <= 1 ? 0u : (uint32_t)(((1ull << 32) + TW - 1) / TW);
-    a.div_pw = (uint32_t)(((1ull << 32) + (TW + 2) - 1) / (TW + 2));
-    const size_t lds_bytes = fused_ir_lds_bytes(TH, TW, nslots);
-    if (nslots <= 0 || nslots % 32 || nslots > 192 || (TH + 2) * (TW + 2) > 256 || a.nt3 < 1 || a.nt3 > 2 || C1 > 32 || C1 % 8 || F3 % 4 || lds_bytes > 160 * 1024 || (residual && F3 != C1)) {
-        set_error("fused inverted residual: unsupported shape (slots %d, C1 %d, F3 %d, LDS %zu)", nslots, C1, F3, lds_bytes);
+    a.div_pw = (uint32_t)(((1ull << 32) + PW - 1) / PW);
+    const size_t lds_bytes = fused_ir_lds_bytes(TH, TW, nslots, stride);
+    if (nslots <= 0 || nslots % 32 || nslots > 192 || TH < 1 || TW < 1 || PH * PW > 256 || a.nt3 < 1 || a.nt3 > 2 || C1 > 32 || C1 % 8 || F3 % 4 ||
+        lds_bytes > 160 * 1024 || (stride != 1 && stride != 2) || (l.residual && (F3 != C1 || stride != 1)) || !l.perm) {
+        set_error("fused inverted residual: unsupported shape (slots %d, C1 %d, F3 %d, stride %d, LDS %zu)", nslots, C1, F3, stride, lds_bytes);
         return NPAS_E_SHAPE;
     }
     const long grid = (long)N * a.tilesY * a.tilesX;

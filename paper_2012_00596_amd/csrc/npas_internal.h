@@ -355,10 +355,19 @@ int launch_conv_wave_f32(const WaveF32Args &a, void *stream);
 bool fpp_supported(int nt1, int nt2);
 int launch_fused_pointwise_pair(int dtype, const void *x, void *y, const void *wblob, int M, int C1, int nt1, int F2,
                                 int act1, int act2, uint32_t use0, uint32_t use1, void *stream);
-size_t fused_ir_lds_bytes(int TH, int TW, int nslots);
-int launch_fused_inverted_residual(int dtype, const void *x, void *y, const void *w1, const void *w3, const uint32_t *wdw, int N,
-                                   int H, int W, int C1, int F3, int nslots, int TH, int TW, int act1, int act2, int act3,
-                                   int residual, void *stream);
+size_t fused_ir_lds_bytes(int TH, int TW, int nslots, int stride);
+// One launch of the fused 1x1 -> depthwise 3x3 -> 1x1 block (all pointers device memory).
+struct IrLaunch {
+    const void *x;
+    void *y;
+    const void *w1, *w3;       // operand images of the two 1x1 layers in slot order
+    const uint32_t *wdw;       // depthwise weights in slot order
+    const int *perm;           // intermediate channel of each slot (-1: padding)
+    const float *b1, *b2, *b3; // biases in channel order, or null
+    int N, H, W, C1, F3, nslots, TH, TW, stride;
+    int act1, act2, act3, residual;
+};
+int launch_fused_inverted_residual(int dtype, const IrLaunch &l, void *stream);
 int launch_depthwise3x3(int dt, const void *x, void *y, const void *w, const float *bias, const void *residual, int N, int H,
                         int W, int C, int stride, int act, void *stream);
 int launch_empty(int count, void *stream);

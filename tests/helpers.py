@@ -3,8 +3,8 @@ through the C-ABI binding, and the error metric."""
 import numpy as np
 
 from workloads import dtypes
-from workloads.harness import (from_dev, new_dev, out_shape, pack_layer, run_layer_gpu, stack_descs,  # noqa: F401
-                               to_dev)
+from workloads.harness import (bias_tensors, from_dev, new_dev, out_shape, pack_layer, run_layer_gpu,  # noqa: F401
+                               stack_descs, to_dev)
 
 TOL = {dtypes.F32: 1e-5, dtypes.BF16: 1e-2, dtypes.F16: 2e-3}
 

@@ -43,7 +43,8 @@ def layerwise(npas, torch, w, check_meta=True):
         if L.res >= 0:
             rs, _ = dtypes.quantize(rounded[L.res], w.dtype)
             res_dev = to_dev(rs, torch)
-        y = run_layer_gpu(npas, torch, L, packed, x_dev, in_shape, w.dtype, res_dev)
+        bias_dev = helpers.bias_tensors([L], torch)[0]
+        y = run_layer_gpu(npas, torch, L, packed, x_dev, in_shape, w.dtype, res_dev, bias_dev)
         got = from_dev(y, w.dtype).reshape(shapes[i + 1])
         err = rel_err(got, rounded[i + 1].reshape(shapes[i + 1]))
         print(f"  layer {i:2d} {L.name or L.kind:12s} in={in_shape} out={shapes[i + 1]} err={err:.3e}", flush=True)
@@ -322,19 +323,28 @@ def test_depthwise3x3(npas, torch, case):
     assert err <= TOL[dtype]
 
 
-@pytest.mark.parametrize("stride", [1, 2])
-def test_inverted_residual_block_layerwise_and_stack(npas, torch, stride):
-    """1x1 -> depthwise 3x3 -> 1x1 (+ input): each layer against the oracle, then the stack call end to end."""
+@pytest.mark.parametrize("stride,bias,act,HW", [(1, False, configs.ACT_RELU6, 13), (2, False, configs.ACT_RELU6, 13),
+                                                (1, True, configs.ACT_RELU6, 13), (2, True, configs.ACT_RELU6, 13),
+                                                (2, True, configs.ACT_HARDSWISH, 14), (1, True, configs.ACT_HARDSWISH, 9),
+                                                (2, False, configs.ACT_RELU6, 31)],
+                         ids=["s1", "s2", "s1_bias", "s2_bias", "s2_bias_hswish_even", "s1_bias_hswish", "s2_several_tiles"])
+def test_inverted_residual_block_layerwise_and_stack(npas, torch, stride, bias, act, HW):
+    """1x1 -> depthwise 3x3 (stride 1 or 2) -> 1x1 (+ input at stride 1), with and without a bias per layer: each layer
+    against the oracle, then the stack call end to end, per layer and as one fused launch.  With a bias the padding
+    of the depthwise layer must still be zero (not act(bias)): the border pixels are where that shows."""
     from workloads import sweeps
-    w = sweeps.inverted_residual_block(batch=2, HW=13, stride=stride)
-    print(f"inverted residual block, stride {stride}", flush=True)
+    w = sweeps.inverted_residual_block(batch=2, HW=HW, stride=stride, bias=bias, act=act)
+    print(f"inverted residual block, stride {stride} bias {bias} act {act} {HW}x{HW}", flush=True)
     layerwise(npas, torch, w)
     rounded, _ = oracle.run_stack(w.x_exact, w.layers, w.dtype)
     for flags in (0, 1, 3):          # per layer; pointwise-pair fusion (not applicable); whole-block fusion
         got, st = _run_stack_gpu(npas, torch, w, flags)
-        assert st.num_launches() == (1 if flags == 3 and stride == 1 else 3)
+        assert st.num_launches() == (1 if flags == 3 else 3)
         norm, worst = helpers.check_stack_output(got, rounded[-1], STACK_NORM_TOL)
         print(f"  run_stack flags={flags} launches={st.num_launches()} norm-wise {norm:.3e} worst element {worst:.3e}", flush=True)
+        border = np.concatenate([got[:, 0].ravel(), got[:, -1].ravel(), got[:, :, 0].ravel(), got[:, :, -1].ravel()])
+        want = np.concatenate([rounded[-1][:, 0].ravel(), rounded[-1][:, -1].ravel(), rounded[-1][:, :, 0].ravel(), rounded[-1][:, :, -1].ravel()])
+        assert rel_err(border, want) <= 0.1, "border pixels (padding of the depthwise layer)"
 
 
 def test_run_stack_in_a_hip_graph_replays_like_the_eager_call(npas, torch):
@@ -467,7 +477,8 @@ def test_garbage_under_the_mask_changes_nothing(npas, torch):
 
 def _run_stack_gpu(npas, torch, w, flags=0):
     packed = [pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
-    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed), w.x_shape[1], w.x_shape[2], flags)
+    biases = helpers.bias_tensors(w.layers, torch)   # alive until the run below has finished
+    st = npas.Stack(helpers.stack_descs(npas, w.layers, packed, biases), w.x_shape[1], w.x_shape[2], flags)
     N = w.x_shape[0]
     shape = w.x_shape
     shapes = {0: shape}

@@ -392,3 +392,23 @@ def test_run_stack_wiring_and_rounding_against_plain_numpy():
     np.testing.assert_allclose(raw[8], t8, rtol=0, atol=1e-12)
     _assert_same_rounded(rounded[8], _bf16(t8), "logits")
     assert np.abs(t6).max() > 0 and (t6 == 0).any()
+    # (c) the cascade 1x1 -> depthwise 3x3 -> 1x1 with a bias per layer: the walker hands each layer its own bias,
+    # which enters before the residual and the activation (a bias dropped, given to the wrong layer or added after
+    # the clamp changes the rounded tensors)
+    from workloads import sweeps
+    for stride in (1, 2):
+        w = sweeps.inverted_residual_block(batch=1, HW=7, stride=stride, bias=True)
+        L1, L2, L3 = w.layers
+        assert all(L.bias is not None and np.abs(L.bias).max() > 0.05 for L in w.layers)
+        rounded, raw = oracle.run_stack(w.x_exact, w.layers, w.dtype)
+        x = w.x_exact
+        t1 = _bf16(np.clip(x.reshape(-1, L1.C) @ (L1.w_exact * L1.mask).reshape(L1.F, L1.C).T + L1.bias, 0.0, 6.0)).reshape(1, 7, 7, L1.F)
+        dw = torch.nn.functional.conv2d(torch.from_numpy(t1.transpose(0, 3, 1, 2)), torch.from_numpy(L2.w_exact.reshape(L2.C, 1, 3, 3)),
+                                        stride=stride, padding=1, groups=L2.C).numpy().transpose(0, 2, 3, 1)
+        t2 = _bf16(np.clip(dw + L2.bias, 0.0, 6.0))
+        t3 = t2.reshape(-1, L3.C) @ (L3.w_exact * L3.mask).reshape(L3.F, L3.C).T + L3.bias
+        if stride == 1:
+            t3 = t3 + x.reshape(-1, L1.C)
+        _assert_same_rounded(rounded[1], t1, f"expansion, stride {stride}")
+        _assert_same_rounded(rounded[2], t2, f"depthwise, stride {stride}")
+        np.testing.assert_allclose(raw[3].reshape(t3.shape), t3, rtol=0, atol=1e-12)

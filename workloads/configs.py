@@ -45,6 +45,7 @@ class Layer:
     library: Optional[np.ndarray] = None   # pattern scheme: uint8 [n_pat][9]
     pat_id: Optional[np.ndarray] = None    # pattern scheme: uint8 [F][C], 255 = removed
     name: str = ""
+    bias: Optional[np.ndarray] = None      # float32 [F], added before the residual and the activation
 
 
 @dataclass

@@ -81,8 +81,16 @@ def run_layer_gpu(npas, torch, L, packed, x_dev, in_shape, dtype, res_dev=None, 
     return y
 
 
-def stack_descs(npas, layers, packed):
+def stack_descs(npas, layers, packed, biases=None):
+    """Layer descriptions for npas.Stack; biases: per layer a device tensor (fp32, kept alive by the caller) or None."""
     kinds = {"conv": npas.LAYER_CONV, "fc": npas.LAYER_FC, "maxpool": npas.LAYER_MAXPOOL3X3S2,
              "avgpool": npas.LAYER_GLOBAL_AVGPOOL, "dwconv": npas.LAYER_DEPTHWISE3X3}
-    return [dict(kind=kinds[L.kind], packed=packed[i], stride=L.stride, pad=L.pad, act=L.act, src=L.src, res=L.res)
+    return [dict(kind=kinds[L.kind], packed=packed[i], stride=L.stride, pad=L.pad, act=L.act, src=L.src, res=L.res,
+                 bias=None if biases is None else biases[i])
             for i, L in enumerate(layers)]
+
+
+def bias_tensors(layers, torch):
+    """Per layer its bias on the device (fp32) or None."""
+    return [None if getattr(L, "bias", None) is None else torch.from_numpy(np.ascontiguousarray(L.bias, dtype=np.float32)).cuda()
+            for L in layers]

@@ -14,7 +14,9 @@ from __future__ import annotations
 
 from fractions import Fraction
 
-from . import configs, dtypes, masks
+import numpy as np
+
+from . import configs, dtypes, masks, prng
 from .configs import ACT_NONE, Layer, Workload, _tensor
 
 RATE_SCHEMES = ("block_punched", "unstructured", "whole_tensor", "pattern", "filter")
@@ -48,7 +50,7 @@ def rate_sweep_layer(scheme, rate, batch=1, HW=56, C=256, F=256, seed=configs.BA
 
 
 def inverted_residual_block(batch=64, HW=56, C=24, t=6, stride=1, Bf=8, Bc=8, rate=4, seed=configs.BASE_SEED + 7,
-                            dtype=dtypes.BF16):
+                            dtype=dtypes.BF16, bias=False, act=configs.ACT_RELU6):
     """The cascade "1x1 & 3x3 DW & 1x1" of the search space (section 5.1.1) in its usual
     inverted-residual form: 1x1 expansion C -> t C, ReLU6, depthwise 3x3 (stride 1 or 2), ReLU6,
     1x1 projection back to C, plus the block input when the stride is 1.  The 1x1 layers are
@@ -56,11 +58,14 @@ def inverted_residual_block(batch=64, HW=56, C=24, t=6, stride=1, Bf=8, Bc=8, ra
     those of configs.config2."""
     xs, xe = _tensor(seed, 1, (batch, HW, HW, C), 1.0, dtype)
     mid = t * C
-    L1 = configs._bp_conv(seed, 0, C, mid, 1, 1, 0, Bf, Bc, rate, 0.3, dtype, configs.ACT_RELU6, src=0, name="expand1x1")
+    L1 = configs._bp_conv(seed, 0, C, mid, 1, 1, 0, Bf, Bc, rate, 0.3, dtype, act, src=0, name="expand1x1")
     dw_store, dw_exact = _tensor(seed, 150, (mid, 3, 3), 0.3, dtype)
-    L2 = Layer("dwconv", "", mid, mid, 3, 3, stride, 1, 1, 1, 1.0, configs.ACT_RELU6, 1, -1, dw_store, dw_exact, name="dw3x3")
+    L2 = Layer("dwconv", "", mid, mid, 3, 3, stride, 1, 1, 1, 1.0, act, 1, -1, dw_store, dw_exact, name="dw3x3")
     L3 = configs._bp_conv(seed, 1, mid, C, 1, 1, 0, Bf, Bc, rate, 0.1, dtype, ACT_NONE, src=2,
                           res=0 if stride == 1 else -1, name="project1x1")
+    if bias:  # a bias per layer (what folding a batch normalisation into the layer leaves), fp32
+        for i, L in enumerate((L1, L2, L3)):
+            L.bias = (0.5 * prng.normal(seed, 300 + i, L.F)).astype(np.float32)
     return Workload("inverted_residual_block", dtype, (batch, HW, HW, C), xs, xe, [L1, L2, L3])
 
 
