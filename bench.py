@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--sweep", type=str, default="", choices=["", "rate", "block"],
                     help="rate: 3x3 conv 56x56x256->256 over pruning schemes and rates; block: residual stack over block sizes at 6x")
     ap.add_argument("--only", type=str, default="", help="with --per-layer: comma-separated layer indices to run")
+    ap.add_argument("--ir", type=str, default="", choices=["", "s2", "bias", "s2bias"],
+                    help="config 6 (inverted-residual block): depthwise stride 2 and / or a bias on every layer")
     ap.add_argument("--reps", type=int, default=20, help="with --per-layer / --stack / --sweep: timed launches")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -84,7 +86,8 @@ class StackRunner:
         self.w, self.torch, self.npas = w, torch, npas
         self.N, self.H, self.W = w.x_shape[0], w.x_shape[1], w.x_shape[2]
         self.packed = [harness.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
-        self.st = npas.Stack(harness.stack_descs(npas, w.layers, self.packed), self.H, self.W, flags)
+        self.biases = harness.bias_tensors(w.layers, torch)   # device tensors the stack's layers point at
+        self.st = npas.Stack(harness.stack_descs(npas, w.layers, self.packed, self.biases), self.H, self.W, flags)
         self.wsb = self.st.workspace_bytes(self.N)
         shapes = {0: w.x_shape}
         for i, L in enumerate(w.layers):
@@ -100,21 +103,25 @@ class StackRunner:
         k = i % self.nsets
         self.st.run(self.xs[k], self.ys[k], self.N, self.wss[k], self.wsb, self.stream)
 
-    def timed(self, steps, warmup):
-        """(wall seconds per step over all steps, per-step device milliseconds from events on the launch stream)."""
+    def timed(self, steps, warmup, chunk=1):
+        """(wall seconds per step over all steps, per-step device milliseconds from events on the launch stream).
+        chunk > 1: an event every `chunk` steps and their mean per step (an event between two launches of a few
+        microseconds costs about as much as the launch)."""
         torch = self.torch
         for i in range(warmup):
             self.step(i)
         torch.cuda.synchronize()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        steps = steps // chunk * chunk
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps // chunk + 1)]
         t0 = time.perf_counter()
         ev[0].record()
         for i in range(steps):
             self.step(i)
-            ev[i + 1].record()
+            if (i + 1) % chunk == 0:
+                ev[(i + 1) // chunk].record()
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) / steps
-        per = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)])
+        per = np.array([ev[i].elapsed_time(ev[i + 1]) / chunk for i in range(steps // chunk)])
         return wall, per
 
 
@@ -195,16 +202,17 @@ def time_layers(w, packed, rows, torch, npas, reps, only=()):
             xs = [torch.randn(nin, device="cuda").to(torch.float16).view(torch.int16) for _ in range(nsets)]
         ys = [torch.empty(nout, dtype=td, device="cuda") for _ in range(nsets)]
         rs = [torch.zeros(nout, dtype=td, device="cuda") for _ in range(nsets)] if L.res >= 0 else None
+        bias = None if getattr(L, "bias", None) is None else torch.from_numpy(np.ascontiguousarray(L.bias, dtype=np.float32)).cuda()
 
         def run(k):
             if L.kind == "conv":
                 N, H, W_, _ = ishape
-                npas.conv2d_sparse(p, xs[k], ys[k], N, H, W_, L.stride, L.pad, None, rs[k] if rs else None, L.act, stream)
+                npas.conv2d_sparse(p, xs[k], ys[k], N, H, W_, L.stride, L.pad, bias, rs[k] if rs else None, L.act, stream)
             elif L.kind == "fc":
-                npas.fc_sparse(p, xs[k], ys[k], ishape[0], None, L.act, stream)
+                npas.fc_sparse(p, xs[k], ys[k], ishape[0], bias, L.act, stream)
             elif L.kind == "dwconv":
                 N, H, W_, _ = ishape
-                npas.depthwise3x3(p, xs[k], ys[k], N, H, W_, L.stride, None, rs[k] if rs else None, L.act, stream)
+                npas.depthwise3x3(p, xs[k], ys[k], N, H, W_, L.stride, bias, rs[k] if rs else None, L.act, stream)
             elif L.kind == "maxpool":
                 N, H, W_, C = ishape
                 npas.maxpool3x3s2(xs[k], ys[k], N, H, W_, C, w.dtype, stream)
@@ -334,18 +342,19 @@ def headline(args, torch, npas, harness, configs):
         torch.cuda.empty_cache()
         w1 = configs.config5(batch=1)
         r1 = StackRunner(w1, torch, npas, harness, flags, 4)
-        _, p1 = r1.timed(100, 20)
-        out["batch1"] = {"workload": "configs[4] at batch 1", "median_us": float(np.median(p1)) * 1e3, "min_us": float(p1.min()) * 1e3,
+        _, p1 = r1.timed(200, 20, chunk=10)
+        out["batch1"] = {"workload": "configs[4] at batch 1", "timing": "means over 10 consecutive steps", "median_us": float(np.median(p1)) * 1e3, "min_us": float(p1.min()) * 1e3,
                          "launches": r1.st.num_launches(), "floor_us": stack_floor_us(layer_costs(w1, r1.packed, harness)),
                          "launch_floor_us": out["launch_floor_us"]["empty_kernel"] * r1.st.num_launches()}
         del r1
         w2 = configs.config2(batch=64)
         x2 = int(np.prod(w2.x_shape)) * 2
         r2 = StackRunner(w2, torch, npas, harness, flags, max(2, -(-640 * 2**20 // (2 * x2))))
-        _, p2 = r2.timed(200, 20)
+        _, p2 = r2.timed(1000, 50, chunk=50)
         b2 = 2 * x2 + sum(4 * p.info()["K_total"] + p.info()["compact_weight_bytes"] for p in r2.packed)
         med2 = float(np.median(p2)) * 1e3
-        out["config2_fused_pair"] = {"workload": "configs[1]: 24->144->24, batch 64, 56x56, one fused launch", "median_us": med2,
+        out["config2_fused_pair"] = {"workload": "configs[1]: 24->144->24, batch 64, 56x56, one fused launch",
+                                     "timing": "means over 50 consecutive launches", "median_us": med2,
                                      "min_us": float(p2.min()) * 1e3, "launches": r2.st.num_launches(),
                                      "algorithmic_bytes": b2, "GBps": b2 / med2 / 1e3, "hbm_frac": b2 / med2 / 1e3 / HBM_PEAK_GBS,
                                      "TFLOPs_dense_equiv": 2.0 * w2.dense_macs() / med2 / 1e6}
@@ -445,7 +454,7 @@ def stack_mode(args, torch, npas, harness, configs):
     from workloads import sweeps
     batch = args.batch or 64
     w = {2: lambda: configs.config2(batch=batch), 5: lambda: configs.config5(batch=batch),
-         6: lambda: sweeps.inverted_residual_block(batch=batch)}[cfg]()
+         6: lambda: sweeps.inverted_residual_block(batch=batch, stride=2 if "s2" in args.ir else 1, bias="bias" in args.ir)}[cfg]()
     us, launches, wsb = time_stack(w, args.reps, torch, npas, harness, fuse=not args.no_fuse, graph=args.graph)
     flop = 2.0 * w.dense_macs()
     print("# config %d %s batch %d: npas_run_stack%s %.1f us per call, %d launches, workspace %.1f MB, %.1f TFLOP/s dense-equivalent, %.1f images/s"
@@ -503,7 +512,8 @@ def per_layer(args, torch, npas, harness, configs):
     from workloads import sweeps
     batch = args.batch or (128 if cfg == 5 else 64)
     w = {1: configs.config1, 2: lambda: configs.config2(batch=batch), 3: configs.config3, 4: configs.config4,
-         5: lambda: configs.config5(batch=batch), 6: lambda: sweeps.inverted_residual_block(batch=batch)}[cfg]()
+         5: lambda: configs.config5(batch=batch),
+         6: lambda: sweeps.inverted_residual_block(batch=batch, stride=2 if "s2" in args.ir else 1, bias="bias" in args.ir)}[cfg]()
     packed = [harness.pack_layer(npas, L, w.dtype) if L.kind in ("conv", "fc", "dwconv") else None for L in w.layers]
     rows = layer_costs(w, packed, harness)
     only = set(int(t) for t in args.only.split(",") if t)

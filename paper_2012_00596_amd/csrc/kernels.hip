@@ -1683,8 +1683,11 @@ struct IrArgs {
     uint32_t div_tw, div_pw;
 };
 
-template <int DT>
-__global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
+// BIAS: some layer of the block has one (bias tables in LDS, halo pixels outside the image zeroed explicitly: the
+// padding of the depthwise layer is zero, not act1(b1)).  Without, x = 0 there already gives zero, and the kernel
+// keeps the registers that let three workgroups share a CU.
+template <int DT, bool BIAS>
+__global__ __launch_bounds__(256, 3) void fused_inverted_residual_kernel(IrArgs a) // three workgroups per CU: at most 168 registers
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -1724,12 +1727,14 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
     }
 #pragma unroll
     for (int t = 0; t < 12; ++t) w1r[t] = t < a.nt1 ? w1[t * 64] : uint4{0u, 0u, 0u, 0u};
-    for (int i = tid; i < nslots; i += 256) { // bias tables, asked for behind the loads above
-        const int c = a.b1 || a.b2 ? a.perm[i] : -1;
-        lb1[i] = a.b1 && c >= 0 ? a.b1[c] : 0.f;
-        lb2[i] = a.b2 && c >= 0 ? a.b2[c] : 0.f;
+    if (BIAS) {
+        for (int i = tid; i < nslots; i += 256) { // bias tables, asked for behind the loads above
+            const int c = a.b1 || a.b2 ? a.perm[i] : -1;
+            lb1[i] = a.b1 && c >= 0 ? a.b1[c] : 0.f;
+            lb2[i] = a.b2 && c >= 0 ? a.b2[c] : 0.f;
+        }
+        __syncthreads();
     }
-    __syncthreads();
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int hb = wave + 4 * r;
@@ -1738,11 +1743,12 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
         for (int t = 0; t < 12; ++t) {
             if (hb < nhb && t < a.nt1) {
                 const f32x4 d = mfma16<DT>(w1r[t], xv[r], f32x4{0.f, 0.f, 0.f, 0.f});
-                const float4 bb = *reinterpret_cast<const float4 *>(lb1 + 16 * t + 4 * q); // result register i: slot 16 t + 4 q + i
+                float4 bb = float4{0.f, 0.f, 0.f, 0.f};
+                if (BIAS) bb = *reinterpret_cast<const float4 *>(lb1 + 16 * t + 4 * q); // result register i: slot 16 t + 4 q + i
                 uint2 o;
                 o.x = pack2<DT>(clampf(d[0] + bb.x, cl1), clampf(d[1] + bb.y, cl1));
                 o.y = pack2<DT>(clampf(d[2] + bb.z, cl1), clampf(d[3] + bb.w, cl1));
-                if (!inside[r]) o = uint2{0u, 0u}; // padding of the depthwise layer, whatever the bias
+                if (BIAS && !inside[r]) o = uint2{0u, 0u}; // padding of the depthwise layer, whatever the bias
                 *reinterpret_cast<uint2 *>(dst + t * 32) = o;
             }
         }
@@ -1762,7 +1768,11 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
         f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int k = 0; k < a.nk; ++k) {
             const uint4 w3a = w3[k * 64], w3b = a.nt3 == 2 ? w3[(a.nk + k) * 64] : uint4{0u, 0u, 0u, 0u}; // asked for before the taps
-            const float4 ba = *reinterpret_cast<const float4 *>(lb2 + 32 * k + 8 * q), bb = *reinterpret_cast<const float4 *>(lb2 + 32 * k + 8 * q + 4);
+            float4 ba = float4{0.f, 0.f, 0.f, 0.f}, bb = ba;
+            if (BIAS) {
+                ba = *reinterpret_cast<const float4 *>(lb2 + 32 * k + 8 * q);
+                bb = *reinterpret_cast<const float4 *>(lb2 + 32 * k + 8 * q + 4);
+            }
             float s[8] = {ba.x, ba.y, ba.z, ba.w, bb.x, bb.y, bb.z, bb.w};
             uint4 vt[9]; // all nine taps asked for before the first is used
 #pragma unroll
@@ -1797,7 +1807,7 @@ __global__ __launch_bounds__(256) void fused_inverted_residual_kernel(IrArgs a)
             if (f >= a.F3) continue;
             const f32x4 d = u == 0 ? acc0 : acc1;
             float v[4] = {d[0], d[1], d[2], d[3]};
-            if (a.b3) {
+            if (BIAS && a.b3) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[i] += a.b3[f + i];
             }
@@ -1844,15 +1854,18 @@ int launch_fused_inverted_residual(int dtype, const IrLaunch &l, void *stream)
         return NPAS_E_SHAPE;
     }
     const long grid = (long)N * a.tilesY * a.tilesX;
-    static std::once_flag once[2];
+    const bool bias = l.b1 || l.b2 || l.b3;
+    static std::once_flag once[4];
+    auto go = [&](auto kern, std::once_flag &flag) {
+        allow_lds_once(flag, kern, 160 * 1024);
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, st, a);
+    };
     if (dtype == NPAS_BF16) {
-        auto kern = fused_inverted_residual_kernel<NPAS_BF16>;
-        allow_lds_once(once[0], kern, 160 * 1024);
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, st, a);
+        if (bias) go(fused_inverted_residual_kernel<NPAS_BF16, true>, once[0]);
+        else go(fused_inverted_residual_kernel<NPAS_BF16, false>, once[1]);
     } else if (dtype == NPAS_F16) {
-        auto kern = fused_inverted_residual_kernel<NPAS_F16>;
-        allow_lds_once(once[1], kern, 160 * 1024);
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, st, a);
+        if (bias) go(fused_inverted_residual_kernel<NPAS_F16, true>, once[2]);
+        else go(fused_inverted_residual_kernel<NPAS_F16, false>, once[3]);
     } else {
         set_error("fused inverted residual needs a 16-bit storage type");
         return NPAS_E_DTYPE;
