@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--no-rotate", action="store_true", help="reuse one buffer set")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the batch-1, configs[1] and per-layer legs of the headline run")
+    ap.add_argument("--no-small", action="store_true", help="skip the batch-1 and configs[1] legs of the headline run (profiling: only batch-128 launches remain)")
     ap.add_argument("--per-layer", type=int, default=0, metavar="CFG",
                     help="instead of the headline line, print a per-layer table (us, dense-equivalent TFLOP/s, "
                          "algorithmic GB/s, roofline fraction) for config CFG in 1..5 (BASELINE.json's configs[CFG-1]); "
@@ -336,7 +337,7 @@ def headline(args, torch, npas, harness, configs):
         roof.update(bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=floor_us / 1e3 / med_ms, traffic=None)
     out["roofline"] = roof
 
-    if not args.no_extras and cfg == 5:
+    if not args.no_extras and not args.no_small and cfg == 5:
         # the same stack at batch 1 (latency), and the configs[1] fused pair
         del run
         torch.cuda.empty_cache()
