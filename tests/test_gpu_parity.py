@@ -717,6 +717,12 @@ HS_CASES = [
     (("hs_smallc", 2, 21, 23, 3, 32, 5, 5, 2, 2, 8, 3, 2, dtypes.BF16, 3, False, True), None, "conv_smallc_mfma"),
     (("hs_gather", 1, 8, 8, 20, 18, 3, 3, 1, 1, 6, 4, 2, dtypes.BF16, 3, False, True), None, "conv_gather_mfma"),
     (("hs_fp32", 2, 9, 9, 8, 12, 3, 3, 1, 1, 4, 4, 2, dtypes.F32, 3, True, True), None, None),
+    # the compiled epilogue variants of the spatial kernels (activation kind x residual), partial filter blocks, stride 2
+    (("epi_spatial_hs_res", 3, 14, 14, 128, 128, 3, 3, 1, 1, 8, 4, 2, dtypes.BF16, 3, True, True), "spatial", "spatial_ring"),
+    (("epi_spatial_s2_relu_res", 2, 28, 28, 64, 128, 3, 3, 2, 1, 8, 4, 2, dtypes.BF16, 1, True, True), "spatial", "spatial_ring"),
+    (("epi_spatial_relu6_res_fp16_f200", 2, 9, 9, 64, 200, 3, 3, 1, 1, 8, 4, 3, dtypes.F16, 2, True, False), "spatial", "spatial_ring"),
+    (("epi_resident_none_nores", 2, 12, 10, 64, 64, 3, 3, 1, 1, 8, 4, 2, dtypes.BF16, 0, False, True), "resident", "spatial_resident"),
+    (("epi_pointwise_hs_nores_partial", 2, 7, 9, 64, 72, 1, 1, 1, 0, 8, 4, 2, dtypes.BF16, 3, False, False), None, None),
 ]
 
 
