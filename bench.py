@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the sparse-inference hot path on one MI355X.
 
-Default: one step = one npas_run_stack call on the benchmark's configs[4] at batch 128 (the 50-layer
+Default: one step = one npas_run_stack call on configs[4] of the benchmark definition at batch 128 (the 50-layer
 bottleneck residual stack, every conv block-punched 8x4 at a per-layer rate from {2, 3, 5}, block-based
 FC), bf16, inputs resident in HBM.  Prints ONE JSON line: dense-equivalent TFLOP/s of the whole stack
 (value), median / min per step, the roofline of the stack (sum of per-layer floors / measured) and of the
@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--no-small", action="store_true", help="skip the batch-1 and configs[1] legs of the headline run (profiling: only batch-128 launches remain)")
     ap.add_argument("--per-layer", type=int, default=0, metavar="CFG",
                     help="instead of the headline line, print a per-layer table (us, dense-equivalent TFLOP/s, "
-                         "algorithmic GB/s, roofline fraction) for config CFG in 1..5 (BASELINE.json's configs[CFG-1]); "
+                         "algorithmic GB/s, roofline fraction) for config CFG in 1..5 (configs[CFG-1] of the benchmark definition); "
                          "6 = the inverted-residual block 1x1, depthwise 3x3, 1x1 of workloads/sweeps.py")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MB",
                     help="instead of the benchmark, run 5 plain device copies of MB megabytes (known traffic for "
