@@ -183,9 +183,8 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
         const uint8_t *zb = reinterpret_cast<const uint8_t *>(a.zeros) + (uint32_t)(lane & 7) * 16u;
         const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u;
         const int nblk = (a.npb - wl + kSpatialFetchWaves - 1) / kSpatialFetchWaves; // this wave's blocks: wl, wl + 4, ...
-        // blocks per stage, spread over all but the chunk's last two stages (the patch must have landed at the barrier
-        // of the last one)
-        const int per = (nblk + max(1, T - 2) - 1) / max(1, T - 2);
+        // blocks per stage, spread over all but the chunk's last stage
+        const int per = (nblk + max(1, T - 1) - 1) / max(1, T - 1);
         // Blocks first + 4 k, k in [k0, k1), of the pixel table go to LDS at dst + 4096 k; (y0, x0) is the tile origin in
         // input coordinates.  Four at a time: the table entries are read first and the four address computations are
         // independent, so they overlap (the loads themselves are ordered against the table reads); one at a time a
@@ -260,7 +259,6 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
         }
         patch(it, 0, 0, 0, nblk);
         bias_block(it, 0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // the first chunk's patch, before the first barrier
         uint32_t pbuf = 0, bbuf = 0;
         for (;;) {
             const bool more_items = c_item + nwg < nitems;
@@ -269,16 +267,12 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
             for (int cc = 0; cc < nch; ++cc) {
                 const bool within = cc + 1 < nch;
                 for (int tap = 0; tap < T; ++tap) {
-                    // the next chunk's patch (asked for during the stages before) has landed: the multiplying waves
-                    // read their first fragments of it during this, the chunk's last, stage
-                    if (tap == T - 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    if (tap == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this chunk's patch has landed
                     __builtin_amdgcn_s_barrier();
-                    if (tap < T - 1) {
-                        if (within) patch(it, cc + 1, pbuf ^ 1u, tap * per, (tap + 1) * per);
-                        else if (more_items) {
-                            patch(nit, 0, pbuf ^ 1u, tap * per, (tap + 1) * per);
-                            if (tap == 0) bias_block(nit, bbuf ^ 1u);
-                        }
+                    if (within) patch(it, cc + 1, pbuf ^ 1u, tap * per, (tap + 1) * per);
+                    else if (more_items) {
+                        patch(nit, 0, pbuf ^ 1u, tap * per, (tap + 1) * per);
+                        if (tap == 0) bias_block(nit, bbuf ^ 1u);
                     }
                 }
                 pbuf ^= 1u;
@@ -329,10 +323,9 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
         for (;;) {
             const bool more_items = c_item + nwg < nitems;
             for (int st = 0; st < nch * T; ++st) {
-                // stride 1: the stage about to be multiplied AND the one after it have landed (the multiplying waves
-                // read the first fragments of stage t + 1 during stage t): at most D-3 stages stay in flight
+                // at most the D-2 stages issued after the one about to be multiplied stay in flight
                 static_assert(kImgs * 4 <= 63, "a wave can have 63 loads in flight");
-                wait_vmcnt((uint32_t)kImgs * (D - (S2 ? 2u : 3u)));
+                wait_vmcnt((uint32_t)kImgs * (D - 2u));
                 __builtin_amdgcn_s_barrier();
                 produce_w(); // the stage D-1 ahead, into the slot the barrier freed
             }
@@ -368,114 +361,48 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
             for (int s = 0; s < S; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
         const bool more_items = c_item + nwg < nitems;
 
-        if constexpr (!S2) {
-            // Stride 1.  Timestamps around the barrier showed both multiplying waves of a SIMD idle for the first
-            // 350-500 cycles of every stage: all of them had just been released and were waiting for their first
-            // fragments.  The first fragments of stage t + 1 (four weight tiles, two pixel blocks) are therefore read
-            // during the second half of stage t, into the registers its first half has released, and are there when
-            // the barrier opens.  The fetching waves guarantee one stage more: weights of stage t + 1 landed at
-            // barrier t, the next chunk's patch at the barrier of a chunk's last stage.  Nothing is read ahead across
-            // an item's end (the epilogue needs the registers).  Within a stage a pixel fragment is asked for as soon as
-            // the four MFMAs of the one before are issued (a second buffer, asked for one group earlier, measured the
-            // same and costs the registers that then spill); the scheduling barriers pin that order.
-            uint4 A0[4], A1[4], Bc;
-            bool pref = false;
-            for (int cc = 0; cc < nch; ++cc) {
-                const uint8_t *pbp = lds + pbuf * ppb;
-                uint32_t kh = 0, kw = 0;
-                for (int tap = 0; tap < T; ++tap) {
-                    __builtin_amdgcn_s_barrier(); // this stage's and the next stage's weights are in LDS
-                    asm volatile("" ::: "memory");
-                    const uint8_t *wsp = lds + wring + c_slot * kSpatialWStage + arow;
-                    if (++c_slot == D) c_slot = 0;
-                    const uint32_t toff = kh * (uint32_t)a.PW + kw;
-                    if (++kw == (uint32_t)a.KW) { kw = 0; ++kh; }
-                    uint32_t baddr[S]; // of the first step's fragments; the second step's are 64 bytes on, modulo the swizzle: ^ 64
+        for (int cc = 0; cc < nch; ++cc) {
+            const uint8_t *pbp = lds + (S2 ? 0u : pbuf * ppb);
+            uint32_t kh = 0, kw = 0;
+            for (int tap = 0; tap < T; ++tap) {
+                __builtin_amdgcn_s_barrier(); // this stage's weights (and, at its first stage, a chunk's patch or plane) are in LDS
+                asm volatile("" ::: "memory");
+                const uint8_t *wsp = lds + wring + c_slot * kSpatialWStage + arow;
+                if (++c_slot == D) c_slot = 0;
+                uint32_t toff = kh * (uint32_t)a.PW + kw;
+                if (++kw == (uint32_t)a.KW) { kw = 0; ++kh; }
+                if (S2) { // stage `tap` of the plane order: which plane, and 0 or 1 rows / columns into it
+                    const uint32_t pl = (uint32_t)a.npb * 8u, st = (uint32_t)tap;
+                    toff = st < 4u ? (st >> 1) * (uint32_t)a.PW + (st & 1u)
+                         : st < 6u ? pl + (st - 4u) * (uint32_t)a.PW
+                         : st < 8u ? 2u * pl + (st - 6u)
+                                   : 3u * pl;
+                }
+                // Per step: its 4 + S fragments are asked for, then its 4 S MFMAs follow.  The scheduling barrier keeps
+                // the reads together (left alone the compiler holds half of the pixel fragments back until just before
+                // their use: 4 % slower).  Measured against this on 28 x 28 x 128 / 14 x 14 x 256 / 7 x 7 x 512 at batch 128
+                // (38.0 / 34.0 / 39.1 us): all twelve fragments of a stage asked for at once and the weight tiles of the
+                // second step rotated into the first step's registers 41.8 / 37.5 / 39.7; the first fragments of the
+                // next stage read before its barrier and one pixel fragment in flight per wave 40.3 / 35.8 / 42.9, with
+                // two in flight (spills) 48.4 / 41.1 / 51.8; pixel fragments three ahead of their use 46 / 39 / 52.
 #pragma unroll
-                    for (int s = 0; s < S; ++s) {
-                        const uint32_t pp = pb0[s] + toff;
-                        baddr[s] = pp * 128u + ((((uint32_t)q) ^ (pp & 7u)) << 4);
-                    }
-                    // the stage after this one (of the same item): next tap, or tap 0 of the next chunk in the other buffer
-                    const bool last_tap = tap + 1 == T, last_stage = last_tap && cc + 1 == nch;
-                    const uint8_t *wsn = lds + wring + c_slot * kSpatialWStage + arow;
-                    const uint8_t *pbn = last_tap ? lds + (pbuf ^ 1u) * ppb : pbp;
-                    const uint32_t toffn = last_tap ? 0u : kh * (uint32_t)a.PW + kw;
-                    const uint32_t ppn = pb0[0] + toffn;
-                    const uint32_t baddrn = ppn * 128u + ((((uint32_t)q) ^ (ppn & 7u)) << 4);
-                    if (!pref) {
+                for (int step = 0; step < 2; ++step) {
+                    uint4 A[4], B[S];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) A0[j] = *reinterpret_cast<const uint4 *>(wsp + j * 1024);
-                        Bc = *reinterpret_cast<const uint4 *>(pbp + baddr[0]);
+                    for (int j = 0; j < 4; ++j) A[j] = *reinterpret_cast<const uint4 *>(wsp + step * 8192 + j * 1024);
+#pragma unroll
+                    for (int s2 = 0; s2 < S; ++s2) {
+                        const uint32_t pp = pb0[s2] + toff;
+                        B[s2] = *reinterpret_cast<const uint4 *>(pbp + pp * 128u + ((((uint32_t)(4 * step + q)) ^ (pp & 7u)) << 4));
                     }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int i = 0; i < NB; ++i) {
+                    for (int s2 = 0; s2 < S; ++s2)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) acc[j][i % S] = mfma16<DT>(Bc, i < S ? A0[j] : A1[j], acc[j][i % S]);
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (i + 1 < NB) Bc = *reinterpret_cast<const uint4 *>(pbp + (i + 1 < S ? baddr[i + 1] : baddr[i + 1 - S] ^ 64u));
-                        else if (!last_stage) Bc = *reinterpret_cast<const uint4 *>(pbn + baddrn);
-                        if (i < S) { // the second step's weight fragments, during the first step
-                            if (S == 4) A1[i] = *reinterpret_cast<const uint4 *>(wsp + 8192 + i * 1024);
-                            if (S == 2 && i == 0) {
-#pragma unroll
-                                for (int j = 0; j < 4; ++j) A1[j] = *reinterpret_cast<const uint4 *>(wsp + 8192 + j * 1024);
-                            }
-                        } else if (!last_stage) { // the next stage's first weight fragments, during the second step
-#pragma unroll
-                            for (int j = (i - S) * (4 / S); j < (i - S + 1) * (4 / S); ++j) A0[j] = *reinterpret_cast<const uint4 *>(wsn + j * 1024);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    pref = !last_stage;
+                        for (int j = 0; j < 4; ++j) acc[j][s2] = mfma16<DT>(B[s2], A[j], acc[j][s2]);
                 }
-                pbuf ^= 1u;
             }
-        } else {
-            for (int cc = 0; cc < nch; ++cc) {
-                const uint8_t *pbp = lds + (S2 ? 0u : pbuf * ppb);
-                for (int tap = 0; tap < T; ++tap) {
-                    __builtin_amdgcn_s_barrier(); // this stage's weights (and, at tap 0, the chunk's patch) are in LDS
-                    asm volatile("" ::: "memory");
-                    const uint8_t *wsp = lds + wring + c_slot * kSpatialWStage + arow;
-                    if (++c_slot == D) c_slot = 0;
-                    const uint32_t kh = (uint32_t)tap / (uint32_t)a.KW, kw = (uint32_t)tap - kh * (uint32_t)a.KW;
-                    uint32_t toff = kh * (uint32_t)a.PW + kw;
-                    if (S2) { // stage `tap` of the plane order: which plane, and 0 or 1 rows / columns into it
-                        const uint32_t pl = (uint32_t)a.npb * 8u, st = (uint32_t)tap;
-                        toff = st < 4u ? (st >> 1) * (uint32_t)a.PW + (st & 1u)
-                             : st < 6u ? pl + (st - 4u) * (uint32_t)a.PW
-                             : st < 8u ? 2u * pl + (st - 6u)
-                                       : 3u * pl;
-                    }
-                    // the NB B fragments of the stage (2 steps x S pixel blocks) in use order, fetched
-                    // three ahead of their use; A fragments one step ahead
-                    uint32_t baddr[NB];
-    #pragma unroll
-                    for (int s = 0; s < S; ++s) {
-                        const uint32_t pp = pb0[s] + toff;
-                        baddr[s] = pp * 128u + ((((uint32_t)q) ^ (pp & 7u)) << 4);
-                        baddr[S + s] = pp * 128u + ((((uint32_t)(4 + q)) ^ (pp & 7u)) << 4);
-                    }
-                    uint4 A[2][4], B[NB];
-    #pragma unroll
-                    for (int j = 0; j < 4; ++j) A[0][j] = *reinterpret_cast<const uint4 *>(wsp + j * 1024);
-    #pragma unroll
-                    for (int i = 0; i < 3; ++i) B[i] = *reinterpret_cast<const uint4 *>(pbp + baddr[i]);
-    #pragma unroll
-                    for (int i = 0; i < NB; ++i) {
-                        if (i + 3 < NB) B[i + 3] = *reinterpret_cast<const uint4 *>(pbp + baddr[i + 3]);
-                        if (i == (S == 4 ? 1 : 0)) {
-    #pragma unroll
-                            for (int j = 0; j < 4; ++j) A[1][j] = *reinterpret_cast<const uint4 *>(wsp + 8192 + j * 1024);
-                        }
-    #pragma unroll
-                        for (int j = 0; j < 4; ++j) acc[j][i % S] = mfma16<DT>(B[i], A[i / S][j], acc[j][i % S]);
-                    }
-                }
-                pbuf ^= 1u;
-            }
+            pbuf ^= 1u;
         }
         // ---- bias (from LDS), residual, activation, round, store ------------------------------
         // The patch is the MFMA's row operand and the weight images its column operand, and row r of weight tile j
