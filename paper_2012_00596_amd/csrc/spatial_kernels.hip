@@ -26,10 +26,8 @@ namespace npas {
 // hold it back, and either would hold back a multiplying wave.
 //   waves 0-7   multiply: 4 pixel groups x 2 filter groups, 64 x 64 outputs each; no
 //               global loads in their main loop
-//   waves 8-11  fetch the weight stages, depth-1 stages ahead
-//   waves 12-15 fetch the patches, a few blocks per stage, finishing well before the chunk ends
-// (four of each: one wave gets a global->LDS load issued only every ~160 cycles, measured, so
-// the 16 loads of a weight stage have to come from several waves to keep up with the matrix cores)
+//   wave 8      fetches the weight stages, depth-1 stages ahead
+//   waves 9-15  fetch the patches, a few blocks per stage, finishing well before the chunk ends
 // One s_barrier per stage, executed by all sixteen: a fetching wave first waits for the loads
 // of the stage about to be multiplied; after the barrier the slot (or patch buffer) of the
 // stage before is free to be refilled.
@@ -38,13 +36,14 @@ constexpr uint32_t kSpatialWStage = 16384;
 // of 64.  PG == 2 (launches whose 256-pixel tiles would leave most CUs without one): also eight, 4 pixel
 // groups of 32 x 2 filter groups of 64.
 constexpr int spatial_waves(int pg) { return pg == 2 ? 8 : 2 * pg; } // multiplying waves
-// Fetching waves of each kind.  (Two of each on 256-pixel tiles, which leaves every wave 170 registers instead of
-// 128: 44 -> 49 us on 28 x 28 x 128 -> 128 at batch 128, the loads of a stage are issued too slowly.  With the
-// registers of sixteen waves the compiler keeps one pixel fragment per wave in flight (read, wait, four MFMAs);
-// pinning a three-fragment read-ahead with sched_group_barrier was slower as well, 15.4 -> 16.5 us on the
-// pattern layer: two waves per SIMD already cover each other's waits.)
-constexpr int spatial_fetch_waves(int) { return 4; }
-constexpr int spatial_threads(int pg) { return (spatial_waves(pg) + 2 * spatial_fetch_waves(pg)) * 64; }
+// Fetching waves: one brings the weight stages (its sixteen lane-linear loads per stage are issued in a few hundred
+// cycles), seven the patch, whose loads cost their wave far more (pixel table entry from LDS behind the multiplying
+// waves' reads, bounds, address arithmetic).  With four of each the patch waves of the stride-2 mode were the last at
+// every second barrier by up to two stage times: 58.8 / 55.0 / 47.8 us on the three stride-2 layers of the 50-layer stack
+// at batch 128, 57.8 / 53.2 / 47.6 with 3 + 5, 53.1 / 50.9 / 45.3 with 2 + 6, 51.2 / 49.6 / 45.2 with 1 + 7; the stride-1
+// layers are the same with either split (38.5 / 34.1 / 39.4), and 2.5 % slower with 1 + 3 (twelve waves, 168 registers each).
+constexpr int kSpatialFetchTotal = 8;
+constexpr int spatial_threads(int pg) { return (spatial_waves(pg) + kSpatialFetchTotal) * 64; }
 
 struct SpatialItem {
     int n0, ty0, tx0, fb;
@@ -140,7 +139,8 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     // PG == 4: 8 waves of 64 pixels x 64 filters.  PG == 2: 8 waves of 32 x 64 (two per SIMD; four waves of
     // 64 x 64, one per SIMD, left the operand latency of every step exposed)
     constexpr int NCW = spatial_waves(PG), S = PG == 2 ? 2 : 4, NB = 2 * S;
-    constexpr int kSpatialThreads = spatial_threads(PG), kSpatialFetchWaves = spatial_fetch_waves(PG);
+    constexpr int kSpatialThreads = spatial_threads(PG);
+    constexpr int kWeightWaves = 1, kPatchWaves = kSpatialFetchTotal - kWeightWaves;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const uint32_t lbase = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -176,13 +176,13 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     spatial_out_table(a, reinterpret_cast<uint32_t *>(lds + lotab), 64 * PG, tid, kSpatialThreads);
     __syncthreads();
 
-    if (wave >= NCW + kSpatialFetchWaves) {
+    if (wave >= NCW + kWeightWaves) {
         // ---- patch fetch ------------------------------------------------------------------
-        const int wl = __builtin_amdgcn_readfirstlane(wave - NCW - kSpatialFetchWaves); // (the compiler cannot see that a wave index is uniform)
+        const int wl = __builtin_amdgcn_readfirstlane(wave - NCW - kWeightWaves); // (the compiler cannot see that a wave index is uniform)
         const uint8_t *xb = reinterpret_cast<const uint8_t *>(a.x);
         const uint8_t *zb = reinterpret_cast<const uint8_t *>(a.zeros) + (uint32_t)(lane & 7) * 16u;
         const uint32_t pcv = (uint32_t)((lane & 7) ^ (lane >> 3)) * 16u;
-        const int nblk = (a.npb - wl + kSpatialFetchWaves - 1) / kSpatialFetchWaves; // this wave's blocks: wl, wl + 4, ...
+        const int nblk = max(0, (a.npb - wl + kPatchWaves - 1) / kPatchWaves); // this wave's blocks: wl, wl + kPatchWaves, ...
         // blocks per stage, spread over all but the chunk's last stage
         const int per = (nblk + max(1, T - 1) - 1) / max(1, T - 1);
         // Blocks first + 4 k, k in [k0, k1), of the pixel table go to LDS at dst + 4096 k; (y0, x0) is the tile origin in
@@ -195,14 +195,14 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
             for (; k0 < k1; k0 += 4) {
                 uint32_t e[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) e[j] = tab[min(k0 + j, k1 - 1) * (kSpatialFetchWaves * 8)];
+                for (int j = 0; j < 4; ++j) e[j] = tab[min(k0 + j, k1 - 1) * (kPatchWaves * 8)];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     if (k0 + j >= k1) break;
                     const int n = pi.n0 + (int)(e[j] >> 20), iy = y0 + (int)((e[j] >> 10) & 1023u), ix = x0 + (int)(e[j] & 1023u);
                     const bool inb = e[j] != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
                     const uint8_t *src = inb ? xb + ((uint32_t)((n * a.H + iy) * a.W + ix) * (uint32_t)a.C + (uint32_t)cc * 64u) * 2u + pcv : zb;
-                    lds_dma16(src, dst + (uint32_t)(k0 + j) * (kSpatialFetchWaves * 1024u));
+                    lds_dma16(src, dst + (uint32_t)(k0 + j) * (kPatchWaves * 1024u));
                 }
             }
         };
@@ -287,10 +287,10 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
     }
 
     if (wave >= NCW) {
-        // ---- weight stage fetch: images wl*4 .. wl*4+3 of every stage ------------------------
-        const int wl = wave - NCW;
-        constexpr int kImgs = 16 / kSpatialFetchWaves;
-        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)(wl * kImgs) * 1024u + (uint32_t)lane * 16u;
+        // ---- weight stage fetch: this wave's share of the 16 images of every stage -----------
+        const int wl = __builtin_amdgcn_readfirstlane(wave - NCW);
+        const int img0 = 16 * wl / kWeightWaves, kImgs = 16 * (wl + 1) / kWeightWaves - img0; // 4 each, or 5, 5, 6
+        const uint8_t *wb = reinterpret_cast<const uint8_t *>(a.wimg) + (uint32_t)img0 * 1024u + (uint32_t)lane * 16u;
         uint32_t p_item = c_item, p_slot = 0;
         int p_fb = it.fb, p_cc = 0, p_tap = 0;
         bool p_done = false;
@@ -298,9 +298,10 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
             // stride 2: the taps in plane order (kh, kw both even; kw = 1; kh = 1; the centre)
             const int tapi = S2 ? (int)((0x453718620ull >> (4 * p_tap)) & 15ull) : p_tap;
             const uint8_t *wsrc = wb + (size_t)((p_fb * nch + p_cc) * T + tapi) * kSpatialWStage;
-            const uint32_t dst = lbase + wring + p_slot * kSpatialWStage + (uint32_t)(wl * kImgs) * 1024u;
+            const uint32_t dst = lbase + wring + p_slot * kSpatialWStage + (uint32_t)img0 * 1024u;
 #pragma unroll
-            for (int i = 0; i < kImgs; ++i) lds_dma16(wsrc + i * 1024, dst + (uint32_t)i * 1024u);
+            for (int i = 0; i < 16; ++i)
+                if (i < kImgs) lds_dma16(wsrc + i * 1024, dst + (uint32_t)i * 1024u);
             if (++p_slot == D) p_slot = 0;
             if (!p_done) {
                 if (++p_tap == T) {
@@ -324,8 +325,7 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
             const bool more_items = c_item + nwg < nitems;
             for (int st = 0; st < nch * T; ++st) {
                 // at most the D-2 stages issued after the one about to be multiplied stay in flight
-                static_assert(kImgs * 4 <= 63, "a wave can have 63 loads in flight");
-                wait_vmcnt((uint32_t)kImgs * (D - 2u));
+                wait_vmcnt((uint32_t)kImgs * (D - 2u)); // (at most 6 x 4: a wave can have 63 loads in flight)
                 __builtin_amdgcn_s_barrier();
                 produce_w(); // the stage D-1 ahead, into the slot the barrier freed
             }
