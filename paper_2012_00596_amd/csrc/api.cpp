@@ -216,7 +216,7 @@ static bool plan_spatial_search(const npas_packed *p, int N, int H, int W, int p
     const int lds_total = 160 * 1024 - 2048 /* bias buffers */ - (s2 ? 4096 : 2048) /* patch pixel table */ - 1024 /* tile pixel table */, wstage = 16384;
     const int nbuf = s2 ? 4 : 2; // patch buffers (planes) of npb KB each
     const int max_npb = std::min(s2 ? 124 : 1 << 20, (lds_total - 3 * wstage) / (1024 * nbuf));
-    if (T < 2 || p->C % 64 != 0 || Ho <= 0 || Wo <= 0) return false;
+    if (T < 2 || p->C % 64 != 0 || Ho <= 0 || Wo <= 0 || (long)N * H * W >= (1L << 24)) return false; // (the kernel forms patch addresses with 24-bit multiplies)
     double best = -1.0;
     int bNI = 0, bTH = 0, bTW = 0;
     for (int TH = 1; TH <= std::min(Ho, 255); ++TH)

@@ -201,7 +201,13 @@ __global__ __launch_bounds__(spatial_threads(PG)) void spatial_ring_kernel(Spati
                     if (k0 + j >= k1) break;
                     const int n = pi.n0 + (int)(e[j] >> 20), iy = y0 + (int)((e[j] >> 10) & 1023u), ix = x0 + (int)(e[j] & 1023u);
                     const bool inb = e[j] != 0xffffffffu && n < a.N && (uint32_t)iy < (uint32_t)a.H && (uint32_t)ix < (uint32_t)a.W;
-                    const uint8_t *src = inb ? xb + ((uint32_t)((n * a.H + iy) * a.W + ix) * (uint32_t)a.C + (uint32_t)cc * 64u) * 2u + pcv : zb;
+                    // the offset is formed for every lane (24-bit multiplies: the launcher checks N H W < 2^24) and the
+                    // source selected afterwards, so that the loads of a group are straight-line code the compiler can
+                    // interleave: behind a branch per load each was a chain of some 25 dependent operations
+                    const uint32_t pix = __umul24(__umul24((uint32_t)n, (uint32_t)a.H) + (uint32_t)iy, (uint32_t)a.W) + (uint32_t)ix;
+                    const uint32_t off = __umul24(pix & 0xffffffu, (uint32_t)a.C * 2u) + ((uint32_t)cc * 128u + pcv);
+                    const uint64_t sx = (uint64_t)(uintptr_t)xb + off, sz = (uint64_t)(uintptr_t)zb;
+                    const uint8_t *src = reinterpret_cast<const uint8_t *>(inb ? sx : sz);
                     lds_dma16(src, dst + (uint32_t)(k0 + j) * (kPatchWaves * 1024u));
                 }
             }
@@ -435,7 +441,7 @@ int launch_spatial_ring(int dtype, const SpatialRingArgs &a, void *stream)
     const size_t lds_bytes = (size_t)(s2 ? 4 : 2) * a.npb * (1024 + (s2 ? 32 : 16)) + (size_t)a.depth * kSpatialWStage + 2048 + 1024;
     const long items = (long)a.tilesN * a.tilesY * a.tilesX * a.nfb;
     const unsigned grid = (unsigned)std::min<long>(items, 256);
-    if (lds_bytes > 160 * 1024 || a.depth < 3 || a.depth > 6 || (a.pg != 4 && a.pg != 2) || a.NI * a.TH * a.TW > 64 * a.pg ||
+    if (lds_bytes > 160 * 1024 || a.depth < 3 || a.depth > 6 || (long)a.N * a.H * a.W >= (1L << 24) /* 24-bit multiplies in the patch addresses */ || (a.pg != 4 && a.pg != 2) || a.NI * a.TH * a.TW > 64 * a.pg ||
         a.TH > 255 || a.TW > 255 || a.PH > 1023 || a.PW > 1023 || (a.stride != 1 && a.stride != 2) ||
         (s2 && (a.pg != 2 || a.KH != 3 || a.KW != 3 || a.pad != 1 || a.PH != a.TH + 1 || a.PW != a.TW + 1 || a.npb > 4 * 31))) {
         set_error("spatial_ring: tile plan does not fit the kernel");
