@@ -252,6 +252,22 @@ def launch_floor_us(torch, npas, n=2000):
     return e0.elapsed_time(e1) * 1e3 / n
 
 
+def stored_traffic(layer_ids):
+    """Mean measured HBM bytes per launch of the given layers of configs[4] at batch 128, from the committed counter
+    summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, one run each; counters cannot be read from inside this process).
+    None when the table is not there or lacks a layer."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "cfg5_batch128_hbm_traffic_per_layer.md")
+    try:
+        rows = {}
+        for line in open(path):
+            f = [c.strip() for c in line.split("|")]
+            if len(f) >= 8 and f[1].isdigit():
+                rows[int(f[1])] = (float(f[5]) + float(f[6])) * 1e6
+        return float(np.mean([rows[i] for i in layer_ids]))
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 # ---- the headline line -----------------------------------------------------------------------------------------
 
 def headline(args, torch, npas, harness, configs):
@@ -325,8 +341,12 @@ def headline(args, torch, npas, harness, configs):
             roof.update(bound="mfma", achieved=ach, peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_PEAK_TFLOPS,
                         launches_counted=len(mm_rows), avg_launch_us=mm_us / len(mm_rows),
                         algorithmic_flop_per_launch=sum(r["flop"] for r in mm_rows) / len(mm_rows))
-        roof.update(kernel=dom, traffic=None,
-                    traffic_note="not measured inside this run; rocprofv3 --pmc figures per layer are in profiles/",
+        counted = hbm_rows if hbm_us >= mm_us else mm_rows
+        stored = stored_traffic([r["i"] for r in counted]) if cfg == 5 and batch == 128 else None
+        roof.update(kernel=dom, traffic=stored,
+                    traffic_note=("STORED figure, not measured in this run: mean HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain "
+                                  "copy) of the same launches, read from profiles/cfg5_batch128_hbm_traffic_per_layer.md" if stored is not None else
+                                  "not measured inside this run; rocprofv3 --pmc figures per layer are in profiles/"),
                     kernel_share_of_stack_time=d["us"] / sum(k["us"] for k in per_kernel.values()))
         out["per_kernel"] = {n: {a: (round(b, 4) if isinstance(b, float) else b) for a, b in k.items() if a not in ("bytes", "flop")}
                              for n, k in per_kernel.items()}
