@@ -252,6 +252,23 @@ def launch_floor_us(torch, npas, n=2000):
     return e0.elapsed_time(e1) * 1e3 / n
 
 
+def graph_replay_floor_us(torch, npas, per_graph=55, replays=200):
+    """The same floor with the empty launches captured in a HIP graph (per_graph launches per replay)."""
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        npas.launch_empty(per_graph, torch.cuda.current_stream().cuda_stream)
+    for _ in range(5):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (replays * per_graph)
+
+
 def stored_traffic(layer_ids):
     """Mean measured HBM bytes per launch of the given layers of configs[4] at batch 128, from the committed counter
     summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, one run each; counters cannot be read from inside this process).
@@ -302,6 +319,7 @@ def headline(args, torch, npas, harness, configs):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3,
         "device_ms_per_step": {"median": med_ms, "min": min_ms, "mean": float(per.mean())},
+        "kept_TFLOPs": kept_flop / wall / 1e12,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": name, "launches_per_step": launches, "buffer_sets": nsets, "images_per_s": batch / wall,
@@ -352,7 +370,8 @@ def headline(args, torch, npas, harness, configs):
                              for n, k in per_kernel.items()}
         out["per_layer_sum_ms"] = sum(r["us"] for r in rows) / 1e3
         floor = launch_floor_us(torch, npas)
-        out["launch_floor_us"] = {"empty_kernel": floor, "times_launches": floor * launches}
+        out["launch_floor_us"] = {"empty_kernel": floor, "times_launches": floor * launches,
+                                  "empty_kernel_in_graph_replay": graph_replay_floor_us(torch, npas, launches)}
     else:
         roof.update(bound="hbm", achieved=None, peak=HBM_PEAK_GBS, unit="GB/s", frac=floor_us / 1e3 / med_ms, traffic=None)
     out["roofline"] = roof
@@ -380,6 +399,10 @@ def headline(args, torch, npas, harness, configs):
                                      "algorithmic_bytes": b2, "GBps": b2 / med2 / 1e3, "hbm_frac": b2 / med2 / 1e3 / HBM_PEAK_GBS,
                                      "TFLOPs_dense_equiv": 2.0 * w2.dense_macs() / med2 / 1e6}
         del r2
+        r2w = StackRunner(w2, torch, npas, harness, flags, 1)   # one buffer set: input and output stay in the Infinity Cache
+        _, p2w = r2w.timed(1000, 50, chunk=50)
+        out["config2_fused_pair"]["warm_median_us"] = float(np.median(p2w)) * 1e3
+        del r2w
         torch.cuda.empty_cache()
 
     if not args.no_cpu:
