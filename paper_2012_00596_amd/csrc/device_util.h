@@ -67,9 +67,11 @@ __device__ __forceinline__ Clamp clamp_of(int act)
     return Clamp{act == NPAS_ACT_NONE ? -INFINITY : 0.0f, (act == NPAS_ACT_RELU6 || act == NPAS_ACT_HARDSWISH) ? 6.0f : INFINITY,
                  act == NPAS_ACT_HARDSWISH};
 }
-__device__ __forceinline__ float clampf(float v, Clamp c)
+// HSW: the launch has a hard-swish somewhere (a kernel body is instantiated with and without; without, an activation
+// is the one clamp instruction and nothing else)
+template <bool HSW = true> __device__ __forceinline__ float clampf(float v, Clamp c)
 {
-    if (c.hs) return v * __builtin_amdgcn_fmed3f(v + 3.0f, 0.0f, 6.0f) * (1.0f / 6.0f);
+    if (HSW && c.hs) return v * __builtin_amdgcn_fmed3f(v + 3.0f, 0.0f, 6.0f) * (1.0f / 6.0f);
     return __builtin_amdgcn_fmed3f(v, c.lo, c.hi);
 }
 

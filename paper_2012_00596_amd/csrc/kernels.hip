@@ -66,8 +66,8 @@ __device__ __forceinline__ void stage_patch(const ConvMfmaArgs &a, uint8_t *lds,
     }
 }
 
-template <int DT, int S>
-__global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
+template <int DT, int S, bool HSW>
+__device__ __forceinline__ void conv_gather_mfma_kernel_body(ConvMfmaArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const ConvGeom &g = a.g;
@@ -192,8 +192,8 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
                                 v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
                             }
                             uint2 out;
-                            out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-                            out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                            out.x = pack2<DT>(clampf<HSW>(v[0], cl), clampf<HSW>(v[1], cl));
+                            out.y = pack2<DT>(clampf<HSW>(v[2], cl), clampf<HSW>(v[3], cl));
                             *reinterpret_cast<uint2 *>(y16 + o) = out;
                         } else {
 #pragma unroll
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
                                 if (f0 + i < g.F) {
                                     float t = v[i];
                                     if (r16) t += from_storage<DT>(r16[o + i]);
-                                    y16[o + i] = (uint16_t)(pack2<DT>(clampf(t, cl), 0.f) & 0xffffu);
+                                    y16[o + i] = (uint16_t)(pack2<DT>(clampf<HSW>(t, cl), 0.f) & 0xffffu);
                                 }
                         }
                     }
@@ -209,6 +209,14 @@ __global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
             }
         }
     }
+}
+// The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
+// interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
+template <int DT, int S>
+__global__ __launch_bounds__(256) void conv_gather_mfma_kernel(ConvMfmaArgs a)
+{
+    if (a.g.act == NPAS_ACT_HARDSWISH) conv_gather_mfma_kernel_body<DT, S, true>(a);
+    else conv_gather_mfma_kernel_body<DT, S, false>(a);
 }
 
 // ------------------------------------------------------------------------------
@@ -315,8 +323,8 @@ __device__ __forceinline__ void slab_patch_store(uint8_t *buf, const SlabDesc<NP
     for (int i = 0; i < NPF; ++i) *reinterpret_cast<uint4 *>(buf + d.loff[i]) = pf[i];
 }
 
-template <int DT, int WT, int WB, int WGF, int NPF, int OCC>
-__global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a)
+template <int DT, int WT, int WB, int WGF, int NPF, int OCC, bool HSW>
+__device__ __forceinline__ void conv_slab_mfma_kernel_body(ConvMfmaArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const ConvGeom &g = a.g;
@@ -445,8 +453,8 @@ __global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a
                             acc[j][s][3] += from_storage<DT>((uint16_t)(res[j][s].y >> 16));
                         }
                         uint2 out;
-                        out.x = pack2<DT>(clampf(acc[j][s][0], cl), clampf(acc[j][s][1], cl));
-                        out.y = pack2<DT>(clampf(acc[j][s][2], cl), clampf(acc[j][s][3], cl));
+                        out.x = pack2<DT>(clampf<HSW>(acc[j][s][0], cl), clampf<HSW>(acc[j][s][1], cl));
+                        out.y = pack2<DT>(clampf<HSW>(acc[j][s][2], cl), clampf<HSW>(acc[j][s][3], cl));
                         *reinterpret_cast<uint2 *>(yb + obyte[s] + 32u * j) = out;
                     }
                 }
@@ -458,6 +466,14 @@ __global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a
         item = nitem;
         it = nit;
     }
+}
+// The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
+// interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
+template <int DT, int WT, int WB, int WGF, int NPF, int OCC>
+__global__ __launch_bounds__(256, OCC) void conv_slab_mfma_kernel(ConvMfmaArgs a)
+{
+    if (a.g.act == NPAS_ACT_HARDSWISH) conv_slab_mfma_kernel_body<DT, WT, WB, WGF, NPF, OCC, true>(a);
+    else conv_slab_mfma_kernel_body<DT, WT, WB, WGF, NPF, OCC, false>(a);
 }
 
 template <int DT, int WT, int WB, int WGF, int NPF, int OCC>
@@ -881,8 +897,8 @@ constexpr int kSmallCLoads = 24;
 // POOL: the layer is followed by a 3 x 3 / stride 2 / pad 1 max pool.  The tile's conv outputs (after bias,
 // activation and rounding; positions outside the conv output as -inf) go to LDS instead of memory, and the
 // workgroup then writes the pooled pixels that lie wholly inside the tile: the conv output never reaches HBM.
-template <int DT, int NS, bool WIDE, bool POOL>
-__global__ __launch_bounds__(256, POOL ? 2 : 1) void conv_smallc_mfma_kernel(SmallCArgs a) // (two waves per SIMD: 256 registers; left alone the pooled variant takes 264 and one workgroup per CU)
+template <int DT, int NS, bool WIDE, bool POOL, bool HSW>
+__device__ __forceinline__ void conv_smallc_mfma_kernel_body(SmallCArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -1005,8 +1021,8 @@ __global__ __launch_bounds__(256, POOL ? 2 : 1) void conv_smallc_mfma_kernel(Sma
                     const uint32_t ninf = DT == NPAS_BF16 ? 0xff80ff80u : 0xfc00fc00u; // -inf, -inf
                     uint2 out{ninf, ninf};
                     if (valid) {
-                        out.x = pack2<DT>(clampf(acc[0][i], cl), clampf(acc[1][i], cl));
-                        out.y = pack2<DT>(clampf(acc[2][i], cl), clampf(acc[3][i], cl));
+                        out.x = pack2<DT>(clampf<HSW>(acc[0][i], cl), clampf<HSW>(acc[1][i], cl));
+                        out.y = pack2<DT>(clampf<HSW>(acc[2][i], cl), clampf<HSW>(acc[3][i], cl));
                     }
                     *reinterpret_cast<uint2 *>(ctile + (m0 + (uint32_t)i) * 128u + (uint32_t)n16 * 8u) = out;
                     continue;
@@ -1022,8 +1038,8 @@ __global__ __launch_bounds__(256, POOL ? 2 : 1) void conv_smallc_mfma_kernel(Sma
                     v[3] += from_storage<DT>((uint16_t)(r2.y >> 16));
                 }
                 uint2 out;
-                out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-                out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+                out.x = pack2<DT>(clampf<HSW>(v[0], cl), clampf<HSW>(v[1], cl));
+                out.y = pack2<DT>(clampf<HSW>(v[2], cl), clampf<HSW>(v[3], cl));
                 *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o) = out;
             }
         }
@@ -1064,6 +1080,14 @@ __global__ __launch_bounds__(256, POOL ? 2 : 1) void conv_smallc_mfma_kernel(Sma
         }
         item = next;
     }
+}
+// The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
+// interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
+template <int DT, int NS, bool WIDE, bool POOL>
+__global__ __launch_bounds__(256, POOL ? 2 : 1) void conv_smallc_mfma_kernel(SmallCArgs a) // (two waves per SIMD: 256 registers; left alone the pooled variant takes 264 and one workgroup per CU)
+{
+    if (a.act == NPAS_ACT_HARDSWISH) conv_smallc_mfma_kernel_body<DT, NS, WIDE, POOL, true>(a);
+    else conv_smallc_mfma_kernel_body<DT, NS, WIDE, POOL, false>(a);
 }
 
 // Persistent workgroups, exactly as many as are resident at once (a workgroup that had to wait for
@@ -1151,8 +1175,8 @@ struct SmallMPix {
     int n, iy0, ix0; // image and input coordinates of tap (0, 0); n < 0: no such pixel
 };
 
-template <int DT>
-__global__ __launch_bounds__(1024) void conv_smallm_mfma_kernel(SmallMArgs a)
+template <int DT, bool HSW>
+__device__ __forceinline__ void conv_smallm_mfma_kernel_body(SmallMArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -1233,8 +1257,16 @@ __global__ __launch_bounds__(1024) void conv_smallm_mfma_kernel(SmallMArgs a)
         if (a.bias) v += a.bias[f];
         const size_t o = (size_t)m * a.F + (size_t)f;
         if (r16) v += from_storage<DT>(r16[o]);
-        y16[o] = to_storage<DT>(clampf(v, cl));
+        y16[o] = to_storage<DT>(clampf<HSW>(v, cl));
     }
+}
+// The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
+// interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
+template <int DT>
+__global__ __launch_bounds__(1024) void conv_smallm_mfma_kernel(SmallMArgs a)
+{
+    if (a.act == NPAS_ACT_HARDSWISH) conv_smallm_mfma_kernel_body<DT, true>(a);
+    else conv_smallm_mfma_kernel_body<DT, false>(a);
 }
 
 int launch_conv_smallm(int dtype, const SmallMArgs &a, void *stream)
@@ -1301,7 +1333,7 @@ constexpr int kFppBlocksPerWave = 8; // 16-pixel blocks a wave owns; all their l
 // Straight-line body for a wave that owns exactly CNT blocks starting at block b0.
 // No branch between the loads and their uses, so the compiler can wait for block k's
 // activations alone (s_waitcnt vmcnt(n)) while later blocks are still in flight.
-template <int DT, int NT1, int NT2, int CNT>
+template <int DT, int NT1, int NT2, int CNT, bool HSW>
 __device__ __forceinline__ void fpp_body(const FppArgs &a, int b0, int n16, int q, int lane)
 {
     constexpr int NCH = NT1 / 2;
@@ -1353,10 +1385,10 @@ __device__ __forceinline__ void fpp_body(const FppArgs &a, int b0, int n16, int 
 #pragma unroll
         for (int j = 0; j < NCH; ++j) {
             uint4 b;
-            b.x = pack2<DT>(clampf(d1[2 * j][0], c1), clampf(d1[2 * j][1], c1));
-            b.y = pack2<DT>(clampf(d1[2 * j][2], c1), clampf(d1[2 * j][3], c1));
-            b.z = pack2<DT>(clampf(d1[2 * j + 1][0], c1), clampf(d1[2 * j + 1][1], c1));
-            b.w = pack2<DT>(clampf(d1[2 * j + 1][2], c1), clampf(d1[2 * j + 1][3], c1));
+            b.x = pack2<DT>(clampf<HSW>(d1[2 * j][0], c1), clampf<HSW>(d1[2 * j][1], c1));
+            b.y = pack2<DT>(clampf<HSW>(d1[2 * j][2], c1), clampf<HSW>(d1[2 * j][3], c1));
+            b.z = pack2<DT>(clampf<HSW>(d1[2 * j + 1][0], c1), clampf<HSW>(d1[2 * j + 1][1], c1));
+            b.w = pack2<DT>(clampf<HSW>(d1[2 * j + 1][2], c1), clampf<HSW>(d1[2 * j + 1][3], c1));
 #pragma unroll
             for (int u = 0; u < NT2; ++u) d2[u] = mfma16<DT>(A2[u][j], b, d2[u]);
         }
@@ -1364,8 +1396,8 @@ __device__ __forceinline__ void fpp_body(const FppArgs &a, int b0, int n16, int 
 #pragma unroll
         for (int u = 0; u < NT2; ++u) {
             uint2 o;
-            o.x = pack2<DT>(clampf(d2[u][0], c2), clampf(d2[u][1], c2));
-            o.y = pack2<DT>(clampf(d2[u][2], c2), clampf(d2[u][3], c2));
+            o.x = pack2<DT>(clampf<HSW>(d2[u][0], c2), clampf<HSW>(d2[u][1], c2));
+            o.y = pack2<DT>(clampf<HSW>(d2[u][2], c2), clampf<HSW>(d2[u][3], c2));
             store_stream8(y16 + (size_t)pix * a.F2 + fst[u], o); // written once, read by nobody in this launch
         }
     }
@@ -1380,17 +1412,23 @@ __global__ __launch_bounds__(256, 2) void fused_pointwise_pair_kernel(FppArgs a)
     // contiguous run of blocks per wave, remainder spread over the first waves
     const int base = nblk / nw, extra = nblk % nw;
     const int b0 = gw * base + min(gw, extra), cnt = base + (gw < extra ? 1 : 0);
-    switch (cnt) { // wave-uniform
-    case 1: fpp_body<DT, NT1, NT2, 1>(a, b0, n16, q, lane); break;
-    case 2: fpp_body<DT, NT1, NT2, 2>(a, b0, n16, q, lane); break;
-    case 3: fpp_body<DT, NT1, NT2, 3>(a, b0, n16, q, lane); break;
-    case 4: fpp_body<DT, NT1, NT2, 4>(a, b0, n16, q, lane); break;
-    case 5: fpp_body<DT, NT1, NT2, 5>(a, b0, n16, q, lane); break;
-    case 6: fpp_body<DT, NT1, NT2, 6>(a, b0, n16, q, lane); break;
-    case 7: fpp_body<DT, NT1, NT2, 7>(a, b0, n16, q, lane); break;
-    case 8: fpp_body<DT, NT1, NT2, 8>(a, b0, n16, q, lane); break;
-    default: break;
-    }
+    // (the activation kinds compiled in: see clampf)
+    auto run = [&](auto hsw) __attribute__((always_inline)) {
+        constexpr bool H = decltype(hsw)::value;
+        switch (cnt) { // wave-uniform
+        case 1: fpp_body<DT, NT1, NT2, 1, H>(a, b0, n16, q, lane); break;
+        case 2: fpp_body<DT, NT1, NT2, 2, H>(a, b0, n16, q, lane); break;
+        case 3: fpp_body<DT, NT1, NT2, 3, H>(a, b0, n16, q, lane); break;
+        case 4: fpp_body<DT, NT1, NT2, 4, H>(a, b0, n16, q, lane); break;
+        case 5: fpp_body<DT, NT1, NT2, 5, H>(a, b0, n16, q, lane); break;
+        case 6: fpp_body<DT, NT1, NT2, 6, H>(a, b0, n16, q, lane); break;
+        case 7: fpp_body<DT, NT1, NT2, 7, H>(a, b0, n16, q, lane); break;
+        case 8: fpp_body<DT, NT1, NT2, 8, H>(a, b0, n16, q, lane); break;
+        default: break;
+        }
+    };
+    if (a.act1 == NPAS_ACT_HARDSWISH || a.act2 == NPAS_ACT_HARDSWISH) run(std::true_type{});
+    else run(std::false_type{});
 }
 
 template <int DT, int NT1, int NT2> static void fpp_launch(const FppArgs &a, unsigned grid, hipStream_t st)
@@ -1686,8 +1724,8 @@ struct IrArgs {
 // BIAS: some layer of the block has one (bias tables in LDS, halo pixels outside the image zeroed explicitly: the
 // padding of the depthwise layer is zero, not act1(b1)).  Without, x = 0 there already gives zero, and the kernel
 // keeps the registers that let three workgroups share a CU.
-template <int DT, bool BIAS>
-__global__ __launch_bounds__(256, 3) void fused_inverted_residual_kernel(IrArgs a) // three workgroups per CU: at most 168 registers
+template <int DT, bool BIAS, bool HSW>
+__device__ __forceinline__ void fused_inverted_residual_kernel_body(IrArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -1746,8 +1784,8 @@ __global__ __launch_bounds__(256, 3) void fused_inverted_residual_kernel(IrArgs 
                 float4 bb = float4{0.f, 0.f, 0.f, 0.f};
                 if (BIAS) bb = *reinterpret_cast<const float4 *>(lb1 + 16 * t + 4 * q); // result register i: slot 16 t + 4 q + i
                 uint2 o;
-                o.x = pack2<DT>(clampf(d[0] + bb.x, cl1), clampf(d[1] + bb.y, cl1));
-                o.y = pack2<DT>(clampf(d[2] + bb.z, cl1), clampf(d[3] + bb.w, cl1));
+                o.x = pack2<DT>(clampf<HSW>(d[0] + bb.x, cl1), clampf<HSW>(d[1] + bb.y, cl1));
+                o.y = pack2<DT>(clampf<HSW>(d[2] + bb.z, cl1), clampf<HSW>(d[3] + bb.w, cl1));
                 if (BIAS && !inside[r]) o = uint2{0u, 0u}; // padding of the depthwise layer, whatever the bias
                 *reinterpret_cast<uint2 *>(dst + t * 32) = o;
             }
@@ -1793,10 +1831,10 @@ __global__ __launch_bounds__(256, 3) void fused_inverted_residual_kernel(IrArgs 
                 s[7] = dot2acc<DT>(v.w, wb.w, s[7]);
             }
             uint4 b;
-            b.x = pack2<DT>(clampf(s[0], cl2), clampf(s[1], cl2));
-            b.y = pack2<DT>(clampf(s[2], cl2), clampf(s[3], cl2));
-            b.z = pack2<DT>(clampf(s[4], cl2), clampf(s[5], cl2));
-            b.w = pack2<DT>(clampf(s[6], cl2), clampf(s[7], cl2));
+            b.x = pack2<DT>(clampf<HSW>(s[0], cl2), clampf<HSW>(s[1], cl2));
+            b.y = pack2<DT>(clampf<HSW>(s[2], cl2), clampf<HSW>(s[3], cl2));
+            b.z = pack2<DT>(clampf<HSW>(s[4], cl2), clampf<HSW>(s[5], cl2));
+            b.w = pack2<DT>(clampf<HSW>(s[6], cl2), clampf<HSW>(s[7], cl2));
             acc0 = mfma16<DT>(w3a, b, acc0);
             if (a.nt3 == 2) acc1 = mfma16<DT>(w3b, b, acc1);
         }
@@ -1819,11 +1857,19 @@ __global__ __launch_bounds__(256, 3) void fused_inverted_residual_kernel(IrArgs 
                 v[3] += from_storage<DT>((uint16_t)(r.y >> 16));
             }
             uint2 o;
-            o.x = pack2<DT>(clampf(v[0], cl3), clampf(v[1], cl3));
-            o.y = pack2<DT>(clampf(v[2], cl3), clampf(v[3], cl3));
+            o.x = pack2<DT>(clampf<HSW>(v[0], cl3), clampf<HSW>(v[1], cl3));
+            o.y = pack2<DT>(clampf<HSW>(v[2], cl3), clampf<HSW>(v[3], cl3));
             store_stream8(y16 + pix * a.F3 + f, o);
         }
     }
+}
+// The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
+// interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
+template <int DT, bool BIAS>
+__global__ __launch_bounds__(256, 3) void fused_inverted_residual_kernel(IrArgs a) // three workgroups per CU: at most 168 registers
+{
+    if (a.act1 == NPAS_ACT_HARDSWISH || a.act2 == NPAS_ACT_HARDSWISH || a.act3 == NPAS_ACT_HARDSWISH) fused_inverted_residual_kernel_body<DT, BIAS, true>(a);
+    else fused_inverted_residual_kernel_body<DT, BIAS, false>(a);
 }
 
 size_t fused_ir_lds_bytes(int TH, int TW, int nslots, int stride)
@@ -1965,8 +2011,8 @@ struct DwArgs {
     uint32_t div_cv, div_wo, div_nyb;   // fastdiv magics
 };
 
-template <int DT, int STRIDE>
-__global__ __launch_bounds__(256, 3) void depthwise3x3_rows_kernel(DwArgs a)
+template <int DT, int STRIDE, bool HSW>
+__device__ __forceinline__ void depthwise3x3_rows_kernel_body(DwArgs a)
 {
     const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= a.total) return;
@@ -2043,12 +2089,20 @@ __global__ __launch_bounds__(256, 3) void depthwise3x3_rows_kernel(DwArgs a)
             }
         }
         uint4 out;
-        out.x = pack2<DT>(clampf(acc[j][0], cl), clampf(acc[j][1], cl));
-        out.y = pack2<DT>(clampf(acc[j][2], cl), clampf(acc[j][3], cl));
-        out.z = pack2<DT>(clampf(acc[j][4], cl), clampf(acc[j][5], cl));
-        out.w = pack2<DT>(clampf(acc[j][6], cl), clampf(acc[j][7], cl));
+        out.x = pack2<DT>(clampf<HSW>(acc[j][0], cl), clampf<HSW>(acc[j][1], cl));
+        out.y = pack2<DT>(clampf<HSW>(acc[j][2], cl), clampf<HSW>(acc[j][3], cl));
+        out.z = pack2<DT>(clampf<HSW>(acc[j][4], cl), clampf<HSW>(acc[j][5], cl));
+        out.w = pack2<DT>(clampf<HSW>(acc[j][6], cl), clampf<HSW>(acc[j][7], cl));
         store_stream16(reinterpret_cast<uint16_t *>(a.y) + yo, out);
     }
+}
+// The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
+// interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
+template <int DT, int STRIDE>
+__global__ __launch_bounds__(256, 3) void depthwise3x3_rows_kernel(DwArgs a)
+{
+    if (a.act == NPAS_ACT_HARDSWISH) depthwise3x3_rows_kernel_body<DT, STRIDE, true>(a);
+    else depthwise3x3_rows_kernel_body<DT, STRIDE, false>(a);
 }
 
 static uint32_t magic32(uint32_t d) { return d <= 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d); }

@@ -29,8 +29,8 @@ namespace npas {
 // lane (pixel n, quarter q) is filter 16 t + 4 q + i.
 constexpr int kFcSteps = 4; // list steps whose loads are issued together
 
-template <int DT>
-__global__ __launch_bounds__(512) void fc_gather_mfma_kernel(FcGatherArgs a)
+template <int DT, bool HSW>
+__device__ __forceinline__ void fc_gather_mfma_kernel_body(FcGatherArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n16 = lane & 15, q = lane >> 4;
@@ -126,9 +126,17 @@ __global__ __launch_bounds__(512) void fc_gather_mfma_kernel(FcGatherArgs a)
         v[3] += from_storage<DT>((uint16_t)(r2.y >> 16));
     }
     uint2 out;
-    out.x = pack2<DT>(clampf(v[0], cl), clampf(v[1], cl));
-    out.y = pack2<DT>(clampf(v[2], cl), clampf(v[3], cl));
+    out.x = pack2<DT>(clampf<HSW>(v[0], cl), clampf<HSW>(v[1], cl));
+    out.y = pack2<DT>(clampf<HSW>(v[2], cl), clampf<HSW>(v[3], cl));
     *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(a.y) + o) = out;
+}
+// The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
+// interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
+template <int DT>
+__global__ __launch_bounds__(512) void fc_gather_mfma_kernel(FcGatherArgs a)
+{
+    if (a.act == NPAS_ACT_HARDSWISH) fc_gather_mfma_kernel_body<DT, true>(a);
+    else fc_gather_mfma_kernel_body<DT, false>(a);
 }
 
 int launch_fc_gather(int dtype, const FcGatherArgs &a, void *stream)
