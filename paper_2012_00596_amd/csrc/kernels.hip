@@ -1865,11 +1865,10 @@ __device__ __forceinline__ void fused_inverted_residual_kernel_body(IrArgs a)
 }
 // The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
 // interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
-template <int DT, bool BIAS>
+template <int DT, bool BIAS, bool HSW>
 __global__ __launch_bounds__(256, 3) void fused_inverted_residual_kernel(IrArgs a) // three workgroups per CU: at most 168 registers
 {
-    if (a.act1 == NPAS_ACT_HARDSWISH || a.act2 == NPAS_ACT_HARDSWISH || a.act3 == NPAS_ACT_HARDSWISH) fused_inverted_residual_kernel_body<DT, BIAS, true>(a);
-    else fused_inverted_residual_kernel_body<DT, BIAS, false>(a);
+    fused_inverted_residual_kernel_body<DT, BIAS, HSW>(a); // (a kernel per activation class, chosen at the launch: registers are tight here)
 }
 
 size_t fused_ir_lds_bytes(int TH, int TW, int nslots, int stride)
@@ -1901,17 +1900,22 @@ int launch_fused_inverted_residual(int dtype, const IrLaunch &l, void *stream)
     }
     const long grid = (long)N * a.tilesY * a.tilesX;
     const bool bias = l.b1 || l.b2 || l.b3;
-    static std::once_flag once[4];
+    const bool hsw = l.act1 == NPAS_ACT_HARDSWISH || l.act2 == NPAS_ACT_HARDSWISH || l.act3 == NPAS_ACT_HARDSWISH;
+    static std::once_flag once[8];
     auto go = [&](auto kern, std::once_flag &flag) {
         allow_lds_once(flag, kern, 160 * 1024);
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds_bytes, st, a);
     };
     if (dtype == NPAS_BF16) {
-        if (bias) go(fused_inverted_residual_kernel<NPAS_BF16, true>, once[0]);
-        else go(fused_inverted_residual_kernel<NPAS_BF16, false>, once[1]);
+        if (bias && hsw) go(fused_inverted_residual_kernel<NPAS_BF16, true, true>, once[0]);
+        else if (bias) go(fused_inverted_residual_kernel<NPAS_BF16, true, false>, once[1]);
+        else if (hsw) go(fused_inverted_residual_kernel<NPAS_BF16, false, true>, once[2]);
+        else go(fused_inverted_residual_kernel<NPAS_BF16, false, false>, once[3]);
     } else if (dtype == NPAS_F16) {
-        if (bias) go(fused_inverted_residual_kernel<NPAS_F16, true>, once[2]);
-        else go(fused_inverted_residual_kernel<NPAS_F16, false>, once[3]);
+        if (bias && hsw) go(fused_inverted_residual_kernel<NPAS_F16, true, true>, once[4]);
+        else if (bias) go(fused_inverted_residual_kernel<NPAS_F16, true, false>, once[5]);
+        else if (hsw) go(fused_inverted_residual_kernel<NPAS_F16, false, true>, once[6]);
+        else go(fused_inverted_residual_kernel<NPAS_F16, false, false>, once[7]);
     } else {
         set_error("fused inverted residual needs a 16-bit storage type");
         return NPAS_E_DTYPE;
@@ -2098,13 +2102,10 @@ __device__ __forceinline__ void depthwise3x3_rows_kernel_body(DwArgs a)
 }
 // The activation kind is compiled in: hard-swish behind a (wave-uniform) branch per value kept the compiler from
 // interleaving loads, MFMAs and epilogue arithmetic across values and cost the launches without it 15-50 %.
-template <int DT, int STRIDE>
+template <int DT, int STRIDE, bool HSW>
 __global__ __launch_bounds__(256, 3) void depthwise3x3_rows_kernel(DwArgs a)
 {
-    // stride 2 keeps one body with the activation kind looked up per value: with two, its spills moved into the row loop
-    // (62 -> 106 us on 56 x 56 x 144 at batch 64)
-    if (STRIDE == 2 || a.act == NPAS_ACT_HARDSWISH) depthwise3x3_rows_kernel_body<DT, STRIDE, true>(a);
-    else depthwise3x3_rows_kernel_body<DT, STRIDE, false>(a);
+    depthwise3x3_rows_kernel_body<DT, STRIDE, HSW>(a); // (one body per kernel: with two behind a branch the stride-2 variant's spills moved into its row loop)
 }
 
 static uint32_t magic32(uint32_t d) { return d <= 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d); }
@@ -2124,11 +2125,18 @@ int launch_depthwise3x3(int dt, const void *x, void *y, const void *w, const flo
                      magic32(CV), magic32((uint32_t)Wo), magic32(nyb)};
             const unsigned grid = (a.total + 255u) / 256u;
             if (dt == NPAS_BF16) {
-                if (stride == 1) hipLaunchKernelGGL((depthwise3x3_rows_kernel<NPAS_BF16, 1>), dim3(grid), dim3(256), 0, st, a);
-                else hipLaunchKernelGGL((depthwise3x3_rows_kernel<NPAS_BF16, 2>), dim3(grid), dim3(256), 0, st, a);
+#define NPAS_DWR(DT_)                                                                                                           \
+    do {                                                                                                                         \
+        const bool hs = a.act == NPAS_ACT_HARDSWISH;                                                                            \
+        if (stride == 1 && hs) hipLaunchKernelGGL((depthwise3x3_rows_kernel<DT_, 1, true>), dim3(grid), dim3(256), 0, st, a);   \
+        else if (stride == 1) hipLaunchKernelGGL((depthwise3x3_rows_kernel<DT_, 1, false>), dim3(grid), dim3(256), 0, st, a);   \
+        else if (hs) hipLaunchKernelGGL((depthwise3x3_rows_kernel<DT_, 2, true>), dim3(grid), dim3(256), 0, st, a);            \
+        else hipLaunchKernelGGL((depthwise3x3_rows_kernel<DT_, 2, false>), dim3(grid), dim3(256), 0, st, a);                   \
+    } while (0)
+                NPAS_DWR(NPAS_BF16);
             } else {
-                if (stride == 1) hipLaunchKernelGGL((depthwise3x3_rows_kernel<NPAS_F16, 1>), dim3(grid), dim3(256), 0, st, a);
-                else hipLaunchKernelGGL((depthwise3x3_rows_kernel<NPAS_F16, 2>), dim3(grid), dim3(256), 0, st, a);
+                NPAS_DWR(NPAS_F16);
+#undef NPAS_DWR
             }
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) {
