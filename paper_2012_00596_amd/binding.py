@@ -9,7 +9,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 _LIB = os.path.join(_HERE, "libnpas.so")
-SOURCES = ["pack.cpp", "api.cpp", "kernels.hip", "spatial_kernels.hip", "small_kernels.hip", "noalloc.hip"]
+SOURCES = ["pack.cpp", "api.cpp", "kernels.hip", "spatial_kernels.hip", "small_kernels.hip", "block_kernels.hip", "noalloc.hip"]
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "npas.h")
 
 F32, BF16, F16 = 0, 1, 2

@@ -108,6 +108,18 @@ template <int DT> __device__ __forceinline__ float from_storage(uint16_t b)
     return (float)__builtin_bit_cast(_Float16, b);
 }
 
+// element i of an activation tensor of storage type DT as fp32, and back
+template <int DT> __device__ __forceinline__ float ld_act(const void *p, size_t i)
+{
+    if (DT == NPAS_F32) return reinterpret_cast<const float *>(p)[i];
+    return from_storage<DT>(reinterpret_cast<const uint16_t *>(p)[i]);
+}
+template <int DT> __device__ __forceinline__ void st_act(void *p, size_t i, float v)
+{
+    if (DT == NPAS_F32) reinterpret_cast<float *>(p)[i] = v;
+    else reinterpret_cast<uint16_t *>(p)[i] = to_storage<DT>(v);
+}
+
 template <int DT> __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c)
 {
     if (DT == NPAS_BF16)
