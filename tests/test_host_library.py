@@ -277,3 +277,12 @@ def test_switches_are_read_once_and_can_be_replaced():
     finally:
         npas.set_switches(None)
     assert npas.conv2d_kernel_name(p, 2, 14, 14, 1, 1) == "conv_smallm_mfma"
+
+
+def test_spatial_ring_is_not_planned_beyond_its_24_bit_pixel_count():
+    """The spatial ring forms its patch addresses with 24-bit multiplies: a launch with 2^24 input pixels or more
+    gets another kernel (the planner's rule, checked on the host)."""
+    p = _bp_layer(128, 128, 3, 43)
+    assert npas.conv2d_kernel_name(p, 128, 28, 28, 1, 1) == "spatial_ring"
+    assert 21400 * 28 * 28 >= 1 << 24
+    assert npas.conv2d_kernel_name(p, 21400, 28, 28, 1, 1) != "spatial_ring"
